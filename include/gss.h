@@ -1,0 +1,151 @@
+/*
+ * libgss: guided source separation (GSS) hot path for AMD MI355X (gfx950).
+ *
+ * The calls follow the problem statement of arXiv 2212.05271, Section 2:
+ * multichannel STFT Y[f,t,:] in C^D plus binary speaker activities a[k,t]
+ * -> cACGMM masks gamma[k,f,t] (Section 2.2) -> mask-based MVDR output
+ * X[f,t] for one target class (Section 2.3), with the STFT and its inverse
+ * around them (Section 3, the list of operations moved to the GPU).
+ *
+ * Conventions common to every entry point
+ *   - Plain C ABI.  Pointers are DEVICE pointers unless the comment says "host".
+ *   - The caller owns every input and output buffer.  The library owns only its
+ *     context and the scratch memory inside it (grown on demand with hipMalloc,
+ *     freed by gss_destroy).
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns without synchronising the host,
+ *     except that growing the scratch memory synchronises the device once.
+ *   - Calls that share one context must be issued on one stream (or be ordered
+ *     by the caller): they share the context's scratch memory.
+ *   - Return value: GSS_OK (0) or a negative gss_status.  Nothing is written on
+ *     error.  The library never aborts and never writes outside the outputs.
+ *   - Complex numbers are interleaved (re, im) float pairs ("complex64").
+ *   - Layouts are C order, last index fastest.
+ *   - D = number of channels, K = number of mixture classes INCLUDING the noise
+ *     class (the noise class is simply a row of `activity` that is all ones),
+ *     F = frequency bins, S = segments in the batch, Tmax = padded frame count.
+ *   - T_len[s] (device, may be NULL = every segment has Tmax frames) gives the
+ *     number of valid frames of segment s; outputs at t >= T_len[s] are exact 0.
+ */
+#ifndef GSS_H
+#define GSS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum gss_status {
+  GSS_OK = 0,
+  GSS_EINVAL = -1,       /* null pointer, non-positive size, out-of-range argument   */
+  GSS_EUNSUPPORTED = -2, /* shape outside what the kernels are built for             */
+  GSS_ENOMEM = -3,       /* scratch allocation failed                                */
+  GSS_EHIP = -4          /* the HIP runtime reported an error (launch, device, ...)  */
+} gss_status;
+
+/* Limits of the kernels in this build. */
+#define GSS_MAX_D 32
+#define GSS_MAX_K 8
+
+/* Bits of the device status word (gss_get_status). */
+#define GSS_STATUS_NONPD_B 1u        /* a class scatter matrix had a non-positive pivot; the pivot was floored */
+#define GSS_STATUS_NONPD_PHI 2u      /* the loaded background covariance had a non-positive pivot; floored     */
+
+typedef struct gss_ctx gss_ctx;
+
+/* Create / destroy a context on HIP device `device_id`.  *out is set only on success. */
+int gss_create(gss_ctx** out, int device_id);
+void gss_destroy(gss_ctx* ctx);
+
+/* Static, human-readable text for a gss_status value. */
+const char* gss_strerror(int code);
+
+/* Library version string ("major.minor.patch"), static storage. */
+const char* gss_version(void);
+
+/* Copies the device status word (OR of GSS_STATUS_* bits raised by earlier calls on this context)
+ * to *host_out (host pointer) and clears it.  Synchronises `stream`. */
+int gss_get_status(gss_ctx* ctx, uint32_t* host_out, void* stream);
+
+/* Scratch bytes currently held by the context (host query, no device work). */
+int64_t gss_scratch_bytes(const gss_ctx* ctx);
+
+/*
+ * STFT (Section 3 of the paper lists feature extraction among the operations run on the GPU; the paper
+ * fixes only "513 bins", i.e. n_fft = 1024).
+ *   x   [S][D][N] float32 time-domain samples
+ *   Y   [S][F][T][D] complex64, F = n_fft/2 + 1, T = ceil(N / hop) + 3  (must equal the T passed in)
+ * Periodic Hann window of n_fft samples; the signal is zero-padded by n_fft - hop samples on both
+ * sides, so frame t covers samples [(t-3)*hop, (t+1)*hop).  Only n_fft = 1024, hop = 256 is built.
+ */
+int gss_stft(gss_ctx* ctx, const float* x, int S, int D, int64_t N, int n_fft, int hop,
+             float* Y, int T, void* stream);
+
+/*
+ * Guided cACGMM EM, independent per (segment, frequency): Eq. (2)-(5) and the EM loop of Section 2.2.
+ *   Y        [S][F][Tmax][D] complex64, any scale (unit-normalised internally, Eq. (2))
+ *   activity [S][K][Tmax] uint8, non-zero = class k may be active in frame t (a_{t,k} of Eq. (5))
+ *   T_len    [S] int32 or NULL
+ *   iters    >= 0 EM iterations (each = M-step then E-step); 0 returns the normalised activity
+ *   weight_mode  1: pi_{f,k} proportional to sum_t gamma; 0: pi uniform
+ *   gamma    [S][K][F][Tmax] float32 out: the state posteriors after the last E-step = the masks.
+ *            Exact 0 where activity is 0 and at t >= T_len[s].
+ * Limits: 1 <= D <= GSS_MAX_D, 1 <= K <= GSS_MAX_K.
+ */
+int gss_cacgmm_em(gss_ctx* ctx, const float* Y, const uint8_t* activity, const int32_t* T_len,
+                  int S, int F, int Tmax, int D, int K, int iters, int weight_mode,
+                  float* gamma, void* stream);
+
+/*
+ * Mask-based MVDR (Souden form), Eq. (6)-(9) of Section 2.3, per segment and frequency.
+ *   Y      [S][F][Tmax][D] complex64: used as handed over (NOT normalised inside)
+ *   gamma  [S][K][F][Tmax] float32 masks
+ *   target [S] int32: index of the class to extract, 0 <= target[s] < K
+ *   ref    [S] int32 in/out: >= 0 = use this reference channel; < 0 = choose the channel with the
+ *          largest ratio of beamformed target power to beamformed background power summed over
+ *          frequency (lowest index on ties); on return holds the channel used
+ *   X      [S][F][Tmax] complex64 out: h(f)^H y_{t,f}; exact 0 at t >= T_len[s]
+ */
+int gss_mvdr(gss_ctx* ctx, const float* Y, const float* gamma, const int32_t* T_len,
+             int S, int F, int Tmax, int D, int K, const int32_t* target, int32_t* ref,
+             float* X, void* stream);
+
+/*
+ * Inverse STFT matching gss_stft: inverse real FFT, synthesis window w / sum_shifts(w^2), overlap-add,
+ * padding stripped.
+ *   X  [S][F][T] complex64   (F = n_fft/2 + 1)
+ *   x  [S][N] float32 out, with ceil(N / hop) + 3 == T
+ */
+int gss_istft(gss_ctx* ctx, const float* X, int S, int T, int n_fft, int hop,
+              float* x, int64_t N, void* stream);
+
+/*
+ * Segment + context -> sample span and frame range (host, integers only; Section 2.2 "context window",
+ * Section 3 item (ii)).  All pointers are HOST pointers.
+ *   seg_start/seg_end [n_seg] target segment [start, end) in samples of a recording of n_samples
+ *   ctx_left/ctx_right  context in samples added before / after (clipped to the recording)
+ * Outputs, each [n_seg] (any may be NULL):
+ *   ext_start, ext_end : the extended span snapped outward to multiples of hop (clipped to the
+ *                        hop-rounded recording length)
+ *   frame0, n_frames   : its frames in the recording's STFT (gss_stft numbering);
+ *                        n_frames = (ext_end - ext_start)/hop + 3
+ *   cut_start, cut_end : the target region as sample offsets inside the inverse STFT of those frames
+ */
+int gss_frames_from_segments(const int64_t* seg_start, const int64_t* seg_end, int n_seg,
+                             int64_t n_samples, int64_t ctx_left, int64_t ctx_right, int hop,
+                             int64_t* ext_start, int64_t* ext_end, int64_t* frame0, int32_t* n_frames,
+                             int64_t* cut_start, int64_t* cut_end);
+
+/*
+ * Frame-level activity from sample-level activity (host, integers only).
+ *   act_samples [K][n_samples] uint8 (host); frame t of the recording is centred on sample (t-1)*hop,
+ *   clamped into the recording; out [K][n_frames] uint8 (host) for frames frame0 .. frame0+n_frames-1.
+ */
+int gss_frame_activity(const uint8_t* act_samples, int K, int64_t n_samples, int64_t frame0,
+                       int32_t n_frames, int hop, uint8_t* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GSS_H */

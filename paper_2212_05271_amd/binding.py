@@ -1,0 +1,229 @@
+"""Thin ctypes binding over libgss.so: argument marshalling only.
+
+Every function here has the name and the arguments of the C entry point in include/gss.h; tensors are
+torch CUDA (HIP) tensors used purely as device memory, and the current torch stream is passed down as
+the HIP stream.  No step of the method is computed in Python.  If the shared library is missing the
+import of this module fails loudly; there is no fallback path.
+"""
+
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgss.so")
+
+GSS_OK, GSS_EINVAL, GSS_EUNSUPPORTED, GSS_ENOMEM, GSS_EHIP = 0, -1, -2, -3, -4
+GSS_MAX_D, GSS_MAX_K = 32, 8
+
+EXPORTS = (
+    "gss_create", "gss_destroy", "gss_strerror", "gss_version", "gss_get_status", "gss_scratch_bytes",
+    "gss_stft", "gss_cacgmm_em", "gss_mvdr", "gss_istft", "gss_frames_from_segments", "gss_frame_activity",
+)
+
+
+class GssError(RuntimeError):
+    def __init__(self, code, what):
+        self.code = code
+        super().__init__(f"{what}: {strerror(code)} ({code})")
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2212_05271_amd.build` "
+            "(there is no fallback implementation)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int, C.c_int64
+    lib.gss_create.argtypes = [C.POINTER(vp), i32]
+    lib.gss_create.restype = i32
+    lib.gss_destroy.argtypes = [vp]
+    lib.gss_destroy.restype = None
+    lib.gss_strerror.argtypes = [i32]
+    lib.gss_strerror.restype = C.c_char_p
+    lib.gss_version.argtypes = []
+    lib.gss_version.restype = C.c_char_p
+    lib.gss_get_status.argtypes = [vp, C.POINTER(C.c_uint32), vp]
+    lib.gss_get_status.restype = i32
+    lib.gss_scratch_bytes.argtypes = [vp]
+    lib.gss_scratch_bytes.restype = i64
+    lib.gss_stft.argtypes = [vp, vp, i32, i32, i64, i32, i32, vp, i32, vp]
+    lib.gss_stft.restype = i32
+    lib.gss_cacgmm_em.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]
+    lib.gss_cacgmm_em.restype = i32
+    lib.gss_mvdr.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp]
+    lib.gss_mvdr.restype = i32
+    lib.gss_istft.argtypes = [vp, vp, i32, i32, i32, i32, vp, i64, vp]
+    lib.gss_istft.restype = i32
+    lib.gss_frames_from_segments.argtypes = [vp, vp, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, vp]
+    lib.gss_frames_from_segments.restype = i32
+    lib.gss_frame_activity.argtypes = [vp, i32, i64, i64, C.c_int32, i32, vp]
+    lib.gss_frame_activity.restype = i32
+    return lib
+
+
+_lib = _load()
+
+
+def strerror(code):
+    return _lib.gss_strerror(int(code)).decode()
+
+
+def version():
+    return _lib.gss_version().decode()
+
+
+def _check(rc, what):
+    if rc != GSS_OK:
+        raise GssError(rc, what)
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t, dtype=None, name="tensor"):
+    """Device pointer of a contiguous CUDA tensor (None -> NULL)."""
+    if t is None:
+        return C.c_void_p(0)
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a CUDA tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    return C.c_void_p(t.data_ptr())
+
+
+class Context:
+    """Owns a gss_ctx (the library's scratch memory and status word) on one device."""
+
+    def __init__(self, device_id=0):
+        h = C.c_void_p()
+        _check(_lib.gss_create(C.byref(h), int(device_id)), "gss_create")
+        self._h = h
+        self.device_id = int(device_id)
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            _lib.gss_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise RuntimeError("context is closed")
+        return self._h
+
+    def get_status(self):
+        out = C.c_uint32(0)
+        _check(_lib.gss_get_status(self.handle, C.byref(out), _stream()), "gss_get_status")
+        return int(out.value)
+
+    def scratch_bytes(self):
+        return int(_lib.gss_scratch_bytes(self.handle))
+
+
+def gss_stft(ctx, x, n_fft=1024, hop=256, out=None):
+    """x[S,D,N] float32 -> Y[S,F,T,D] complex64."""
+    import torch
+    S, D, N = x.shape
+    T = -(-N // hop) + 3
+    F = n_fft // 2 + 1
+    if out is None:
+        out = torch.empty((S, F, T, D), dtype=torch.complex64, device=x.device)
+    _check(_lib.gss_stft(ctx.handle, _ptr(x, torch.float32, "x"), S, D, N, n_fft, hop,
+                         _ptr(out, torch.complex64, "Y"), T, _stream()), "gss_stft")
+    return out
+
+
+def gss_cacgmm_em(ctx, Y, activity, T_len=None, iters=20, weight_mode=1, out=None):
+    """Y[S,F,Tmax,D] complex64, activity[S,K,Tmax] uint8, T_len[S] int32|None -> gamma[S,K,F,Tmax] float32."""
+    import torch
+    S, F, Tmax, D = Y.shape
+    K = activity.shape[1]
+    if tuple(activity.shape) != (S, K, Tmax):
+        raise ValueError("activity must be [S,K,Tmax]")
+    if T_len is not None and tuple(T_len.shape) != (S,):
+        raise ValueError("T_len must be [S]")
+    if out is None:
+        out = torch.empty((S, K, F, Tmax), dtype=torch.float32, device=Y.device)
+    _check(_lib.gss_cacgmm_em(ctx.handle, _ptr(Y, torch.complex64, "Y"), _ptr(activity, torch.uint8, "activity"),
+                              _ptr(T_len, torch.int32, "T_len"), S, F, Tmax, D, K, int(iters), int(weight_mode),
+                              _ptr(out, torch.float32, "gamma"), _stream()), "gss_cacgmm_em")
+    return out
+
+
+def gss_mvdr(ctx, Y, gamma, target, ref, T_len=None, out=None):
+    """Y[S,F,Tmax,D], gamma[S,K,F,Tmax], target[S] int32, ref[S] int32 (in/out) -> X[S,F,Tmax] complex64."""
+    import torch
+    S, F, Tmax, D = Y.shape
+    K = gamma.shape[1]
+    if tuple(gamma.shape) != (S, K, F, Tmax):
+        raise ValueError("gamma must be [S,K,F,Tmax]")
+    if tuple(target.shape) != (S,) or tuple(ref.shape) != (S,):
+        raise ValueError("target and ref must be [S]")
+    if out is None:
+        out = torch.empty((S, F, Tmax), dtype=torch.complex64, device=Y.device)
+    _check(_lib.gss_mvdr(ctx.handle, _ptr(Y, torch.complex64, "Y"), _ptr(gamma, torch.float32, "gamma"),
+                         _ptr(T_len, torch.int32, "T_len"), S, F, Tmax, D, K,
+                         _ptr(target, torch.int32, "target"), _ptr(ref, torch.int32, "ref"),
+                         _ptr(out, torch.complex64, "X"), _stream()), "gss_mvdr")
+    return out
+
+
+def gss_istft(ctx, X, N, n_fft=1024, hop=256, out=None):
+    """X[S,F,T] complex64 -> x[S,N] float32."""
+    import torch
+    S, F, T = X.shape
+    if out is None:
+        out = torch.empty((S, N), dtype=torch.float32, device=X.device)
+    _check(_lib.gss_istft(ctx.handle, _ptr(X, torch.complex64, "X"), S, T, n_fft, hop,
+                          _ptr(out, torch.float32, "x"), int(N), _stream()), "gss_istft")
+    return out
+
+
+def _np_ptr(a):
+    return C.c_void_p(a.ctypes.data) if a is not None else C.c_void_p(0)
+
+
+def gss_frames_from_segments(seg_start, seg_end, n_samples, ctx_left, ctx_right, hop=256):
+    """Host integer helper; returns a dict of numpy arrays (ext_start, ext_end, frame0, n_frames, cut_start, cut_end)."""
+    s = np.ascontiguousarray(seg_start, dtype=np.int64)
+    e = np.ascontiguousarray(seg_end, dtype=np.int64)
+    n = int(s.shape[0])
+    out = {k: np.zeros(n, dtype=np.int64) for k in ("ext_start", "ext_end", "frame0", "cut_start", "cut_end")}
+    out["n_frames"] = np.zeros(n, dtype=np.int32)
+    _check(_lib.gss_frames_from_segments(_np_ptr(s), _np_ptr(e), n, int(n_samples), int(ctx_left), int(ctx_right),
+                                         int(hop), _np_ptr(out["ext_start"]), _np_ptr(out["ext_end"]),
+                                         _np_ptr(out["frame0"]), _np_ptr(out["n_frames"]),
+                                         _np_ptr(out["cut_start"]), _np_ptr(out["cut_end"])),
+           "gss_frames_from_segments")
+    return out
+
+
+def gss_frame_activity(act_samples, frame0, n_frames, hop=256):
+    """Host integer helper: act_samples[K,N] uint8 -> [K,n_frames] uint8."""
+    a = np.ascontiguousarray(act_samples, dtype=np.uint8)
+    K, N = a.shape
+    out = np.zeros((K, int(n_frames)), dtype=np.uint8)
+    _check(_lib.gss_frame_activity(_np_ptr(a), K, N, int(frame0), int(n_frames), int(hop), _np_ptr(out)),
+           "gss_frame_activity")
+    return out

@@ -1,0 +1,138 @@
+// Context management, error strings and the host-side integer helpers of libgss.
+#include "gss_internal.h"
+
+#include <new>
+
+extern "C" {
+
+const char* gss_version(void) { return "0.1.0"; }
+
+const char* gss_strerror(int code) {
+  switch (code) {
+    case GSS_OK: return "ok";
+    case GSS_EINVAL: return "invalid argument";
+    case GSS_EUNSUPPORTED: return "shape not supported by this build";
+    case GSS_ENOMEM: return "out of device memory";
+    case GSS_EHIP: return "HIP runtime error";
+    default: return "unknown error";
+  }
+}
+
+int gss_create(gss_ctx** out, int device_id) {
+  if (!out || device_id < 0) return GSS_EINVAL;
+  int n = 0;
+  if (hipGetDeviceCount(&n) != hipSuccess || device_id >= n) return GSS_EHIP;
+  GSS_HIP_CHECK(hipSetDevice(device_id));
+  gss_ctx* c = new (std::nothrow) gss_ctx();
+  if (!c) return GSS_ENOMEM;
+  c->device = device_id;
+  c->scratch = nullptr;
+  c->scratch_cap = 0;
+  c->status = nullptr;
+  c->num_cu = 256;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, device_id) == hipSuccess && prop.multiProcessorCount > 0)
+    c->num_cu = prop.multiProcessorCount;
+  if (hipMalloc((void**)&c->status, sizeof(uint32_t)) != hipSuccess) {
+    delete c;
+    return GSS_ENOMEM;
+  }
+  if (hipMemset(c->status, 0, sizeof(uint32_t)) != hipSuccess) {
+    (void)hipFree(c->status);
+    delete c;
+    return GSS_EHIP;
+  }
+  *out = c;
+  return GSS_OK;
+}
+
+void gss_destroy(gss_ctx* ctx) {
+  if (!ctx) return;
+  (void)hipSetDevice(ctx->device);
+  (void)hipDeviceSynchronize();
+  if (ctx->scratch) (void)hipFree(ctx->scratch);
+  if (ctx->status) (void)hipFree(ctx->status);
+  delete ctx;
+}
+
+int gss_get_status(gss_ctx* ctx, uint32_t* host_out, void* stream) {
+  if (!ctx || !host_out) return GSS_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  GSS_HIP_CHECK(hipMemcpyAsync(host_out, ctx->status, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+  GSS_HIP_CHECK(hipStreamSynchronize(st));
+  uint32_t zero = 0;
+  GSS_HIP_CHECK(hipMemcpyAsync(ctx->status, &zero, sizeof(uint32_t), hipMemcpyHostToDevice, st));
+  GSS_HIP_CHECK(hipStreamSynchronize(st));
+  return GSS_OK;
+}
+
+int64_t gss_scratch_bytes(const gss_ctx* ctx) { return ctx ? (int64_t)ctx->scratch_cap : 0; }
+
+int gss_frames_from_segments(const int64_t* seg_start, const int64_t* seg_end, int n_seg,
+                             int64_t n_samples, int64_t ctx_left, int64_t ctx_right, int hop,
+                             int64_t* ext_start, int64_t* ext_end, int64_t* frame0, int32_t* n_frames,
+                             int64_t* cut_start, int64_t* cut_end) {
+  if (!seg_start || !seg_end || n_seg < 0 || n_samples <= 0 || hop <= 0 || ctx_left < 0 || ctx_right < 0)
+    return GSS_EINVAL;
+  const int64_t h = hop;
+  const int64_t n_round = (n_samples + h - 1) / h * h;
+  for (int i = 0; i < n_seg; ++i) {
+    const int64_t s = seg_start[i], e = seg_end[i];
+    if (s < 0 || e <= s || e > n_samples) return GSS_EINVAL;
+  }
+  for (int i = 0; i < n_seg; ++i) {
+    const int64_t s = seg_start[i], e = seg_end[i];
+    int64_t a = s - ctx_left;
+    if (a < 0) a = 0;
+    int64_t b = e + ctx_right;
+    if (b > n_samples) b = n_samples;
+    const int64_t es = a / h * h;
+    int64_t ee = (b + h - 1) / h * h;
+    if (ee > n_round) ee = n_round;
+    if (ext_start) ext_start[i] = es;
+    if (ext_end) ext_end[i] = ee;
+    if (frame0) frame0[i] = es / h;
+    if (n_frames) n_frames[i] = (int32_t)((ee - es) / h + 3);
+    if (cut_start) cut_start[i] = s - es;
+    if (cut_end) cut_end[i] = e - es;
+  }
+  return GSS_OK;
+}
+
+int gss_frame_activity(const uint8_t* act_samples, int K, int64_t n_samples, int64_t frame0,
+                       int32_t n_frames, int hop, uint8_t* out) {
+  if (!act_samples || !out || K <= 0 || n_samples <= 0 || n_frames < 0 || hop <= 0 || frame0 < 0)
+    return GSS_EINVAL;
+  for (int k = 0; k < K; ++k) {
+    const uint8_t* a = act_samples + (size_t)k * (size_t)n_samples;
+    uint8_t* o = out + (size_t)k * (size_t)n_frames;
+    for (int32_t i = 0; i < n_frames; ++i) {
+      int64_t c = (frame0 + i - 1) * (int64_t)hop;
+      if (c < 0) c = 0;
+      if (c > n_samples - 1) c = n_samples - 1;
+      o[i] = a[c] != 0;
+    }
+  }
+  return GSS_OK;
+}
+
+}  // extern "C"
+
+int gss_ensure_scratch(gss_ctx* ctx, size_t bytes) {
+  if (bytes <= ctx->scratch_cap) return GSS_OK;
+  if (hipDeviceSynchronize() != hipSuccess) return GSS_EHIP;
+  if (ctx->scratch) {
+    (void)hipFree(ctx->scratch);
+    ctx->scratch = nullptr;
+    ctx->scratch_cap = 0;
+  }
+  size_t want = gss_align_up(bytes + bytes / 8, (size_t)1 << 20);
+  void* p = nullptr;
+  if (hipMalloc(&p, want) != hipSuccess) {
+    (void)hipGetLastError();
+    return GSS_ENOMEM;
+  }
+  ctx->scratch = p;
+  ctx->scratch_cap = want;
+  return GSS_OK;
+}

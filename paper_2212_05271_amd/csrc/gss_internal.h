@@ -1,0 +1,43 @@
+// Internal declarations shared by the translation units of libgss (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "gss.h"
+
+// Constants of the algorithm (regularisation and guards).  The paper is silent on all of them; they are
+// part of the algorithm's definition and are documented with the readings of the paper.
+#define GSS_EPS_NORM_SQ 1e-20   // floor on ||y||^2 in the unit normalisation, Eq. (2)
+#define GSS_EPS_N 1e-10         // floor on sum_t gamma and on a trace
+#define GSS_EPS_Q 1e-10         // floor on y^H B^-1 y, Eq. (4)
+#define GSS_EPS_PI 1e-30        // floor inside log(pi)
+#define GSS_DELTA 1e-6          // diagonal loading of B (after scaling to trace D)
+#define GSS_DELTA_BF 1e-6       // relative diagonal loading of Phi_bg
+#define GSS_EPS_TRACE 1e-20     // added to Re tr(Phi_bg^-1 Phi_k), Eq. (8)
+#define GSS_EPS_SNR 1e-300      // floor on the background power in the reference-channel ratio
+
+struct gss_ctx {
+  int device;
+  void* scratch;          // device
+  size_t scratch_cap;
+  uint32_t* status;       // device, one word
+  int num_cu;
+};
+
+// Makes sure ctx->scratch holds at least `bytes`.  Growing synchronises the device (the old block may
+// still be in use by kernels already enqueued) and reallocates.
+int gss_ensure_scratch(gss_ctx* ctx, size_t bytes);
+
+static inline size_t gss_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+#define GSS_HIP_CHECK(expr)                      \
+  do {                                           \
+    hipError_t e_ = (expr);                      \
+    if (e_ != hipSuccess) return GSS_EHIP;       \
+  } while (0)
+
+// Packed real layout of a D x D Hermitian matrix used by the EM kernels, D*D reals in the order the
+// per-frame outer product is generated:  for i = 0..D-1: [H_ii, then for j = i+1..D-1: Re H_ij, Im H_ij].
+__host__ __device__ constexpr int gss_packed_row(int i, int D) { return 2 * i * D - i * i; }
