@@ -22,6 +22,7 @@
 // costs registers, not time.  The posterior itself (log, exp, normalisation over K) is fp32.
 #include "gss_internal.h"
 
+#include <cstdlib>
 #include <type_traits>
 
 namespace {
@@ -115,112 +116,154 @@ __device__ __forceinline__ double packed_entry(const double (&yr)[D], const doub
   else return yi[i] * yr[j] - yr[i] * yi[j];                            // Im(y_i conj(y_j))
 }
 
+// Orders this wavefront's LDS traffic: everything written before is visible to every lane of the
+// wavefront after.  (The LDS executes one wavefront's instructions in order; this only has to stop the
+// compiler from moving accesses across and make it wait for outstanding ones.)
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // ----------------------------------------------------------------------------------------------
-// Pass kernel for D <= 8 (E = D*D <= 64 packed reals).  One wavefront per workgroup, tiles of 64 frames.
+// Pass kernel for D <= 8.  Workgroup = kPassWaves wavefronts that all work on the same
+// (segment, frequency), so that the class coefficients they stream through the scalar cache are shared;
+// every wavefront owns whole tiles of 64 frames and a private LDS region, and there is no workgroup
+// barrier inside the tile loop.
 //
-// Phase 1 (lane = frame): outer product P = y y^H in fp64; q_k = <coef_k, P> with the class
-//   coefficients wave-uniform, read through the scalar path; posterior over the active classes as
+// Phase 1 (lane = frame): q_k = <coef_k, y y^H> with the outer product generated entry by entry in fp64
+//   and the coefficients wave-uniform (scalar loads); posterior over the active classes as
 //   pi_k / det B_k * q_k^-D in (mantissa, exponent) form, fp64, no log/exp; weights w_k = gamma_k / q_k.
-//   P (fp64, column-rotated per row against bank conflicts) and w go to LDS.
-// Phase 2 (lane = (frame group tg, entry group eg), 8 x 8): R_k[e] += w_k[t] * P_t[e] in fp64 for the
-//   lane's entries e = eg + 8c and frames 4*tg .. 4*tg+3 of a 32-frame half tile.  The half tile keeps
-//   the LDS footprint at 16 KB + weights, i.e. two wavefronts per SIMD.  The accumulators stay in
-//   registers across the tiles of the chunk.
+//   y (as fp64) and w go to the wavefront's LDS tile.
+// Phase 2 (lane = (frame group tg, block eg), 8 x 8; frames tg, tg+8, ... of the tile): the Hermitian 8 x 8 outer product is cut into 2 x 2
+//   blocks of channels; lanes eg = 0..5 own the six off-diagonal blocks (4 complex = 8 real entries),
+//   lanes eg = 6, 7 own two diagonal blocks each (2 real diagonals + 1 complex entry per block = 8 real
+//   entries).  For its 8 frames per tile a lane reads 4 channels of y and the K weights, forms its 8
+//   entries exactly and accumulates R_k[e] += w_k * P[e] in fp64.  Channels >= D are zero padding.
+//   The accumulators stay in registers across the tiles of the chunk.
 //
-// Grid: blockIdx.x = chunk + C * (f + F * s).  A chunk is `tiles_per_chunk` tiles of 64 frames.
+// Grid: blockIdx.x = chunk + C * (f + F * s).  A chunk is `tiles_per_chunk` tiles of 64 frames, dealt to
+// the wavefronts round-robin.
 // ----------------------------------------------------------------------------------------------
-template <int D, int K, bool FINAL>
-__global__ __launch_bounds__(kWave, 2) void em_pass_small(
-    const float2* __restrict__ Y, const uint8_t* __restrict__ act, const int32_t* __restrict__ T_len,
-    const double* __restrict__ coef, const double* __restrict__ cmant, const int32_t* __restrict__ cexp,
-    double* __restrict__ part, double* __restrict__ npart, float* __restrict__ gamma,
-    int F, int Tmax, int C, int tiles_per_chunk) {
-  constexpr int E = D * D;
-  constexpr int EPL = (E + 7) / 8;          // packed entries per lane in phase 2
-  constexpr int RS = 64;                    // LDS row stride (doubles); columns rotated by the row index
-  constexpr int KP = K | 1;                 // odd row stride of the weight tile
-  __shared__ double sP[FINAL ? 1 : 32 * RS];
-  __shared__ double sW[FINAL ? 1 : kWave * KP];
+constexpr int kPassWaves = 4;
+constexpr int kYStride = 18;   // doubles per frame row of the y tile: 8 complex + 2 pad (16-byte units: 9 per row)
 
-  const int lane = threadIdx.x;
-  const int chunk = blockIdx.x % C;
-  const long sf = blockIdx.x / C;
-  const int s = (int)(sf / F);
-  const int f = (int)(sf % F);
-  int T = T_len ? T_len[s] : Tmax;
-  T = T < 0 ? 0 : (T > Tmax ? Tmax : T);
-  const int t_end = FINAL ? Tmax : T;       // the final pass also writes the zero padding
 
-  typedef const __attribute__((address_space(4))) double* const_ptr_t;
-  const double* __restrict__ cf = coef + sf * (long)(K * E);
-  const double* __restrict__ cm = cmant + sf * K;
-  const int32_t* __restrict__ ce = cexp + sf * K;
+// Channel-block pair (A, B) of phase-2 lane type eg: off-diagonal block (A < B) for eg < 6, the two
+// diagonal blocks A and B for eg = 6, 7.
+__host__ __device__ constexpr int blk_a(int eg) { return eg == 0 || eg == 1 || eg == 2 ? 0 : (eg == 3 || eg == 4 ? 1 : (eg == 5 ? 2 : (eg == 6 ? 0 : 2))); }
+__host__ __device__ constexpr int blk_b(int eg) { return eg == 0 ? 1 : (eg == 1 ? 2 : (eg == 2 ? 3 : (eg == 3 ? 2 : (eg == 4 ? 3 : (eg == 5 ? 3 : (eg == 6 ? 1 : 3)))))); }
 
-  double acc[EPL][K];
-  double nacc[K];
-#pragma unroll
-  for (int k = 0; k < K; ++k) {
-    nacc[k] = 0.0;
-#pragma unroll
-    for (int c = 0; c < EPL; ++c) acc[c][k] = 0.0;
+// Packed index (gss_packed_row order, matrix size D) of accumulator slot n of lane type eg, or -1 if the
+// slot lies in the zero padding.
+__host__ __device__ constexpr int slot_packed_index(int eg, int n, int D) {
+  const int cu = 2 * blk_a(eg), cv = 2 * blk_b(eg);
+  int i = 0, j = 0, part = 0;
+  if (eg < 6) {
+    i = cu + (n >> 2);
+    j = cv + ((n >> 1) & 1);
+    part = 1 + (n & 1);
+  } else {
+    const int c0 = n < 4 ? cu : cv;
+    const int m = n & 3;
+    if (m == 0) { i = c0; j = c0; part = 0; }
+    else if (m == 1) { i = c0 + 1; j = c0 + 1; part = 0; }
+    else { i = c0; j = c0 + 1; part = m - 1; }
   }
+  if (i >= D || j >= D) return -1;
+  return part == 0 ? gss_packed_row(i, D) : gss_packed_row(i, D) + 1 + 2 * (j - i - 1) + (part - 1);
+}
+
+// Frames per lane in phase 1.  Every class coefficient that comes through the scalar path is applied to
+// kNF frames; the scalar data path returns about one dword per clock per pair of compute units, so
+// at kNF = 1 it is as busy as the vector ALUs.
+constexpr int kNF = 2;
+
+// One unit of work of a wavefront: NF consecutive tiles of 64 frames starting at frame t0.
+template <int D, int K, int NF, bool FINAL>
+__device__ __forceinline__ void pass_unit(
+    const float2* __restrict__ Yrow, const uint8_t* __restrict__ arow, const double* __restrict__ cf,
+    const double* __restrict__ cm, const int32_t* __restrict__ ce, float* __restrict__ gamma_row /* + k*F*Tmax */,
+    long gamma_kstride, int T, int Tmax, int t0, int lane, double* __restrict__ sY, double* __restrict__ sW,
+    double (&acc)[8][K], double (&nacc)[K]) {
+  constexpr int E = D * D;
+  constexpr int WS = K | 1;
+  typedef const __attribute__((address_space(4))) double* const_ptr_t;
   const int tg = lane >> 3, eg = lane & 7;
+  const int cu = 2 * blk_a(eg), cv = 2 * blk_b(eg);
 
-  const float2* __restrict__ Yrow = Y + sf * (long)Tmax * D;
-  const uint8_t* __restrict__ arow = act + (long)s * K * Tmax;
-
-  for (int tile = 0; tile < tiles_per_chunk; ++tile) {
-    const int t0 = (chunk * tiles_per_chunk + tile) * kWave;
-    if (t0 >= t_end) break;                  // uniform
-    const int t = t0 + lane;
-    const bool valid = t < T;
-    const const_ptr_t cf4 = (const_ptr_t)(uintptr_t)cf;
-    int goff = 0;
-    asm volatile("" : "+s"(goff));          // opaque (uniform) offset of the first coefficient group
-
-    // ---- phase 1 ----
-    double yr[D], yi[D];
+  // ---- phase 1: load y ----
+  int t[NF];
+  bool valid[NF];
+  double yr[NF][D], yi[NF][D];
+#pragma unroll
+  for (int f = 0; f < NF; ++f) {
+    t[f] = t0 + f * kWave + lane;
+    valid[f] = t[f] < T;
 #pragma unroll
     for (int d = 0; d < D; ++d) {
-      const float2 v = Yrow[(long)(valid ? t : 0) * D + d];     // frame 0 always exists; masked below
-      yr[d] = valid ? (double)v.x : 0.0;
-      yi[d] = valid ? (double)v.y : 0.0;
+      const float2 v = Yrow[(long)(valid[f] ? t[f] : 0) * D + d];   // frame 0 always exists; masked below
+      yr[f][d] = valid[f] ? (double)v.x : 0.0;
+      yi[f][d] = valid[f] ? (double)v.y : 0.0;
     }
-    // q_k = <coef_k, P>, P = y y^H generated entry by entry.  The coefficients are loop-invariant and
-    // wave-uniform.  Left alone, the compiler hoists all K*E scalar loads out of the tile loop and spills
-    // them into vector-register lanes; the empty asm statements below make each group's pointer depend
-    // on the previous group's first product and route every partial sum through a fence, which keeps
-    // one group's loads next to its use and lets the next group's loads overlap the arithmetic.
-    double q[K];
+  }
+
+  // ---- q_k = <coef_k, y y^H> ----
+  // The coefficients are wave-uniform and loop-invariant and come through the scalar path, one group of
+  // G packed entries (K*G doubles) at a time.  Left alone, the compiler hoists all K*E scalar loads out
+  // of the loop and spills them into vector-register lanes; the empty asm statements make each group's
+  // offset depend on the previous group's first product and route every partial sum through a fence,
+  // which keeps one group's loads next to its use.
+  double q[NF][K];
+  double n2[NF];
 #pragma unroll
-    for (int k = 0; k < K; ++k) q[k] = 0.0;
-    double n2 = 0.0;
-    constexpr int kGroup = 4;
-    static_for<0, (E + kGroup - 1) / kGroup>([&](auto GI) {
-      constexpr int g = GI.value * kGroup;
-      constexpr int ng = (E - g) < kGroup ? (E - g) : kGroup;
-      double Pg[ng];
+  for (int f = 0; f < NF; ++f) {
+    n2[f] = 0.0;
+#pragma unroll
+    for (int k = 0; k < K; ++k) q[f][k] = 0.0;
+  }
+  constexpr int G = 4;
+  constexpr int NG = (E + G - 1) / G;
+  const const_ptr_t cf4 = (const_ptr_t)(uintptr_t)cf;
+  int goff = 0;
+  asm volatile("" : "+s"(goff));            // opaque (uniform) offset: keeps the loads inside this unit
+  static_for<0, NG>([&](auto GI) {
+    constexpr int g = GI.value * G;
+    constexpr int ng = (E - g) < G ? (E - g) : G;
+    double Pg[NF][ng];
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
       static_for<0, ng>([&](auto EI) {
         constexpr int e = EI.value;
-        Pg[e] = packed_entry<D, g + e>(yr, yi);
-        if constexpr (packed_part(g + e, D) == 0) n2 += Pg[e];
+        Pg[f][e] = packed_entry<D, g + e>(yr[f], yi[f]);
+        if constexpr (packed_part(g + e, D) == 0) n2[f] += Pg[f][e];
       });
-      const const_ptr_t cg = cf4 + goff;
-      q[0] = fma(cg[0], Pg[0], q[0]);
-      int noff = g + kGroup;
-      asm volatile("" : "+s"(noff), "+v"(q[0]));
+    }
+    const const_ptr_t cg = cf4 + goff;
+    q[0][0] = fma(cg[0], Pg[0][0], q[0][0]);      // first use of this group: waits for its loads
+    int noff = g + G;
+    asm volatile("" : "+s"(noff), "+v"(q[0][0]));   // the next group's offset exists only from here on
 #pragma unroll
-      for (int k = 1; k < K; ++k) asm volatile("" : "+v"(q[k]));
+    for (int f = 0; f < NF; ++f)
 #pragma unroll
-      for (int k = 0; k < K; ++k) {
+      for (int k = 0; k < K; ++k)
+        if (f != 0 || k != 0) asm volatile("" : "+v"(q[f][k]));
 #pragma unroll
-        for (int e = (k == 0 ? 1 : 0); e < ng; ++e) q[k] = fma(cg[k * E + e], Pg[e], q[k]);
+    for (int k = 0; k < K; ++k) {
+#pragma unroll
+      for (int e = 0; e < ng; ++e) {
+#pragma unroll
+        for (int f = 0; f < NF; ++f)
+          if (!(k == 0 && e == 0 && f == 0)) q[f][k] = fma(cg[k * E + e], Pg[f][e], q[f][k]);
       }
-      goff = noff;
-    });
+    }
+    goff = noff;
+  });
 
+#pragma unroll
+  for (int f = 0; f < NF; ++f) {
     // posterior over the active classes: pi_k / det B_k * q_k^-D with q_k = max(qraw_k / n2c, eps_q)
-    const double n2c = fmax(n2, GSS_EPS_NORM_SQ);
+    const double n2c = fmax(n2[f], GSS_EPS_NORM_SQ);
     const double qfloor = GSS_EPS_Q * n2c;
     double rq[K], mant[K];
     int ex[K];
@@ -228,8 +271,8 @@ __global__ __launch_bounds__(kWave, 2) void em_pass_small(
     int emax = -(1 << 28);
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      a[k] = valid && (arow[(long)k * Tmax + (valid ? t : 0)] != 0);
-      rq[k] = rcp_f64(fmax(q[k], qfloor));           // 1 / (q_k * n2c): the M-step weight is gamma_k * rq
+      a[k] = valid[f] && (arow[(long)k * Tmax + (valid[f] ? t[f] : 0)] != 0);
+      rq[k] = rcp_f64(fmax(q[f][k], qfloor));        // 1 / (q_k * n2c): the M-step weight is gamma_k * rq
       const double u = rq[k] * n2c;                  // 1 / q_k
       const double mu = __builtin_amdgcn_frexp_mant(u);
       const int eu = __builtin_amdgcn_frexp_exp(u);
@@ -247,81 +290,174 @@ __global__ __launch_bounds__(kWave, 2) void em_pass_small(
       Z += v[k];
     }
     const double rz = Z > 0.0 ? rcp_f64(Z) : 0.0;
-    if (FINAL) {
-      if (t < Tmax) {
+    if constexpr (FINAL) {
+      if (t[f] < Tmax) {
 #pragma unroll
-        for (int k = 0; k < K; ++k) gamma[(((long)s * K + k) * F + f) * Tmax + t] = (float)(v[k] * rz);
+        for (int k = 0; k < K; ++k) gamma_row[k * gamma_kstride + t[f]] = (float)(v[k] * rz);
       }
-      continue;
-    }
+    } else {
+      // this tile's y and weights go to LDS, then phase 2 runs over it
+      if (t0 + f * kWave >= T) break;              // uniform: nothing valid in this tile
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-      const double g = v[k] * rz;
-      nacc[k] += g;
-      sW[lane * KP + k] = g * rq[k];
-    }
+      for (int d = 0; d < 8; ++d) {
+        double2 yv = make_double2(0.0, 0.0);
+        if (d < D) yv = make_double2(yr[f][d < D ? d : 0], yi[f][d < D ? d : 0]);
+        *reinterpret_cast<double2*>(&sY[lane * kYStride + 2 * d]) = yv;
+      }
+#pragma unroll
+      for (int k = 0; k < K; ++k) {
+        const double g = v[k] * rz;
+        nacc[k] += g;
+        sW[lane * WS + k] = g * rq[k];
+      }
+      wave_lds_sync();
 
-    // ---- phase 2, two half tiles ----
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      // The 32 lanes of this half rebuild their outer product from y and put it in LDS (cheaper than
-      // keeping E doubles alive per lane through the posterior).
-#pragma unroll
-      for (int d = 0; d < D; ++d) asm volatile("" : "+v"(yr[d]), "+v"(yi[d]));
-      if ((lane >> 5) == half) {
-        const int row = lane & 31;
-        static_for<0, E>([&](auto EI) {
-          constexpr int e = EI.value;
-          sP[row * RS + ((e + row) & 63)] = packed_entry<D, e>(yr, yi);
-          if constexpr ((e & 7) == 7) __builtin_amdgcn_sched_barrier(0);   // bounds the live range of the products
-        });
-      }
-      __syncthreads();
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int r = 4 * tg + j;              // row in the half tile; its frame is t0 + 32*half + r
+      // ---- phase 2 ----
+#pragma unroll 2
+      for (int j = 0; j < 8; ++j) {
+        const int r = tg + 8 * j;              // rows of the 8 frame groups are adjacent: distinct LDS banks
         double w[K];
 #pragma unroll
-        for (int k = 0; k < K; ++k) w[k] = sW[(32 * half + r) * KP + k];
+        for (int k = 0; k < K; ++k) w[k] = sW[r * WS + k];
+        const double2 u0 = *reinterpret_cast<const double2*>(&sY[r * kYStride + 2 * cu]);
+        const double2 u1 = *reinterpret_cast<const double2*>(&sY[r * kYStride + 2 * cu + 2]);
+        const double2 v0 = *reinterpret_cast<const double2*>(&sY[r * kYStride + 2 * cv]);
+        const double2 v1 = *reinterpret_cast<const double2*>(&sY[r * kYStride + 2 * cv + 2]);
+        double e[8];
+        if (eg < 6) {   // off-diagonal block: u_a conj(v_b)
+          e[0] = u0.x * v0.x + u0.y * v0.y;  e[1] = u0.y * v0.x - u0.x * v0.y;
+          e[2] = u0.x * v1.x + u0.y * v1.y;  e[3] = u0.y * v1.x - u0.x * v1.y;
+          e[4] = u1.x * v0.x + u1.y * v0.y;  e[5] = u1.y * v0.x - u1.x * v0.y;
+          e[6] = u1.x * v1.x + u1.y * v1.y;  e[7] = u1.y * v1.x - u1.x * v1.y;
+        } else {        // two diagonal blocks: |u0|^2, |u1|^2, u0 conj(u1), and the same for v
+          e[0] = u0.x * u0.x + u0.y * u0.y;  e[1] = u1.x * u1.x + u1.y * u1.y;
+          e[2] = u0.x * u1.x + u0.y * u1.y;  e[3] = u0.y * u1.x - u0.x * u1.y;
+          e[4] = v0.x * v0.x + v0.y * v0.y;  e[5] = v1.x * v1.x + v1.y * v1.y;
+          e[6] = v0.x * v1.x + v0.y * v1.y;  e[7] = v0.y * v1.x - v0.x * v1.y;
+        }
 #pragma unroll
-        for (int c = 0; c < EPL; ++c) {
-          const int e = eg + 8 * c;
-          if (e < E) {
-            const double p = sP[r * RS + ((e + r) & 63)];
+        for (int n = 0; n < 8; ++n) {
 #pragma unroll
-            for (int k = 0; k < K; ++k) acc[c][k] = fma(w[k], p, acc[c][k]);
-          }
+          for (int k = 0; k < K; ++k) acc[n][k] = fma(w[k], e[n], acc[n][k]);
         }
       }
-      __syncthreads();
+      wave_lds_sync();
+    }
+  }
+}
+
+template <int D, int K, bool FINAL>
+__global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
+    const float2* __restrict__ Y, const uint8_t* __restrict__ act, const int32_t* __restrict__ T_len,
+    const double* __restrict__ coef, const double* __restrict__ cmant, const int32_t* __restrict__ cexp,
+    double* __restrict__ part, double* __restrict__ npart, float* __restrict__ gamma,
+    int F, int Tmax, int C, int tiles_per_chunk) {
+  constexpr int E = D * D;
+  constexpr int WS = K | 1;
+  constexpr int kTileDoubles = kWave * kYStride + kWave * WS;
+  // per-wavefront tiles; reused at the end for the cross-wavefront reduction (needs kPassWaves*(64*K+K))
+  constexpr int kRedDoubles = kPassWaves * (64 * K + K);
+  constexpr int kLdsDoubles = FINAL ? 1 : (kPassWaves * kTileDoubles > kRedDoubles ? kPassWaves * kTileDoubles : kRedDoubles);
+  __shared__ __attribute__((aligned(16))) double lds[kLdsDoubles];
+
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  const int chunk = blockIdx.x % C;
+  const long sf = blockIdx.x / C;
+  const int s = (int)(sf / F);
+  const int f = (int)(sf % F);
+  int T = T_len ? T_len[s] : Tmax;
+  T = T < 0 ? 0 : (T > Tmax ? Tmax : T);
+  const int t_end = FINAL ? Tmax : T;       // the final pass also writes the zero padding
+
+  const double* __restrict__ cf = coef + sf * (long)(K * E);
+  const double* __restrict__ cm = cmant + sf * K;
+  const int32_t* __restrict__ ce = cexp + sf * K;
+  double* __restrict__ sY = lds + (FINAL ? 0 : wave * kTileDoubles);
+  double* __restrict__ sW = sY + (FINAL ? 0 : kWave * kYStride);
+
+  double acc[8][K];
+  double nacc[K];
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    nacc[k] = 0.0;
+#pragma unroll
+    for (int n = 0; n < 8; ++n) acc[n][k] = 0.0;
+  }
+  const int tg = lane >> 3, eg = lane & 7;
+
+  const float2* __restrict__ Yrow = Y + sf * (long)Tmax * D;
+  const uint8_t* __restrict__ arow = act + (long)s * K * Tmax;
+  float* __restrict__ gamma_row = FINAL ? gamma + ((long)s * K * F + f) * Tmax : nullptr;
+  const long gamma_kstride = (long)F * Tmax;
+
+  // The chunk's tiles, as units of kNF tiles followed by single tiles, dealt to the wavefronts round-robin.
+  const int tile_lo = chunk * tiles_per_chunk;
+  int tile_hi = tile_lo + tiles_per_chunk;
+  const int tile_end = (t_end + kWave - 1) / kWave;
+  tile_hi = tile_hi < tile_end ? tile_hi : tile_end;
+  const int n_tiles = tile_hi > tile_lo ? tile_hi - tile_lo : 0;
+  const int n_big = n_tiles / kNF;
+  const int n_units = n_big + (n_tiles - n_big * kNF);
+  for (int u = wave; u < n_units; u += kPassWaves) {
+    if (u < n_big) {
+      pass_unit<D, K, kNF, FINAL>(Yrow, arow, cf, cm, ce, gamma_row, gamma_kstride, T, Tmax,
+                                  (tile_lo + u * kNF) * kWave, lane, sY, sW, acc, nacc);
+    } else {
+      pass_unit<D, K, 1, FINAL>(Yrow, arow, cf, cm, ce, gamma_row, gamma_kstride, T, Tmax,
+                                (tile_lo + n_big * kNF + (u - n_big)) * kWave, lane, sY, sW, acc, nacc);
     }
   }
   if (FINAL) return;
 
-  // reduce over the 8 frame groups (lane bits 3..5); lanes 0..7 then hold the chunk's partial sums
+  // Reduce over the 8 frame groups (lane bits 3..5), then over the wavefronts through LDS.
 #pragma unroll
   for (int k = 0; k < K; ++k) {
 #pragma unroll
-    for (int c = 0; c < EPL; ++c) {
-      double x = acc[c][k];
+    for (int n = 0; n < 8; ++n) {
+      double x = acc[n][k];
 #pragma unroll
       for (int off = 8; off < kWave; off <<= 1) x += __shfl_xor(x, off, kWave);
-      acc[c][k] = x;
+      acc[n][k] = x;
     }
     double nv = nacc[k];
 #pragma unroll
     for (int off = 1; off < kWave; off <<= 1) nv += __shfl_xor(nv, off, kWave);
-    if (lane == 0) npart[(sf * C + chunk) * K + k] = nv;
+    nacc[k] = nv;
   }
-  if (lane < 8) {
+  __syncthreads();                           // every wavefront is done with its tiles
+  double* __restrict__ red = lds;            // [wave][k][64 slots (eg*8+n)] then [wave][k]
+  if (tg == 0) {
 #pragma unroll
-    for (int c = 0; c < EPL; ++c) {
-      const int e = lane + 8 * c;
-      if (e < E) {
+    for (int n = 0; n < 8; ++n)
 #pragma unroll
-        for (int k = 0; k < K; ++k) part[((sf * C + chunk) * K + k) * (long)E + e] = acc[c][k];
-      }
-    }
+      for (int k = 0; k < K; ++k) red[(wave * K + k) * 64 + eg * 8 + n] = acc[n][k];
+  }
+  if (lane == 0) {
+#pragma unroll
+    for (int k = 0; k < K; ++k) red[kPassWaves * K * 64 + wave * K + k] = nacc[k];
+  }
+  __syncthreads();
+  // thread x < 64*K: class k = x / 64, slot = x % 64
+  for (int x = threadIdx.x; x < 64 * K; x += kWave * kPassWaves) {
+    const int k = x / 64, slot = x % 64;
+    double sum = 0.0;
+#pragma unroll
+    for (int w = 0; w < kPassWaves; ++w) sum += red[(w * K + k) * 64 + slot];
+    // slot -> packed index for matrix size D (padding slots are dropped)
+    int pidx = -1;
+    static_for<0, 64>([&](auto SI) {
+      constexpr int sl = SI.value;
+      constexpr int pi = slot_packed_index(sl / 8, sl % 8, D);
+      if (slot == sl) pidx = pi;
+    });
+    if (pidx >= 0) part[((sf * C + chunk) * K + k) * (long)E + pidx] = sum;
+  }
+  if (threadIdx.x < K) {
+    double sum = 0.0;
+#pragma unroll
+    for (int w = 0; w < kPassWaves; ++w) sum += red[kPassWaves * K * 64 + w * K + threadIdx.x];
+    npart[(sf * C + chunk) * K + threadIdx.x] = sum;
   }
 }
 
@@ -463,14 +599,21 @@ struct EmPlan {
 EmPlan make_plan(const gss_ctx* ctx, long n_sf, int Tmax, int D, int K) {
   EmPlan p;
   const int tiles = (Tmax + kWave - 1) / kWave;
-  // Aim for ~24 single-wave workgroups per compute unit so the tail of a launch is short, but never
-  // split finer than one tile per chunk.
-  const long target = (long)ctx->num_cu * 24;
-  long C = (target + n_sf - 1) / n_sf;
-  if (C < 1) C = 1;
-  if (C > tiles) C = tiles;
-  p.tiles_per_chunk = (int)((tiles + C - 1) / C);
-  p.C = (tiles + p.tiles_per_chunk - 1) / p.tiles_per_chunk;
+  // A chunk is a whole number of rounds of the workgroup's wavefronts.  Splitting a (segment, frequency)
+  // over several workgroups costs a partial-sum round trip and a second reduction, so it is done only
+  // when there are fewer problems than about two workgroups per compute unit.
+  // GSS_EM_TPC overrides the tiles per chunk (tuning aid).
+  const long target = (long)ctx->num_cu * 2;
+  long c_target = (target + n_sf - 1) / n_sf;
+  if (c_target < 1) c_target = 1;
+  int tpc = (int)((tiles + c_target - 1) / c_target);
+  tpc = (tpc + kPassWaves - 1) / kPassWaves * kPassWaves;
+  if (const char* e = getenv("GSS_EM_TPC")) {
+    const int v = atoi(e);
+    if (v > 0) tpc = v;
+  }
+  p.tiles_per_chunk = tpc;
+  p.C = (tiles + tpc - 1) / tpc;
   const size_t E = (size_t)D * D;
   size_t o = 0;
   p.off_coef = o;  o = gss_align_up(o + (size_t)n_sf * K * E * sizeof(double), 256);
@@ -500,12 +643,12 @@ int run_small(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_t* 
   const dim3 grid((unsigned)(n_sf * p.C));
   hipLaunchKernelGGL(em_init_coef, dim3(1024), dim3(256), 0, st, coef, cm, ce, D, K, n_sf);
   for (int it = 0; it < iters; ++it) {
-    hipLaunchKernelGGL((em_pass_small<D, K, false>), grid, dim3(kWave), 0, st, Y, act, T_len, coef, cm, ce, part, npart,
+    hipLaunchKernelGGL((em_pass_small<D, K, false>), grid, dim3(kWave * kPassWaves), 0, st, Y, act, T_len, coef, cm, ce, part, npart,
                        (float*)nullptr, F, Tmax, p.C, p.tiles_per_chunk);
     hipLaunchKernelGGL((em_factor_small<D, K>), dim3((unsigned)n_sf), dim3(kWave * K), 0, st, part, npart, coef, cm, ce,
                        ctx->status, p.C, weight_mode);
   }
-  hipLaunchKernelGGL((em_pass_small<D, K, true>), grid, dim3(kWave), 0, st, Y, act, T_len, coef, cm, ce,
+  hipLaunchKernelGGL((em_pass_small<D, K, true>), grid, dim3(kWave * kPassWaves), 0, st, Y, act, T_len, coef, cm, ce,
                      (double*)nullptr, (double*)nullptr, gamma, F, Tmax, p.C, p.tiles_per_chunk);
   if (hipGetLastError() != hipSuccess) return GSS_EHIP;
   return GSS_OK;
