@@ -51,6 +51,7 @@ typedef enum gss_status {
 /* Bits of the device status word (gss_get_status). */
 #define GSS_STATUS_NONPD_B 1u        /* a class scatter matrix had a non-positive pivot; the pivot was floored */
 #define GSS_STATUS_NONPD_PHI 2u      /* the loaded background covariance had a non-positive pivot; floored     */
+#define GSS_STATUS_BAD_TARGET 4u     /* a target index was outside [0, K); it was clamped                       */
 
 typedef struct gss_ctx gss_ctx;
 
@@ -101,7 +102,8 @@ int gss_cacgmm_em(gss_ctx* ctx, const float* Y, const uint8_t* activity, const i
  * Mask-based MVDR (Souden form), Eq. (6)-(9) of Section 2.3, per segment and frequency.
  *   Y      [S][F][Tmax][D] complex64: used as handed over (NOT normalised inside)
  *   gamma  [S][K][F][Tmax] float32 masks
- *   target [S] int32: index of the class to extract, 0 <= target[s] < K
+ *   target [S] int32: index of the class to extract, 0 <= target[s] < K (a value outside is clamped and
+ *          raises GSS_STATUS_BAD_TARGET in the status word)
  *   ref    [S] int32 in/out: >= 0 = use this reference channel; < 0 = choose the channel with the
  *          largest ratio of beamformed target power to beamformed background power summed over
  *          frequency (lowest index on ties); on return holds the channel used

@@ -1,0 +1,195 @@
+// Device-side building blocks shared by the EM and the MVDR kernels (internal, not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <type_traits>
+
+#include "gss_internal.h"
+
+namespace {
+
+constexpr int kWave = 64;
+
+__host__ __device__ constexpr int next_pow2(int x) {
+  int p = 1;
+  while (p < x) p <<= 1;
+  return p;
+}
+
+// ----------------------------------------------------------------------------------------------
+// fp64 helpers (no transcendental functions anywhere in the EM loop)
+// ----------------------------------------------------------------------------------------------
+__device__ __forceinline__ double rcp_f64(double x) {
+  double r = __builtin_amdgcn_rcp(x);
+  r = fma(fma(-x, r, 1.0), r, r);
+  r = fma(fma(-x, r, 1.0), r, r);
+  return r;
+}
+
+template <int N>
+__device__ __forceinline__ double ipow(double x) {
+  if constexpr (N == 1) {
+    return x;
+  } else if constexpr (N % 2 == 0) {
+    const double h = ipow<N / 2>(x);
+    return h * h;
+  } else {
+    return x * ipow<N - 1>(x);
+  }
+}
+
+// Compile-time loop: f(std::integral_constant<int, B>{}), ..., f(std::integral_constant<int, E_ - 1>{}).
+template <int B, int E_, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (B < E_) {
+    f(std::integral_constant<int, B>{});
+    static_for<B + 1, E_>(f);
+  }
+}
+
+// Position (row i, column j >= i, part: 0 diagonal, 1 real, 2 imaginary) of packed index idx.
+__host__ __device__ constexpr int packed_i(int idx, int D) {
+  int i = 0;
+  for (int r = 1; r < D; ++r)
+    if (idx >= gss_packed_row(r, D)) i = r;
+  return i;
+}
+__host__ __device__ constexpr int packed_j(int idx, int D) {
+  const int i = packed_i(idx, D);
+  const int off = idx - gss_packed_row(i, D);
+  return off == 0 ? i : i + 1 + (off - 1) / 2;
+}
+__host__ __device__ constexpr int packed_part(int idx, int D) {
+  const int off = idx - gss_packed_row(packed_i(idx, D), D);
+  return off == 0 ? 0 : 1 + ((off - 1) & 1);
+}
+
+// Entry IDX of the Hermitian outer product y y^H in the packed order (see gss_packed_row), fp64.
+template <int D, int IDX>
+__device__ __forceinline__ double packed_entry(const double (&yr)[D], const double (&yi)[D]) {
+  constexpr int i = packed_i(IDX, D), j = packed_j(IDX, D), part = packed_part(IDX, D);
+  if constexpr (part == 0) return yr[i] * yr[i] + yi[i] * yi[i];
+  else if constexpr (part == 1) return yr[i] * yr[j] + yi[i] * yi[j];   // Re(y_i conj(y_j))
+  else return yi[i] * yr[j] - yr[i] * yi[j];                            // Im(y_i conj(y_j))
+}
+
+// Orders this wavefront's LDS traffic: everything written before is visible to every lane of the
+// wavefront after.  (The LDS executes one wavefront's instructions in order; this only has to stop the
+// compiler from moving accesses across and make it wait for outstanding ones.)
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Tile geometry shared by the kernels that accumulate weighted outer products: a workgroup is
+// kPassWaves wavefronts, each wavefront owns whole tiles of 64 frames and a private LDS region.
+constexpr int kPassWaves = 4;
+constexpr int kYStride = 18;   // doubles per frame row of the y tile: 8 complex + 2 pad (16-byte units: 9 per row)
+
+
+// Channel-block pair (A, B) of phase-2 lane type eg: off-diagonal block (A < B) for eg < 6, the two
+// diagonal blocks A and B for eg = 6, 7.
+__host__ __device__ constexpr int blk_a(int eg) { return eg == 0 || eg == 1 || eg == 2 ? 0 : (eg == 3 || eg == 4 ? 1 : (eg == 5 ? 2 : (eg == 6 ? 0 : 2))); }
+__host__ __device__ constexpr int blk_b(int eg) { return eg == 0 ? 1 : (eg == 1 ? 2 : (eg == 2 ? 3 : (eg == 3 ? 2 : (eg == 4 ? 3 : (eg == 5 ? 3 : (eg == 6 ? 1 : 3)))))); }
+
+// Packed index (gss_packed_row order, matrix size D) of accumulator slot n of lane type eg, or -1 if the
+// slot lies in the zero padding.
+__host__ __device__ constexpr int slot_packed_index(int eg, int n, int D) {
+  const int cu = 2 * blk_a(eg), cv = 2 * blk_b(eg);
+  int i = 0, j = 0, part = 0;
+  if (eg < 6) {
+    i = cu + (n >> 2);
+    j = cv + ((n >> 1) & 1);
+    part = 1 + (n & 1);
+  } else {
+    const int c0 = n < 4 ? cu : cv;
+    const int m = n & 3;
+    if (m == 0) { i = c0; j = c0; part = 0; }
+    else if (m == 1) { i = c0 + 1; j = c0 + 1; part = 0; }
+    else { i = c0; j = c0 + 1; part = m - 1; }
+  }
+  if (i >= D || j >= D) return -1;
+  return part == 0 ? gss_packed_row(i, D) : gss_packed_row(i, D) + 1 + 2 * (j - i - 1) + (part - 1);
+}
+
+
+// Phase 2 of a tile: lane (tg, eg) accumulates acc[n][k] += w_k[r] * P_r[entry n of block eg] over its 8
+// frames r = tg, tg + 8, ... of the 64-frame tile in LDS.  sY: [64][kYStride] doubles (8 complex channels
+// per frame, zero beyond D), sW: [64][WS] doubles (KW weights per frame).
+template <int KW, int WS>
+__device__ __forceinline__ void accumulate_tile(const double* __restrict__ sY, const double* __restrict__ sW,
+                                                int tg, int eg, double (&acc)[8][KW]) {
+  const int cu = 2 * blk_a(eg), cv = 2 * blk_b(eg);
+#pragma unroll 2
+  for (int j = 0; j < 8; ++j) {
+    const int r = tg + 8 * j;              // rows of the 8 frame groups are adjacent: distinct LDS banks
+    double w[KW];
+#pragma unroll
+    for (int k = 0; k < KW; ++k) w[k] = sW[r * WS + k];
+    const double2 u0 = *reinterpret_cast<const double2*>(&sY[r * kYStride + 2 * cu]);
+    const double2 u1 = *reinterpret_cast<const double2*>(&sY[r * kYStride + 2 * cu + 2]);
+    const double2 v0 = *reinterpret_cast<const double2*>(&sY[r * kYStride + 2 * cv]);
+    const double2 v1 = *reinterpret_cast<const double2*>(&sY[r * kYStride + 2 * cv + 2]);
+    double e[8];
+    if (eg < 6) {   // off-diagonal block: u_a conj(v_b)
+      e[0] = u0.x * v0.x + u0.y * v0.y;  e[1] = u0.y * v0.x - u0.x * v0.y;
+      e[2] = u0.x * v1.x + u0.y * v1.y;  e[3] = u0.y * v1.x - u0.x * v1.y;
+      e[4] = u1.x * v0.x + u1.y * v0.y;  e[5] = u1.y * v0.x - u1.x * v0.y;
+      e[6] = u1.x * v1.x + u1.y * v1.y;  e[7] = u1.y * v1.x - u1.x * v1.y;
+    } else {        // two diagonal blocks: |u0|^2, |u1|^2, u0 conj(u1), and the same for v
+      e[0] = u0.x * u0.x + u0.y * u0.y;  e[1] = u1.x * u1.x + u1.y * u1.y;
+      e[2] = u0.x * u1.x + u0.y * u1.y;  e[3] = u0.y * u1.x - u0.x * u1.y;
+      e[4] = v0.x * v0.x + v0.y * v0.y;  e[5] = v1.x * v1.x + v1.y * v1.y;
+      e[6] = v0.x * v1.x + v0.y * v1.y;  e[7] = v0.y * v1.x - v0.x * v1.y;
+    }
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+#pragma unroll
+      for (int k = 0; k < KW; ++k) acc[n][k] = fma(w[k], e[n], acc[n][k]);
+    }
+  }
+}
+
+// Reduction of the per-lane accumulators of a workgroup of kPassWaves wavefronts into packed partial
+// sums: out[k * E + packed index] for k < KW, matrix size D.  `red` is LDS scratch of at least
+// kPassWaves * 64 * KW doubles that no wavefront uses any more (the function starts with a barrier).
+template <int D, int KW>
+__device__ __forceinline__ void reduce_and_store_partials(double (&acc)[8][KW], double* __restrict__ red,
+                                                          double* __restrict__ out, int lane, int wave) {
+  constexpr int E = D * D;
+  const int tg = lane >> 3, eg = lane & 7;
+#pragma unroll
+  for (int k = 0; k < KW; ++k) {
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      double x = acc[n][k];
+#pragma unroll
+      for (int off = 8; off < kWave; off <<= 1) x += __shfl_xor(x, off, kWave);
+      acc[n][k] = x;
+    }
+  }
+  __syncthreads();                           // every wavefront is done with its tiles
+  if (tg == 0) {
+#pragma unroll
+    for (int n = 0; n < 8; ++n)
+#pragma unroll
+      for (int k = 0; k < KW; ++k) red[(wave * KW + k) * 64 + eg * 8 + n] = acc[n][k];
+  }
+  __syncthreads();
+  for (int x = threadIdx.x; x < 64 * KW; x += kWave * kPassWaves) {
+    const int k = x / 64, slot = x % 64;
+    double sum = 0.0;
+#pragma unroll
+    for (int w = 0; w < kPassWaves; ++w) sum += red[(w * KW + k) * 64 + slot];
+    int pidx = -1;                           // slot -> packed index for matrix size D; padding slots are dropped
+    static_for<0, 64>([&](auto SI) {
+      constexpr int sl = SI.value;
+      constexpr int pi = slot_packed_index(sl / 8, sl % 8, D);
+      if (slot == sl) pidx = pi;
+    });
+    if (pidx >= 0) out[k * E + pidx] = sum;
+  }
+}
+
+}  // namespace

@@ -1,0 +1,342 @@
+// Mask-based MVDR beamforming (arXiv 2212.05271, Section 2.3, Eq. (6)-(9)) for gfx950.
+//
+//   cov    : Phi_k = sum_t gamma_target y y^H,  Phi_bg = sum_t (sum_{k != target} gamma_k) y y^H
+//            (Eq. (6), (7); the common 1/T cancels in Eq. (8)), fp64 partial sums per chunk of frames.
+//   solve  : per (segment, frequency): Phi_bg += delta * tr(Phi_bg)/D * I, G = Phi_bg^-1 Phi_k,
+//            H = G / (Re tr G + eps): column r of H is the filter of Eq. (8) for reference channel r;
+//            also the beamformed target and background powers of every candidate r.
+//   ref    : per segment: the reference channel with the largest ratio of the two powers summed over
+//            frequency (lowest index on ties), unless the caller fixed it.
+//   apply  : X = h_ref^H y  (Eq. (9)).
+//
+// Everything up to the filter is fp64 (the solve amplifies errors of the covariances by the condition
+// number of Phi_bg); the output is rounded to complex64 at the end.  Y is used as handed over, without
+// normalisation.
+#include "gss_internal.h"
+
+#include "gss_device.h"
+
+namespace {
+
+// ----------------------------------------------------------------------------------------------
+// Covariance accumulation for D <= 8.  Same tile machinery as the EM pass: a workgroup of kPassWaves
+// wavefronts per (segment, frequency, chunk); per tile, lane = frame loads y and the two weights into the
+// wavefront's LDS region, then lane = (frame group, 2 x 2 channel block) accumulates the two weighted
+// outer products.  Output: part[sf][chunk][2][E] packed (0: target, 1: background).
+// ----------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kWave * kPassWaves) void mvdr_cov_small(
+    const float2* __restrict__ Y, const float* __restrict__ gamma, const int32_t* __restrict__ T_len,
+    const int32_t* __restrict__ target, double* __restrict__ part, uint32_t* __restrict__ status,
+    int F, int Tmax, int K, int C, int tiles_per_chunk) {
+  constexpr int E = D * D;
+  constexpr int WS = 3;
+  constexpr int kTileDoubles = kWave * kYStride + kWave * WS;
+  constexpr int kRedDoubles = kPassWaves * 64 * 2;
+  constexpr int kLdsDoubles = kPassWaves * kTileDoubles > kRedDoubles ? kPassWaves * kTileDoubles : kRedDoubles;
+  __shared__ __attribute__((aligned(16))) double lds[kLdsDoubles];
+
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  const int chunk = blockIdx.x % C;
+  const long sf = blockIdx.x / C;
+  const int s = (int)(sf / F);
+  const int f = (int)(sf % F);
+  int T = T_len ? T_len[s] : Tmax;
+  T = T < 0 ? 0 : (T > Tmax ? Tmax : T);
+  int tgt = target[s];
+  if (tgt < 0 || tgt >= K) {                        // out of range: flagged, then clamped
+    if (threadIdx.x == 0 && chunk == 0 && f == 0) atomicOr(status, GSS_STATUS_BAD_TARGET);
+    tgt = tgt < 0 ? 0 : K - 1;
+  }
+
+  double* __restrict__ sY = lds + wave * kTileDoubles;
+  double* __restrict__ sW = sY + kWave * kYStride;
+  double acc[8][2];
+#pragma unroll
+  for (int n = 0; n < 8; ++n) { acc[n][0] = 0.0; acc[n][1] = 0.0; }
+  const int tg = lane >> 3, eg = lane & 7;
+
+  const float2* __restrict__ Yrow = Y + sf * (long)Tmax * D;
+  const float* __restrict__ grow = gamma + ((long)s * K * F + f) * Tmax;   // + k * F * Tmax + t
+  const long gk = (long)F * Tmax;
+
+  const int tile_lo = chunk * tiles_per_chunk;
+  int tile_hi = tile_lo + tiles_per_chunk;
+  const int tile_end = (T + kWave - 1) / kWave;
+  tile_hi = tile_hi < tile_end ? tile_hi : tile_end;
+  for (int tile = tile_lo + wave; tile < tile_hi; tile += kPassWaves) {
+    const int t = tile * kWave + lane;
+    const bool valid = t < T;
+    const int tc = valid ? t : 0;
+#pragma unroll
+    for (int d = 0; d < 8; ++d) {
+      double2 yv = make_double2(0.0, 0.0);
+      if (d < D) {
+        const float2 v = Yrow[(long)tc * D + (d < D ? d : 0)];
+        if (valid) yv = make_double2((double)v.x, (double)v.y);
+      }
+      *reinterpret_cast<double2*>(&sY[lane * kYStride + 2 * d]) = yv;
+    }
+    double wt = 0.0, wb = 0.0;
+    for (int k = 0; k < K; ++k) {
+      const double g = (double)grow[k * gk + tc];
+      if (k == tgt) wt = g; else wb += g;
+    }
+    sW[lane * WS + 0] = valid ? wt : 0.0;
+    sW[lane * WS + 1] = valid ? wb : 0.0;
+    wave_lds_sync();
+    accumulate_tile<2, WS>(sY, sW, tg, eg, acc);
+    wave_lds_sync();
+  }
+  reduce_and_store_partials<D, 2>(acc, lds, part + (sf * C + chunk) * (long)(2 * E), lane, wave);
+}
+
+// ----------------------------------------------------------------------------------------------
+// Solve for D <= 8: one wavefront per (segment, frequency), lane (i, j) = (l / D, l % D).
+// Outputs: H[sf][r][d] (complex fp64, filter for reference r, channel d) and pw[sf][r][2] =
+// (Re h_r^H Phi_k h_r, Re h_r^H Phi_bg' h_r) with Phi_bg' the loaded background covariance.
+// ----------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kWave) void mvdr_solve_small(
+    const double* __restrict__ part, double2* __restrict__ H, double* __restrict__ pw,
+    uint32_t* __restrict__ status, int C) {
+  constexpr int E = D * D;
+  __shared__ double sR[2][E];
+  __shared__ double sKr[D][D], sKi[D][D];      // Phi_k
+  __shared__ double sBr[D][D], sBi[D][D];      // loaded Phi_bg (kept for the power terms)
+  __shared__ double sMr[D][D], sMi[D][D];      // working copy -> inverse
+  __shared__ double sGr[D][D], sGi[D][D];      // G, then H
+
+  const long sf = blockIdx.x;
+  const int l = threadIdx.x;
+  const bool on = l < E;
+  const int i = l / D, j = l % D;
+
+  if (on) {
+    double a = 0.0, b = 0.0;
+    for (int c = 0; c < C; ++c) {
+      a += part[((sf * C + c) * 2 + 0) * (long)E + l];
+      b += part[((sf * C + c) * 2 + 1) * (long)E + l];
+    }
+    sR[0][l] = a;
+    sR[1][l] = b;
+  }
+  __syncthreads();
+  double trb = 0.0;
+#pragma unroll
+  for (int r = 0; r < D; ++r) trb += sR[1][gss_packed_row(r, D)];
+  if (on) {
+    double kr, ki = 0.0, br, bi = 0.0;
+    if (i == j) {
+      kr = sR[0][gss_packed_row(i, D)];
+      br = sR[1][gss_packed_row(i, D)] + GSS_DELTA_BF * trb / (double)D;
+    } else {
+      const int lo = i < j ? i : j, hi = i < j ? j : i;
+      const int p = gss_packed_row(lo, D) + 1 + 2 * (hi - lo - 1);
+      kr = sR[0][p]; ki = sR[0][p + 1];
+      br = sR[1][p]; bi = sR[1][p + 1];
+      if (i > j) { ki = -ki; bi = -bi; }
+    }
+    sKr[i][j] = kr; sKi[i][j] = ki;
+    sBr[i][j] = br; sBi[i][j] = bi;
+    sMr[i][j] = br; sMi[i][j] = bi;
+  }
+  __syncthreads();
+  // in-place Gauss-Jordan inversion of the Hermitian positive-definite loaded Phi_bg
+  for (int p = 0; p < D; ++p) {
+    double piv = sMr[p][p];
+    if (!(piv > 1e-300)) {
+      piv = 1e-300;
+      if (l == 0) atomicOr(status, GSS_STATUS_NONPD_PHI);
+    }
+    const double rp = 1.0 / piv;
+    double nr = 0.0, ni = 0.0;
+    if (on) {
+      const double air = sMr[i][p], aii = sMi[i][p];
+      const double apr = sMr[p][j], api = sMi[p][j];
+      if (i == p && j == p) {
+        nr = rp;
+      } else if (i == p) {
+        nr = apr * rp; ni = api * rp;
+      } else if (j == p) {
+        nr = -air * rp; ni = -aii * rp;
+      } else {
+        nr = sMr[i][j] - (air * apr - aii * api) * rp;
+        ni = sMi[i][j] - (air * api + aii * apr) * rp;
+      }
+    }
+    __syncthreads();
+    if (on) { sMr[i][j] = nr; sMi[i][j] = ni; }
+    __syncthreads();
+  }
+  // G = Phi_bg^-1 Phi_k
+  if (on) {
+    double gr = 0.0, gi = 0.0;
+#pragma unroll
+    for (int m = 0; m < D; ++m) {
+      const double ar = sMr[i][m], ai = sMi[i][m], br = sKr[m][j], bi = sKi[m][j];
+      gr += ar * br - ai * bi;
+      gi += ar * bi + ai * br;
+    }
+    sGr[i][j] = gr; sGi[i][j] = gi;
+  }
+  __syncthreads();
+  double tr = 0.0;
+#pragma unroll
+  for (int r = 0; r < D; ++r) tr += sGr[r][r];
+  const double inv = 1.0 / (tr + GSS_EPS_TRACE);
+  if (on) {
+    const double hr = sGr[i][j] * inv, hi = sGi[i][j] * inv;   // H[d = i][r = j]
+    H[(sf * D + j) * D + i] = make_double2(hr, hi);
+    sGr[i][j] = hr; sGi[i][j] = hi;
+  }
+  __syncthreads();
+  // powers of candidate r: h_r^H Phi h_r, lanes l < D handle r = l
+  if (l < D) {
+    const int r = l;
+    double pk = 0.0, pb = 0.0;
+    for (int a = 0; a < D; ++a) {
+      double tkr = 0.0, tki = 0.0, tbr = 0.0, tbi = 0.0;       // (Phi h_r)[a]
+      for (int b = 0; b < D; ++b) {
+        const double hr = sGr[b][r], hi = sGi[b][r];
+        tkr += sKr[a][b] * hr - sKi[a][b] * hi;  tki += sKr[a][b] * hi + sKi[a][b] * hr;
+        tbr += sBr[a][b] * hr - sBi[a][b] * hi;  tbi += sBr[a][b] * hi + sBi[a][b] * hr;
+      }
+      const double hr = sGr[a][r], hi = sGi[a][r];
+      pk += hr * tkr + hi * tki;                               // Re(conj(h_a) * t_a)
+      pb += hr * tbr + hi * tbi;
+    }
+    pw[(sf * D + r) * 2 + 0] = pk;
+    pw[(sf * D + r) * 2 + 1] = pb;
+  }
+}
+
+// ----------------------------------------------------------------------------------------------
+// Reference channel per segment: one workgroup per segment; thread r < D sums its candidate's powers
+// over frequency in a fixed order (deterministic), then thread 0 takes the arg-max (lowest index on
+// ties).  ref_io[s] >= 0 on entry is kept.
+// ----------------------------------------------------------------------------------------------
+__global__ void mvdr_ref(const double* __restrict__ pw, int32_t* __restrict__ ref_io, int F, int D) {
+  __shared__ double score[GSS_MAX_D];
+  const int s = blockIdx.x;
+  const int r = threadIdx.x;
+  if (r < D) {
+    double num = 0.0, den = 0.0;
+    for (int f = 0; f < F; ++f) {
+      num += pw[(((long)s * F + f) * D + r) * 2 + 0];
+      den += pw[(((long)s * F + f) * D + r) * 2 + 1];
+    }
+    score[r] = num / fmax(den, GSS_EPS_SNR);
+  }
+  __syncthreads();
+  if (r == 0) {
+    int cur = ref_io[s];
+    if (cur < 0 || cur >= D) {
+      int best = 0;
+      for (int c = 1; c < D; ++c)
+        if (score[c] > score[best]) best = c;
+      cur = best;
+    }
+    ref_io[s] = cur;
+  }
+}
+
+// ----------------------------------------------------------------------------------------------
+// Apply: X[s][f][t] = sum_d conj(h[d]) y[t][d], lane = frame; the filter is wave-uniform.
+// Grid: blockIdx.x = chunk + C * (f + F * s), 256 frames per workgroup step.
+// ----------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void mvdr_apply_small(
+    const float2* __restrict__ Y, const double2* __restrict__ H, const int32_t* __restrict__ ref,
+    const int32_t* __restrict__ T_len, float2* __restrict__ X, int F, int Tmax, int C, int frames_per_chunk) {
+  const int chunk = blockIdx.x % C;
+  const long sf = blockIdx.x / C;
+  const int s = (int)(sf / F);
+  int T = T_len ? T_len[s] : Tmax;
+  T = T < 0 ? 0 : (T > Tmax ? Tmax : T);
+  int r = ref[s];
+  r = r < 0 ? 0 : (r >= D ? D - 1 : r);
+  double hr[D], hi[D];
+#pragma unroll
+  for (int d = 0; d < D; ++d) {
+    const double2 h = H[(sf * D + r) * D + d];
+    hr[d] = h.x;
+    hi[d] = h.y;
+  }
+  const float2* __restrict__ Yrow = Y + sf * (long)Tmax * D;
+  float2* __restrict__ Xrow = X + sf * (long)Tmax;
+  const int t_lo = chunk * frames_per_chunk;
+  int t_hi = t_lo + frames_per_chunk;
+  t_hi = t_hi < Tmax ? t_hi : Tmax;
+  for (int t = t_lo + threadIdx.x; t < t_hi; t += blockDim.x) {
+    double xr = 0.0, xi = 0.0;
+    if (t < T) {
+#pragma unroll
+      for (int d = 0; d < D; ++d) {
+        const float2 v = Yrow[(long)t * D + d];
+        xr += hr[d] * (double)v.x + hi[d] * (double)v.y;     // conj(h) * y
+        xi += hr[d] * (double)v.y - hi[d] * (double)v.x;
+      }
+    }
+    Xrow[t] = make_float2((float)xr, (float)xi);
+  }
+}
+
+template <int D>
+int run_mvdr_small(gss_ctx* ctx, const float2* Y, const float* gamma, const int32_t* T_len, int S, int F, int Tmax,
+                   int K, const int32_t* target, int32_t* ref, float2* X, hipStream_t st) {
+  const long n_sf = (long)S * F;
+  constexpr int E = D * D;
+  const int tiles = (Tmax + kWave - 1) / kWave;
+  long c_target = ((long)ctx->num_cu * 4 + n_sf - 1) / n_sf;
+  if (c_target < 1) c_target = 1;
+  int tpc = (int)((tiles + c_target - 1) / c_target);
+  tpc = (tpc + kPassWaves - 1) / kPassWaves * kPassWaves;
+  const int C = (tiles + tpc - 1) / tpc;
+  if (n_sf * C > 0x7fffffffL) return GSS_EUNSUPPORTED;
+
+  size_t o = 0;
+  const size_t off_part = o; o = gss_align_up(o + (size_t)n_sf * C * 2 * E * sizeof(double), 256);
+  const size_t off_H = o;    o = gss_align_up(o + (size_t)n_sf * E * sizeof(double2), 256);
+  const size_t off_pw = o;   o = gss_align_up(o + (size_t)n_sf * D * 2 * sizeof(double), 256);
+  int rc = gss_ensure_scratch(ctx, o);
+  if (rc != GSS_OK) return rc;
+  char* base = (char*)ctx->scratch;
+  double* part = (double*)(base + off_part);
+  double2* H = (double2*)(base + off_H);
+  double* pw = (double*)(base + off_pw);
+
+  hipLaunchKernelGGL((mvdr_cov_small<D>), dim3((unsigned)(n_sf * C)), dim3(kWave * kPassWaves), 0, st, Y, gamma, T_len,
+                     target, part, ctx->status, F, Tmax, K, C, tpc);
+  hipLaunchKernelGGL((mvdr_solve_small<D>), dim3((unsigned)n_sf), dim3(kWave), 0, st, part, H, pw, ctx->status, C);
+  hipLaunchKernelGGL(mvdr_ref, dim3((unsigned)S), dim3(GSS_MAX_D), 0, st, pw, ref, F, D);
+  const int fpc = 1024;
+  const int CA = (Tmax + fpc - 1) / fpc;
+  if (n_sf * CA > 0x7fffffffL) return GSS_EUNSUPPORTED;
+  hipLaunchKernelGGL((mvdr_apply_small<D>), dim3((unsigned)(n_sf * CA)), dim3(256), 0, st, Y, H, ref, T_len, X, F, Tmax,
+                     CA, fpc);
+  if (hipGetLastError() != hipSuccess) return GSS_EHIP;
+  return GSS_OK;
+}
+
+}  // namespace
+
+extern "C" int gss_mvdr(gss_ctx* ctx, const float* Y, const float* gamma, const int32_t* T_len,
+                        int S, int F, int Tmax, int D, int K, const int32_t* target, int32_t* ref,
+                        float* X, void* stream) {
+  if (!ctx || !Y || !gamma || !target || !ref || !X) return GSS_EINVAL;
+  if (S <= 0 || F <= 0 || Tmax <= 0 || D <= 0 || K <= 0) return GSS_EINVAL;
+  if (D > GSS_MAX_D || K > GSS_MAX_K) return GSS_EUNSUPPORTED;
+  if (hipSetDevice(ctx->device) != hipSuccess) return GSS_EHIP;
+  hipStream_t st = (hipStream_t)stream;
+  const float2* Yc = (const float2*)Y;
+  float2* Xc = (float2*)X;
+  switch (D) {
+#define GSS_CASE_D(DD) \
+  case DD: return run_mvdr_small<DD>(ctx, Yc, gamma, T_len, S, F, Tmax, K, target, ref, Xc, st);
+    GSS_CASE_D(1) GSS_CASE_D(2) GSS_CASE_D(3) GSS_CASE_D(4) GSS_CASE_D(5) GSS_CASE_D(6) GSS_CASE_D(7) GSS_CASE_D(8)
+#undef GSS_CASE_D
+    default: return GSS_EUNSUPPORTED;
+  }
+}
