@@ -123,9 +123,20 @@ __global__ __launch_bounds__(kWave) void mvdr_solve_small(
     sR[1][l] = b;
   }
   __syncthreads();
-  double trb = 0.0;
+  double trb = 0.0, trk = 0.0;
 #pragma unroll
-  for (int r = 0; r < D; ++r) trb += sR[1][gss_packed_row(r, D)];
+  for (int r = 0; r < D; ++r) {
+    trb += sR[1][gss_packed_row(r, D)];
+    trk += sR[0][gss_packed_row(r, D)];
+  }
+  if (!(trb > 0.0)) {
+    // No background energy at all (an empty segment, or all-zero input): the filter is defined as zero.
+    // With target energy but no background Eq. (8) has no solution; that case is flagged.
+    if (trk > 0.0 && l == 0) atomicOr(status, GSS_STATUS_NONPD_PHI);
+    if (on) H[(sf * D + j) * D + i] = make_double2(0.0, 0.0);
+    if (l < D) { pw[(sf * D + l) * 2 + 0] = 0.0; pw[(sf * D + l) * 2 + 1] = 0.0; }
+    return;
+  }
   if (on) {
     double kr, ki = 0.0, br, bi = 0.0;
     if (i == j) {

@@ -1,0 +1,110 @@
+"""Host-side checks of the C-ABI library that need no GPU: every symbol declared in include/gss.h is
+exported, error strings exist, and the integer helpers (segment + context -> frames, frame activity)
+agree bit for bit with the oracle."""
+
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import gss_oracle as o
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2212_05271_amd", "libgss.so")
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "gss.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gss_[a-z_0-9]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def binding():
+    if not os.path.exists(LIB):
+        pytest.fail(f"{LIB} missing: run `python -m paper_2212_05271_amd.build`")
+    from paper_2212_05271_amd import binding as b
+    return b
+
+
+def test_every_declared_symbol_is_exported(binding):
+    names = _declared()
+    assert {"gss_create", "gss_destroy", "gss_stft", "gss_cacgmm_em", "gss_mvdr", "gss_istft",
+            "gss_frames_from_segments", "gss_frame_activity", "gss_strerror", "gss_get_status"} <= set(names)
+    lib = ctypes.CDLL(LIB)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in gss.h but not exported"
+    assert set(binding.EXPORTS) == set(names)
+
+
+def test_error_strings_and_version(binding):
+    assert binding.strerror(0) == "ok"
+    for code in (-1, -2, -3, -4):
+        assert binding.strerror(code) not in ("ok", "unknown error")
+    assert binding.strerror(-99) == "unknown error"
+    assert re.fullmatch(r"\d+\.\d+\.\d+", binding.version())
+
+
+def test_frames_from_segments_matches_oracle_exhaustive_small(binding):
+    hop = 4
+    for n in (5, 8, 13, 16):
+        segs = [(s, e) for s in range(n) for e in range(s + 1, n + 1)]
+        st = np.array([a for a, _ in segs], dtype=np.int64)
+        en = np.array([b for _, b in segs], dtype=np.int64)
+        for cl, cr in ((0, 0), (3, 2), (6, 9)):
+            got = binding.gss_frames_from_segments(st, en, n, cl, cr, hop)
+            for i, (s, e) in enumerate(segs):
+                ref = o.segment_frames(s, e, n, cl, cr, hop)
+                for key in ("ext_start", "ext_end", "frame0", "n_frames", "cut_start", "cut_end"):
+                    assert int(got[key][i]) == ref[key], (n, s, e, cl, cr, key)
+
+
+def test_frames_from_segments_matches_oracle_recording_scale(binding):
+    rng = np.random.default_rng(0)
+    n = 57_600_000
+    st = np.sort(rng.integers(0, n - 400_000, size=1200)).astype(np.int64)
+    en = st + rng.integers(16_000, 320_000, size=1200)
+    ctxs = 120_000
+    got = binding.gss_frames_from_segments(st, en, n, ctxs, ctxs, 256)
+    for i in range(0, 1200, 7):
+        ref = o.segment_frames(int(st[i]), int(en[i]), n, ctxs, ctxs, 256)
+        for key, v in ref.items():
+            assert int(got[key][i]) == v
+    assert got["n_frames"].dtype == np.int32 and got["frame0"].dtype == np.int64
+
+
+def test_frames_from_segments_rejects_bad_input(binding):
+    with pytest.raises(binding.GssError) as e:
+        binding.gss_frames_from_segments([5], [5], 100, 0, 0, 4)      # empty segment
+    assert e.value.code == binding.GSS_EINVAL
+    with pytest.raises(binding.GssError):
+        binding.gss_frames_from_segments([0], [101], 100, 0, 0, 4)    # beyond the recording
+    with pytest.raises(binding.GssError):
+        binding.gss_frames_from_segments([0], [10], 100, -1, 0, 4)    # negative context
+    with pytest.raises(binding.GssError):
+        binding.gss_frames_from_segments([0], [10], 100, 0, 0, 0)     # hop
+
+
+def test_frame_activity_matches_oracle(binding):
+    rng = np.random.default_rng(1)
+    n, hop = 1000, 8
+    act = (rng.random((3, n)) < 0.4).astype(np.uint8)
+    for frame0, nf in ((0, 20), (5, 60), (100, 28), (0, n // hop + 3)):
+        got = binding.gss_frame_activity(act, frame0, nf, hop)
+        ref = o.frame_activity(act, frame0, nf, hop)
+        assert got.dtype == np.uint8 and np.array_equal(got, ref)
+
+
+def test_create_without_gpu_fails_cleanly(binding):
+    try:
+        import torch
+        has_gpu = torch.cuda.is_available()
+    except Exception:
+        has_gpu = False
+    if has_gpu:
+        pytest.skip("a GPU is present")
+    with pytest.raises(binding.GssError) as e:
+        binding.Context(0)
+    assert e.value.code < 0

@@ -1,0 +1,311 @@
+"""GPU parity: the HIP path, called through the C ABI, against the float64 oracle on the same seeded
+inputs.  Tolerances are the ones stated for this build: masks max|d gamma| <= 1e-3 after the configured
+EM iterations, beamformed STFT relative L2 error <= 1e-4, integer/index handling and structural zeros
+bit-exact.  STFT / iSTFT (fp32 arithmetic against an fp64 reference): relative L2 <= 1e-5.
+"""
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+TOL_GAMMA = 1e-3
+TOL_X = 1e-4
+TOL_STFT = 1e-5
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from oracle import gss_oracle as o
+    from paper_2212_05271_amd import binding as gss
+    from paper_2212_05271_amd import synth
+    ctx = gss.Context(0)
+    yield dict(torch=torch, o=o, gss=gss, synth=synth, ctx=ctx)
+    ctx.close()
+
+
+def _cn(rng, shape):
+    return (rng.standard_normal(shape) + 1j * rng.standard_normal(shape)) / np.sqrt(2)
+
+
+def _gpu_em(env, Y, act, T_len, iters, weight_mode=1):
+    t = env["torch"]
+    Yd = t.from_numpy(np.ascontiguousarray(Y)).cuda()
+    ad = t.from_numpy(np.ascontiguousarray(act)).cuda()
+    Td = None if T_len is None else t.from_numpy(np.asarray(T_len, dtype=np.int32)).cuda()
+    g = env["gss"].gss_cacgmm_em(env["ctx"], Yd, ad, Td, iters, weight_mode)
+    t.cuda.synchronize()
+    return g.cpu().numpy()
+
+
+def _gpu_mvdr(env, Y, gamma, T_len, target, ref):
+    t = env["torch"]
+    Yd = t.from_numpy(np.ascontiguousarray(Y)).cuda()
+    gd = t.from_numpy(np.ascontiguousarray(gamma, dtype=np.float32)).cuda()
+    Td = None if T_len is None else t.from_numpy(np.asarray(T_len, dtype=np.int32)).cuda()
+    tg = t.from_numpy(np.asarray(target, dtype=np.int32)).cuda()
+    rf = t.from_numpy(np.asarray(ref, dtype=np.int32)).cuda()
+    X = env["gss"].gss_mvdr(env["ctx"], Yd, gd, tg, rf, Td)
+    t.cuda.synchronize()
+    return X.cpu().numpy(), rf.cpu().numpy()
+
+
+def _check_segment(env, seg, fsel=None, weight_mode=1, iters=None):
+    """EM + MVDR of one segment against the oracle (on the frequency bins in fsel)."""
+    o = env["o"]
+    iters = seg.iters if iters is None else iters
+    g = _gpu_em(env, seg.Y[None], seg.activity[None], None, iters, weight_mode)[0]
+    F = seg.Y.shape[0]
+    fs = np.arange(F) if fsel is None else np.asarray(fsel)
+    go = o.cacgmm_em(seg.Y[fs], seg.activity, iters, weight_mode)
+    dg = float(np.max(np.abs(g[:, fs] - go)))
+    assert dg <= TOL_GAMMA, f"{seg.name}: max|d gamma| = {dg}"
+    assert np.all(g[np.broadcast_to((seg.activity == 0)[:, None, :], g.shape)] == 0.0)
+    # beamformer on the oracle's masks, reference channel forced to the oracle's choice
+    Xo, ro, _ = o.mvdr(seg.Y[fs], go, seg.target)
+    Xg, rg = _gpu_mvdr(env, seg.Y[None][:, fs], go[None].astype(np.float32), None, [seg.target], [ro])
+    rel = float(np.linalg.norm(Xg[0] - Xo) / np.linalg.norm(Xo))
+    assert rel <= TOL_X, f"{seg.name}: rel L2(X) = {rel}"
+    assert int(rg[0]) == ro
+    return dg, rel
+
+
+# ---------------------------------------------------------------------------------------------
+# EM + MVDR on the configurations
+# ---------------------------------------------------------------------------------------------
+def test_config0_full(env):
+    _check_segment(env, env["synth"].config0())
+
+
+def test_config0_small_ragged(env):
+    _check_segment(env, env["synth"].config0(F=33, T=77))
+
+
+def test_config1_small(env):
+    _check_segment(env, env["synth"].config1(F=33, T=200))
+
+
+def test_config1_full_size_sampled_bins(env):
+    """Full-size single long segment (F = 513, T = 1560, D = 8, K = 5, 20 iterations), in the launch
+    configuration the benchmark times; the oracle runs every 16th bin (bins are independent)."""
+    seg = env["synth"].config1()
+    o = env["o"]
+    g = _gpu_em(env, seg.Y[None], seg.activity[None], None, seg.iters)[0]
+    fs = np.arange(0, 513, 16)
+    go = o.cacgmm_em(seg.Y[fs], seg.activity, seg.iters)
+    assert np.max(np.abs(g[:, fs] - go)) <= TOL_GAMMA
+    s = g.sum(axis=0)
+    assert np.all(np.abs(s - 1.0) < 1e-5)                      # the noise class is always active
+    Xg, rg = _gpu_mvdr(env, seg.Y[None], g[None], None, [0], [-1])
+    Xo, ro, _ = o.mvdr(seg.Y, g.astype(np.float64), 0)        # whole tensor: the covariances are cheap on the CPU
+    assert int(rg[0]) == ro
+    assert np.linalg.norm(Xg[0] - Xo) / np.linalg.norm(Xo) <= TOL_X
+
+
+def test_weight_mode_uniform_and_zero_iterations(env):
+    seg = env["synth"].config1(F=17, T=150)
+    _check_segment(env, seg, weight_mode=0)
+    g = _gpu_em(env, seg.Y[None], seg.activity[None], None, 0)[0]
+    go = env["o"].cacgmm_em(seg.Y, seg.activity, 0)
+    assert np.max(np.abs(g - go)) < 1e-7
+
+
+@pytest.mark.parametrize("D,K", [(1, 2), (2, 3), (3, 2), (4, 4), (5, 3), (6, 2), (7, 5), (8, 8), (8, 1)])
+def test_channel_and_class_counts(env, D, K):
+    rng = np.random.default_rng(100 * D + K)
+    F, T = 9, 150
+    Y = (_cn(rng, (F, T, D)) * np.exp(rng.standard_normal((F, T, 1)))).astype(np.complex64)
+    act = (rng.random((K, T)) < 0.6).astype(np.uint8)
+    act[K - 1] = 1
+    g = _gpu_em(env, Y[None], act[None], None, 6)[0]
+    go = env["o"].cacgmm_em(Y, act, 6)
+    assert np.max(np.abs(g - go)) <= TOL_GAMMA
+    if D >= 2 and K >= 2:
+        Xo, ro, _ = env["o"].mvdr(Y, go, 0)
+        Xg, rg = _gpu_mvdr(env, Y[None], go[None], None, [0], [ro])
+        assert np.linalg.norm(Xg[0] - Xo) / np.linalg.norm(Xo) <= TOL_X
+
+
+def test_padded_batch_ragged_lengths(env):
+    """Batch of segments of different lengths and speaker counts, padded with masks (config-2 style)."""
+    synth, o = env["synth"], env["o"]
+    Ts = [190, 64, 131, 1, 77, 200]
+    ns = [4, 1, 2, 3, 4, 2]
+    segs = [synth.config2_segment(i, Ts[i], ns[i], F=11) for i in range(len(Ts))]
+    Y, act, T_len, target = synth.pad_batch(segs)
+    T_len[3] = 0                                               # an empty segment in the batch
+    rng = np.random.default_rng(5)
+    Yj = Y.copy()
+    for i, T in enumerate(T_len):                              # junk in the padding must not matter
+        Yj[i, :, T:] = _cn(rng, Yj[i, :, T:].shape).astype(np.complex64)
+    g = _gpu_em(env, Yj, act, T_len, 15)
+    go = o.cacgmm_em_batch(Y, act, T_len, 15)
+    assert np.max(np.abs(g - go)) <= TOL_GAMMA
+    for i, T in enumerate(T_len):
+        assert np.all(g[i, :, :, T:] == 0.0)
+    ref_o = np.full(len(Ts), -1, dtype=np.int32)
+    Xo, ro = o.mvdr_batch(Y, go, T_len, target, ref_o)
+    Xg, rg = _gpu_mvdr(env, Yj, go.astype(np.float32), T_len, target, ro)
+    for i, T in enumerate(T_len):
+        assert np.all(Xg[i, :, T:] == 0)
+        if T > 0:
+            assert np.linalg.norm(Xg[i, :, :T] - Xo[i, :, :T]) <= TOL_X * np.linalg.norm(Xo[i, :, :T])
+
+
+def test_degenerate_frames(env):
+    """Zero-energy frames, frames with no active class, a class that is never active."""
+    rng = np.random.default_rng(7)
+    F, T, D, K = 6, 130, 4, 4
+    Y = _cn(rng, (F, T, D)).astype(np.complex64)
+    Y[:, 10] = 0
+    Y[2, 64:70] = 0
+    act = (rng.random((K, T)) < 0.7).astype(np.uint8)
+    act[:, 20:25] = 0
+    act[2] = 0
+    env["ctx"].get_status()                                    # clear whatever earlier tests raised
+    g = _gpu_em(env, Y[None], act[None], None, 8)[0]
+    go = env["o"].cacgmm_em(Y, act, 8)
+    assert np.all(np.isfinite(g))
+    assert np.max(np.abs(g - go)) <= TOL_GAMMA
+    assert np.all(g[:, :, 20:25] == 0) and np.all(g[2] == 0)
+    assert env["ctx"].get_status() == 0
+
+
+def test_bitwise_determinism_and_frequency_independence(env):
+    seg = env["synth"].config1(F=20, T=333)
+    g1 = _gpu_em(env, seg.Y[None], seg.activity[None], None, 10)
+    g2 = _gpu_em(env, seg.Y[None], seg.activity[None], None, 10)
+    assert np.array_equal(g1, g2)
+    sel = [3, 17, 4]
+    g3 = _gpu_em(env, seg.Y[None][:, sel], seg.activity[None], None, 10)
+    assert np.array_equal(g3[0], g1[0][:, sel])
+    perm = [4, 0, 2, 1, 3]
+    g4 = _gpu_em(env, seg.Y[None], seg.activity[None][:, perm], None, 10)
+    assert np.max(np.abs(g4[0] - g1[0][perm])) <= 1e-6
+
+
+def test_reference_channel_choice(env):
+    """Auto mode returns the oracle's channel whenever the oracle's best and second-best scores differ by
+    more than 1e-4 relative; a fixed channel is honoured."""
+    o = env["o"]
+    for seed in range(4):
+        rng = np.random.default_rng(40 + seed)
+        F, T, D = 12, 300, 6
+        v, u = _cn(rng, (F, D)), _cn(rng, (F, D))
+        v[:, seed % D] *= 3.0
+        lab = rng.random((F, T)) < 0.5
+        s = _cn(rng, (F, T))
+        Y = (np.where(lab[..., None], v[:, None, :] * s[..., None], u[:, None, :] * s[..., None])
+             + 0.1 * _cn(rng, (F, T, D))).astype(np.complex64)
+        g = np.stack([lab, ~lab]).astype(np.float32)
+        phi_k, phi_bg = o.masked_covariances(Y, g, 0)
+        pbl = o.load_background(phi_bg)
+        H = o.souden_filters(phi_k, pbl)
+        sc = np.sort(o.reference_channel_scores(H, phi_k, pbl))[::-1]
+        Xo, ro, _ = o.mvdr(Y, g, 0)
+        Xg, rg = _gpu_mvdr(env, Y[None], g[None], None, [0], [-1])
+        if (sc[0] - sc[1]) > 1e-4 * sc[0]:
+            assert int(rg[0]) == ro
+        Xf, rf = _gpu_mvdr(env, Y[None], g[None], None, [0], [2])
+        Xo2, _, _ = o.mvdr(Y, g, 0, ref=2)
+        assert int(rf[0]) == 2 and np.linalg.norm(Xf[0] - Xo2) <= TOL_X * np.linalg.norm(Xo2)
+
+
+def test_mvdr_target_class_and_literal_normalised_input(env):
+    """Target other than 0, and the paper's literal reading (beamformer fed the unit-normalised Y)."""
+    o = env["o"]
+    seg = env["synth"].config1(F=15, T=260)
+    go = o.cacgmm_em(seg.Y, seg.activity, 5)
+    Yn = o.unit_normalise(seg.Y).astype(np.complex64)
+    for tgt, Yin in ((2, seg.Y), (0, Yn)):
+        Xo, ro, _ = o.mvdr(Yin, go, tgt)
+        Xg, rg = _gpu_mvdr(env, Yin[None], go[None], None, [tgt], [ro])
+        assert np.linalg.norm(Xg[0] - Xo) <= TOL_X * np.linalg.norm(Xo)
+
+
+# ---------------------------------------------------------------------------------------------
+# STFT / inverse STFT and the chained pipeline
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("S,D,N", [(1, 2, 5000), (2, 3, 4096), (1, 9, 2500), (1, 1, 255)])
+def test_stft_istft(env, S, D, N):
+    t, o, gss = env["torch"], env["o"], env["gss"]
+    rng = np.random.default_rng(N + D)
+    x = rng.standard_normal((S, D, N)).astype(np.float32)
+    Y = gss.gss_stft(env["ctx"], t.from_numpy(x).cuda()).cpu().numpy()
+    Yo = np.stack([o.stft_channels_last(x[s]) for s in range(S)])
+    assert Y.shape == Yo.shape
+    assert np.linalg.norm(Y - Yo) <= TOL_STFT * np.linalg.norm(Yo)
+    T = Yo.shape[2]
+    X = (rng.standard_normal((S, 513, T)) + 1j * rng.standard_normal((S, 513, T))).astype(np.complex64)
+    xr = gss.gss_istft(env["ctx"], t.from_numpy(X).cuda(), N).cpu().numpy()
+    xo = np.stack([o.istft(X[s], N) for s in range(S)])
+    assert np.linalg.norm(xr - xo) <= TOL_STFT * np.linalg.norm(xo)
+    back = gss.gss_istft(env["ctx"], t.from_numpy(np.ascontiguousarray(Y[..., 0])).cuda(), N).cpu().numpy()
+    assert np.linalg.norm(back - x[:, 0]) <= TOL_STFT * np.linalg.norm(x[:, 0])
+
+
+def test_full_chain_time_domain(env):
+    """x -> STFT -> EM -> MVDR -> iSTFT on the GPU against the same chain in the oracle (the oracle's STFT
+    is rounded to complex64, the type of the boundary between the stages)."""
+    t, o, gss = env["torch"], env["o"], env["gss"]
+    rng = np.random.default_rng(11)
+    D, N, K = 4, 12000, 3
+    T = o.stft_num_frames(N, 256)
+    src = rng.standard_normal((2, N)) * (np.sin(2 * np.pi * 3.0 * np.arange(N) / 16000.0)[None] ** 2 + 0.1)
+    act_s = np.zeros((K, N), np.uint8)
+    act_s[0, : 2 * N // 3] = 1
+    act_s[1, N // 3:] = 1
+    act_s[2] = 1
+    mix = rng.standard_normal((2, D))
+    x = ((mix.T @ (src * act_s[:2])) + 0.05 * rng.standard_normal((D, N))).astype(np.float32)
+    act = gss.gss_frame_activity(act_s, 0, T)
+    assert np.array_equal(act, o.frame_activity(act_s, 0, T))
+    ctx = env["ctx"]
+    Y = gss.gss_stft(ctx, t.from_numpy(x[None]).cuda())
+    g = gss.gss_cacgmm_em(ctx, Y, t.from_numpy(act[None]).cuda(), None, 10)
+    ref = t.full((1,), -1, dtype=t.int32).cuda()
+    X = gss.gss_mvdr(ctx, Y, g, t.zeros(1, dtype=t.int32).cuda(), ref)
+    xh = gss.gss_istft(ctx, X, N).cpu().numpy()[0]
+    Yo = o.stft_channels_last(x).astype(np.complex64)
+    go = o.cacgmm_em(Yo, act, 10)
+    Xo, ro, _ = o.mvdr(Yo, go, 0)
+    xo = o.istft(Xo, N)
+    assert int(ref.item()) == ro
+    assert np.max(np.abs(g.cpu().numpy()[0] - go)) <= TOL_GAMMA
+    assert np.linalg.norm(X.cpu().numpy()[0] - Xo) <= TOL_X * np.linalg.norm(Xo)
+    assert np.linalg.norm(xh - xo) <= TOL_X * np.linalg.norm(xo)
+
+
+# ---------------------------------------------------------------------------------------------
+# error handling through the ABI
+# ---------------------------------------------------------------------------------------------
+def test_argument_errors(env):
+    t, gss, ctx = env["torch"], env["gss"], env["ctx"]
+    Y = t.zeros((1, 3, 10, 2), dtype=t.complex64).cuda()
+    act = t.ones((1, 2, 10), dtype=t.uint8).cuda()
+    with pytest.raises(gss.GssError) as e:
+        gss.gss_cacgmm_em(ctx, Y, act, None, -1)
+    assert e.value.code == gss.GSS_EINVAL
+    with pytest.raises(gss.GssError) as e:
+        gss.gss_cacgmm_em(ctx, Y, act, None, 1, weight_mode=3)
+    assert e.value.code == gss.GSS_EINVAL
+    act9 = t.ones((1, 9, 10), dtype=t.uint8).cuda()
+    with pytest.raises(gss.GssError) as e:
+        gss.gss_cacgmm_em(ctx, Y, act9, None, 1)
+    assert e.value.code == gss.GSS_EUNSUPPORTED
+    Y33 = t.zeros((1, 3, 10, 33), dtype=t.complex64).cuda()
+    with pytest.raises(gss.GssError) as e:
+        gss.gss_cacgmm_em(ctx, Y33, act, None, 1)
+    assert e.value.code == gss.GSS_EUNSUPPORTED
+    x = t.zeros((1, 2, 1000)).cuda()
+    with pytest.raises(gss.GssError) as e:
+        gss.gss_stft(ctx, x, n_fft=512, hop=128)
+    assert e.value.code == gss.GSS_EUNSUPPORTED
+    with pytest.raises(TypeError):
+        gss.gss_cacgmm_em(ctx, Y.cpu(), act, None, 1)
+    # an out-of-range target is clamped and flagged, never faults
+    g = gss.gss_cacgmm_em(ctx, Y, act, None, 1)
+    ref = t.zeros(1, dtype=t.int32).cuda()
+    gss.gss_mvdr(ctx, Y, g, t.full((1,), 7, dtype=t.int32).cuda(), ref)
+    assert ctx.get_status() & 4
