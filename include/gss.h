@@ -73,6 +73,17 @@ int gss_get_status(gss_ctx* ctx, uint32_t* host_out, void* stream);
 int64_t gss_scratch_bytes(const gss_ctx* ctx);
 
 /*
+ * Per-kernel timing for measurements (not part of the method): when enabled, the launches of the
+ * dominant kernels are bracketed with HIP events on the stream they are launched on.
+ *   which = 0: the accumulating EM pass kernel (one launch per EM iteration)
+ *   which = 1: the EM factor kernel (one launch per EM iteration)
+ * gss_profile_get waits for the recorded launches, returns their summed duration in milliseconds and
+ * their count since the last call (both host pointers), and resets both.
+ */
+int gss_profile_enable(gss_ctx* ctx, int on);
+int gss_profile_get(gss_ctx* ctx, int which, double* total_ms, int64_t* launches);
+
+/*
  * STFT (Section 3 of the paper lists feature extraction among the operations run on the GPU; the paper
  * fixes only "513 bins", i.e. n_fft = 1024).
  *   x   [S][D][N] float32 time-domain samples

@@ -21,6 +21,7 @@ GSS_MAX_D, GSS_MAX_K = 32, 8
 
 EXPORTS = (
     "gss_create", "gss_destroy", "gss_strerror", "gss_version", "gss_get_status", "gss_scratch_bytes",
+    "gss_profile_enable", "gss_profile_get",
     "gss_stft", "gss_cacgmm_em", "gss_mvdr", "gss_istft", "gss_frames_from_segments", "gss_frame_activity",
 )
 
@@ -50,6 +51,10 @@ def _load():
     lib.gss_get_status.restype = i32
     lib.gss_scratch_bytes.argtypes = [vp]
     lib.gss_scratch_bytes.restype = i64
+    lib.gss_profile_enable.argtypes = [vp, i32]
+    lib.gss_profile_enable.restype = i32
+    lib.gss_profile_get.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    lib.gss_profile_get.restype = i32
     lib.gss_stft.argtypes = [vp, vp, i32, i32, i64, i32, i32, vp, i32, vp]
     lib.gss_stft.restype = i32
     lib.gss_cacgmm_em.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]
@@ -139,6 +144,15 @@ class Context:
 
     def scratch_bytes(self):
         return int(_lib.gss_scratch_bytes(self.handle))
+
+    def profile_enable(self, on=True):
+        _check(_lib.gss_profile_enable(self.handle, 1 if on else 0), "gss_profile_enable")
+
+    def profile_get(self, which=0):
+        """(total milliseconds, launches) of kernel `which` since the last call."""
+        ms, n = C.c_double(0.0), C.c_int64(0)
+        _check(_lib.gss_profile_get(self.handle, int(which), C.byref(ms), C.byref(n)), "gss_profile_get")
+        return float(ms.value), int(n.value)
 
 
 def gss_stft(ctx, x, n_fft=1024, hop=256, out=None):

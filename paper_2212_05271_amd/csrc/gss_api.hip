@@ -30,6 +30,13 @@ int gss_create(gss_ctx** out, int device_id) {
   c->scratch_cap = 0;
   c->status = nullptr;
   c->num_cu = 256;
+  c->profile = 0;
+  for (int k = 0; k < GSS_PROFILE_KERNELS; ++k) {
+    c->ev_used[k] = 0;
+    c->prof_ms[k] = 0.0;
+    c->prof_launches[k] = 0;
+    for (int i = 0; i < GSS_PROFILE_SLOTS; ++i) { c->ev_start[k][i] = nullptr; c->ev_stop[k][i] = nullptr; }
+  }
   hipDeviceProp_t prop;
   if (hipGetDeviceProperties(&prop, device_id) == hipSuccess && prop.multiProcessorCount > 0)
     c->num_cu = prop.multiProcessorCount;
@@ -52,6 +59,11 @@ void gss_destroy(gss_ctx* ctx) {
   (void)hipDeviceSynchronize();
   if (ctx->scratch) (void)hipFree(ctx->scratch);
   if (ctx->status) (void)hipFree(ctx->status);
+  for (int k = 0; k < GSS_PROFILE_KERNELS; ++k)
+    for (int i = 0; i < GSS_PROFILE_SLOTS; ++i) {
+      if (ctx->ev_start[k][i]) (void)hipEventDestroy(ctx->ev_start[k][i]);
+      if (ctx->ev_stop[k][i]) (void)hipEventDestroy(ctx->ev_stop[k][i]);
+    }
   delete ctx;
 }
 
@@ -67,6 +79,43 @@ int gss_get_status(gss_ctx* ctx, uint32_t* host_out, void* stream) {
 }
 
 int64_t gss_scratch_bytes(const gss_ctx* ctx) { return ctx ? (int64_t)ctx->scratch_cap : 0; }
+
+int gss_profile_enable(gss_ctx* ctx, int on) {
+  if (!ctx) return GSS_EINVAL;
+  if (on) {
+    if (hipSetDevice(ctx->device) != hipSuccess) return GSS_EHIP;
+    for (int k = 0; k < GSS_PROFILE_KERNELS; ++k)
+      for (int i = 0; i < GSS_PROFILE_SLOTS; ++i) {
+        if (!ctx->ev_start[k][i]) GSS_HIP_CHECK(hipEventCreate(&ctx->ev_start[k][i]));
+        if (!ctx->ev_stop[k][i]) GSS_HIP_CHECK(hipEventCreate(&ctx->ev_stop[k][i]));
+      }
+  }
+  ctx->profile = on ? 1 : 0;
+  return GSS_OK;
+}
+
+static int drain_profile(gss_ctx* ctx, int which) {
+  for (int i = 0; i < ctx->ev_used[which]; ++i) {
+    GSS_HIP_CHECK(hipEventSynchronize(ctx->ev_stop[which][i]));
+    float ms = 0.f;
+    GSS_HIP_CHECK(hipEventElapsedTime(&ms, ctx->ev_start[which][i], ctx->ev_stop[which][i]));
+    ctx->prof_ms[which] += (double)ms;
+    ctx->prof_launches[which] += 1;
+  }
+  ctx->ev_used[which] = 0;
+  return GSS_OK;
+}
+
+int gss_profile_get(gss_ctx* ctx, int which, double* total_ms, int64_t* launches) {
+  if (!ctx || which < 0 || which >= GSS_PROFILE_KERNELS || !total_ms || !launches) return GSS_EINVAL;
+  int rc = drain_profile(ctx, which);
+  if (rc != GSS_OK) return rc;
+  *total_ms = ctx->prof_ms[which];
+  *launches = ctx->prof_launches[which];
+  ctx->prof_ms[which] = 0.0;
+  ctx->prof_launches[which] = 0;
+  return GSS_OK;
+}
 
 int gss_frames_from_segments(const int64_t* seg_start, const int64_t* seg_end, int n_seg,
                              int64_t n_samples, int64_t ctx_left, int64_t ctx_right, int hop,
@@ -117,6 +166,18 @@ int gss_frame_activity(const uint8_t* act_samples, int K, int64_t n_samples, int
 }
 
 }  // extern "C"
+
+void gss_profile_begin(gss_ctx* ctx, int which, hipStream_t st) {
+  if (!ctx->profile) return;
+  if (ctx->ev_used[which] == GSS_PROFILE_SLOTS) (void)drain_profile(ctx, which);   // waits for the oldest launches
+  (void)hipEventRecord(ctx->ev_start[which][ctx->ev_used[which]], st);
+}
+
+void gss_profile_end(gss_ctx* ctx, int which, hipStream_t st) {
+  if (!ctx->profile) return;
+  (void)hipEventRecord(ctx->ev_stop[which][ctx->ev_used[which]], st);
+  ctx->ev_used[which] += 1;
+}
 
 int gss_ensure_scratch(gss_ctx* ctx, size_t bytes) {
   if (bytes <= ctx->scratch_cap) return GSS_OK;

@@ -486,10 +486,14 @@ int run_small(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_t* 
   const dim3 grid((unsigned)(n_sf * p.C));
   hipLaunchKernelGGL(em_init_coef, dim3(1024), dim3(256), 0, st, coef, cm, ce, D, K, n_sf);
   for (int it = 0; it < iters; ++it) {
+    gss_profile_begin(ctx, 0, st);
     hipLaunchKernelGGL((em_pass_small<D, K, false>), grid, dim3(kWave * kPassWaves), 0, st, Y, act, T_len, coef, cm, ce, part, npart,
                        (float*)nullptr, F, Tmax, p.C, p.tiles_per_chunk);
+    gss_profile_end(ctx, 0, st);
+    gss_profile_begin(ctx, 1, st);
     hipLaunchKernelGGL((em_factor_small<D, K>), dim3((unsigned)n_sf), dim3(kWave * K), 0, st, part, npart, coef, cm, ce,
                        ctx->status, p.C, weight_mode);
+    gss_profile_end(ctx, 1, st);
   }
   hipLaunchKernelGGL((em_pass_small<D, K, true>), grid, dim3(kWave * kPassWaves), 0, st, Y, act, T_len, coef, cm, ce,
                      (double*)nullptr, (double*)nullptr, gamma, F, Tmax, p.C, p.tiles_per_chunk);

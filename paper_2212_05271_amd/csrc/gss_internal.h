@@ -18,13 +18,26 @@
 #define GSS_EPS_TRACE 1e-20     // added to Re tr(Phi_bg^-1 Phi_k), Eq. (8)
 #define GSS_EPS_SNR 1e-300      // floor on the background power in the reference-channel ratio
 
+#define GSS_PROFILE_SLOTS 64
+#define GSS_PROFILE_KERNELS 2     // 0: EM pass (accumulating), 1: EM factor
+
 struct gss_ctx {
   int device;
   void* scratch;          // device
   size_t scratch_cap;
   uint32_t* status;       // device, one word
   int num_cu;
+  // optional per-kernel timing with HIP events (gss_profile_enable / gss_profile_get)
+  int profile;
+  hipEvent_t ev_start[GSS_PROFILE_KERNELS][GSS_PROFILE_SLOTS], ev_stop[GSS_PROFILE_KERNELS][GSS_PROFILE_SLOTS];
+  int ev_used[GSS_PROFILE_KERNELS];
+  double prof_ms[GSS_PROFILE_KERNELS];
+  int64_t prof_launches[GSS_PROFILE_KERNELS];
 };
+
+// Brackets one kernel launch with HIP events on `st` when profiling is on.
+void gss_profile_begin(gss_ctx* ctx, int which, hipStream_t st);
+void gss_profile_end(gss_ctx* ctx, int which, hipStream_t st);
 
 // Makes sure ctx->scratch holds at least `bytes`.  Growing synchronises the device (the old block may
 // still be in use by kernels already enqueued) and reallocates.
