@@ -32,8 +32,8 @@ FS, HOP = 16000, 256
 # Published MI355X vector peak for the arithmetic type of the EM kernels (fp64 FMA): 78.6 TFLOP/s.
 PEAK_TFLOPS_F64 = 78.6
 # HBM bytes per launch of the accumulating EM pass on this workload, from rocprofv3 --pmc runs
-# (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel calibration); None until measured.
-EM_PASS_TRAFFIC_BYTES = None
+# (FETCH_SIZE + WRITE_SIZE in KiB, each scaled by the copy-kernel calibration).
+EM_PASS_TRAFFIC_BYTES = (53320 + 1315) * 1024   # profiles/em_config1_hbm_traffic.md
 
 
 def em_pass_flops(F, T, D, K):

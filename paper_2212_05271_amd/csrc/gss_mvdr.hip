@@ -224,24 +224,33 @@ __global__ __launch_bounds__(kWave) void mvdr_solve_small(
 }
 
 // ----------------------------------------------------------------------------------------------
-// Reference channel per segment: one workgroup per segment; thread r < D sums its candidate's powers
-// over frequency in a fixed order (deterministic), then thread 0 takes the arg-max (lowest index on
-// ties).  ref_io[s] >= 0 on entry is kept.
+// Reference channel per segment: one workgroup of 1024 threads per segment; thread (r, j) sums candidate
+// r's powers over the frequencies f = j, j + 32, ..., the 32 partial sums per candidate are added in a
+// fixed order (deterministic), then thread 0 takes the arg-max (lowest index on ties).
+// ref_io[s] >= 0 on entry is kept.
 // ----------------------------------------------------------------------------------------------
-__global__ void mvdr_ref(const double* __restrict__ pw, int32_t* __restrict__ ref_io, int F, int D) {
+__global__ __launch_bounds__(1024) void mvdr_ref(const double* __restrict__ pw, int32_t* __restrict__ ref_io, int F, int D) {
+  __shared__ double snum[32][33], sden[32][33];
   __shared__ double score[GSS_MAX_D];
   const int s = blockIdx.x;
-  const int r = threadIdx.x;
+  const int r = threadIdx.x & 31, j = threadIdx.x >> 5;
+  double num = 0.0, den = 0.0;
   if (r < D) {
-    double num = 0.0, den = 0.0;
-    for (int f = 0; f < F; ++f) {
+    for (int f = j; f < F; f += 32) {
       num += pw[(((long)s * F + f) * D + r) * 2 + 0];
       den += pw[(((long)s * F + f) * D + r) * 2 + 1];
     }
-    score[r] = num / fmax(den, GSS_EPS_SNR);
+  }
+  snum[r][j] = num;
+  sden[r][j] = den;
+  __syncthreads();
+  if (j == 0 && r < D) {
+    double n = 0.0, d = 0.0;
+    for (int q = 0; q < 32; ++q) { n += snum[r][q]; d += sden[r][q]; }
+    score[r] = n / fmax(d, GSS_EPS_SNR);
   }
   __syncthreads();
-  if (r == 0) {
+  if (threadIdx.x == 0) {
     int cur = ref_io[s];
     if (cur < 0 || cur >= D) {
       int best = 0;
@@ -321,7 +330,7 @@ int run_mvdr_small(gss_ctx* ctx, const float2* Y, const float* gamma, const int3
   hipLaunchKernelGGL((mvdr_cov_small<D>), dim3((unsigned)(n_sf * C)), dim3(kWave * kPassWaves), 0, st, Y, gamma, T_len,
                      target, part, ctx->status, F, Tmax, K, C, tpc);
   hipLaunchKernelGGL((mvdr_solve_small<D>), dim3((unsigned)n_sf), dim3(kWave), 0, st, part, H, pw, ctx->status, C);
-  hipLaunchKernelGGL(mvdr_ref, dim3((unsigned)S), dim3(GSS_MAX_D), 0, st, pw, ref, F, D);
+  hipLaunchKernelGGL(mvdr_ref, dim3((unsigned)S), dim3(1024), 0, st, pw, ref, F, D);
   const int fpc = 1024;
   const int CA = (Tmax + fpc - 1) / fpc;
   if (n_sf * CA > 0x7fffffffL) return GSS_EUNSUPPORTED;
