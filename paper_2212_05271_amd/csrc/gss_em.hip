@@ -106,6 +106,16 @@ __device__ __forceinline__ void pass_unit(
       yi[f][d] = valid[f] ? (double)v.y : 0.0;
     }
   }
+  // activity bits of the lane's frames, fetched here so that the loads overlap the q loop
+  unsigned abits[NF];
+#pragma unroll
+  for (int f = 0; f < NF; ++f) {
+    unsigned b = 0;
+#pragma unroll
+    for (int k = 0; k < K; ++k) b |= (arow[(long)k * Tmax + (valid[f] ? t[f] : 0)] != 0 ? 1u : 0u) << k;
+    abits[f] = valid[f] ? b : 0u;
+    asm volatile("" : "+v"(abits[f]));
+  }
 
   // ---- q_k = <coef_k, y y^H> ----
   // The coefficients are wave-uniform and loop-invariant and come through the scalar path, one group of
@@ -170,7 +180,7 @@ __device__ __forceinline__ void pass_unit(
     int emax = -(1 << 28);
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      a[k] = valid[f] && (arow[(long)k * Tmax + (valid[f] ? t[f] : 0)] != 0);
+      a[k] = (abits[f] >> k) & 1u;
       rq[k] = rcp_f64(fmax(q[f][k], qfloor));        // 1 / (q_k * n2c): the M-step weight is gamma_k * rq
       const double u = rq[k] * n2c;                  // 1 / q_k
       const double mu = __builtin_amdgcn_frexp_mant(u);
