@@ -540,6 +540,6 @@ extern "C" int gss_cacgmm_em(gss_ctx* ctx, const float* Y, const uint8_t* activi
   case DD: return dispatch_k<DD>(ctx, Yc, activity, T_len, S, F, Tmax, K, iters, weight_mode, gamma, st);
     GSS_CASE_D(1) GSS_CASE_D(2) GSS_CASE_D(3) GSS_CASE_D(4) GSS_CASE_D(5) GSS_CASE_D(6) GSS_CASE_D(7) GSS_CASE_D(8)
 #undef GSS_CASE_D
-    default: return GSS_EUNSUPPORTED;
+    default: return gss_em_large(ctx, Y, activity, T_len, S, F, Tmax, D, K, iters, weight_mode, gamma, st);
   }
 }

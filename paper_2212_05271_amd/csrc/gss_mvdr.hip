@@ -330,7 +330,7 @@ int run_mvdr_small(gss_ctx* ctx, const float2* Y, const float* gamma, const int3
   hipLaunchKernelGGL((mvdr_cov_small<D>), dim3((unsigned)(n_sf * C)), dim3(kWave * kPassWaves), 0, st, Y, gamma, T_len,
                      target, part, ctx->status, F, Tmax, K, C, tpc);
   hipLaunchKernelGGL((mvdr_solve_small<D>), dim3((unsigned)n_sf), dim3(kWave), 0, st, part, H, pw, ctx->status, C);
-  hipLaunchKernelGGL(mvdr_ref, dim3((unsigned)S), dim3(1024), 0, st, pw, ref, F, D);
+  gss_launch_mvdr_ref(pw, ref, S, F, D, st);
   const int fpc = 1024;
   const int CA = (Tmax + fpc - 1) / fpc;
   if (n_sf * CA > 0x7fffffffL) return GSS_EUNSUPPORTED;
@@ -341,6 +341,10 @@ int run_mvdr_small(gss_ctx* ctx, const float2* Y, const float* gamma, const int3
 }
 
 }  // namespace
+
+void gss_launch_mvdr_ref(const double* pw, int32_t* ref, int S, int F, int D, hipStream_t st) {
+  hipLaunchKernelGGL(mvdr_ref, dim3((unsigned)S), dim3(1024), 0, st, pw, ref, F, D);
+}
 
 extern "C" int gss_mvdr(gss_ctx* ctx, const float* Y, const float* gamma, const int32_t* T_len,
                         int S, int F, int Tmax, int D, int K, const int32_t* target, int32_t* ref,
@@ -357,6 +361,6 @@ extern "C" int gss_mvdr(gss_ctx* ctx, const float* Y, const float* gamma, const 
   case DD: return run_mvdr_small<DD>(ctx, Yc, gamma, T_len, S, F, Tmax, K, target, ref, Xc, st);
     GSS_CASE_D(1) GSS_CASE_D(2) GSS_CASE_D(3) GSS_CASE_D(4) GSS_CASE_D(5) GSS_CASE_D(6) GSS_CASE_D(7) GSS_CASE_D(8)
 #undef GSS_CASE_D
-    default: return GSS_EUNSUPPORTED;
+    default: return gss_mvdr_large(ctx, Y, gamma, T_len, S, F, Tmax, D, K, target, ref, X, st);
   }
 }

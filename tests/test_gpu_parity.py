@@ -127,6 +127,42 @@ def test_channel_and_class_counts(env, D, K):
         assert np.linalg.norm(Xg[0] - Xo) / np.linalg.norm(Xo) <= TOL_X
 
 
+@pytest.mark.parametrize("D,K,T", [(9, 3, 100), (12, 5, 150), (16, 2, 70), (24, 5, 200), (32, 4, 130)])
+def test_large_arrays(env, D, K, T):
+    """9 <= D <= 32 channels (run-time D kernels)."""
+    rng = np.random.default_rng(1000 + D)
+    F = 5
+    v = _cn(rng, (K, F, D))
+    lab = rng.integers(0, K, size=(F, T))
+    Y = (v[lab, np.arange(F)[:, None]] * _cn(rng, (F, T, 1)) * np.exp(rng.standard_normal((F, T, 1)))
+         + 0.3 * _cn(rng, (F, T, D))).astype(np.complex64)
+    act = (rng.random((K, T)) < 0.7).astype(np.uint8)
+    act[K - 1] = 1
+    T_len = np.array([T - 7], dtype=np.int32)
+    g = _gpu_em(env, Y[None], act[None], T_len, 6)[0]
+    go = env["o"].cacgmm_em_batch(Y[None], act[None], T_len, 6)[0]
+    assert np.max(np.abs(g - go)) <= TOL_GAMMA
+    assert np.all(g[:, :, T - 7:] == 0)
+    Xo, ro = env["o"].mvdr_batch(Y[None], go[None], T_len, [0], [-1])
+    Xg, rg = _gpu_mvdr(env, Y[None], go[None], T_len, [0], ro)
+    assert np.linalg.norm(Xg - Xo) <= TOL_X * np.linalg.norm(Xo)
+    Xa, ra = _gpu_mvdr(env, Y[None], go[None], T_len, [0], [-1])
+    assert int(ra[0]) == int(ro[0])
+
+
+def test_config3_full_size_sampled_bins(env):
+    """24-channel multi-array segment (F = 513, T = 1500, K = 5, 20 iterations); oracle on every 64th bin."""
+    seg = env["synth"].config3()
+    o = env["o"]
+    g = _gpu_em(env, seg.Y[None], seg.activity[None], None, seg.iters)[0]
+    fs = np.arange(0, 513, 64)
+    go = o.cacgmm_em(seg.Y[fs], seg.activity, seg.iters)
+    assert np.max(np.abs(g[:, fs] - go)) <= TOL_GAMMA
+    Xo, ro, _ = o.mvdr(seg.Y[fs], go, 0)
+    Xg, rg = _gpu_mvdr(env, seg.Y[None][:, fs], go[None], None, [0], [ro])
+    assert np.linalg.norm(Xg[0] - Xo) <= TOL_X * np.linalg.norm(Xo)
+
+
 def test_padded_batch_ragged_lengths(env):
     """Batch of segments of different lengths and speaker counts, padded with masks (config-2 style)."""
     synth, o = env["synth"], env["o"]
@@ -294,7 +330,7 @@ def test_argument_errors(env):
     with pytest.raises(gss.GssError) as e:
         gss.gss_cacgmm_em(ctx, Y, act9, None, 1)
     assert e.value.code == gss.GSS_EUNSUPPORTED
-    Y33 = t.zeros((1, 3, 10, 33), dtype=t.complex64).cuda()
+    Y33 = t.zeros((1, 3, 10, 33), dtype=t.complex64).cuda()   # more channels than GSS_MAX_D
     with pytest.raises(gss.GssError) as e:
         gss.gss_cacgmm_em(ctx, Y33, act, None, 1)
     assert e.value.code == gss.GSS_EUNSUPPORTED
