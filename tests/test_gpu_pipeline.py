@@ -1,0 +1,83 @@
+"""Full-size batch (config 2) and the recording-level pipeline (config 4, at reduced duration) on the GPU
+against the oracle, on sampled segments / bins that the oracle can finish in seconds."""
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+TOL_GAMMA = 1e-3
+TOL_X = 1e-4
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from oracle import gss_oracle as o
+    from paper_2212_05271_amd import binding as gss
+    from paper_2212_05271_amd import pipeline, synth
+    ctx = gss.Context(0)
+    yield dict(torch=torch, o=o, gss=gss, synth=synth, ctx=ctx, pipeline=pipeline)
+    ctx.close()
+
+
+def test_config2_full_size_batch(env):
+    """64 segments, T in [125, 1875], 1-4 speakers + noise (K padded to 5), 15 iterations, bucketed by length
+    into 4 padded batches: the launch configuration of the batched workload.  The oracle checks one segment per
+    bucket on four frequency bins (segments and bins are independent)."""
+    t, o, gss, synth, ctx = env["torch"], env["o"], env["gss"], env["synth"], env["ctx"]
+    T, ns = synth.config2_plan()
+    buckets = synth.buckets_by_length(T, 4)
+    bins = np.array([5, 130, 300, 500])
+    for bi, idx in enumerate(buckets):
+        segs = [synth.config2_segment(i, T[i], ns[i]) for i in idx]
+        Y, act, T_len, target = synth.pad_batch(segs)
+        Yd = t.from_numpy(Y).cuda()
+        Td = t.from_numpy(T_len).cuda()
+        g = gss.gss_cacgmm_em(ctx, Yd, t.from_numpy(act).cuda(), Td, 15)
+        ref = t.zeros(len(idx), dtype=t.int32).cuda()
+        X = gss.gss_mvdr(ctx, Yd, g, t.from_numpy(target).cuda(), ref, Td)
+        t.cuda.synchronize()
+        pick = len(idx) // 2 + (bi % 3)
+        seg = segs[pick]
+        Ts = seg.Y.shape[1]
+        go = o.cacgmm_em(seg.Y[bins], seg.activity, 15)
+        gg = g[pick].cpu().numpy()
+        assert np.max(np.abs(gg[:, bins, :Ts] - go)) <= TOL_GAMMA
+        assert np.all(gg[:, :, Ts:] == 0)
+        Xo, _, _ = o.mvdr(seg.Y[bins], gg[:, bins, :Ts].astype(np.float64), 0, ref=0)
+        Xg = X[pick].cpu().numpy()
+        assert np.linalg.norm(Xg[bins, :Ts] - Xo) <= TOL_X * np.linalg.norm(Xo)
+        assert np.all(Xg[:, Ts:] == 0)
+        del Yd, g, X
+
+
+def test_recording_pipeline_reduced_meeting(env):
+    """Config 4 at reduced duration: a 60 s, 8-channel synthetic meeting with 16 diarization segments, 7.5 s of
+    context per side: STFT of the recording once, segments as frame ranges, batched EM (15 iterations) + MVDR +
+    iSTFT, target regions cut out.  Two segments are re-done end to end by the oracle."""
+    t, o, gss, synth, ctx, pipeline = (env[k] for k in ("torch", "o", "gss", "synth", "ctx", "pipeline"))
+    x, act_s, (st, en, spk) = synth.meeting(duration_s=60.0, n_segments=16)
+    D, N = x.shape
+    ctx_s = 120_000
+    xd = t.from_numpy(x).cuda()
+    outs, fr = pipeline.enhance_recording(ctx, xd, act_s, st, en, spk, ctx_s, ctx_s, iters=15)
+    t.cuda.synchronize()
+    assert len(outs) == len(st)
+    for i in range(len(st)):
+        assert outs[i].shape[0] == int(en[i] - st[i])
+        ref = o.segment_frames(int(st[i]), int(en[i]), N, ctx_s, ctx_s)
+        for key in ("ext_start", "ext_end", "frame0", "n_frames", "cut_start", "cut_end"):
+            assert int(fr[key][i]) == ref[key]
+    Yrec = o.stft_channels_last(x).astype(np.complex64)
+    order = np.argsort(fr["n_frames"])
+    for i in (int(order[0]), int(order[len(order) // 2])):
+        f0, nf = int(fr["frame0"][i]), int(fr["n_frames"][i])
+        Ys = Yrec[:, f0:f0 + nf]
+        act = np.concatenate([o.frame_activity(act_s, f0, nf), np.ones((1, nf), np.uint8)])
+        go = o.cacgmm_em(Ys, act, 15)
+        Xo, ro, _ = o.mvdr(Ys, go, int(spk[i]))
+        xo = o.istft(Xo, (nf - 3) * 256)[int(fr["cut_start"][i]):int(fr["cut_end"][i])]
+        xg = outs[i].cpu().numpy()
+        assert int(fr["ref"][i]) == ro
+        assert np.linalg.norm(xg - xo) <= TOL_X * np.linalg.norm(xo)
