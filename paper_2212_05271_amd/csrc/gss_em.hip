@@ -73,6 +73,35 @@ __global__ void em_init_coef(double* __restrict__ coef, double* __restrict__ cma
 // the wavefronts round-robin.
 // ----------------------------------------------------------------------------------------------
 
+// How the (segment, frequency) problems are cut into workgroups.  The first n_main problems get c_main
+// chunks of tpc_main tiles each; the remaining ones (the tail that would otherwise run alone on an almost
+// empty chip after the last full round of workgroups) are cut finer, into c_tail chunks of tpc_tail tiles.
+// Workgroup b writes partial-sum slot b.
+struct ChunkMap {
+  int n_main, c_main, tpc_main, c_tail, tpc_tail;
+};
+__host__ __device__ inline void chunk_decode(const ChunkMap& m, long b, long& sf, int& chunk, int& tpc) {
+  const long main_wgs = (long)m.n_main * m.c_main;
+  if (b < main_wgs) {
+    sf = b / m.c_main;
+    chunk = (int)(b % m.c_main);
+    tpc = m.tpc_main;
+  } else {
+    const long r = b - main_wgs;
+    sf = m.n_main + r / m.c_tail;
+    chunk = (int)(r % m.c_tail);
+    tpc = m.tpc_tail;
+  }
+}
+__host__ __device__ inline long chunk_base(const ChunkMap& m, long sf, int& count) {
+  if (sf < m.n_main) {
+    count = m.c_main;
+    return sf * m.c_main;
+  }
+  count = m.c_tail;
+  return (long)m.n_main * m.c_main + (sf - m.n_main) * m.c_tail;
+}
+
 // Frames per lane in phase 1.  Every class coefficient that comes through the scalar path is applied to
 // kNF frames; the scalar data path returns about one dword per clock per pair of compute units, so
 // at kNF = 1 it is as busy as the vector ALUs.
@@ -233,7 +262,7 @@ __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
     const float2* __restrict__ Y, const uint8_t* __restrict__ act, const int32_t* __restrict__ T_len,
     const double* __restrict__ coef, const double* __restrict__ cmant, const int32_t* __restrict__ cexp,
     double* __restrict__ part, double* __restrict__ npart, float* __restrict__ gamma,
-    int F, int Tmax, int C, int tiles_per_chunk) {
+    int F, int Tmax, ChunkMap cmap) {
   constexpr int E = D * D;
   constexpr int WS = K | 1;
   constexpr int kTileDoubles = kWave * kYStride + kWave * WS;
@@ -244,8 +273,9 @@ __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
 
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
-  const int chunk = blockIdx.x % C;
-  const long sf = blockIdx.x / C;
+  long sf;
+  int chunk, tiles_per_chunk;
+  chunk_decode(cmap, blockIdx.x, sf, chunk, tiles_per_chunk);
   const int s = (int)(sf / F);
   const int f = (int)(sf % F);
   int T = T_len ? T_len[s] : Tmax;
@@ -291,7 +321,7 @@ __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
   if (FINAL) return;
 
   // Reduce over the 8 frame groups and over the wavefronts; write the chunk's packed partial sums.
-  reduce_and_store_partials<D, K>(acc, lds, part + (sf * C + chunk) * (long)(K * E), lane, wave);
+  reduce_and_store_partials<D, K>(acc, lds, part + (long)blockIdx.x * (K * E), lane, wave);
 #pragma unroll
   for (int k = 0; k < K; ++k) {
     double nv = nacc[k];
@@ -310,7 +340,7 @@ __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
     double sum = 0.0;
 #pragma unroll
     for (int w = 0; w < kPassWaves; ++w) sum += redn[w * K + threadIdx.x];
-    npart[(sf * C + chunk) * K + threadIdx.x] = sum;
+    npart[(long)blockIdx.x * K + threadIdx.x] = sum;
   }
 }
 
@@ -325,7 +355,7 @@ template <int D, int K>
 __global__ __launch_bounds__(kWave * K) void em_factor_small(
     const double* __restrict__ part, const double* __restrict__ npart,
     double* __restrict__ coef, double* __restrict__ cmant, int32_t* __restrict__ cexp, uint32_t* __restrict__ status,
-    int C, int weight_mode) {
+    ChunkMap cmap, int weight_mode) {
   constexpr int E = D * D;
   __shared__ double sR[K][E];
   __shared__ double sMr[K][D][D], sMi[K][D][D];
@@ -336,15 +366,17 @@ __global__ __launch_bounds__(kWave * K) void em_factor_small(
   const long sf = blockIdx.x;
   const int k = threadIdx.x / kWave;
   const int l = threadIdx.x % kWave;
+  int C;
+  const long slot0 = chunk_base(cmap, sf, C);
 
   if (l < E) {
     double r = 0.0;
-    for (int c = 0; c < C; ++c) r += part[((sf * C + c) * K + k) * (long)E + l];
+    for (int c = 0; c < C; ++c) r += part[((slot0 + c) * K + k) * (long)E + l];
     sR[k][l] = r;
   }
   if (l == 0) {
     double n = 0.0;
-    for (int c = 0; c < C; ++c) n += npart[(sf * C + c) * K + k];
+    for (int c = 0; c < C; ++c) n += npart[(slot0 + c) * K + k];
     sN[k] = n;
   }
   __syncthreads();
@@ -444,36 +476,69 @@ __global__ __launch_bounds__(kWave * K) void em_factor_small(
 // Host-side plan and dispatch
 // ----------------------------------------------------------------------------------------------
 struct EmPlan {
-  int C;                 // chunks per (segment, frequency)
-  int tiles_per_chunk;   // 64-frame tiles per chunk
+  ChunkMap acc;          // chunking of the accumulating passes
+  ChunkMap fin;          // chunking of the final pass (no state across tiles: always fine-grained)
+  long wgs_acc, wgs_fin;
   size_t off_coef, off_cm, off_ce, off_part, off_npart, total;
 };
 
-EmPlan make_plan(const gss_ctx* ctx, long n_sf, int Tmax, int D, int K) {
+int env_int(const char* name, int dflt) {
+  if (const char* e = getenv(name)) {
+    const int v = atoi(e);
+    if (v > 0) return v;
+  }
+  return dflt;
+}
+
+long map_wgs(const ChunkMap& m, long n_sf) { return (long)m.n_main * m.c_main + (n_sf - m.n_main) * m.c_tail; }
+
+EmPlan make_plan(const gss_ctx* ctx, long n_sf, int Tmax, int D, int K, int wgs_per_cu) {
   EmPlan p;
   const int tiles = (Tmax + kWave - 1) / kWave;
-  // A chunk is a whole number of rounds of the workgroup's wavefronts.  Splitting a (segment, frequency)
-  // over several workgroups costs a partial-sum round trip and a second reduction, so it is done only
-  // when there are fewer problems than about two workgroups per compute unit.
-  // GSS_EM_TPC overrides the tiles per chunk (tuning aid).
-  const long target = (long)ctx->num_cu * 2;
-  long c_target = (target + n_sf - 1) / n_sf;
+  const int round_up = kPassWaves * kNF;               // a chunk is a whole number of rounds of units
+  auto chunks_for = [&](int tpc) { return (tiles + tpc - 1) / tpc; };
+  auto tpc_for = [&](long c) {
+    int tpc = (int)((tiles + c - 1) / c);
+    tpc = (tpc + round_up - 1) / round_up * round_up;
+    return tpc;
+  };
+  // Splitting a (segment, frequency) over several workgroups costs a partial-sum round trip and a second
+  // reduction, so it is done only as far as needed to fill the chip's resident workgroup slots.
+  // GSS_EM_TPC overrides the tiles per chunk of the main part (tuning aid).
+  const long slots = (long)ctx->num_cu * wgs_per_cu;
+  long c_target = (slots + n_sf - 1) / n_sf;
   if (c_target < 1) c_target = 1;
-  int tpc = (int)((tiles + c_target - 1) / c_target);
-  tpc = (tpc + kPassWaves - 1) / kPassWaves * kPassWaves;
-  if (const char* e = getenv("GSS_EM_TPC")) {
-    const int v = atoi(e);
-    if (v > 0) tpc = v;
+  p.acc.tpc_main = env_int("GSS_EM_TPC", tpc_for(c_target));
+  p.acc.c_main = chunks_for(p.acc.tpc_main);
+  p.acc.n_main = (int)n_sf;
+  p.acc.c_tail = p.acc.c_main;
+  p.acc.tpc_tail = p.acc.tpc_main;
+  // Tail: the workgroups left over after the last full round of resident slots.  If they fill less than a
+  // quarter of the chip, the problems they belong to are cut finer so that the remainder spreads out.
+  const long wgs = n_sf * p.acc.c_main;
+  const long rem = wgs % slots;
+  if (wgs > slots && rem > 0 && rem * 4 <= slots && env_int("GSS_EM_NOTAIL", 0) == 0) {
+    const long tail_sf = (rem + p.acc.c_main - 1) / p.acc.c_main;
+    const long want = slots / (2 * tail_sf) > 1 ? slots / (2 * tail_sf) : 1;    // chunks per tail problem
+    const int tpc_t = tpc_for(want * p.acc.c_main);
+    if (tpc_t < p.acc.tpc_main) {
+      p.acc.n_main = (int)(n_sf - tail_sf);
+      p.acc.tpc_tail = tpc_t;
+      p.acc.c_tail = chunks_for(tpc_t);
+    }
   }
-  p.tiles_per_chunk = tpc;
-  p.C = (tiles + tpc - 1) / tpc;
+  p.wgs_acc = map_wgs(p.acc, n_sf);
+  p.fin.tpc_main = p.fin.tpc_tail = round_up;
+  p.fin.c_main = p.fin.c_tail = chunks_for(round_up);
+  p.fin.n_main = (int)n_sf;
+  p.wgs_fin = map_wgs(p.fin, n_sf);
   const size_t E = (size_t)D * D;
   size_t o = 0;
   p.off_coef = o;  o = gss_align_up(o + (size_t)n_sf * K * E * sizeof(double), 256);
   p.off_cm = o;    o = gss_align_up(o + (size_t)n_sf * K * sizeof(double), 256);
   p.off_ce = o;    o = gss_align_up(o + (size_t)n_sf * K * sizeof(int32_t), 256);
-  p.off_part = o;  o = gss_align_up(o + (size_t)n_sf * p.C * K * E * sizeof(double), 256);
-  p.off_npart = o; o = gss_align_up(o + (size_t)n_sf * p.C * K * sizeof(double), 256);
+  p.off_part = o;  o = gss_align_up(o + (size_t)p.wgs_acc * K * E * sizeof(double), 256);
+  p.off_npart = o; o = gss_align_up(o + (size_t)p.wgs_acc * K * sizeof(double), 256);
   p.total = o;
   return p;
 }
@@ -482,7 +547,11 @@ template <int D, int K>
 int run_small(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_t* T_len, int S, int F, int Tmax,
               int iters, int weight_mode, float* gamma, hipStream_t st) {
   const long n_sf = (long)S * F;
-  const EmPlan p = make_plan(ctx, n_sf, Tmax, D, K);
+  int wgs_per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&wgs_per_cu, em_pass_small<D, K, false>, kWave * kPassWaves, 0) !=
+          hipSuccess || wgs_per_cu < 1)
+    wgs_per_cu = 2;
+  const EmPlan p = make_plan(ctx, n_sf, Tmax, D, K, wgs_per_cu);
   int rc = gss_ensure_scratch(ctx, p.total);
   if (rc != GSS_OK) return rc;
   char* base = (char*)ctx->scratch;
@@ -492,21 +561,21 @@ int run_small(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_t* 
   double* part = (double*)(base + p.off_part);
   double* npart = (double*)(base + p.off_npart);
 
-  if ((long)n_sf * p.C > 0x7fffffffL) return GSS_EUNSUPPORTED;
-  const dim3 grid((unsigned)(n_sf * p.C));
+  if (p.wgs_acc > 0x7fffffffL || p.wgs_fin > 0x7fffffffL) return GSS_EUNSUPPORTED;
+  const dim3 block(kWave * kPassWaves);
   hipLaunchKernelGGL(em_init_coef, dim3(1024), dim3(256), 0, st, coef, cm, ce, D, K, n_sf);
   for (int it = 0; it < iters; ++it) {
     gss_profile_begin(ctx, 0, st);
-    hipLaunchKernelGGL((em_pass_small<D, K, false>), grid, dim3(kWave * kPassWaves), 0, st, Y, act, T_len, coef, cm, ce, part, npart,
-                       (float*)nullptr, F, Tmax, p.C, p.tiles_per_chunk);
+    hipLaunchKernelGGL((em_pass_small<D, K, false>), dim3((unsigned)p.wgs_acc), block, 0, st, Y, act, T_len, coef, cm, ce,
+                       part, npart, (float*)nullptr, F, Tmax, p.acc);
     gss_profile_end(ctx, 0, st);
     gss_profile_begin(ctx, 1, st);
     hipLaunchKernelGGL((em_factor_small<D, K>), dim3((unsigned)n_sf), dim3(kWave * K), 0, st, part, npart, coef, cm, ce,
-                       ctx->status, p.C, weight_mode);
+                       ctx->status, p.acc, weight_mode);
     gss_profile_end(ctx, 1, st);
   }
-  hipLaunchKernelGGL((em_pass_small<D, K, true>), grid, dim3(kWave * kPassWaves), 0, st, Y, act, T_len, coef, cm, ce,
-                     (double*)nullptr, (double*)nullptr, gamma, F, Tmax, p.C, p.tiles_per_chunk);
+  hipLaunchKernelGGL((em_pass_small<D, K, true>), dim3((unsigned)p.wgs_fin), block, 0, st, Y, act, T_len, coef, cm, ce,
+                     (double*)nullptr, (double*)nullptr, gamma, F, Tmax, p.fin);
   if (hipGetLastError() != hipSuccess) return GSS_EHIP;
   return GSS_OK;
 }
