@@ -360,8 +360,6 @@ __global__ __launch_bounds__(kWave * K) void em_factor_small(
   __shared__ double sR[K][E];
   __shared__ double sMr[K][D][D], sMi[K][D][D];
   __shared__ double sN[K];
-  __shared__ double sDetM[K];
-  __shared__ int sDetE[K];
 
   const long sf = blockIdx.x;
   const int k = threadIdx.x / kWave;
@@ -410,7 +408,7 @@ __global__ __launch_bounds__(kWave * K) void em_factor_small(
     sMr[k][i][j] = mr;
     sMi[k][i][j] = mi;
   }
-  __syncthreads();
+  wave_lds_sync();          // from here on every wavefront works on its own class matrix only
 
   double detm = 1.0;   // det B = detm * 2^dete, renormalised after every pivot
   int dete = 0;
@@ -423,7 +421,7 @@ __global__ __launch_bounds__(kWave * K) void em_factor_small(
     detm *= piv;
     dete += __builtin_amdgcn_frexp_exp(detm);
     detm = __builtin_amdgcn_frexp_mant(detm);
-    const double rp = 1.0 / piv;
+    const double rp = rcp_f64(piv);
     double nr = 0.0, ni = 0.0;
     if (on) {
       const double air = sMr[k][i][p], aii = sMi[k][i][p];
@@ -439,11 +437,10 @@ __global__ __launch_bounds__(kWave * K) void em_factor_small(
         ni = sMi[k][i][j] - (air * api + aii * apr) * rp;
       }
     }
-    __syncthreads();
+    wave_lds_sync();
     if (on) { sMr[k][i][j] = nr; sMi[k][i][j] = ni; }
-    __syncthreads();
+    wave_lds_sync();
   }
-  if (l == 0) { sDetM[k] = detm; sDetE[k] = dete; }
 
   // packed coefficients of q = sum_i A_ii P_ii + 2 sum_{i<j} (Re A_ij Re P_ij + Im A_ij Im P_ij), A = B^-1
   if (on && i <= j) {
@@ -456,7 +453,6 @@ __global__ __launch_bounds__(kWave * K) void em_factor_small(
       cf[p + 1] = 2.0 * sMi[k][i][j];
     }
   }
-  __syncthreads();
   if (l == 0) {
     double pi;
     if (weight_mode == 1) {
@@ -466,9 +462,9 @@ __global__ __launch_bounds__(kWave * K) void em_factor_small(
     } else {
       pi = 1.0 / (double)K;
     }
-    const double c = fmax(pi, GSS_EPS_PI) / sDetM[k];        // pi_k / det B_k = c * 2^-dete
+    const double c = fmax(pi, GSS_EPS_PI) / detm;            // pi_k / det B_k = c * 2^-dete
     cmant[sf * K + k] = __builtin_amdgcn_frexp_mant(c);
-    cexp[sf * K + k] = __builtin_amdgcn_frexp_exp(c) - sDetE[k];
+    cexp[sf * K + k] = __builtin_amdgcn_frexp_exp(c) - dete;
   }
 }
 
