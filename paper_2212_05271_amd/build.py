@@ -31,8 +31,27 @@ HIP_FLAGS = [
 ]
 
 
+# Sources that are compiled several times, once per value of a macro, so that their template
+# instantiations build in parallel.
+MULTI = {
+    "gss_em_inst.hip": [("GSS_INST_D", d) for d in range(1, 9)],
+    "gss_large_inst.hip": [("GSS_INST_K", k) for k in range(1, 9)],
+}
+
+
 def sources():
-    return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
+    """List of (source path, object name, extra flags)."""
+    jobs = []
+    for f in sorted(os.listdir(CSRC)):
+        if not f.endswith(".hip"):
+            continue
+        src = os.path.join(CSRC, f)
+        if f in MULTI:
+            for macro, val in MULTI[f]:
+                jobs.append((src, f"{f}.{macro}_{val}.o", [f"-D{macro}={val}"]))
+        else:
+            jobs.append((src, f + ".o", []))
+    return jobs
 
 
 def _hipcc():
@@ -42,9 +61,10 @@ def _hipcc():
     return "hipcc"
 
 
-def _compile(src, extra):
-    obj = os.path.join(BUILD, os.path.basename(src) + ".o")
-    cmd = [_hipcc(), *HIP_FLAGS, *extra, "-c", src, "-o", obj]
+def _compile(job, extra):
+    src, objname, flags = job
+    obj = os.path.join(BUILD, objname)
+    cmd = [_hipcc(), *HIP_FLAGS, *flags, *extra, "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")
@@ -56,6 +76,9 @@ def build(verbose=True, jobs=None, extra=()):
     os.makedirs(BUILD, exist_ok=True)
     srcs = sources()
     jobs = jobs or min(8, len(srcs))
+    for f in os.listdir(BUILD):
+        if f.endswith('.o'):
+            os.remove(os.path.join(BUILD, f))
     objs = []
     with cf.ThreadPoolExecutor(max_workers=jobs) as ex:
         for obj, warn in ex.map(lambda s: _compile(s, list(extra)), srcs):

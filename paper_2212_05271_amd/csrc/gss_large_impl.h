@@ -1,0 +1,695 @@
+// EM and MVDR kernels for large arrays, 9 <= D <= 32 channels (e.g. multi-array set-ups with 24
+// microphones).  Same algorithm, same fp64 arithmetic and the same pass / factor structure as the D <= 8
+// kernels (arXiv 2212.05271, Section 2.2 and 2.3); what changes is the mapping:
+//
+//   * D is a run-time value; the Hermitian outer product has M = D (D + 1) / 2 "items" (i <= j), each a
+//     real diagonal entry or a complex off-diagonal one.  All per-class data is laid out per item:
+//     coef[sf][m][k][2] (the two real coefficients that multiply Re and Im of item m), partial sums
+//     part[sf][chunk][m][k][2].
+//   * The frames of a tile sit in LDS as fp32 (exactly as they came), because D * 16 bytes of fp64 per
+//     frame would not leave room for two workgroups per compute unit.
+//   * Phase 1 (lane = frame) walks the items in a run-time loop, reading y_i, y_j of its own frame from
+//     LDS and the class coefficients through the scalar path.
+//   * Phase 2 (lane = a few items, frames in sequence): each lane owns NR items m = lane, lane + 64, ...,
+//     forms them for every frame of the tile from LDS and accumulates K weighted sums per real part.
+#pragma once
+
+#include "gss_internal.h"
+
+#include "gss_device.h"
+
+namespace {
+
+constexpr int kLargeWaves = 4;
+
+__host__ __device__ inline int item_index(int i, int j, int D) { return i * D - i * (i - 1) / 2 + (j - i); }   // i <= j
+__host__ __device__ inline int num_items(int D) { return D * (D + 1) / 2; }
+
+// (i, j) of item m, by walking the rows (run once per lane and item at kernel start).
+__device__ __forceinline__ void item_ij(int m, int D, int& i, int& j) {
+  int r = 0, left = m;
+  while (left >= D - r) { left -= D - r; ++r; }
+  i = r;
+  j = r + left;
+}
+
+__device__ __forceinline__ double ipow_rt(double x, int n) {   // x^n, n >= 1
+  double r = 1.0, b = x;
+  while (n) {
+    if (n & 1) r *= b;
+    b *= b;
+    n >>= 1;
+  }
+  return r;
+}
+
+__global__ void em_init_coef_large(double* __restrict__ coef, double* __restrict__ cmant, int32_t* __restrict__ cexp,
+                                   int D, int K, long n_sf) {
+  const int M = num_items(D);
+  const long per = (long)M * K * 2;
+  const long total = n_sf * per;
+  for (long x = blockIdx.x * (long)blockDim.x + threadIdx.x; x < total; x += (long)gridDim.x * blockDim.x) {
+    const long r = x % per;
+    const int m = (int)(r / (2 * K));
+    const int part = (int)(r & 1);
+    int i, j;
+    item_ij(m, D, i, j);
+    coef[x] = (i == j && part == 0) ? 1.0 : 0.0;
+  }
+  const long nl = n_sf * K;
+  for (long x = blockIdx.x * (long)blockDim.x + threadIdx.x; x < nl; x += (long)gridDim.x * blockDim.x) {
+    cmant[x] = 0.5;
+    cexp[x] = 1;
+  }
+}
+
+// Cooperative, coalesced copy of one tile of frames [t0, t0 + 64) of a (segment, frequency) row into the
+// wavefront's LDS tile sY[frame][D] (float2, row stride RS float2); frames at or beyond T become zero.
+__device__ __forceinline__ void load_tile(const float2* __restrict__ Yrow, int t0, int T, int D, int RS,
+                                          float2* __restrict__ sY, int lane) {
+  const int n = kWave * D;
+  for (int x = lane; x < n; x += kWave) {
+    const int r = x / D, c = x - r * D;
+    const int t = t0 + r;
+    sY[r * RS + c] = (t < T) ? Yrow[(long)t * D + c] : make_float2(0.f, 0.f);
+  }
+}
+
+// Phase 2 for the lane's NR items over the 64 frames of the tile.
+template <int KW, int NR>
+__device__ __forceinline__ void accumulate_items(const float2* __restrict__ sY, const double* __restrict__ sW, int RS,
+                                                 int WS, const int (&oi)[NR], const int (&oj)[NR],
+                                                 double (&acc)[NR][2][KW]) {
+#pragma unroll 2
+  for (int r = 0; r < kWave; ++r) {
+    double w[KW];
+#pragma unroll
+    for (int k = 0; k < KW; ++k) w[k] = sW[r * WS + k];
+#pragma unroll
+    for (int n = 0; n < NR; ++n) {
+      const float2 a = sY[r * RS + oi[n]];
+      const float2 b = sY[r * RS + oj[n]];
+      const double ar = a.x, ai = a.y, br = b.x, bi = b.y;
+      const double re = ar * br + ai * bi;          // Re(y_i conj(y_j)); |y_i|^2 on the diagonal
+      const double im = ai * br - ar * bi;          // Im(y_i conj(y_j)); 0 on the diagonal
+#pragma unroll
+      for (int k = 0; k < KW; ++k) {
+        acc[n][0][k] = fma(w[k], re, acc[n][0][k]);
+        acc[n][1][k] = fma(w[k], im, acc[n][1][k]);
+      }
+    }
+  }
+}
+
+// Sums the accumulators of the workgroup's wavefronts through LDS and writes out[m][k][2].
+template <int KW, int NR>
+__device__ __forceinline__ void reduce_items(double (&acc)[NR][2][KW], double* __restrict__ red, double* __restrict__ out,
+                                             int M, int lane, int wave) {
+  __syncthreads();
+  for (int w = 0; w < kLargeWaves; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int n = 0; n < NR; ++n) {
+        const int m = lane + kWave * n;
+        if (m < M) {
+#pragma unroll
+          for (int k = 0; k < KW; ++k)
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+              double* dst = &red[((long)m * KW + k) * 2 + p];
+              *dst = (w == 0) ? acc[n][p][k] : *dst + acc[n][p][k];
+            }
+        }
+      }
+    }
+    __syncthreads();
+  }
+  const int total = M * KW * 2;
+  for (int x = threadIdx.x; x < total; x += kWave * kLargeWaves) out[x] = red[x];
+}
+
+// ----------------------------------------------------------------------------------------------
+// EM pass, 9 <= D <= 32.  Grid: blockIdx.x = chunk + C * (f + F * s); the chunk's tiles are dealt to the
+// wavefronts round-robin.  Dynamic LDS: kLargeWaves * (64 * RS float2 + 64 * WS doubles), reused for the
+// final reduction (needs M * K * 2 doubles).
+// ----------------------------------------------------------------------------------------------
+template <int K, int NR, bool FINAL>
+__global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
+    const float2* __restrict__ Y, const uint8_t* __restrict__ act, const int32_t* __restrict__ T_len,
+    const double* __restrict__ coef, const double* __restrict__ cmant, const int32_t* __restrict__ cexp,
+    double* __restrict__ part, double* __restrict__ npart, float* __restrict__ gamma,
+    int F, int Tmax, int D, int C, int tiles_per_chunk, int RS, int tile_bytes) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  constexpr int WS = K | 1;
+  const int M = num_items(D);
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  const int chunk = blockIdx.x % C;
+  const long sf = blockIdx.x / C;
+  const int s = (int)(sf / F);
+  const int f = (int)(sf % F);
+  int T = T_len ? T_len[s] : Tmax;
+  T = T < 0 ? 0 : (T > Tmax ? Tmax : T);
+  const int t_end = FINAL ? Tmax : T;
+
+  float2* __restrict__ sY = reinterpret_cast<float2*>(lds_raw + (size_t)wave * tile_bytes);
+  double* __restrict__ sW = reinterpret_cast<double*>(lds_raw + (size_t)wave * tile_bytes + (size_t)kWave * RS * sizeof(float2));
+
+  const double* __restrict__ cf = coef + sf * (long)M * K * 2;
+  const double* __restrict__ cm = cmant + sf * K;
+  const int32_t* __restrict__ ce = cexp + sf * K;
+  const float2* __restrict__ Yrow = Y + sf * (long)Tmax * D;
+  const uint8_t* __restrict__ arow = act + (long)s * K * Tmax;
+
+  int oi[NR], oj[NR];
+  double acc[NR][2][K];
+#pragma unroll
+  for (int n = 0; n < NR; ++n) {
+    int m = lane + kWave * n;
+    if (m >= M) m = 0;                       // idle slot: computes item 0, never written out
+    item_ij(m, D, oi[n], oj[n]);
+#pragma unroll
+    for (int k = 0; k < K; ++k) { acc[n][0][k] = 0.0; acc[n][1][k] = 0.0; }
+  }
+  double nacc[K];
+#pragma unroll
+  for (int k = 0; k < K; ++k) nacc[k] = 0.0;
+
+  const int tile_lo = chunk * tiles_per_chunk;
+  int tile_hi = tile_lo + tiles_per_chunk;
+  const int tile_end = (t_end + kWave - 1) / kWave;
+  tile_hi = tile_hi < tile_end ? tile_hi : tile_end;
+  for (int tile = tile_lo + wave; tile < tile_hi; tile += kLargeWaves) {
+    const int t0 = tile * kWave;
+    const int t = t0 + lane;
+    const bool valid = t < T;
+    load_tile(Yrow, t0, T, D, RS, sY, lane);
+    unsigned abits = 0;
+#pragma unroll
+    for (int k = 0; k < K; ++k) abits |= (arow[(long)k * Tmax + (valid ? t : 0)] != 0 ? 1u : 0u) << k;
+    if (!valid) abits = 0;
+    wave_lds_sync();
+
+    // ---- phase 1: q_k = <coef_k, y y^H> for the lane's frame ----
+    double q[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) q[k] = 0.0;
+    double n2 = 0.0;
+    const float2* __restrict__ yrow = sY + lane * RS;
+    const double* __restrict__ c = cf;
+    for (int i = 0; i < D; ++i) {
+      const float2 a = yrow[i];
+      const double ar = a.x, ai = a.y;
+      const double pii = ar * ar + ai * ai;
+      n2 += pii;
+#pragma unroll
+      for (int k = 0; k < K; ++k) q[k] = fma(c[2 * k], pii, q[k]);
+      c += 2 * K;
+#pragma unroll 2
+      for (int j = i + 1; j < D; ++j) {
+        const float2 b = yrow[j];
+        const double br = b.x, bi = b.y;
+        const double re = ar * br + ai * bi;
+        const double im = ai * br - ar * bi;
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+          q[k] = fma(c[2 * k], re, q[k]);
+          q[k] = fma(c[2 * k + 1], im, q[k]);
+        }
+        c += 2 * K;
+      }
+    }
+    // posterior over the active classes: pi_k / det B_k * q_k^-D, mantissa / exponent form
+    const double n2c = fmax(n2, GSS_EPS_NORM_SQ);
+    const double qfloor = GSS_EPS_Q * n2c;
+    double rq[K], mant[K];
+    int ex[K];
+    int emax = -(1 << 28);
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      const bool a = (abits >> k) & 1u;
+      rq[k] = rcp_f64(fmax(q[k], qfloor));
+      const double u = rq[k] * n2c;
+      const double mu = __builtin_amdgcn_frexp_mant(u);
+      const int eu = __builtin_amdgcn_frexp_exp(u);
+      const double pw = ipow_rt(mu, D);            // >= 2^-32
+      mant[k] = cm[k] * __builtin_amdgcn_frexp_mant(pw);
+      ex[k] = a ? ce[k] + eu * D + __builtin_amdgcn_frexp_exp(pw) : -(1 << 28);
+      emax = ex[k] > emax ? ex[k] : emax;
+    }
+    double v[K], Z = 0.0;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      int de = ex[k] - emax;
+      de = de < -1100 ? -1100 : de;
+      v[k] = ((abits >> k) & 1u) ? ldexp(mant[k], de) : 0.0;
+      Z += v[k];
+    }
+    const double rz = Z > 0.0 ? rcp_f64(Z) : 0.0;
+    if (FINAL) {
+      if (t < Tmax) {
+#pragma unroll
+        for (int k = 0; k < K; ++k) gamma[(((long)s * K + k) * F + f) * Tmax + t] = (float)(v[k] * rz);
+      }
+      wave_lds_sync();                       // the tile is overwritten by the next iteration
+      continue;
+    }
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      const double g = v[k] * rz;
+      nacc[k] += g;
+      sW[lane * WS + k] = g * rq[k];
+    }
+    wave_lds_sync();
+    // ---- phase 2 ----
+    accumulate_items<K, NR>(sY, sW, RS, WS, oi, oj, acc);
+    wave_lds_sync();
+  }
+  if (FINAL) return;
+
+  double* __restrict__ red = reinterpret_cast<double*>(lds_raw);
+  reduce_items<K, NR>(acc, red, part + (sf * C + chunk) * (long)M * K * 2, M, lane, wave);
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    double nv = nacc[k];
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) nv += __shfl_xor(nv, off, kWave);
+    nacc[k] = nv;
+  }
+  __syncthreads();
+  if (lane == 0) {
+#pragma unroll
+    for (int k = 0; k < K; ++k) red[wave * K + k] = nacc[k];
+  }
+  __syncthreads();
+  if (threadIdx.x < K) {
+    double sum = 0.0;
+    for (int w = 0; w < kLargeWaves; ++w) sum += red[w * K + threadIdx.x];
+    npart[(sf * C + chunk) * K + threadIdx.x] = sum;
+  }
+}
+
+// In-place Gauss-Jordan inversion of the D x D Hermitian positive-definite matrix in (sMr, sMi), thread
+// (i, j) = (tid / D, tid % D), all threads of the workgroup call it.  Returns det as mant * 2^exp.
+__device__ __forceinline__ void gauss_jordan_large(double (*sMr)[33], double (*sMi)[33], int D, int i, int j, bool on,
+                                                   uint32_t* status, uint32_t flag, double& detm, int& dete) {
+  detm = 1.0;
+  dete = 0;
+  for (int p = 0; p < D; ++p) {
+    double piv = sMr[p][p];
+    if (!(piv > 1e-300)) {
+      piv = 1e-300;
+      if (threadIdx.x == 0) atomicOr(status, flag);
+    }
+    detm *= piv;
+    dete += __builtin_amdgcn_frexp_exp(detm);
+    detm = __builtin_amdgcn_frexp_mant(detm);
+    const double rp = 1.0 / piv;
+    double nr = 0.0, ni = 0.0;
+    if (on) {
+      const double air = sMr[i][p], aii = sMi[i][p];
+      const double apr = sMr[p][j], api = sMi[p][j];
+      if (i == p && j == p) {
+        nr = rp;
+      } else if (i == p) {
+        nr = apr * rp; ni = api * rp;
+      } else if (j == p) {
+        nr = -air * rp; ni = -aii * rp;
+      } else {
+        nr = sMr[i][j] - (air * apr - aii * api) * rp;
+        ni = sMi[i][j] - (air * api + aii * apr) * rp;
+      }
+    }
+    __syncthreads();
+    if (on) { sMr[i][j] = nr; sMi[i][j] = ni; }
+    __syncthreads();
+  }
+}
+
+// ----------------------------------------------------------------------------------------------
+// Factor kernel, 9 <= D <= 32: one workgroup per (segment, frequency, class), D*D active threads.
+// ----------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void em_factor_large(
+    const double* __restrict__ part, const double* __restrict__ npart,
+    double* __restrict__ coef, double* __restrict__ cmant, int32_t* __restrict__ cexp, uint32_t* __restrict__ status,
+    int D, int K, int C, int weight_mode) {
+  __shared__ double sMr[32][33], sMi[32][33];
+  __shared__ double sN[GSS_MAX_K];
+  const int M = num_items(D);
+  const long sf = blockIdx.x / K;
+  const int k = blockIdx.x % K;
+  const int tid = threadIdx.x;
+  const int i = tid / D, j = tid % D;
+  const bool on = tid < D * D;
+
+  if (tid < K) {
+    double n = 0.0;
+    for (int c = 0; c < C; ++c) n += npart[(sf * C + c) * K + tid];
+    sN[tid] = n;
+  }
+  if (on && i <= j) {
+    const int m = item_index(i, j, D);
+    double re = 0.0, im = 0.0;
+    for (int c = 0; c < C; ++c) {
+      const double* p = part + (((sf * C + c) * (long)M + m) * K + k) * 2;
+      re += p[0];
+      im += p[1];
+    }
+    sMr[i][j] = re; sMi[i][j] = im;
+    if (i != j) { sMr[j][i] = re; sMi[j][i] = -im; }
+  }
+  __syncthreads();
+  double tr = 0.0;
+  for (int r = 0; r < D; ++r) tr += sMr[r][r];
+  const double Nk = sN[k];
+  const double trB = (double)D * tr / fmax(Nk, GSS_EPS_N);
+  const bool dead = !(trB > GSS_EPS_N);
+  __syncthreads();
+  if (on) {
+    double mr, mi;
+    if (dead) {
+      mr = (i == j) ? 1.0 : 0.0;
+      mi = 0.0;
+    } else {
+      const double sc = (double)D / tr;
+      mr = sMr[i][j] * sc;
+      mi = (i == j) ? 0.0 : sMi[i][j] * sc;
+    }
+    if (i == j) mr += GSS_DELTA;
+    sMr[i][j] = mr; sMi[i][j] = mi;
+  }
+  __syncthreads();
+  double detm;
+  int dete;
+  gauss_jordan_large(sMr, sMi, D, i, j, on, status, GSS_STATUS_NONPD_B, detm, dete);
+  if (on && i <= j) {
+    const int m = item_index(i, j, D);
+    double* c = coef + ((sf * (long)M + m) * K + k) * 2;
+    if (i == j) { c[0] = sMr[i][i]; c[1] = 0.0; }
+    else { c[0] = 2.0 * sMr[i][j]; c[1] = 2.0 * sMi[i][j]; }
+  }
+  if (tid == 0) {
+    double pi;
+    if (weight_mode == 1) {
+      double tot = 0.0;
+      for (int kk = 0; kk < K; ++kk) tot += sN[kk];
+      pi = Nk / fmax(tot, GSS_EPS_N);
+    } else {
+      pi = 1.0 / (double)K;
+    }
+    const double cst = fmax(pi, GSS_EPS_PI) / detm;
+    cmant[sf * K + k] = __builtin_amdgcn_frexp_mant(cst);
+    cexp[sf * K + k] = __builtin_amdgcn_frexp_exp(cst) - dete;
+  }
+}
+
+// ----------------------------------------------------------------------------------------------
+// MVDR, 9 <= D <= 32
+// ----------------------------------------------------------------------------------------------
+template <int NR>
+__global__ __launch_bounds__(kWave * kLargeWaves) void mvdr_cov_large(
+    const float2* __restrict__ Y, const float* __restrict__ gamma, const int32_t* __restrict__ T_len,
+    const int32_t* __restrict__ target, double* __restrict__ part, uint32_t* __restrict__ status,
+    int F, int Tmax, int D, int K, int C, int tiles_per_chunk, int RS, int tile_bytes) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  constexpr int WS = 3;
+  const int M = num_items(D);
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  const int chunk = blockIdx.x % C;
+  const long sf = blockIdx.x / C;
+  const int s = (int)(sf / F);
+  const int f = (int)(sf % F);
+  int T = T_len ? T_len[s] : Tmax;
+  T = T < 0 ? 0 : (T > Tmax ? Tmax : T);
+  int tgt = target[s];
+  if (tgt < 0 || tgt >= K) {
+    if (threadIdx.x == 0 && chunk == 0 && f == 0) atomicOr(status, GSS_STATUS_BAD_TARGET);
+    tgt = tgt < 0 ? 0 : K - 1;
+  }
+  float2* __restrict__ sY = reinterpret_cast<float2*>(lds_raw + (size_t)wave * tile_bytes);
+  double* __restrict__ sW = reinterpret_cast<double*>(lds_raw + (size_t)wave * tile_bytes + (size_t)kWave * RS * sizeof(float2));
+  const float2* __restrict__ Yrow = Y + sf * (long)Tmax * D;
+  const float* __restrict__ grow = gamma + ((long)s * K * F + f) * Tmax;
+  const long gk = (long)F * Tmax;
+
+  int oi[NR], oj[NR];
+  double acc[NR][2][2];
+#pragma unroll
+  for (int n = 0; n < NR; ++n) {
+    int m = lane + kWave * n;
+    if (m >= M) m = 0;
+    item_ij(m, D, oi[n], oj[n]);
+    acc[n][0][0] = acc[n][0][1] = acc[n][1][0] = acc[n][1][1] = 0.0;
+  }
+  const int tile_lo = chunk * tiles_per_chunk;
+  int tile_hi = tile_lo + tiles_per_chunk;
+  const int tile_end = (T + kWave - 1) / kWave;
+  tile_hi = tile_hi < tile_end ? tile_hi : tile_end;
+  for (int tile = tile_lo + wave; tile < tile_hi; tile += kLargeWaves) {
+    const int t0 = tile * kWave;
+    const int t = t0 + lane;
+    const bool valid = t < T;
+    load_tile(Yrow, t0, T, D, RS, sY, lane);
+    double wt = 0.0, wb = 0.0;
+    for (int k = 0; k < K; ++k) {
+      const double g = (double)grow[k * gk + (valid ? t : 0)];
+      if (k == tgt) wt = g; else wb += g;
+    }
+    sW[lane * WS + 0] = valid ? wt : 0.0;
+    sW[lane * WS + 1] = valid ? wb : 0.0;
+    wave_lds_sync();
+    accumulate_items<2, NR>(sY, sW, RS, WS, oi, oj, acc);
+    wave_lds_sync();
+  }
+  double* __restrict__ red = reinterpret_cast<double*>(lds_raw);
+  reduce_items<2, NR>(acc, red, part + (sf * C + chunk) * (long)M * 4, M, lane, wave);
+}
+
+// One workgroup per (segment, frequency), D*D active threads.  H[sf][r][d], pw[sf][r][2] as for D <= 8.
+__global__ __launch_bounds__(1024) void mvdr_solve_large(
+    const double* __restrict__ part, double2* __restrict__ H, double* __restrict__ pw,
+    uint32_t* __restrict__ status, int D, int C) {
+  __shared__ double sKr[32][33], sKi[32][33], sBr[32][33], sBi[32][33], sMr[32][33], sMi[32][33];
+  double (*sGr)[33] = sMr;   // G and then H overwrite the inverse once it has been consumed
+  double (*sGi)[33] = sMi;
+  const int M = num_items(D);
+  const long sf = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int i = tid / D, j = tid % D;
+  const bool on = tid < D * D;
+  if (on && i <= j) {
+    const int m = item_index(i, j, D);
+    double kr = 0.0, ki = 0.0, br = 0.0, bi = 0.0;
+    for (int c = 0; c < C; ++c) {
+      const double* p = part + ((sf * C + c) * (long)M + m) * 4;     // [k = 0 target, 1 background][re, im]
+      kr += p[0]; ki += p[1]; br += p[2]; bi += p[3];
+    }
+    if (i == j) { ki = 0.0; bi = 0.0; }
+    sKr[i][j] = kr; sKi[i][j] = ki; sBr[i][j] = br; sBi[i][j] = bi;
+    if (i != j) { sKr[j][i] = kr; sKi[j][i] = -ki; sBr[j][i] = br; sBi[j][i] = -bi; }
+  }
+  __syncthreads();
+  double trb = 0.0, trk = 0.0;
+  for (int r = 0; r < D; ++r) { trb += sBr[r][r]; trk += sKr[r][r]; }
+  if (!(trb > 0.0)) {
+    if (trk > 0.0 && tid == 0) atomicOr(status, GSS_STATUS_NONPD_PHI);
+    if (on) H[(sf * D + j) * D + i] = make_double2(0.0, 0.0);
+    if (tid < D) { pw[(sf * D + tid) * 2 + 0] = 0.0; pw[(sf * D + tid) * 2 + 1] = 0.0; }
+    return;
+  }
+  __syncthreads();
+  if (on) {
+    if (i == j) sBr[i][i] += GSS_DELTA_BF * trb / (double)D;
+  }
+  __syncthreads();
+  if (on) { sMr[i][j] = sBr[i][j]; sMi[i][j] = sBi[i][j]; }
+  __syncthreads();
+  double detm;
+  int dete;
+  gauss_jordan_large(sMr, sMi, D, i, j, on, status, GSS_STATUS_NONPD_PHI, detm, dete);
+  double gr = 0.0, gi = 0.0;
+  if (on) {
+    for (int m = 0; m < D; ++m) {
+      const double ar = sMr[i][m], ai = sMi[i][m], br = sKr[m][j], bi = sKi[m][j];
+      gr += ar * br - ai * bi;
+      gi += ar * bi + ai * br;
+    }
+  }
+  __syncthreads();
+  if (on) { sGr[i][j] = gr; sGi[i][j] = gi; }
+  __syncthreads();
+  double tr = 0.0;
+  for (int r = 0; r < D; ++r) tr += sGr[r][r];
+  const double inv = 1.0 / (tr + GSS_EPS_TRACE);
+  __syncthreads();
+  if (on) {
+    const double hr = sGr[i][j] * inv, hi = sGi[i][j] * inv;
+    H[(sf * D + j) * D + i] = make_double2(hr, hi);
+    sGr[i][j] = hr; sGi[i][j] = hi;
+  }
+  __syncthreads();
+  if (tid < D) {
+    const int r = tid;
+    double pk = 0.0, pb = 0.0;
+    for (int a = 0; a < D; ++a) {
+      double tkr = 0.0, tki = 0.0, tbr = 0.0, tbi = 0.0;
+      for (int b = 0; b < D; ++b) {
+        const double hr = sGr[b][r], hi = sGi[b][r];
+        tkr += sKr[a][b] * hr - sKi[a][b] * hi;  tki += sKr[a][b] * hi + sKi[a][b] * hr;
+        tbr += sBr[a][b] * hr - sBi[a][b] * hi;  tbi += sBr[a][b] * hi + sBi[a][b] * hr;
+      }
+      const double hr = sGr[a][r], hi = sGi[a][r];
+      pk += hr * tkr + hi * tki;
+      pb += hr * tbr + hi * tbi;
+    }
+    pw[(sf * D + r) * 2 + 0] = pk;
+    pw[(sf * D + r) * 2 + 1] = pb;
+  }
+}
+
+__global__ __launch_bounds__(256) void mvdr_apply_large(
+    const float2* __restrict__ Y, const double2* __restrict__ H, const int32_t* __restrict__ ref,
+    const int32_t* __restrict__ T_len, float2* __restrict__ X, int F, int Tmax, int D, int C, int frames_per_chunk) {
+  __shared__ double2 sh[GSS_MAX_D];
+  const int chunk = blockIdx.x % C;
+  const long sf = blockIdx.x / C;
+  const int s = (int)(sf / F);
+  int T = T_len ? T_len[s] : Tmax;
+  T = T < 0 ? 0 : (T > Tmax ? Tmax : T);
+  int r = ref[s];
+  r = r < 0 ? 0 : (r >= D ? D - 1 : r);
+  if (threadIdx.x < D) sh[threadIdx.x] = H[(sf * D + r) * D + threadIdx.x];
+  __syncthreads();
+  const float2* __restrict__ Yrow = Y + sf * (long)Tmax * D;
+  float2* __restrict__ Xrow = X + sf * (long)Tmax;
+  const int t_lo = chunk * frames_per_chunk;
+  int t_hi = t_lo + frames_per_chunk;
+  t_hi = t_hi < Tmax ? t_hi : Tmax;
+  for (int t = t_lo + threadIdx.x; t < t_hi; t += blockDim.x) {
+    double xr = 0.0, xi = 0.0;
+    if (t < T) {
+      for (int d = 0; d < D; ++d) {
+        const float2 v = Yrow[(long)t * D + d];
+        const double2 h = sh[d];
+        xr += h.x * (double)v.x + h.y * (double)v.y;
+        xi += h.x * (double)v.y - h.y * (double)v.x;
+      }
+    }
+    Xrow[t] = make_float2((float)xr, (float)xi);
+  }
+}
+
+struct LargePlan {
+  int C, tpc, RS, tile_bytes, lds_bytes;
+};
+
+LargePlan plan_large(const gss_ctx* ctx, long n_sf, int Tmax, int D, int KW) {
+  LargePlan p;
+  const int tiles = (Tmax + kWave - 1) / kWave;
+  long c_target = ((long)ctx->num_cu * 2 + n_sf - 1) / n_sf;
+  if (c_target < 1) c_target = 1;
+  int tpc = (int)((tiles + c_target - 1) / c_target);
+  tpc = (tpc + kLargeWaves - 1) / kLargeWaves * kLargeWaves;
+  p.tpc = tpc;
+  p.C = (tiles + tpc - 1) / tpc;
+  p.RS = D + 1;                                            // float2 per frame row (odd: spreads the banks)
+  const int ws = KW | 1;
+  p.tile_bytes = (int)gss_align_up((size_t)kWave * p.RS * sizeof(float2) + (size_t)kWave * ws * sizeof(double), 16);
+  const int red = num_items(D) * KW * 2 * (int)sizeof(double) + kLargeWaves * KW * (int)sizeof(double);
+  const int tiles_b = kLargeWaves * p.tile_bytes;
+  p.lds_bytes = tiles_b > red ? tiles_b : red;
+  return p;
+}
+
+template <int K, int NR>
+int run_em_large(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_t* T_len, int S, int F, int Tmax,
+                 int D, int iters, int weight_mode, float* gamma, hipStream_t st) {
+  const long n_sf = (long)S * F;
+  const int M = num_items(D);
+  const LargePlan p = plan_large(ctx, n_sf, Tmax, D, K);
+  if (n_sf * p.C > 0x7fffffffL || n_sf * K > 0x7fffffffL) return GSS_EUNSUPPORTED;
+  size_t o = 0;
+  const size_t off_coef = o;  o = gss_align_up(o + (size_t)n_sf * M * K * 2 * sizeof(double), 256);
+  const size_t off_cm = o;    o = gss_align_up(o + (size_t)n_sf * K * sizeof(double), 256);
+  const size_t off_ce = o;    o = gss_align_up(o + (size_t)n_sf * K * sizeof(int32_t), 256);
+  const size_t off_part = o;  o = gss_align_up(o + (size_t)n_sf * p.C * M * K * 2 * sizeof(double), 256);
+  const size_t off_npart = o; o = gss_align_up(o + (size_t)n_sf * p.C * K * sizeof(double), 256);
+  int rc = gss_ensure_scratch(ctx, o);
+  if (rc != GSS_OK) return rc;
+  char* base = (char*)ctx->scratch;
+  double* coef = (double*)(base + off_coef);
+  double* cm = (double*)(base + off_cm);
+  int32_t* ce = (int32_t*)(base + off_ce);
+  double* part = (double*)(base + off_part);
+  double* npart = (double*)(base + off_npart);
+  if (hipFuncSetAttribute((const void*)em_pass_large<K, NR, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                          p.lds_bytes) != hipSuccess ||
+      hipFuncSetAttribute((const void*)em_pass_large<K, NR, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                          p.lds_bytes) != hipSuccess)
+    return GSS_EHIP;
+  const dim3 grid((unsigned)(n_sf * p.C));
+  const dim3 block(kWave * kLargeWaves);
+  const int fthreads = (D * D + 63) / 64 * 64;
+  hipLaunchKernelGGL(em_init_coef_large, dim3(1024), dim3(256), 0, st, coef, cm, ce, D, K, n_sf);
+  for (int it = 0; it < iters; ++it) {
+    gss_profile_begin(ctx, 0, st);
+    hipLaunchKernelGGL((em_pass_large<K, NR, false>), grid, block, p.lds_bytes, st, Y, act, T_len, coef, cm, ce, part,
+                       npart, (float*)nullptr, F, Tmax, D, p.C, p.tpc, p.RS, p.tile_bytes);
+    gss_profile_end(ctx, 0, st);
+    gss_profile_begin(ctx, 1, st);
+    hipLaunchKernelGGL(em_factor_large, dim3((unsigned)(n_sf * K)), dim3(fthreads), 0, st, part, npart, coef, cm, ce,
+                       ctx->status, D, K, p.C, weight_mode);
+    gss_profile_end(ctx, 1, st);
+  }
+  hipLaunchKernelGGL((em_pass_large<K, NR, true>), grid, block, p.lds_bytes, st, Y, act, T_len, coef, cm, ce,
+                     (double*)nullptr, (double*)nullptr, gamma, F, Tmax, D, p.C, p.tpc, p.RS, p.tile_bytes);
+  if (hipGetLastError() != hipSuccess) return GSS_EHIP;
+  return GSS_OK;
+}
+
+template <int K>
+int dispatch_nr(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_t* T_len, int S, int F, int Tmax,
+                int D, int iters, int weight_mode, float* gamma, hipStream_t st) {
+  const int nr = (num_items(D) + kWave - 1) / kWave;       // 1 .. 9
+  if (nr <= 3) return run_em_large<K, 3>(ctx, Y, act, T_len, S, F, Tmax, D, iters, weight_mode, gamma, st);
+  if (nr <= 5) return run_em_large<K, 5>(ctx, Y, act, T_len, S, F, Tmax, D, iters, weight_mode, gamma, st);
+  if (nr <= 7) return run_em_large<K, 7>(ctx, Y, act, T_len, S, F, Tmax, D, iters, weight_mode, gamma, st);
+  return run_em_large<K, 9>(ctx, Y, act, T_len, S, F, Tmax, D, iters, weight_mode, gamma, st);
+}
+
+template <int NR>
+int run_mvdr_large(gss_ctx* ctx, const float2* Y, const float* gamma, const int32_t* T_len, int S, int F, int Tmax,
+                   int D, int K, const int32_t* target, int32_t* ref, float2* X, hipStream_t st) {
+  const long n_sf = (long)S * F;
+  const int M = num_items(D);
+  const LargePlan p = plan_large(ctx, n_sf, Tmax, D, 2);
+  if (n_sf * p.C > 0x7fffffffL) return GSS_EUNSUPPORTED;
+  size_t o = 0;
+  const size_t off_part = o; o = gss_align_up(o + (size_t)n_sf * p.C * M * 4 * sizeof(double), 256);
+  const size_t off_H = o;    o = gss_align_up(o + (size_t)n_sf * D * D * sizeof(double2), 256);
+  const size_t off_pw = o;   o = gss_align_up(o + (size_t)n_sf * D * 2 * sizeof(double), 256);
+  int rc = gss_ensure_scratch(ctx, o);
+  if (rc != GSS_OK) return rc;
+  char* base = (char*)ctx->scratch;
+  double* part = (double*)(base + off_part);
+  double2* H = (double2*)(base + off_H);
+  double* pw = (double*)(base + off_pw);
+  if (hipFuncSetAttribute((const void*)mvdr_cov_large<NR>, hipFuncAttributeMaxDynamicSharedMemorySize, p.lds_bytes) !=
+      hipSuccess)
+    return GSS_EHIP;
+  hipLaunchKernelGGL((mvdr_cov_large<NR>), dim3((unsigned)(n_sf * p.C)), dim3(kWave * kLargeWaves), p.lds_bytes, st, Y,
+                     gamma, T_len, target, part, ctx->status, F, Tmax, D, K, p.C, p.tpc, p.RS, p.tile_bytes);
+  const int sthreads = (D * D + 63) / 64 * 64;
+  hipLaunchKernelGGL(mvdr_solve_large, dim3((unsigned)n_sf), dim3(sthreads), 0, st, part, H, pw, ctx->status, D, p.C);
+  gss_launch_mvdr_ref(pw, ref, S, F, D, st);
+  const int fpc = 1024;
+  const int CA = (Tmax + fpc - 1) / fpc;
+  if (n_sf * CA > 0x7fffffffL) return GSS_EUNSUPPORTED;
+  hipLaunchKernelGGL(mvdr_apply_large, dim3((unsigned)(n_sf * CA)), dim3(256), 0, st, Y, H, ref, T_len, X, F, Tmax, D,
+                     CA, fpc);
+  if (hipGetLastError() != hipSuccess) return GSS_EHIP;
+  return GSS_OK;
+}
+
+}  // namespace
