@@ -33,7 +33,7 @@ FS, HOP = 16000, 256
 PEAK_TFLOPS_F64 = 78.6
 # HBM bytes per launch of the accumulating EM pass on this workload, from rocprofv3 --pmc runs
 # (FETCH_SIZE + WRITE_SIZE in KiB, each scaled by the copy-kernel calibration).
-EM_PASS_TRAFFIC_BYTES = (53320 + 1315) * 1024   # profiles/em_config1_hbm_traffic.md
+EM_PASS_TRAFFIC_BYTES = (53379 + 1322) * 1024   # profiles/em_config1_hbm_traffic.md
 
 
 def em_pass_flops(F, T, D, K):
@@ -74,6 +74,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--cpu-bins-step", type=int, default=2, help="oracle baseline runs every n-th bin (0 = skip)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run three 256 MiB device-to-device copies (the known-size kernel that the "
+                         "FETCH_SIZE / WRITE_SIZE counters are scaled by) and exit")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (independent segments need no communication; "
@@ -89,6 +92,14 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     dev = torch.device("cuda:0")
+    if a.copy_calibration:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read": 256 << 20, "bytes_written": 256 << 20, "copies": 3}}))
+        return
     ctx = gss.Context(0)
 
     seg = synth.config1()
