@@ -104,6 +104,27 @@ __host__ __device__ inline long chunk_base(const ChunkMap& m, long sf, int& coun
   return (long)m.n_main * m.c_main + (sf - m.n_main) * m.c_tail;
 }
 
+// Entries of the packed outer product per group of scalar coefficient loads (2 or 4 doubles per class
+// and load); two groups are in SGPRs at a time, 2 * K * G * 2 registers of the 100 or so there are.
+__host__ __device__ constexpr int coef_group(int K) { return K <= 5 ? 4 : 2; }
+
+// Scalar load of G doubles from base + BYTES into SGPRs.  Issued as an asm statement: the value is valid only
+// after a later "s_waitcnt lgkmcnt(0)" that names the same registers.
+template <int G, int BYTES, typename R>
+__device__ __forceinline__ void coef_load(R& r, const double* base) {
+  static_assert(G == 2 || G == 4, "group size");
+  if constexpr (G == 2) asm volatile("s_load_dwordx4 %0, %1, %2" : "=&s"(r) : "s"(base), "n"(BYTES));
+  else asm volatile("s_load_dwordx8 %0, %1, %2" : "=&s"(r) : "s"(base), "n"(BYTES));
+}
+
+// The same, issued before any use of `cur` (the group that has just arrived), so that the whole arithmetic
+// of one group lies between the issue of the next group's loads and the wait for them.
+template <int G, int BYTES, typename R>
+__device__ __forceinline__ void coef_load_after(R& r, const double* base, R& cur) {
+  if constexpr (G == 2) asm volatile("s_load_dwordx4 %0, %2, %3" : "=&s"(r), "+s"(cur) : "s"(base), "n"(BYTES));
+  else asm volatile("s_load_dwordx8 %0, %2, %3" : "=&s"(r), "+s"(cur) : "s"(base), "n"(BYTES));
+}
+
 // Frames per lane in phase 1.  Every class coefficient that comes through the scalar path is applied to
 // kNF frames; the scalar data path returns about one dword per clock per pair of compute units, so
 // at kNF = 1 it is as busy as the vector ALUs.
@@ -122,6 +143,8 @@ __device__ __forceinline__ void pass_unit(
   const int tg = lane >> 3, eg = lane & 7;
 
   // ---- phase 1: load y ----
+  // A lane whose frame lies beyond T reads frame 0 instead (it exists whenever a tile is processed at all, or is
+  // padding in the final pass); its activity bits are forced to zero, so its posterior and weights are zero.
   int t[NF];
   bool valid[NF];
   double yr[NF][D], yi[NF][D];
@@ -131,9 +154,9 @@ __device__ __forceinline__ void pass_unit(
     valid[f] = t[f] < T;
 #pragma unroll
     for (int d = 0; d < D; ++d) {
-      const float2 v = Yrow[(long)(valid[f] ? t[f] : 0) * D + d];   // frame 0 always exists; masked below
-      yr[f][d] = valid[f] ? (double)v.x : 0.0;
-      yi[f][d] = valid[f] ? (double)v.y : 0.0;
+      const float2 v = Yrow[(long)(valid[f] ? t[f] : 0) * D + d];
+      yr[f][d] = (double)v.x;
+      yi[f][d] = (double)v.y;
     }
   }
   // activity bits of the lane's frames, fetched here so that the loads overlap the q loop
@@ -148,11 +171,13 @@ __device__ __forceinline__ void pass_unit(
   }
 
   // ---- q_k = <coef_k, y y^H> ----
-  // The coefficients are wave-uniform and loop-invariant and come through the scalar path, one group of
-  // G packed entries (K*G doubles) at a time.  Left alone, the compiler hoists all K*E scalar loads out
-  // of the loop and spills them into vector-register lanes; the empty asm statements make each group's
-  // offset depend on the previous group's first product and route every partial sum through a fence,
-  // which keeps one group's loads next to its use.
+  // The coefficients are wave-uniform and come through the scalar path straight into the FMAs as SGPR
+  // operands, one group of G packed entries (K loads of G doubles) at a time, double-buffered by hand: the
+  // loads of group g + 1 are issued before the arithmetic of group g, and waited for (all outstanding
+  // scalar loads: they may return out of order) at the top of group g + 1.  The loads and the wait are asm
+  // statements (and every partial sum passes through an empty one at the end of its group) because the
+  // compiler, left alone, either hoists all K*E loads out of the tile loop and
+  // spills them, or puts every load directly in front of its first use.
   double q[NF][K];
   double n2[NF];
 #pragma unroll
@@ -161,14 +186,23 @@ __device__ __forceinline__ void pass_unit(
 #pragma unroll
     for (int k = 0; k < K; ++k) q[f][k] = 0.0;
   }
-  constexpr int G = 4;
+  constexpr int G = coef_group(K);
   constexpr int NG = (E + G - 1) / G;
-  const const_ptr_t cf4 = (const_ptr_t)(uintptr_t)cf;
-  int goff = 0;
-  asm volatile("" : "+s"(goff));            // opaque (uniform) offset: keeps the loads inside this unit
+  typedef double creg __attribute__((ext_vector_type(G)));
+  creg cbuf[2][K];
+  static_for<0, K>([&](auto KI) { coef_load<G, KI.value * E * 8>(cbuf[0][KI.value], cf); });
   static_for<0, NG>([&](auto GI) {
-    constexpr int g = GI.value * G;
+    constexpr int gi = GI.value;
+    constexpr int g = gi * G;
     constexpr int ng = (E - g) < G ? (E - g) : G;
+    constexpr int cb = gi & 1;
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(cbuf[cb][0]));
+#pragma unroll
+    for (int k = 1; k < K; ++k) asm volatile("" : "+s"(cbuf[cb][k]));
+    if constexpr (gi + 1 < NG)
+      static_for<0, K>([&](auto KI) {
+        coef_load_after<G, (KI.value * E + g + G) * 8>(cbuf[(gi + 1) & 1][KI.value], cf, cbuf[cb][KI.value]);
+      });
     double Pg[NF][ng];
 #pragma unroll
     for (int f = 0; f < NF; ++f) {
@@ -178,25 +212,19 @@ __device__ __forceinline__ void pass_unit(
         if constexpr (packed_part(g + e, D) == 0) n2[f] += Pg[f][e];
       });
     }
-    const const_ptr_t cg = cf4 + goff;
-    q[0][0] = fma(cg[0], Pg[0][0], q[0][0]);      // first use of this group: waits for its loads
-    int noff = g + G;
-    asm volatile("" : "+s"(noff), "+v"(q[0][0]));   // the next group's offset exists only from here on
+    static_for<0, K>([&](auto KI) {
+      constexpr int k = KI.value;
+      static_for<0, ng>([&](auto EI) {
+        constexpr int e = EI.value;
+#pragma unroll
+        for (int f = 0; f < NF; ++f) q[f][k] = fma(cbuf[cb][k][e], Pg[f][e], q[f][k]);
+      });
+    });
+    // the group's arithmetic stays between its own wait and the next one
 #pragma unroll
     for (int f = 0; f < NF; ++f)
 #pragma unroll
-      for (int k = 0; k < K; ++k)
-        if (f != 0 || k != 0) asm volatile("" : "+v"(q[f][k]));
-#pragma unroll
-    for (int k = 0; k < K; ++k) {
-#pragma unroll
-      for (int e = 0; e < ng; ++e) {
-#pragma unroll
-        for (int f = 0; f < NF; ++f)
-          if (!(k == 0 && e == 0 && f == 0)) q[f][k] = fma(cg[k * E + e], Pg[f][e], q[f][k]);
-      }
-    }
-    goff = noff;
+      for (int k = 0; k < K; ++k) asm volatile("" : "+v"(q[f][k]));
   });
 
 #pragma unroll
@@ -531,7 +559,7 @@ EmPlan make_plan(const gss_ctx* ctx, long n_sf, int Tmax, int D, int K, int wgs_
   p.wgs_fin = map_wgs(p.fin, n_sf);
   const size_t E = (size_t)D * D;
   size_t o = 0;
-  p.off_coef = o;  o = gss_align_up(o + (size_t)n_sf * K * E * sizeof(double), 256);
+  p.off_coef = o;  o = gss_align_up(o + (size_t)n_sf * K * E * sizeof(double) + 64, 256);   // + a group's over-read
   p.off_cm = o;    o = gss_align_up(o + (size_t)n_sf * K * sizeof(double), 256);
   p.off_ce = o;    o = gss_align_up(o + (size_t)n_sf * K * sizeof(int32_t), 256);
   p.off_part = o;  o = gss_align_up(o + (size_t)p.wgs_acc * K * E * sizeof(double), 256);
