@@ -104,26 +104,9 @@ __host__ __device__ inline long chunk_base(const ChunkMap& m, long sf, int& coun
   return (long)m.n_main * m.c_main + (sf - m.n_main) * m.c_tail;
 }
 
-// Entries of the packed outer product per group of scalar coefficient loads (2 or 4 doubles per class
-// and load); two groups are in SGPRs at a time, 2 * K * G * 2 registers of the 100 or so there are.
+// Entries of the packed outer product per group of scalar coefficient loads (2 or 4 doubles per class);
+// two groups are in SGPRs at a time, 2 * K * G * 2 registers of the 100 or so there are.
 __host__ __device__ constexpr int coef_group(int K) { return K <= 5 ? 4 : 2; }
-
-// Scalar load of G doubles from base + BYTES into SGPRs.  Issued as an asm statement: the value is valid only
-// after a later "s_waitcnt lgkmcnt(0)" that names the same registers.
-template <int G, int BYTES, typename R>
-__device__ __forceinline__ void coef_load(R& r, const double* base) {
-  static_assert(G == 2 || G == 4, "group size");
-  if constexpr (G == 2) asm volatile("s_load_dwordx4 %0, %1, %2" : "=&s"(r) : "s"(base), "n"(BYTES));
-  else asm volatile("s_load_dwordx8 %0, %1, %2" : "=&s"(r) : "s"(base), "n"(BYTES));
-}
-
-// The same, issued before any use of `cur` (the group that has just arrived), so that the whole arithmetic
-// of one group lies between the issue of the next group's loads and the wait for them.
-template <int G, int BYTES, typename R>
-__device__ __forceinline__ void coef_load_after(R& r, const double* base, R& cur) {
-  if constexpr (G == 2) asm volatile("s_load_dwordx4 %0, %2, %3" : "=&s"(r), "+s"(cur) : "s"(base), "n"(BYTES));
-  else asm volatile("s_load_dwordx8 %0, %2, %3" : "=&s"(r), "+s"(cur) : "s"(base), "n"(BYTES));
-}
 
 // Frames per lane in phase 1.  Every class coefficient that comes through the scalar path is applied to
 // kNF frames; the scalar data path returns about one dword per clock per pair of compute units, so
@@ -139,7 +122,6 @@ __device__ __forceinline__ void pass_unit(
     double (&acc)[8][K], double (&nacc)[K]) {
   constexpr int E = D * D;
   constexpr int WS = K | 1;
-  typedef const __attribute__((address_space(4))) double* const_ptr_t;
   const int tg = lane >> 3, eg = lane & 7;
 
   // ---- phase 1: load y ----
@@ -172,12 +154,13 @@ __device__ __forceinline__ void pass_unit(
 
   // ---- q_k = <coef_k, y y^H> ----
   // The coefficients are wave-uniform and come through the scalar path straight into the FMAs as SGPR
-  // operands, one group of G packed entries (K loads of G doubles) at a time, double-buffered by hand: the
-  // loads of group g + 1 are issued before the arithmetic of group g, and waited for (all outstanding
-  // scalar loads: they may return out of order) at the top of group g + 1.  The loads and the wait are asm
-  // statements (and every partial sum passes through an empty one at the end of its group) because the
-  // compiler, left alone, either hoists all K*E loads out of the tile loop and
-  // spills them, or puts every load directly in front of its first use.
+  // operands, one group of G packed entries (K*G doubles) at a time, two groups in registers: the loads of
+  // group g + 1 are issued during the arithmetic of group g.  Left alone, the compiler either hoists all
+  // K*E loads out of the tile loop and spills them, or puts every load directly in front of its first use.
+  // The empty asm statements steer it: the offset of group g + 1 comes into existence only after the first
+  // product of group g (which is where the wait for group g's loads lands, with nothing else outstanding:
+  // scalar loads may return out of order, so that wait is always for all of them), and every partial sum
+  // passes through a fence at the end of its group, which keeps the group's arithmetic in place.
   double q[NF][K];
   double n2[NF];
 #pragma unroll
@@ -188,21 +171,21 @@ __device__ __forceinline__ void pass_unit(
   }
   constexpr int G = coef_group(K);
   constexpr int NG = (E + G - 1) / G;
-  typedef double creg __attribute__((ext_vector_type(G)));
-  creg cbuf[2][K];
-  static_for<0, K>([&](auto KI) { coef_load<G, KI.value * E * 8>(cbuf[0][KI.value], cf); });
-  static_for<0, NG>([&](auto GI) {
-    constexpr int gi = GI.value;
-    constexpr int g = gi * G;
-    constexpr int ng = (E - g) < G ? (E - g) : G;
-    constexpr int cb = gi & 1;
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(cbuf[cb][0]));
+  typedef const __attribute__((address_space(4))) double* const_ptr_t;
+  const const_ptr_t cf4 = (const_ptr_t)(uintptr_t)cf;
+  double ccur[K][G], cnxt[K][G];
+  {
+    int off0 = 0;
+    asm volatile("" : "+s"(off0));            // opaque (uniform) offset: keeps the loads inside this unit
+    const const_ptr_t c0 = cf4 + off0;
 #pragma unroll
-    for (int k = 1; k < K; ++k) asm volatile("" : "+s"(cbuf[cb][k]));
-    if constexpr (gi + 1 < NG)
-      static_for<0, K>([&](auto KI) {
-        coef_load_after<G, (KI.value * E + g + G) * 8>(cbuf[(gi + 1) & 1][KI.value], cf, cbuf[cb][KI.value]);
-      });
+    for (int k = 0; k < K; ++k)
+#pragma unroll
+      for (int e = 0; e < G; ++e) ccur[k][e] = (e < E) ? c0[k * E + e] : 0.0;
+  }
+  static_for<0, NG>([&](auto GI) {
+    constexpr int g = GI.value * G;
+    constexpr int ng = (E - g) < G ? (E - g) : G;
     double Pg[NF][ng];
 #pragma unroll
     for (int f = 0; f < NF; ++f) {
@@ -212,19 +195,33 @@ __device__ __forceinline__ void pass_unit(
         if constexpr (packed_part(g + e, D) == 0) n2[f] += Pg[f][e];
       });
     }
-    static_for<0, K>([&](auto KI) {
-      constexpr int k = KI.value;
-      static_for<0, ng>([&](auto EI) {
-        constexpr int e = EI.value;
+    q[0][0] = fma(ccur[0][0], Pg[0][0], q[0][0]);      // first use of this group: waits for its loads
+    if constexpr (g + G < E) {
+      int noff = g + G;
+      asm volatile("" : "+s"(noff), "+v"(q[0][0]));   // the next group's offset exists only from here on
+      const const_ptr_t cn = cf4 + noff;
 #pragma unroll
-        for (int f = 0; f < NF; ++f) q[f][k] = fma(cbuf[cb][k][e], Pg[f][e], q[f][k]);
-      });
-    });
-    // the group's arithmetic stays between its own wait and the next one
+      for (int k = 0; k < K; ++k)
+#pragma unroll
+        for (int e = 0; e < G; ++e) cnxt[k][e] = (g + G + e < E) ? cn[k * E + e] : 0.0;
+    }
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+#pragma unroll
+      for (int e = 0; e < ng; ++e) {
+#pragma unroll
+        for (int f = 0; f < NF; ++f)
+          if (!(k == 0 && e == 0 && f == 0)) q[f][k] = fma(ccur[k][e], Pg[f][e], q[f][k]);
+      }
+    }
 #pragma unroll
     for (int f = 0; f < NF; ++f)
 #pragma unroll
       for (int k = 0; k < K; ++k) asm volatile("" : "+v"(q[f][k]));
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+#pragma unroll
+      for (int e = 0; e < G; ++e) ccur[k][e] = cnxt[k][e];
   });
 
 #pragma unroll
@@ -559,7 +556,7 @@ EmPlan make_plan(const gss_ctx* ctx, long n_sf, int Tmax, int D, int K, int wgs_
   p.wgs_fin = map_wgs(p.fin, n_sf);
   const size_t E = (size_t)D * D;
   size_t o = 0;
-  p.off_coef = o;  o = gss_align_up(o + (size_t)n_sf * K * E * sizeof(double) + 64, 256);   // + a group's over-read
+  p.off_coef = o;  o = gss_align_up(o + (size_t)n_sf * K * E * sizeof(double) + 64, 256);
   p.off_cm = o;    o = gss_align_up(o + (size_t)n_sf * K * sizeof(double), 256);
   p.off_ce = o;    o = gss_align_up(o + (size_t)n_sf * K * sizeof(int32_t), 256);
   p.off_part = o;  o = gss_align_up(o + (size_t)p.wgs_acc * K * E * sizeof(double), 256);
