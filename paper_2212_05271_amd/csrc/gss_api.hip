@@ -30,6 +30,7 @@ int gss_create(gss_ctx** out, int device_id) {
   c->scratch_cap = 0;
   c->status = nullptr;
   c->num_cu = 256;
+  c->twiddles = nullptr;
   c->profile = 0;
   for (int k = 0; k < GSS_PROFILE_KERNELS; ++k) {
     c->ev_used[k] = 0;
@@ -59,6 +60,7 @@ void gss_destroy(gss_ctx* ctx) {
   (void)hipDeviceSynchronize();
   if (ctx->scratch) (void)hipFree(ctx->scratch);
   if (ctx->status) (void)hipFree(ctx->status);
+  if (ctx->twiddles) (void)hipFree(ctx->twiddles);
   for (int k = 0; k < GSS_PROFILE_KERNELS; ++k)
     for (int i = 0; i < GSS_PROFILE_SLOTS; ++i) {
       if (ctx->ev_start[k][i]) (void)hipEventDestroy(ctx->ev_start[k][i]);

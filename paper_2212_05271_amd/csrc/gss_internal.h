@@ -27,6 +27,7 @@ struct gss_ctx {
   size_t scratch_cap;
   uint32_t* status;       // device, one word
   int num_cu;
+  void* twiddles;         // device: exp(-2 pi i k / 1024), k = 0..512 (float2), filled by the first STFT/iSTFT call
   // optional per-kernel timing with HIP events (gss_profile_enable / gss_profile_get)
   int profile;
   hipEvent_t ev_start[GSS_PROFILE_KERNELS][GSS_PROFILE_SLOTS], ev_stop[GSS_PROFILE_KERNELS][GSS_PROFILE_SLOTS];
