@@ -117,11 +117,11 @@ __host__ __device__ constexpr int slot_packed_index(int eg, int n, int D) {
 // Phase 2 of a tile: lane (tg, eg) accumulates acc[n][k] += w_k[r] * P_r[entry n of block eg] over its 8
 // frames r = tg, tg + 8, ... of the 64-frame tile in LDS.  sY: [64][kYStride] doubles (8 complex channels
 // per frame, zero beyond D), sW: [64][WS] doubles (KW weights per frame).
-template <int KW, int WS>
+template <int KW, int WS, int UNROLL = 2>
 __device__ __forceinline__ void accumulate_tile(const double* __restrict__ sY, const double* __restrict__ sW,
                                                 int tg, int eg, double (&acc)[8][KW]) {
   const int cu = 2 * blk_a(eg), cv = 2 * blk_b(eg);
-#pragma unroll 2
+#pragma unroll UNROLL
   for (int j = 0; j < 8; ++j) {
     const int r = tg + 8 * j;              // rows of the 8 frame groups are adjacent: distinct LDS banks
     double w[KW];

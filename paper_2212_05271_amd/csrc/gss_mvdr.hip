@@ -65,26 +65,37 @@ __global__ __launch_bounds__(kWave * kPassWaves) void mvdr_cov_small(
   int tile_hi = tile_lo + tiles_per_chunk;
   const int tile_end = (T + kWave - 1) / kWave;
   tile_hi = tile_hi < tile_end ? tile_hi : tile_end;
-  for (int tile = tile_lo + wave; tile < tile_hi; tile += kPassWaves) {
+  // One tile of 64 frames per step; the loads of the wavefront's next tile are issued before the arithmetic
+  // of the current one.  A lane beyond T reads frame 0 (its weights are forced to zero).
+  float2 yv[D];
+  float gv[GSS_MAX_K];
+  auto load_tile = [&](int tile) {
     const int t = tile * kWave + lane;
-    const bool valid = t < T;
-    const int tc = valid ? t : 0;
+    const long tc = t < T ? t : 0;
+#pragma unroll
+    for (int d = 0; d < D; ++d) yv[d] = Yrow[tc * D + d];
+#pragma unroll
+    for (int k = 0; k < GSS_MAX_K; ++k) gv[k] = k < K ? grow[k * gk + tc] : 0.f;
+  };
+  int tile = tile_lo + wave;
+  if (tile < tile_hi) load_tile(tile);
+  for (; tile < tile_hi; tile += kPassWaves) {
+    const bool valid = tile * kWave + lane < T;
 #pragma unroll
     for (int d = 0; d < 8; ++d) {
-      double2 yv = make_double2(0.0, 0.0);
-      if (d < D) {
-        const float2 v = Yrow[(long)tc * D + (d < D ? d : 0)];
-        if (valid) yv = make_double2((double)v.x, (double)v.y);
-      }
-      *reinterpret_cast<double2*>(&sY[lane * kYStride + 2 * d]) = yv;
+      double2 v = make_double2(0.0, 0.0);
+      if (d < D) v = make_double2((double)yv[d < D ? d : 0].x, (double)yv[d < D ? d : 0].y);
+      *reinterpret_cast<double2*>(&sY[lane * kYStride + 2 * d]) = v;
     }
     double wt = 0.0, wb = 0.0;
-    for (int k = 0; k < K; ++k) {
-      const double g = (double)grow[k * gk + tc];
+#pragma unroll
+    for (int k = 0; k < GSS_MAX_K; ++k) {
+      const double g = (double)gv[k];                // 0 for k >= K
       if (k == tgt) wt = g; else wb += g;
     }
     sW[lane * WS + 0] = valid ? wt : 0.0;
     sW[lane * WS + 1] = valid ? wb : 0.0;
+    if (tile + kPassWaves < tile_hi) load_tile(tile + kPassWaves);
     wave_lds_sync();
     accumulate_tile<2, WS>(sY, sW, tg, eg, acc);
     wave_lds_sync();
@@ -309,10 +320,16 @@ int run_mvdr_small(gss_ctx* ctx, const float2* Y, const float* gamma, const int3
   const long n_sf = (long)S * F;
   constexpr int E = D * D;
   const int tiles = (Tmax + kWave - 1) / kWave;
-  long c_target = ((long)ctx->num_cu * 4 + n_sf - 1) / n_sf;
+  // Chunks per problem: as many as fit the resident workgroup slots in one round (the wavefronts of a
+  // workgroup take the chunk's tiles round-robin, so a chunk may hold any number of tiles).
+  int wgs_per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&wgs_per_cu, mvdr_cov_small<D>, kWave * kPassWaves, 0) != hipSuccess ||
+      wgs_per_cu < 1)
+    wgs_per_cu = 2;
+  long c_target = ((long)ctx->num_cu * wgs_per_cu) / n_sf;
   if (c_target < 1) c_target = 1;
-  int tpc = (int)((tiles + c_target - 1) / c_target);
-  tpc = (tpc + kPassWaves - 1) / kPassWaves * kPassWaves;
+  if (c_target > tiles) c_target = tiles;
+  const int tpc = (int)((tiles + c_target - 1) / c_target);
   const int C = (tiles + tpc - 1) / tpc;
   if (n_sf * C > 0x7fffffffL) return GSS_EUNSUPPORTED;
 
