@@ -192,4 +192,82 @@ __device__ __forceinline__ void reduce_and_store_partials(double (&acc)[8][KW], 
   }
 }
 
+// How the (segment, frequency) problems are cut into workgroups.  The first n_main problems get c_main
+// chunks of tpc_main tiles each; the remaining ones (the tail that would otherwise run alone on an almost
+// empty chip after the last full round of workgroups) are cut finer, into c_tail chunks of tpc_tail tiles.
+// Workgroup b writes partial-sum slot b.
+struct ChunkMap {
+  int n_main, c_main, tpc_main, c_tail, tpc_tail;
+};
+__host__ __device__ inline void chunk_decode(const ChunkMap& m, long b, long& sf, int& chunk, int& tpc) {
+  const long main_wgs = (long)m.n_main * m.c_main;
+  if (b < main_wgs) {
+    sf = b / m.c_main;
+    chunk = (int)(b % m.c_main);
+    tpc = m.tpc_main;
+  } else {
+    const long r = b - main_wgs;
+    sf = m.n_main + r / m.c_tail;
+    chunk = (int)(r % m.c_tail);
+    tpc = m.tpc_tail;
+  }
+}
+__host__ __device__ inline long chunk_base(const ChunkMap& m, long sf, int& count) {
+  if (sf < m.n_main) {
+    count = m.c_main;
+    return sf * m.c_main;
+  }
+  count = m.c_tail;
+  return (long)m.n_main * m.c_main + (sf - m.n_main) * m.c_tail;
+}
+
+inline long chunk_map_wgs(const ChunkMap& m, long n_sf) {
+  return (long)m.n_main * m.c_main + (n_sf - m.n_main) * m.c_tail;
+}
+
+// Chunking of n_sf problems of `tiles` tiles each for a kernel with `slots` resident workgroups; chunks are
+// multiples of `round_up` tiles.  Splitting a problem over several workgroups costs a partial-sum round
+// trip and a second reduction, so it is done only as far as needed to fill the slots (tpc_override > 0
+// fixes the tiles per chunk of the main part instead).  Tail: if the workgroups left over after the last
+// full round of slots fill less than a quarter of the chip, the problems they belong to are cut finer so
+// that the remainder spreads out.
+inline ChunkMap plan_chunk_map(long slots, long n_sf, int tiles, int round_up, int tpc_override, bool allow_tail) {
+  ChunkMap m;
+  auto chunks_for = [&](int tpc) { return (tiles + tpc - 1) / tpc; };
+  auto tpc_for = [&](long c) {
+    int tpc = (int)((tiles + c - 1) / c);
+    tpc = (tpc + round_up - 1) / round_up * round_up;
+    return tpc;
+  };
+  long c_target = (slots + n_sf - 1) / n_sf;
+  if (c_target < 1) c_target = 1;
+  m.tpc_main = tpc_override > 0 ? tpc_override : tpc_for(c_target);
+  m.c_main = chunks_for(m.tpc_main);
+  m.n_main = (int)n_sf;
+  m.c_tail = m.c_main;
+  m.tpc_tail = m.tpc_main;
+  const long wgs = n_sf * m.c_main;
+  const long rem = wgs % slots;
+  if (allow_tail && wgs > slots && rem > 0 && rem * 4 <= slots) {
+    const long tail_sf = (rem + m.c_main - 1) / m.c_main;
+    const long want = slots / (2 * tail_sf) > 1 ? slots / (2 * tail_sf) : 1;    // chunks per tail problem
+    const int tpc_t = tpc_for(want * m.c_main);
+    if (tpc_t < m.tpc_main) {
+      m.n_main = (int)(n_sf - tail_sf);
+      m.tpc_tail = tpc_t;
+      m.c_tail = chunks_for(tpc_t);
+    }
+  }
+  return m;
+}
+
+// The same chunk size for every problem.
+inline ChunkMap uniform_chunk_map(long n_sf, int tiles, int tpc) {
+  ChunkMap m;
+  m.tpc_main = m.tpc_tail = tpc;
+  m.c_main = m.c_tail = (tiles + tpc - 1) / tpc;
+  m.n_main = (int)n_sf;
+  return m;
+}
+
 }  // namespace

@@ -75,34 +75,6 @@ __global__ void em_init_coef(double* __restrict__ coef, double* __restrict__ cma
 // the wavefronts round-robin.
 // ----------------------------------------------------------------------------------------------
 
-// How the (segment, frequency) problems are cut into workgroups.  The first n_main problems get c_main
-// chunks of tpc_main tiles each; the remaining ones (the tail that would otherwise run alone on an almost
-// empty chip after the last full round of workgroups) are cut finer, into c_tail chunks of tpc_tail tiles.
-// Workgroup b writes partial-sum slot b.
-struct ChunkMap {
-  int n_main, c_main, tpc_main, c_tail, tpc_tail;
-};
-__host__ __device__ inline void chunk_decode(const ChunkMap& m, long b, long& sf, int& chunk, int& tpc) {
-  const long main_wgs = (long)m.n_main * m.c_main;
-  if (b < main_wgs) {
-    sf = b / m.c_main;
-    chunk = (int)(b % m.c_main);
-    tpc = m.tpc_main;
-  } else {
-    const long r = b - main_wgs;
-    sf = m.n_main + r / m.c_tail;
-    chunk = (int)(r % m.c_tail);
-    tpc = m.tpc_tail;
-  }
-}
-__host__ __device__ inline long chunk_base(const ChunkMap& m, long sf, int& count) {
-  if (sf < m.n_main) {
-    count = m.c_main;
-    return sf * m.c_main;
-  }
-  count = m.c_tail;
-  return (long)m.n_main * m.c_main + (sf - m.n_main) * m.c_tail;
-}
 
 // Entries of the packed outer product per group of scalar coefficient loads (2 or 4 doubles per class);
 // two groups are in SGPRs at a time, 2 * K * G * 2 registers of the 100 or so there are.
@@ -512,48 +484,17 @@ int env_int(const char* name, int dflt) {
   return dflt;
 }
 
-long map_wgs(const ChunkMap& m, long n_sf) { return (long)m.n_main * m.c_main + (n_sf - m.n_main) * m.c_tail; }
-
 EmPlan make_plan(const gss_ctx* ctx, long n_sf, int Tmax, int D, int K, int wgs_per_cu) {
   EmPlan p;
   const int tiles = (Tmax + kWave - 1) / kWave;
   const int round_up = kPassWaves * kNF;               // a chunk is a whole number of rounds of units
-  auto chunks_for = [&](int tpc) { return (tiles + tpc - 1) / tpc; };
-  auto tpc_for = [&](long c) {
-    int tpc = (int)((tiles + c - 1) / c);
-    tpc = (tpc + round_up - 1) / round_up * round_up;
-    return tpc;
-  };
-  // Splitting a (segment, frequency) over several workgroups costs a partial-sum round trip and a second
-  // reduction, so it is done only as far as needed to fill the chip's resident workgroup slots.
-  // GSS_EM_TPC overrides the tiles per chunk of the main part (tuning aid).
+  // GSS_EM_TPC overrides the tiles per chunk of the main part, GSS_EM_NOTAIL switches the tail cut off
+  // (tuning aids).
   const long slots = (long)ctx->num_cu * wgs_per_cu;
-  long c_target = (slots + n_sf - 1) / n_sf;
-  if (c_target < 1) c_target = 1;
-  p.acc.tpc_main = env_int("GSS_EM_TPC", tpc_for(c_target));
-  p.acc.c_main = chunks_for(p.acc.tpc_main);
-  p.acc.n_main = (int)n_sf;
-  p.acc.c_tail = p.acc.c_main;
-  p.acc.tpc_tail = p.acc.tpc_main;
-  // Tail: the workgroups left over after the last full round of resident slots.  If they fill less than a
-  // quarter of the chip, the problems they belong to are cut finer so that the remainder spreads out.
-  const long wgs = n_sf * p.acc.c_main;
-  const long rem = wgs % slots;
-  if (wgs > slots && rem > 0 && rem * 4 <= slots && env_int("GSS_EM_NOTAIL", 0) == 0) {
-    const long tail_sf = (rem + p.acc.c_main - 1) / p.acc.c_main;
-    const long want = slots / (2 * tail_sf) > 1 ? slots / (2 * tail_sf) : 1;    // chunks per tail problem
-    const int tpc_t = tpc_for(want * p.acc.c_main);
-    if (tpc_t < p.acc.tpc_main) {
-      p.acc.n_main = (int)(n_sf - tail_sf);
-      p.acc.tpc_tail = tpc_t;
-      p.acc.c_tail = chunks_for(tpc_t);
-    }
-  }
-  p.wgs_acc = map_wgs(p.acc, n_sf);
-  p.fin.tpc_main = p.fin.tpc_tail = round_up;
-  p.fin.c_main = p.fin.c_tail = chunks_for(round_up);
-  p.fin.n_main = (int)n_sf;
-  p.wgs_fin = map_wgs(p.fin, n_sf);
+  p.acc = plan_chunk_map(slots, n_sf, tiles, round_up, env_int("GSS_EM_TPC", 0), env_int("GSS_EM_NOTAIL", 0) == 0);
+  p.wgs_acc = chunk_map_wgs(p.acc, n_sf);
+  p.fin = uniform_chunk_map(n_sf, tiles, round_up);
+  p.wgs_fin = chunk_map_wgs(p.fin, n_sf);
   const size_t E = (size_t)D * D;
   size_t o = 0;
   p.off_coef = o;  o = gss_align_up(o + (size_t)n_sf * K * E * sizeof(double) + 64, 256);

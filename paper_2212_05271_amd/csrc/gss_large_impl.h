@@ -44,7 +44,7 @@ __device__ __forceinline__ double ipow_rt(double x, int n) {   // x^n, n >= 1
 }
 
 __global__ void em_init_coef_large(double* __restrict__ coef, double* __restrict__ cmant, int32_t* __restrict__ cexp,
-                                   int D, int K, long n_sf) {
+                                   int D, int K, long n_sf, int pad) {
   const int M = num_items(D);
   const long per = (long)M * K * 2;
   const long total = n_sf * per;
@@ -56,6 +56,8 @@ __global__ void em_init_coef_large(double* __restrict__ coef, double* __restrict
     item_ij(m, D, i, j);
     coef[x] = (i == j && part == 0) ? 1.0 : 0.0;
   }
+  for (long x = blockIdx.x * (long)blockDim.x + threadIdx.x; x < pad; x += (long)gridDim.x * blockDim.x)
+    coef[total + x] = 0.0;
   const long nl = n_sf * K;
   for (long x = blockIdx.x * (long)blockDim.x + threadIdx.x; x < nl; x += (long)gridDim.x * blockDim.x) {
     cmant[x] = 0.5;
@@ -133,19 +135,26 @@ __device__ __forceinline__ void reduce_items(double (&acc)[NR][2][KW], double* _
 // wavefronts round-robin.  Dynamic LDS: kLargeWaves * (64 * RS float2 + 64 * WS doubles), reused for the
 // final reduction (needs M * K * 2 doubles).
 // ----------------------------------------------------------------------------------------------
+// Items per group of scalar coefficient loads in phase 1 (2 * K doubles per item, two groups resident).
+template <int K>
+constexpr int kLargeGroup = K <= 5 ? 2 : 1;
+// Zeroed doubles behind the coefficient array: the pipeline reads up to four groups past the last item.
+constexpr int kCoefPadDoubles = 4 * 2 * 2 * GSS_MAX_K;
+
 template <int K, int NR, bool FINAL>
 __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
     const float2* __restrict__ Y, const uint8_t* __restrict__ act, const int32_t* __restrict__ T_len,
     const double* __restrict__ coef, const double* __restrict__ cmant, const int32_t* __restrict__ cexp,
     double* __restrict__ part, double* __restrict__ npart, float* __restrict__ gamma,
-    int F, int Tmax, int D, int C, int tiles_per_chunk, int RS, int tile_bytes) {
+    int F, int Tmax, int D, ChunkMap cmap, int RS, int tile_bytes) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   constexpr int WS = K | 1;
   const int M = num_items(D);
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
-  const int chunk = blockIdx.x % C;
-  const long sf = blockIdx.x / C;
+  long sf;
+  int chunk, tiles_per_chunk;
+  chunk_decode(cmap, blockIdx.x, sf, chunk, tiles_per_chunk);
   const int s = (int)(sf / F);
   const int f = (int)(sf % F);
   int T = T_len ? T_len[s] : Tmax;
@@ -196,28 +205,92 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
     for (int k = 0; k < K; ++k) q[k] = 0.0;
     double n2 = 0.0;
     const float2* __restrict__ yrow = sY + lane * RS;
-    const double* __restrict__ c = cf;
-    for (int i = 0; i < D; ++i) {
-      const float2 a = yrow[i];
-      const double ar = a.x, ai = a.y;
-      const double pii = ar * ar + ai * ai;
-      n2 += pii;
+    // The items in storage order (i ascending, j = i .. D-1), U at a time.  Their coefficients are
+    // wave-uniform and come through the scalar path; two groups are resident in SGPRs and the loads of the
+    // next group are issued during the arithmetic of the current one (the empty asm statements fix that
+    // order: the next group's offset becomes known after the first product of the current group, and every
+    // partial sum passes a fence at the end of the group).  The items' y values are fetched from LDS along
+    // with the coefficients, one group ahead (LDS and scalar loads share one counter: a wait for either is a
+    // wait for both).  A diagonal item is y_i conj(y_i): its imaginary part is exactly zero and its second
+    // coefficient is stored as zero.  The pipeline fetches up to two groups past the last item it uses; the
+    // coefficient array is followed by padding so that those loads stay in bounds.
+    constexpr int U = kLargeGroup<K>;
+    typedef const __attribute__((address_space(4))) double* cptr_t;
+    const cptr_t c4 = (cptr_t)(uintptr_t)cf;
+    const int Mmain = M / (2 * U) * (2 * U);   // items taken by the pipelined loop, two groups per trip
+    double cA[U][2 * K], cB[U][2 * K];         // coefficients of a group (SGPRs)
+    float2 yA[U][2], yB[U][2];                 // y_i, y_j of the group's items, fetched with them
+    int ii = 0, jj = 0;                        // wave-uniform coordinates of the next item to fetch
+    auto fetch = [&](double (&c)[U][2 * K], float2 (&y)[U][2], int off, int m0) {
+      const cptr_t cg = c4 + off;
 #pragma unroll
-      for (int k = 0; k < K; ++k) q[k] = fma(c[2 * k], pii, q[k]);
-      c += 2 * K;
-#pragma unroll 2
-      for (int j = i + 1; j < D; ++j) {
-        const float2 b = yrow[j];
-        const double br = b.x, bi = b.y;
+      for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int x = 0; x < 2 * K; ++x) c[u][x] = cg[u * 2 * K + x];
+        y[u][0] = yrow[ii];
+        y[u][1] = yrow[jj];
+        if (m0 + u + 1 < M) {                  // step to the next item, never past the last one
+          ++jj;
+          if (jj == D) { ++ii; jj = ii; }
+        }
+      }
+    };
+    {
+      int off0 = 0;
+      asm volatile("" : "+s"(off0));          // opaque offset: keeps the loads inside this tile
+      fetch(cA, yA, off0, 0);
+    }
+    auto group = [&](double (&cur)[U][2 * K], float2 (&ycur)[U][2], double (&nxt)[U][2 * K], float2 (&ynxt)[U][2],
+                     int m0) {
+      double re[U], im[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const double ar = ycur[u][0].x, ai = ycur[u][0].y, br = ycur[u][1].x, bi = ycur[u][1].y;
+        re[u] = ar * br + ai * bi;
+        im[u] = ai * br - ar * bi;
+      }
+      q[0] = fma(cur[0][0], re[0], q[0]);      // first use of this group: the wait for its loads lands here
+      int noff = (m0 + U) * 2 * K;
+      asm volatile("" : "+s"(noff), "+v"(q[0]));
+      fetch(nxt, ynxt, noff, m0 + U);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+          if (!(u == 0 && k == 0)) q[k] = fma(cur[u][2 * k], re[u], q[k]);
+          q[k] = fma(cur[u][2 * k + 1], im[u], q[k]);
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < K; ++k) asm volatile("" : "+v"(q[k]));
+    };
+    for (int m0 = 0; m0 < Mmain; m0 += 2 * U) {
+      group(cA, yA, cB, yB, m0);
+      group(cB, yB, cA, yA, m0 + U);
+    }
+    // the last M - Mmain items, one by one
+    {
+      int i, j;
+      if (Mmain < M) item_ij(Mmain, D, i, j); else { i = 0; j = 0; }
+      for (int m = Mmain; m < M; ++m) {
+        const float2 a = yrow[i], b = yrow[j];
+        const double ar = a.x, ai = a.y, br = b.x, bi = b.y;
         const double re = ar * br + ai * bi;
         const double im = ai * br - ar * bi;
+        const double* __restrict__ c = cf + (long)m * 2 * K;
 #pragma unroll
         for (int k = 0; k < K; ++k) {
           q[k] = fma(c[2 * k], re, q[k]);
           q[k] = fma(c[2 * k + 1], im, q[k]);
         }
-        c += 2 * K;
+        ++j;
+        if (j == D) { ++i; j = i; }
       }
+    }
+    // ||y||^2 from the diagonal items
+    for (int d = 0; d < D; ++d) {
+      const float2 a = yrow[d];
+      n2 += (double)a.x * (double)a.x + (double)a.y * (double)a.y;
     }
     // posterior over the active classes: pi_k / det B_k * q_k^-D, mantissa / exponent form
     const double n2c = fmax(n2, GSS_EPS_NORM_SQ);
@@ -268,7 +341,7 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
   if (FINAL) return;
 
   double* __restrict__ red = reinterpret_cast<double*>(lds_raw);
-  reduce_items<K, NR>(acc, red, part + (sf * C + chunk) * (long)M * K * 2, M, lane, wave);
+  reduce_items<K, NR>(acc, red, part + (long)blockIdx.x * M * K * 2, M, lane, wave);
 #pragma unroll
   for (int k = 0; k < K; ++k) {
     double nv = nacc[k];
@@ -285,7 +358,7 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
   if (threadIdx.x < K) {
     double sum = 0.0;
     for (int w = 0; w < kLargeWaves; ++w) sum += red[w * K + threadIdx.x];
-    npart[(sf * C + chunk) * K + threadIdx.x] = sum;
+    npart[(long)blockIdx.x * K + threadIdx.x] = sum;
   }
 }
 
@@ -332,26 +405,28 @@ __device__ __forceinline__ void gauss_jordan_large(double (*sMr)[33], double (*s
 __global__ __launch_bounds__(1024) void em_factor_large(
     const double* __restrict__ part, const double* __restrict__ npart,
     double* __restrict__ coef, double* __restrict__ cmant, int32_t* __restrict__ cexp, uint32_t* __restrict__ status,
-    int D, int K, int C, int weight_mode) {
+    int D, int K, ChunkMap cmap, int weight_mode) {
   __shared__ double sMr[32][33], sMi[32][33];
   __shared__ double sN[GSS_MAX_K];
   const int M = num_items(D);
   const long sf = blockIdx.x / K;
   const int k = blockIdx.x % K;
+  int C;
+  const long slot0 = chunk_base(cmap, sf, C);
   const int tid = threadIdx.x;
   const int i = tid / D, j = tid % D;
   const bool on = tid < D * D;
 
   if (tid < K) {
     double n = 0.0;
-    for (int c = 0; c < C; ++c) n += npart[(sf * C + c) * K + tid];
+    for (int c = 0; c < C; ++c) n += npart[(slot0 + c) * K + tid];
     sN[tid] = n;
   }
   if (on && i <= j) {
     const int m = item_index(i, j, D);
     double re = 0.0, im = 0.0;
     for (int c = 0; c < C; ++c) {
-      const double* p = part + (((sf * C + c) * (long)M + m) * K + k) * 2;
+      const double* p = part + (((slot0 + c) * (long)M + m) * K + k) * 2;
       re += p[0];
       im += p[1];
     }
@@ -410,14 +485,15 @@ template <int NR>
 __global__ __launch_bounds__(kWave * kLargeWaves) void mvdr_cov_large(
     const float2* __restrict__ Y, const float* __restrict__ gamma, const int32_t* __restrict__ T_len,
     const int32_t* __restrict__ target, double* __restrict__ part, uint32_t* __restrict__ status,
-    int F, int Tmax, int D, int K, int C, int tiles_per_chunk, int RS, int tile_bytes) {
+    int F, int Tmax, int D, int K, ChunkMap cmap, int RS, int tile_bytes) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   constexpr int WS = 3;
   const int M = num_items(D);
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
-  const int chunk = blockIdx.x % C;
-  const long sf = blockIdx.x / C;
+  long sf;
+  int chunk, tiles_per_chunk;
+  chunk_decode(cmap, blockIdx.x, sf, chunk, tiles_per_chunk);
   const int s = (int)(sf / F);
   const int f = (int)(sf % F);
   int T = T_len ? T_len[s] : Tmax;
@@ -463,18 +539,20 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void mvdr_cov_large(
     wave_lds_sync();
   }
   double* __restrict__ red = reinterpret_cast<double*>(lds_raw);
-  reduce_items<2, NR>(acc, red, part + (sf * C + chunk) * (long)M * 4, M, lane, wave);
+  reduce_items<2, NR>(acc, red, part + (long)blockIdx.x * M * 4, M, lane, wave);
 }
 
 // One workgroup per (segment, frequency), D*D active threads.  H[sf][r][d], pw[sf][r][2] as for D <= 8.
 __global__ __launch_bounds__(1024) void mvdr_solve_large(
     const double* __restrict__ part, double2* __restrict__ H, double* __restrict__ pw,
-    uint32_t* __restrict__ status, int D, int C) {
+    uint32_t* __restrict__ status, int D, ChunkMap cmap) {
   __shared__ double sKr[32][33], sKi[32][33], sBr[32][33], sBi[32][33], sMr[32][33], sMi[32][33];
   double (*sGr)[33] = sMr;   // G and then H overwrite the inverse once it has been consumed
   double (*sGi)[33] = sMi;
   const int M = num_items(D);
   const long sf = blockIdx.x;
+  int C;
+  const long slot0 = chunk_base(cmap, sf, C);
   const int tid = threadIdx.x;
   const int i = tid / D, j = tid % D;
   const bool on = tid < D * D;
@@ -482,7 +560,7 @@ __global__ __launch_bounds__(1024) void mvdr_solve_large(
     const int m = item_index(i, j, D);
     double kr = 0.0, ki = 0.0, br = 0.0, bi = 0.0;
     for (int c = 0; c < C; ++c) {
-      const double* p = part + ((sf * C + c) * (long)M + m) * 4;     // [k = 0 target, 1 background][re, im]
+      const double* p = part + ((slot0 + c) * (long)M + m) * 4;     // [k = 0 target, 1 background][re, im]
       kr += p[0]; ki += p[1]; br += p[2]; bi += p[3];
     }
     if (i == j) { ki = 0.0; bi = 0.0; }
@@ -581,18 +659,12 @@ __global__ __launch_bounds__(256) void mvdr_apply_large(
 }
 
 struct LargePlan {
-  int C, tpc, RS, tile_bytes, lds_bytes;
+  int RS, tile_bytes, lds_bytes;
 };
 
-LargePlan plan_large(const gss_ctx* ctx, long n_sf, int Tmax, int D, int KW) {
+// LDS geometry of the tile kernels: per wavefront a tile of 64 frame rows of RS float2 plus the weights.
+LargePlan plan_large(int D, int KW) {
   LargePlan p;
-  const int tiles = (Tmax + kWave - 1) / kWave;
-  long c_target = ((long)ctx->num_cu * 2 + n_sf - 1) / n_sf;
-  if (c_target < 1) c_target = 1;
-  int tpc = (int)((tiles + c_target - 1) / c_target);
-  tpc = (tpc + kLargeWaves - 1) / kLargeWaves * kLargeWaves;
-  p.tpc = tpc;
-  p.C = (tiles + tpc - 1) / tpc;
   p.RS = D + 1;                                            // float2 per frame row (odd: spreads the banks)
   const int ws = KW | 1;
   p.tile_bytes = (int)gss_align_up((size_t)kWave * p.RS * sizeof(float2) + (size_t)kWave * ws * sizeof(double), 16);
@@ -602,19 +674,40 @@ LargePlan plan_large(const gss_ctx* ctx, long n_sf, int Tmax, int D, int KW) {
   return p;
 }
 
+// Resident workgroup slots of a tile kernel with its dynamic LDS size.
+template <typename Kern>
+long large_slots(const gss_ctx* ctx, Kern kern, int lds_bytes) {
+  int per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kWave * kLargeWaves, (size_t)lds_bytes) != hipSuccess ||
+      per_cu < 1)
+    per_cu = 1;
+  return (long)ctx->num_cu * per_cu;
+}
+
 template <int K, int NR>
 int run_em_large(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_t* T_len, int S, int F, int Tmax,
                  int D, int iters, int weight_mode, float* gamma, hipStream_t st) {
   const long n_sf = (long)S * F;
   const int M = num_items(D);
-  const LargePlan p = plan_large(ctx, n_sf, Tmax, D, K);
-  if (n_sf * p.C > 0x7fffffffL || n_sf * K > 0x7fffffffL) return GSS_EUNSUPPORTED;
+  const LargePlan p = plan_large(D, K);
+  if (hipFuncSetAttribute((const void*)em_pass_large<K, NR, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                          p.lds_bytes) != hipSuccess ||
+      hipFuncSetAttribute((const void*)em_pass_large<K, NR, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                          p.lds_bytes) != hipSuccess)
+    return GSS_EHIP;
+  const int tiles = (Tmax + kWave - 1) / kWave;
+  const long slots = large_slots(ctx, em_pass_large<K, NR, false>, p.lds_bytes);
+  const ChunkMap acc_map = plan_chunk_map(slots, n_sf, tiles, kLargeWaves, 0, true);
+  const ChunkMap fin_map = plan_chunk_map(large_slots(ctx, em_pass_large<K, NR, true>, p.lds_bytes), n_sf, tiles,
+                                          kLargeWaves, 0, true);
+  const long wgs_acc = chunk_map_wgs(acc_map, n_sf), wgs_fin = chunk_map_wgs(fin_map, n_sf);
+  if (wgs_acc > 0x7fffffffL || wgs_fin > 0x7fffffffL || n_sf * K > 0x7fffffffL) return GSS_EUNSUPPORTED;
   size_t o = 0;
-  const size_t off_coef = o;  o = gss_align_up(o + (size_t)n_sf * M * K * 2 * sizeof(double), 256);
+  const size_t off_coef = o;  o = gss_align_up(o + ((size_t)n_sf * M * K * 2 + kCoefPadDoubles) * sizeof(double), 256);
   const size_t off_cm = o;    o = gss_align_up(o + (size_t)n_sf * K * sizeof(double), 256);
   const size_t off_ce = o;    o = gss_align_up(o + (size_t)n_sf * K * sizeof(int32_t), 256);
-  const size_t off_part = o;  o = gss_align_up(o + (size_t)n_sf * p.C * M * K * 2 * sizeof(double), 256);
-  const size_t off_npart = o; o = gss_align_up(o + (size_t)n_sf * p.C * K * sizeof(double), 256);
+  const size_t off_part = o;  o = gss_align_up(o + (size_t)wgs_acc * M * K * 2 * sizeof(double), 256);
+  const size_t off_npart = o; o = gss_align_up(o + (size_t)wgs_acc * K * sizeof(double), 256);
   int rc = gss_ensure_scratch(ctx, o);
   if (rc != GSS_OK) return rc;
   char* base = (char*)ctx->scratch;
@@ -623,27 +716,21 @@ int run_em_large(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_
   int32_t* ce = (int32_t*)(base + off_ce);
   double* part = (double*)(base + off_part);
   double* npart = (double*)(base + off_npart);
-  if (hipFuncSetAttribute((const void*)em_pass_large<K, NR, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                          p.lds_bytes) != hipSuccess ||
-      hipFuncSetAttribute((const void*)em_pass_large<K, NR, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                          p.lds_bytes) != hipSuccess)
-    return GSS_EHIP;
-  const dim3 grid((unsigned)(n_sf * p.C));
   const dim3 block(kWave * kLargeWaves);
   const int fthreads = (D * D + 63) / 64 * 64;
-  hipLaunchKernelGGL(em_init_coef_large, dim3(1024), dim3(256), 0, st, coef, cm, ce, D, K, n_sf);
+  hipLaunchKernelGGL(em_init_coef_large, dim3(1024), dim3(256), 0, st, coef, cm, ce, D, K, n_sf, kCoefPadDoubles);
   for (int it = 0; it < iters; ++it) {
     gss_profile_begin(ctx, 0, st);
-    hipLaunchKernelGGL((em_pass_large<K, NR, false>), grid, block, p.lds_bytes, st, Y, act, T_len, coef, cm, ce, part,
-                       npart, (float*)nullptr, F, Tmax, D, p.C, p.tpc, p.RS, p.tile_bytes);
+    hipLaunchKernelGGL((em_pass_large<K, NR, false>), dim3((unsigned)wgs_acc), block, p.lds_bytes, st, Y, act, T_len, coef,
+                       cm, ce, part, npart, (float*)nullptr, F, Tmax, D, acc_map, p.RS, p.tile_bytes);
     gss_profile_end(ctx, 0, st);
     gss_profile_begin(ctx, 1, st);
     hipLaunchKernelGGL(em_factor_large, dim3((unsigned)(n_sf * K)), dim3(fthreads), 0, st, part, npart, coef, cm, ce,
-                       ctx->status, D, K, p.C, weight_mode);
+                       ctx->status, D, K, acc_map, weight_mode);
     gss_profile_end(ctx, 1, st);
   }
-  hipLaunchKernelGGL((em_pass_large<K, NR, true>), grid, block, p.lds_bytes, st, Y, act, T_len, coef, cm, ce,
-                     (double*)nullptr, (double*)nullptr, gamma, F, Tmax, D, p.C, p.tpc, p.RS, p.tile_bytes);
+  hipLaunchKernelGGL((em_pass_large<K, NR, true>), dim3((unsigned)wgs_fin), block, p.lds_bytes, st, Y, act, T_len, coef, cm,
+                     ce, (double*)nullptr, (double*)nullptr, gamma, F, Tmax, D, fin_map, p.RS, p.tile_bytes);
   if (hipGetLastError() != hipSuccess) return GSS_EHIP;
   return GSS_OK;
 }
@@ -663,10 +750,16 @@ int run_mvdr_large(gss_ctx* ctx, const float2* Y, const float* gamma, const int3
                    int D, int K, const int32_t* target, int32_t* ref, float2* X, hipStream_t st) {
   const long n_sf = (long)S * F;
   const int M = num_items(D);
-  const LargePlan p = plan_large(ctx, n_sf, Tmax, D, 2);
-  if (n_sf * p.C > 0x7fffffffL) return GSS_EUNSUPPORTED;
+  const LargePlan p = plan_large(D, 2);
+  if (hipFuncSetAttribute((const void*)mvdr_cov_large<NR>, hipFuncAttributeMaxDynamicSharedMemorySize, p.lds_bytes) !=
+      hipSuccess)
+    return GSS_EHIP;
+  const int tiles = (Tmax + kWave - 1) / kWave;
+  const ChunkMap cmap = plan_chunk_map(large_slots(ctx, mvdr_cov_large<NR>, p.lds_bytes), n_sf, tiles, kLargeWaves, 0, true);
+  const long wgs = chunk_map_wgs(cmap, n_sf);
+  if (wgs > 0x7fffffffL) return GSS_EUNSUPPORTED;
   size_t o = 0;
-  const size_t off_part = o; o = gss_align_up(o + (size_t)n_sf * p.C * M * 4 * sizeof(double), 256);
+  const size_t off_part = o; o = gss_align_up(o + (size_t)wgs * M * 4 * sizeof(double), 256);
   const size_t off_H = o;    o = gss_align_up(o + (size_t)n_sf * D * D * sizeof(double2), 256);
   const size_t off_pw = o;   o = gss_align_up(o + (size_t)n_sf * D * 2 * sizeof(double), 256);
   int rc = gss_ensure_scratch(ctx, o);
@@ -675,13 +768,10 @@ int run_mvdr_large(gss_ctx* ctx, const float2* Y, const float* gamma, const int3
   double* part = (double*)(base + off_part);
   double2* H = (double2*)(base + off_H);
   double* pw = (double*)(base + off_pw);
-  if (hipFuncSetAttribute((const void*)mvdr_cov_large<NR>, hipFuncAttributeMaxDynamicSharedMemorySize, p.lds_bytes) !=
-      hipSuccess)
-    return GSS_EHIP;
-  hipLaunchKernelGGL((mvdr_cov_large<NR>), dim3((unsigned)(n_sf * p.C)), dim3(kWave * kLargeWaves), p.lds_bytes, st, Y,
-                     gamma, T_len, target, part, ctx->status, F, Tmax, D, K, p.C, p.tpc, p.RS, p.tile_bytes);
+  hipLaunchKernelGGL((mvdr_cov_large<NR>), dim3((unsigned)wgs), dim3(kWave * kLargeWaves), p.lds_bytes, st, Y, gamma, T_len,
+                     target, part, ctx->status, F, Tmax, D, K, cmap, p.RS, p.tile_bytes);
   const int sthreads = (D * D + 63) / 64 * 64;
-  hipLaunchKernelGGL(mvdr_solve_large, dim3((unsigned)n_sf), dim3(sthreads), 0, st, part, H, pw, ctx->status, D, p.C);
+  hipLaunchKernelGGL(mvdr_solve_large, dim3((unsigned)n_sf), dim3(sthreads), 0, st, part, H, pw, ctx->status, D, cmap);
   gss_launch_mvdr_ref(pw, ref, S, F, D, st);
   const int fpc = 1024;
   const int CA = (Tmax + fpc - 1) / fpc;
