@@ -1,0 +1,116 @@
+"""Per-configuration timing of the EM + MVDR path on one MI355X (the other configurations next to bench.py's).
+
+    python -m paper_2212_05271_amd.measure_configs [--meeting-s 300]
+
+For each synthetic configuration (the same seeded generators the parity tests use): stream time of
+gss_cacgmm_em and gss_mvdr with the inputs resident in HBM, audio seconds per second over the two, EM
+iterations and time-frequency-bin-iterations per second, and the algorithmic fp64 rate of the EM
+((3 + 4K) D^2 + 3D + 30K flops per bin and iteration) against the 78.6 TFLOP/s vector peak.  The padded
+batch (config 2) is reported per length bucket and in total; the recording pipeline (config 4) runs on a
+meeting of --meeting-s seconds with the same segment statistics and reports recording seconds per second
+end to end (STFT once, batches of EM + MVDR + iSTFT, cuts).
+"""
+
+from __future__ import annotations
+
+import argparse
+import time
+
+import numpy as np
+
+FS, HOP = 16000, 256
+PEAK_TFLOPS_F64 = 78.6
+
+
+def _timeit(torch, fn, n):
+    fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / n
+
+
+def measure_batch(torch, gss, ctx, name, Y, act, T_len, iters, target=None, reps=3):
+    S, F, T, D = Y.shape
+    K = act.shape[1]
+    Yd = torch.from_numpy(Y).cuda()
+    ad = torch.from_numpy(act).cuda()
+    Td = None if T_len is None else torch.from_numpy(T_len).cuda()
+    tgt = torch.zeros(S, dtype=torch.int32).cuda() if target is None else torch.from_numpy(target).cuda()
+    ref = torch.zeros(S, dtype=torch.int32).cuda()
+    g = gss.gss_cacgmm_em(ctx, Yd, ad, Td, iters)
+    X = gss.gss_mvdr(ctx, Yd, g, tgt, ref, Td)
+    t_em = _timeit(torch, lambda: gss.gss_cacgmm_em(ctx, Yd, ad, Td, iters, out=g), reps)
+    t_mv = _timeit(torch, lambda: gss.gss_mvdr(ctx, Yd, g, tgt, ref, Td, out=X), reps)
+    frames = T * S if T_len is None else int(T_len.sum())
+    flops = ((3 + 4 * K) * D * D + 3 * D + 30 * K) * F * frames * iters
+    return dict(name=name, S=S, T=T, D=D, K=K, iters=iters, frames=frames, em_ms=t_em * 1e3, mvdr_ms=t_mv * 1e3,
+                audio_s=frames * HOP / FS, flops=flops, bins_iters=F * frames * iters)
+
+
+def row(r):
+    t = (r["em_ms"] + r["mvdr_ms"]) * 1e-3
+    tf = r["flops"] / (r["em_ms"] * 1e-3) / 1e12
+    return (f"| {r['name']} | {r['S']} | {r['T']} | {r['D']} | {r['K']} | {r['iters']} | {r['em_ms']:.2f} | "
+            f"{r['mvdr_ms']:.3f} | {r['audio_s'] / t:,.0f} | {r['iters'] / (r['em_ms'] * 1e-3):,.0f} | "
+            f"{r['bins_iters'] / (r['em_ms'] * 1e-3):.3g} | {tf:.1f} | {100 * tf / PEAK_TFLOPS_F64:.0f} % |")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--meeting-s", type=float, default=300.0, help="duration of the config-4 meeting (0 = skip)")
+    a = ap.parse_args()
+
+    import torch
+    from . import binding as gss
+    from . import pipeline, synth
+
+    ctx = gss.Context(0)
+    print("| config | S | Tmax | D | K | iters | EM ms | MVDR ms | audio-s/s (EM+MVDR) | EM iters/s | bin-iters/s | "
+          "EM TFLOP/s (alg.) | of 78.6 |")
+    print("|---|---:|---:|---:|---:|---:|---:|---:|---:|---:|---:|---:|---:|")
+    for name, seg in (("c0", synth.config0()), ("c1", synth.config1()), ("c3", synth.config3())):
+        print(row(measure_batch(torch, gss, ctx, name, seg.Y[None], seg.activity[None], None, seg.iters)), flush=True)
+    T, ns = synth.config2_plan()
+    tot = None
+    for bi, idx in enumerate(synth.buckets_by_length(T, 4)):
+        segs = [synth.config2_segment(i, T[i], ns[i]) for i in idx]
+        Y, act, T_len, target = synth.pad_batch(segs)
+        r = measure_batch(torch, gss, ctx, f"c2 bucket {bi}", Y, act, T_len, 15, target)
+        print(row(r), flush=True)
+        if tot is None:
+            tot = dict(r, name="c2 all 64 segments")
+        else:
+            for k in ("S", "frames", "em_ms", "mvdr_ms", "audio_s", "flops", "bins_iters"):
+                tot[k] += r[k]
+            tot["T"] = max(tot["T"], r["T"])
+        del Y, act
+    print(row(tot), flush=True)
+
+    if a.meeting_s > 0:
+        n_seg = max(4, int(round(1200 * a.meeting_s / 3600.0)))
+        x, act_s, (st, en, spk) = synth.meeting(duration_s=a.meeting_s, n_segments=n_seg)
+        xd = torch.from_numpy(x).cuda()
+        ctx_samples = int(7.5 * FS)
+
+        def run():
+            return pipeline.enhance_recording(ctx, xd, act_s, st, en, spk, ctx_samples, ctx_samples, iters=15)
+
+        run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        outs, fr = run()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        proc = float(np.sum(fr["n_frames"])) * HOP / FS
+        print(f"\nc4 pipeline: {a.meeting_s:.0f} s meeting, 8 channels, {n_seg} segments with 7.5 s of context per side "
+              f"({proc:.0f} s of audio processed), 15 iterations: {dt * 1e3:.1f} ms end to end = "
+              f"{a.meeting_s / dt:,.0f} recording-s/s, {proc / dt:,.0f} processed audio-s/s "
+              f"(includes the host-side batch assembly)")
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()
