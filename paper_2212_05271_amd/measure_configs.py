@@ -8,7 +8,8 @@ iterations and time-frequency-bin-iterations per second, and the algorithmic fp6
 ((3 + 4K) D^2 + 3D + 30K flops per bin and iteration) against the 78.6 TFLOP/s vector peak.  The padded
 batch (config 2) is reported per length bucket and in total; the recording pipeline (config 4) runs on a
 meeting of --meeting-s seconds with the same segment statistics and reports recording seconds per second
-end to end (STFT once, batches of EM + MVDR + iSTFT, cuts).
+end to end (STFT once, batches of EM + MVDR + iSTFT, cuts), with per-segment context and with
+super-segment batching.
 """
 
 from __future__ import annotations
@@ -105,10 +106,24 @@ def main():
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         proc = float(np.sum(fr["n_frames"])) * HOP / FS
+        def run_super():
+            return pipeline.enhance_recording_super(ctx, xd, act_s, st, en, spk, ctx_samples, ctx_samples,
+                                                    max_batch_s=50.0, iters=15)
+
+        run_super()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        _, info = run_super()
+        torch.cuda.synchronize()
+        dts = time.perf_counter() - t0
+        procs = float(np.sum(info["T"])) * HOP / FS
         print(f"\nc4 pipeline: {a.meeting_s:.0f} s meeting, 8 channels, {n_seg} segments with 7.5 s of context per side "
               f"({proc:.0f} s of audio processed), 15 iterations: {dt * 1e3:.1f} ms end to end = "
               f"{a.meeting_s / dt:,.0f} recording-s/s, {proc / dt:,.0f} processed audio-s/s "
               f"(includes the host-side batch assembly)")
+        print(f"the same with super-segments (same-speaker segments concatenated up to 50 s, one context window each: "
+              f"{len(info['supers'])} super-segments, {procs:.0f} s of audio processed): {dts * 1e3:.1f} ms = "
+              f"{a.meeting_s / dts:,.0f} recording-s/s")
     ctx.close()
 
 

@@ -1,6 +1,11 @@
-"""Recording-level driver over the C-ABI calls: STFT of the whole recording once, context-extended
-segments cut out of it as frame ranges, bucketed by length and padded into batches, then
-gss_cacgmm_em -> gss_mvdr -> gss_istft per batch and the target region cut out of each result.
+"""Recording-level drivers over the C-ABI calls: STFT of the whole recording once, segments cut out of it as
+frame ranges, bucketed by length and padded into batches, then gss_cacgmm_em -> gss_mvdr -> gss_istft per
+batch and the target region cut out of each result.
+
+enhance_recording         every segment on its own, extended by its own context (padded batching);
+enhance_recording_super   segments of one speaker concatenated along time into super-segments that share
+                          one context window and one set of statistics (arXiv 2212.05271, Section 3,
+                          "Segment batching"); the super-segments are then batched with padding like above.
 
 Only orchestration and memory plumbing (slicing, padding, copies) happen here, with torch as the
 allocator; every step of the method runs in the library's kernels.  The bookkeeping integers come from
@@ -78,3 +83,122 @@ def enhance_recording(ctx, x, act_samples, seg_start, seg_end, seg_spk, ctx_left
             refs[i] = ref_h[b]
     fr["ref"] = refs
     return outputs, fr
+
+
+def plan_super_segments(seg_start, seg_end, seg_spk, max_batch_samples):
+    """Packs the segments of each speaker, in time order, into super-segments: a super-segment takes the
+    speaker's next segment as long as the summed duration of its members stays within max_batch_samples
+    (a segment longer than that forms a super-segment alone; max_batch_samples <= 0 puts every segment alone:
+    the "at most one segment per batch" option).  Returns a list of index lists, ordered by the start of
+    their first member."""
+    seg_start = np.asarray(seg_start, dtype=np.int64)
+    seg_end = np.asarray(seg_end, dtype=np.int64)
+    seg_spk = np.asarray(seg_spk)
+    supers = []
+    for spk in np.unique(seg_spk):
+        idx = [int(i) for i in np.flatnonzero(seg_spk == spk)]
+        idx.sort(key=lambda i: (int(seg_start[i]), int(seg_end[i]), i))
+        cur, dur = [], 0
+        for i in idx:
+            d = int(seg_end[i] - seg_start[i])
+            if cur and (max_batch_samples <= 0 or dur + d > max_batch_samples):
+                supers.append(cur)
+                cur, dur = [], 0
+            cur.append(i)
+            dur += d
+        if cur:
+            supers.append(cur)
+    supers.sort(key=lambda m: (int(seg_start[m[0]]), m[0]))
+    return supers
+
+
+def super_segment_pieces(members, seg_start, seg_end, n_samples, ctx_left, ctx_right):
+    """Sample spans of one super-segment, in order: one context span before its first member, the members
+    themselves (no context of their own), one context span after its last member; spans are clipped to the
+    recording and empty ones dropped.  Returns (starts, ends, member_of) with member_of = segment index or -1
+    for a context span."""
+    first, last = members[0], members[-1]
+    starts, ends, member_of = [], [], []
+    lo = max(0, int(seg_start[first]) - int(ctx_left))
+    if lo < int(seg_start[first]):
+        starts.append(lo); ends.append(int(seg_start[first])); member_of.append(-1)
+    for i in members:
+        starts.append(int(seg_start[i])); ends.append(int(seg_end[i])); member_of.append(int(i))
+    hi = min(int(n_samples), int(seg_end[last]) + int(ctx_right))
+    if hi > int(seg_end[last]):
+        starts.append(int(seg_end[last])); ends.append(hi); member_of.append(-1)
+    return np.asarray(starts, np.int64), np.asarray(ends, np.int64), member_of
+
+
+def enhance_recording_super(ctx, x, act_samples, seg_start, seg_end, seg_spk, ctx_left, ctx_right,
+                            max_batch_s=50.0, iters=15, weight_mode=1, max_batch_frames=200_000, Yrec=None):
+    """Super-segment batching.  Arguments as enhance_recording; max_batch_s bounds the summed member
+    duration of a super-segment (seconds at 16 kHz).
+
+    Every span of a super-segment (context, members, context) becomes the frame range that covers it (the
+    same bookkeeping as for a stand-alone segment without context); the ranges are concatenated along time,
+    the EM and the beamformer see the concatenation as one segment (one set of class parameters, one filter
+    and one reference channel per frequency), and every member's slice of the beamformed STFT is inverted on
+    its own and cut to the member.  Returns (outputs, info) with outputs[i] the enhanced segment i and info
+    holding the super-segment membership, lengths and reference channels.
+    """
+    import torch
+
+    D, N = x.shape
+    n_spk = act_samples.shape[0]
+    K = n_spk + 1
+    if Yrec is None:
+        Yrec = gss.gss_stft(ctx, x.reshape(1, D, N).contiguous())          # [1, F, Trec, D]
+    F = Yrec.shape[1]
+    n_seg = len(seg_start)
+    supers = plan_super_segments(seg_start, seg_end, seg_spk, int(round(max_batch_s * 16000)))
+    plans = []
+    for members in supers:
+        ps, pe, member_of = super_segment_pieces(members, seg_start, seg_end, N, ctx_left, ctx_right)
+        fr = gss.gss_frames_from_segments(ps, pe, N, 0, 0, HOP)
+        plans.append(dict(members=members, member_of=member_of, fr=fr, T=int(fr["n_frames"].sum())))
+    outputs = [None] * n_seg
+    super_ref = np.zeros(len(supers), dtype=np.int32)
+    member_X = []                                   # (segment index, X slice [F, n], cut_start, cut_end)
+    for batch in plan_batches([p["T"] for p in plans], max_batch_frames):
+        S = len(batch)
+        Tmax = max(plans[b]["T"] for b in batch)
+        Y = torch.zeros((S, F, Tmax, D), dtype=torch.complex64, device=x.device)
+        act = np.zeros((S, K, Tmax), dtype=np.uint8)
+        T_len = np.zeros(S, dtype=np.int32)
+        for bi, b in enumerate(batch):
+            fr, off = plans[b]["fr"], 0
+            for f0, nf in zip(fr["frame0"], fr["n_frames"]):
+                f0, nf = int(f0), int(nf)
+                Y[bi, :, off:off + nf] = Yrec[0, :, f0:f0 + nf]
+                act[bi, :n_spk, off:off + nf] = gss.gss_frame_activity(act_samples, f0, nf, HOP)
+                off += nf
+            act[bi, n_spk, :off] = 1
+            T_len[bi] = off
+        T_d = torch.from_numpy(T_len).to(x.device)
+        tgt = torch.from_numpy(np.asarray([seg_spk[plans[b]["members"][0]] for b in batch], dtype=np.int32)).to(x.device)
+        ref = torch.full((S,), -1, dtype=torch.int32, device=x.device)
+        gamma = gss.gss_cacgmm_em(ctx, Y, torch.from_numpy(act).to(x.device), T_d, iters, weight_mode)
+        X = gss.gss_mvdr(ctx, Y, gamma, tgt, ref, T_d)
+        ref_h = ref.cpu().numpy()
+        for bi, b in enumerate(batch):
+            super_ref[b] = ref_h[bi]
+            fr, off = plans[b]["fr"], 0
+            for p, i in enumerate(plans[b]["member_of"]):
+                nf = int(fr["n_frames"][p])
+                if i >= 0:
+                    member_X.append((i, X[bi, :, off:off + nf], int(fr["cut_start"][p]), int(fr["cut_end"][p])))
+                off += nf
+    # every member's slice is inverted on its own, in padded batches of similar length
+    for batch in plan_batches([m[1].shape[1] for m in member_X], max_batch_frames):
+        Tm = max(member_X[b][1].shape[1] for b in batch)
+        Xp = torch.zeros((len(batch), F, Tm), dtype=torch.complex64, device=x.device)
+        for bi, b in enumerate(batch):
+            Xp[bi, :, :member_X[b][1].shape[1]] = member_X[b][1]
+        xh = gss.gss_istft(ctx, Xp, (Tm - 3) * HOP)
+        for bi, b in enumerate(batch):
+            i, _, c0, c1 = member_X[b]
+            outputs[i] = xh[bi, c0:c1]
+    info = dict(supers=supers, T=np.asarray([p["T"] for p in plans], dtype=np.int32), ref=super_ref,
+                pieces=[(p["member_of"], p["fr"]) for p in plans])
+    return outputs, info

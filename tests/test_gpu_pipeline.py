@@ -81,3 +81,42 @@ def test_recording_pipeline_reduced_meeting(env):
         xg = outs[i].cpu().numpy()
         assert int(fr["ref"][i]) == ro
         assert np.linalg.norm(xg - xo) <= TOL_X * np.linalg.norm(xo)
+
+
+def test_super_segment_batching_reduced_meeting(env):
+    """Super-segment batching (Section 3, "Segment batching") on the 60 s meeting: same-speaker segments
+    concatenated along time with one context window per super-segment, shared statistics, every member
+    inverted and cut on its own.  One super-segment with several members is re-done end to end by the oracle
+    from the same concatenation rule."""
+    t, o, gss, synth, ctx, pipeline = (env[k] for k in ("torch", "o", "gss", "synth", "ctx", "pipeline"))
+    x, act_s, (st, en, spk) = synth.meeting(duration_s=60.0, n_segments=16)
+    D, N = x.shape
+    ctx_s = 32_000
+    xd = t.from_numpy(x).cuda()
+    outs, info = pipeline.enhance_recording_super(ctx, xd, act_s, st, en, spk, ctx_s, ctx_s, max_batch_s=10.0, iters=15)
+    t.cuda.synchronize()
+    assert sorted(i for m in info["supers"] for i in m) == list(range(len(st)))
+    for i in range(len(st)):
+        assert outs[i].shape[0] == int(en[i] - st[i])
+    multi = [b for b, m in enumerate(info["supers"]) if len(m) > 1]
+    assert multi, "the test meeting must produce a super-segment with more than one member"
+    b = multi[0]
+    members = info["supers"][b]
+    ps, pe, member_of = pipeline.super_segment_pieces(members, st, en, N, ctx_s, ctx_s)
+    Yrec = o.stft_channels_last(x).astype(np.complex64)
+    frames = [o.segment_frames(int(s), int(e), N, 0, 0) for s, e in zip(ps, pe)]
+    Ys = np.concatenate([Yrec[:, f["frame0"]:f["frame0"] + f["n_frames"]] for f in frames], axis=1)
+    act = np.concatenate([o.frame_activity(act_s, f["frame0"], f["n_frames"]) for f in frames], axis=1)
+    act = np.concatenate([act, np.ones((1, act.shape[1]), np.uint8)])
+    assert Ys.shape[1] == int(info["T"][b])
+    go = o.cacgmm_em(Ys, act, 15)
+    Xo, ro, _ = o.mvdr(Ys, go, int(spk[members[0]]))
+    assert int(info["ref"][b]) == ro
+    off = 0
+    for f, i in zip(frames, member_of):
+        nf = f["n_frames"]
+        if i >= 0:
+            xo = o.istft(Xo[:, off:off + nf], (nf - 3) * 256)[f["cut_start"]:f["cut_end"]]
+            xg = outs[i].cpu().numpy()
+            assert np.linalg.norm(xg - xo) <= TOL_X * np.linalg.norm(xo)
+        off += nf
