@@ -12,6 +12,10 @@ import ctypes as C
 import os
 
 import numpy as np
+# torch first: it ships its own HIP runtime, and the tensors this binding takes live in that runtime.
+# Loading libgss.so before torch would bring in the system's copy of the runtime as well, and a process with
+# two HIP runtimes does not work (the library's calls and torch's would talk to different ones).
+import torch  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgss.so")

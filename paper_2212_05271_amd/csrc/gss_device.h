@@ -114,6 +114,15 @@ __host__ __device__ constexpr int slot_packed_index(int eg, int n, int D) {
 }
 
 
+// slot_packed_index for every matrix size 1..8 and slot eg * 8 + n, as a table.
+struct SlotTable { short v[9][64]; };
+constexpr SlotTable make_slot_table() {
+  SlotTable t{};
+  for (int d = 0; d <= 8; ++d)
+    for (int sl = 0; sl < 64; ++sl) t.v[d][sl] = d == 0 ? (short)-1 : (short)slot_packed_index(sl / 8, sl % 8, d);
+  return t;
+}
+
 // Phase 2 of a tile: lane (tg, eg) accumulates acc[n][k] += w_k[r] * P_r[entry n of block eg] over its 8
 // frames r = tg, tg + 8, ... of the 64-frame tile in LDS.  sY: [64][kYStride] doubles (8 complex channels
 // per frame, zero beyond D), sW: [64][WS] doubles (KW weights per frame).
@@ -152,42 +161,57 @@ __device__ __forceinline__ void accumulate_tile(const double* __restrict__ sY, c
 }
 
 // Reduction of the per-lane accumulators of a workgroup of kPassWaves wavefronts into packed partial
-// sums: out[k * E + packed index] for k < KW, matrix size D.  `red` is LDS scratch of at least
-// kPassWaves * 64 * KW doubles that no wavefront uses any more (the function starts with a barrier).
+// sums: out[k * E + packed index] for k < KW, matrix size D.  Sums are taken in a fixed order (frame
+// groups ascending, then wavefronts ascending).
+//   wbuf: LDS private to the calling wavefront, kReduceWaveDoubles doubles (its tile region);
+//   red:  LDS scratch of the workgroup, kPassWaves * 64 * KW doubles, may overlap the wbuf regions.
+// The function starts with a barrier (every wavefront is done with its tiles).  First every wavefront
+// sums over its 8 frame groups through its own LDS region, two classes at a time: entry n of all lanes
+// goes out as one contiguous row (lane = 8 tg + eg), and lane o = 8 n + eg reads the 8 values of slot
+// (eg, n) back.  Then the wavefronts' sums meet in `red`.
+constexpr int kReduceRow = 72;                         // doubles per row of 64 (+ 8: spreads the banks)
+constexpr int kReduceWaveDoubles = 2 * 8 * kReduceRow;
+static_assert(kReduceWaveDoubles <= kWave * kYStride, "the y tile of a wavefront must hold its reduction rows");
+
 template <int D, int KW>
-__device__ __forceinline__ void reduce_and_store_partials(double (&acc)[8][KW], double* __restrict__ red,
-                                                          double* __restrict__ out, int lane, int wave) {
+__device__ __forceinline__ void reduce_and_store_partials(double (&acc)[8][KW], double* wbuf, double* red,
+                                                          double* __restrict__ out,
+                                                          int lane, int wave) {
   constexpr int E = D * D;
-  const int tg = lane >> 3, eg = lane & 7;
+  double S[KW];
+  __syncthreads();
 #pragma unroll
-  for (int k = 0; k < KW; ++k) {
+  for (int k0 = 0; k0 < KW; k0 += 2) {
 #pragma unroll
-    for (int n = 0; n < 8; ++n) {
-      double x = acc[n][k];
+    for (int c = 0; c < 2; ++c) {
+      if (k0 + c < KW) {
 #pragma unroll
-      for (int off = 8; off < kWave; off <<= 1) x += __shfl_xor(x, off, kWave);
-      acc[n][k] = x;
+        for (int n = 0; n < 8; ++n) wbuf[(c * 8 + n) * kReduceRow + lane] = acc[n][k0 + c];
+      }
     }
-  }
-  __syncthreads();                           // every wavefront is done with its tiles
-  if (tg == 0) {
+    wave_lds_sync();
 #pragma unroll
-    for (int n = 0; n < 8; ++n)
+    for (int c = 0; c < 2; ++c) {
+      if (k0 + c < KW) {
+        double sum = 0.0;
 #pragma unroll
-      for (int k = 0; k < KW; ++k) red[(wave * KW + k) * 64 + eg * 8 + n] = acc[n][k];
+        for (int tg = 0; tg < 8; ++tg) sum += wbuf[(c * 8 + (lane >> 3)) * kReduceRow + tg * 8 + (lane & 7)];
+        S[k0 + c] = sum;
+      }
+    }
+    wave_lds_sync();
   }
+  __syncthreads();                           // the private regions are free: `red` may overlap them
+#pragma unroll
+  for (int k = 0; k < KW; ++k) red[(wave * KW + k) * 64 + (lane & 7) * 8 + (lane >> 3)] = S[k];
   __syncthreads();
   for (int x = threadIdx.x; x < 64 * KW; x += kWave * kPassWaves) {
     const int k = x / 64, slot = x % 64;
     double sum = 0.0;
 #pragma unroll
     for (int w = 0; w < kPassWaves; ++w) sum += red[(w * KW + k) * 64 + slot];
-    int pidx = -1;                           // slot -> packed index for matrix size D; padding slots are dropped
-    static_for<0, 64>([&](auto SI) {
-      constexpr int sl = SI.value;
-      constexpr int pi = slot_packed_index(sl / 8, sl % 8, D);
-      if (slot == sl) pidx = pi;
-    });
+    static constexpr SlotTable kSlotTable = make_slot_table();
+    const int pidx = kSlotTable.v[D][slot];   // slot -> packed index for matrix size D; padding slots are dropped
     if (pidx >= 0) out[k * E + pidx] = sum;
   }
 }
@@ -261,13 +285,5 @@ inline ChunkMap plan_chunk_map(long slots, long n_sf, int tiles, int round_up, i
   return m;
 }
 
-// The same chunk size for every problem.
-inline ChunkMap uniform_chunk_map(long n_sf, int tiles, int tpc) {
-  ChunkMap m;
-  m.tpc_main = m.tpc_tail = tpc;
-  m.c_main = m.c_tail = (tiles + tpc - 1) / tpc;
-  m.n_main = (int)n_sf;
-  return m;
-}
 
 }  // namespace

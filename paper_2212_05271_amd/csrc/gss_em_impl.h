@@ -319,7 +319,7 @@ __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
   if (FINAL) return;
 
   // Reduce over the 8 frame groups and over the wavefronts; write the chunk's packed partial sums.
-  reduce_and_store_partials<D, K>(acc, lds, part + (long)blockIdx.x * (K * E), lane, wave);
+  reduce_and_store_partials<D, K>(acc, sY, lds, part + (long)blockIdx.x * (K * E), lane, wave);
 #pragma unroll
   for (int k = 0; k < K; ++k) {
     double nv = nacc[k];
@@ -471,7 +471,7 @@ __global__ __launch_bounds__(kWave * K) void em_factor_small(
 // ----------------------------------------------------------------------------------------------
 struct EmPlan {
   ChunkMap acc;          // chunking of the accumulating passes
-  ChunkMap fin;          // chunking of the final pass (no state across tiles: always fine-grained)
+  ChunkMap fin;          // chunking of the final pass
   long wgs_acc, wgs_fin;
   size_t off_coef, off_cm, off_ce, off_part, off_npart, total;
 };
@@ -484,7 +484,7 @@ int env_int(const char* name, int dflt) {
   return dflt;
 }
 
-EmPlan make_plan(const gss_ctx* ctx, long n_sf, int Tmax, int D, int K, int wgs_per_cu) {
+EmPlan make_plan(const gss_ctx* ctx, long n_sf, int Tmax, int D, int K, int wgs_per_cu, int wgs_per_cu_fin) {
   EmPlan p;
   const int tiles = (Tmax + kWave - 1) / kWave;
   const int round_up = kPassWaves * kNF;               // a chunk is a whole number of rounds of units
@@ -493,7 +493,7 @@ EmPlan make_plan(const gss_ctx* ctx, long n_sf, int Tmax, int D, int K, int wgs_
   const long slots = (long)ctx->num_cu * wgs_per_cu;
   p.acc = plan_chunk_map(slots, n_sf, tiles, round_up, env_int("GSS_EM_TPC", 0), env_int("GSS_EM_NOTAIL", 0) == 0);
   p.wgs_acc = chunk_map_wgs(p.acc, n_sf);
-  p.fin = uniform_chunk_map(n_sf, tiles, round_up);
+  p.fin = plan_chunk_map((long)ctx->num_cu * wgs_per_cu_fin, n_sf, tiles, round_up, 0, true);
   p.wgs_fin = chunk_map_wgs(p.fin, n_sf);
   const size_t E = (size_t)D * D;
   size_t o = 0;
@@ -514,7 +514,11 @@ int run_small(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_t* 
   if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&wgs_per_cu, em_pass_small<D, K, false>, kWave * kPassWaves, 0) !=
           hipSuccess || wgs_per_cu < 1)
     wgs_per_cu = 2;
-  const EmPlan p = make_plan(ctx, n_sf, Tmax, D, K, wgs_per_cu);
+  int wgs_per_cu_fin = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&wgs_per_cu_fin, em_pass_small<D, K, true>, kWave * kPassWaves, 0) !=
+          hipSuccess || wgs_per_cu_fin < 1)
+    wgs_per_cu_fin = 2;
+  const EmPlan p = make_plan(ctx, n_sf, Tmax, D, K, wgs_per_cu, wgs_per_cu_fin);
   int rc = gss_ensure_scratch(ctx, p.total);
   if (rc != GSS_OK) return rc;
   char* base = (char*)ctx->scratch;
