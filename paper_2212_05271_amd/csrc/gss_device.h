@@ -164,7 +164,9 @@ __device__ __forceinline__ void accumulate_tile(const double* __restrict__ sY, c
 // sums: out[k * E + packed index] for k < KW, matrix size D.  Sums are taken in a fixed order (frame
 // groups ascending, then wavefronts ascending).
 //   wbuf: LDS private to the calling wavefront, kReduceWaveDoubles doubles (its tile region);
-//   red:  LDS scratch of the workgroup, kPassWaves * 64 * KW doubles, may overlap the wbuf regions.
+//   red:  LDS scratch of the workgroup, kPassWaves * (64 * KW + KW) doubles, may overlap the wbuf regions.
+// WITH_N: nvals[k] is one more per-lane partial sum per class (lane = frame layout), summed over all lanes and
+// wavefronts into nout[k].
 // The function starts with a barrier (every wavefront is done with its tiles).  First every wavefront
 // sums over its 8 frame groups through its own LDS region, two classes at a time: entry n of all lanes
 // goes out as one contiguous row (lane = 8 tg + eg), and lane o = 8 n + eg reads the 8 values of slot
@@ -173,12 +175,21 @@ constexpr int kReduceRow = 72;                         // doubles per row of 64 
 constexpr int kReduceWaveDoubles = 2 * 8 * kReduceRow;
 static_assert(kReduceWaveDoubles <= kWave * kYStride, "the y tile of a wavefront must hold its reduction rows");
 
-template <int D, int KW>
-__device__ __forceinline__ void reduce_and_store_partials(double (&acc)[8][KW], double* wbuf, double* red,
-                                                          double* __restrict__ out,
-                                                          int lane, int wave) {
+template <int D, int KW, bool WITH_N>
+__device__ __forceinline__ void reduce_and_store_partials(double (&acc)[8][KW], double (&nvals)[KW], double* wbuf,
+                                                          double* red, double* __restrict__ out,
+                                                          double* __restrict__ nout, int lane, int wave) {
   constexpr int E = D * D;
   double S[KW];
+  if constexpr (WITH_N) {                    // per-lane scalars (one per class): summed over the wavefront
+#pragma unroll
+    for (int k = 0; k < KW; ++k) {
+      double nv = nvals[k];
+#pragma unroll
+      for (int off = 1; off < kWave; off <<= 1) nv += __shfl_xor(nv, off, kWave);
+      nvals[k] = nv;
+    }
+  }
   __syncthreads();
 #pragma unroll
   for (int k0 = 0; k0 < KW; k0 += 2) {
@@ -202,8 +213,15 @@ __device__ __forceinline__ void reduce_and_store_partials(double (&acc)[8][KW], 
     wave_lds_sync();
   }
   __syncthreads();                           // the private regions are free: `red` may overlap them
+  double* redn = red + kPassWaves * 64 * KW;
 #pragma unroll
   for (int k = 0; k < KW; ++k) red[(wave * KW + k) * 64 + (lane & 7) * 8 + (lane >> 3)] = S[k];
+  if constexpr (WITH_N) {
+    if (lane == 0) {
+#pragma unroll
+      for (int k = 0; k < KW; ++k) redn[wave * KW + k] = nvals[k];
+    }
+  }
   __syncthreads();
   for (int x = threadIdx.x; x < 64 * KW; x += kWave * kPassWaves) {
     const int k = x / 64, slot = x % 64;
@@ -214,6 +232,14 @@ __device__ __forceinline__ void reduce_and_store_partials(double (&acc)[8][KW], 
     const int pidx = kSlotTable.v[D][slot];   // slot -> packed index for matrix size D; padding slots are dropped
     if (pidx >= 0) out[k * E + pidx] = sum;
   }
+  if constexpr (WITH_N) {
+    if (threadIdx.x < KW) {
+      double sum = 0.0;
+#pragma unroll
+      for (int w = 0; w < kPassWaves; ++w) sum += redn[w * KW + threadIdx.x];
+      nout[threadIdx.x] = sum;
+    }
+  }
 }
 
 // How the (segment, frequency) problems are cut into workgroups.  The first n_main problems get c_main
@@ -223,16 +249,17 @@ __device__ __forceinline__ void reduce_and_store_partials(double (&acc)[8][KW], 
 struct ChunkMap {
   int n_main, c_main, tpc_main, c_tail, tpc_tail;
 };
-__host__ __device__ inline void chunk_decode(const ChunkMap& m, long b, long& sf, int& chunk, int& tpc) {
-  const long main_wgs = (long)m.n_main * m.c_main;
+__host__ __device__ inline void chunk_decode(const ChunkMap& m, unsigned b, long& sf, int& chunk, int& tpc) {
+  // 32-bit arithmetic: the grid has fewer than 2^31 workgroups
+  const unsigned main_wgs = (unsigned)m.n_main * (unsigned)m.c_main;
   if (b < main_wgs) {
-    sf = b / m.c_main;
-    chunk = (int)(b % m.c_main);
+    sf = (long)(b / (unsigned)m.c_main);
+    chunk = (int)(b % (unsigned)m.c_main);
     tpc = m.tpc_main;
   } else {
-    const long r = b - main_wgs;
-    sf = m.n_main + r / m.c_tail;
-    chunk = (int)(r % m.c_tail);
+    const unsigned r = b - main_wgs;
+    sf = (long)((unsigned)m.n_main + r / (unsigned)m.c_tail);
+    chunk = (int)(r % (unsigned)m.c_tail);
     tpc = m.tpc_tail;
   }
 }

@@ -274,8 +274,8 @@ __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
   long sf;
   int chunk, tiles_per_chunk;
   chunk_decode(cmap, blockIdx.x, sf, chunk, tiles_per_chunk);
-  const int s = (int)(sf / F);
-  const int f = (int)(sf % F);
+  const int s = (int)((unsigned)sf / (unsigned)F);
+  const int f = (int)((unsigned)sf % (unsigned)F);
   int T = T_len ? T_len[s] : Tmax;
   T = T < 0 ? 0 : (T > Tmax ? Tmax : T);
   const int t_end = FINAL ? Tmax : T;       // the final pass also writes the zero padding
@@ -318,28 +318,9 @@ __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
   }
   if (FINAL) return;
 
-  // Reduce over the 8 frame groups and over the wavefronts; write the chunk's packed partial sums.
-  reduce_and_store_partials<D, K>(acc, sY, lds, part + (long)blockIdx.x * (K * E), lane, wave);
-#pragma unroll
-  for (int k = 0; k < K; ++k) {
-    double nv = nacc[k];
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) nv += __shfl_xor(nv, off, kWave);
-    nacc[k] = nv;
-  }
-  __syncthreads();
-  double* __restrict__ redn = lds;
-  if (lane == 0) {
-#pragma unroll
-    for (int k = 0; k < K; ++k) redn[wave * K + k] = nacc[k];
-  }
-  __syncthreads();
-  if (threadIdx.x < K) {
-    double sum = 0.0;
-#pragma unroll
-    for (int w = 0; w < kPassWaves; ++w) sum += redn[w * K + threadIdx.x];
-    npart[(long)blockIdx.x * K + threadIdx.x] = sum;
-  }
+  // Reduce over the 8 frame groups and over the wavefronts; write the chunk's packed partial sums and counts.
+  reduce_and_store_partials<D, K, true>(acc, nacc, sY, lds, part + (long)blockIdx.x * (K * E),
+                                        npart + (long)blockIdx.x * K, lane, wave);
 }
 
 // ----------------------------------------------------------------------------------------------

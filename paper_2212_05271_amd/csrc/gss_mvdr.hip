@@ -100,7 +100,8 @@ __global__ __launch_bounds__(kWave * kPassWaves) void mvdr_cov_small(
     accumulate_tile<2, WS>(sY, sW, tg, eg, acc);
     wave_lds_sync();
   }
-  reduce_and_store_partials<D, 2>(acc, sY, lds, part + (sf * C + chunk) * (long)(2 * E), lane, wave);
+  double none[2] = {0.0, 0.0};
+  reduce_and_store_partials<D, 2, false>(acc, none, sY, lds, part + (sf * C + chunk) * (long)(2 * E), nullptr, lane, wave);
 }
 
 // ----------------------------------------------------------------------------------------------
