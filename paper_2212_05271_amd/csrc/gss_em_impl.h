@@ -305,7 +305,8 @@ __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
   const int tile_end = (t_end + kWave - 1) / kWave;
   tile_hi = tile_hi < tile_end ? tile_hi : tile_end;
   const int n_tiles = tile_hi > tile_lo ? tile_hi - tile_lo : 0;
-  const int n_big = n_tiles / kNF;
+  // a chunk with no more tiles than wavefronts is dealt out tile by tile
+  const int n_big = n_tiles <= kPassWaves ? 0 : n_tiles / kNF;
   const int n_units = n_big + (n_tiles - n_big * kNF);
   for (int u = wave; u < n_units; u += kPassWaves) {
     if (u < n_big) {
