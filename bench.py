@@ -79,8 +79,8 @@ def main():
                          "FETCH_SIZE / WRITE_SIZE counters are scaled by) and exit")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU (independent segments need no communication; "
-              "see DESIGN.md 'More than one GPU'); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (segments are independent and would be sharded without any "
+              "communication); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
