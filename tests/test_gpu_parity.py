@@ -221,6 +221,32 @@ def test_bitwise_determinism_and_frequency_independence(env):
     assert np.max(np.abs(g4[0] - g1[0][perm])) <= 1e-6
 
 
+def test_equivariances_on_the_gpu(env):
+    """The invariances that pin the oracle, re-run through the kernels (they catch indexing mistakes that a
+    matching oracle would share): frames permuted, channels permuted (a unitary map), every frame rescaled by
+    its own complex number, padding appended.  Rounding order changes, so the comparison is to 1e-6."""
+    seg = env["synth"].config1(F=12, T=400)
+    rng = np.random.default_rng(5)
+    Y, a = seg.Y, seg.activity
+    g = _gpu_em(env, Y[None], a[None], None, 10)[0]
+    pt = rng.permutation(Y.shape[1])
+    gp = _gpu_em(env, np.ascontiguousarray(Y[:, pt])[None], np.ascontiguousarray(a[:, pt])[None], None, 10)[0]
+    assert np.max(np.abs(gp - g[:, :, pt])) <= 1e-6
+    pd = rng.permutation(Y.shape[2])
+    gd = _gpu_em(env, np.ascontiguousarray(Y[:, :, pd])[None], a[None], None, 10)[0]
+    assert np.max(np.abs(gd - g)) <= 1e-6
+    c = (rng.uniform(0.5, 2.0, Y.shape[:2]) * np.exp(2j * np.pi * rng.uniform(size=Y.shape[:2]))).astype(np.complex64)
+    gs = _gpu_em(env, (Y * c[:, :, None]).astype(np.complex64)[None], a[None], None, 10)[0]
+    assert np.max(np.abs(gs - g)) <= 1e-5            # the rescaled input is rounded to complex64 again
+    Tp = Y.shape[1] + 77
+    Ypad = np.zeros((1, Y.shape[0], Tp, Y.shape[2]), np.complex64)
+    Ypad[0, :, :Y.shape[1]] = Y
+    apad = np.zeros((1, a.shape[0], Tp), np.uint8)
+    apad[0, :, :Y.shape[1]] = a
+    gpad = _gpu_em(env, Ypad, apad, np.array([Y.shape[1]], np.int32), 10)[0]
+    assert np.array_equal(gpad[:, :, :Y.shape[1]], g) and np.all(gpad[:, :, Y.shape[1]:] == 0)
+
+
 def test_reference_channel_choice(env):
     """Auto mode returns the oracle's channel whenever the oracle's best and second-best scores differ by
     more than 1e-4 relative; a fixed channel is honoured."""
