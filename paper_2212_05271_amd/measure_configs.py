@@ -59,9 +59,55 @@ def row(r):
             f"{r['bins_iters'] / (r['em_ms'] * 1e-3):.3g} | {tf:.1f} | {100 * tf / PEAK_TFLOPS_F64:.0f} % |")
 
 
+def sweeps(torch, gss, ctx, synth):
+    """The axes of the paper's ablations (Section 5.3) as speed and mask-change sweeps on config 1: EM
+    iterations, number of channels, noise class on/off, class-weight mode.  No recognition scores: the
+    corpora are not available; what can be reported is the time and how far the masks still move."""
+    seg = synth.config1()
+    F, T, D, K = seg.shape
+    Yd = torch.from_numpy(seg.Y[None]).cuda()
+    ad = torch.from_numpy(seg.activity[None]).cuda()
+    audio = T * HOP / FS
+    g_ref = gss.gss_cacgmm_em(ctx, Yd, ad, None, 20)
+    print("| EM iterations | EM ms | audio-s/s (EM) | max abs mask change vs 20 iterations | mean |")
+    print("|---:|---:|---:|---:|---:|")
+    for it in (1, 2, 3, 5, 10, 15, 20):
+        g = gss.gss_cacgmm_em(ctx, Yd, ad, None, it)
+        t = _timeit(torch, lambda: gss.gss_cacgmm_em(ctx, Yd, ad, None, it, out=g), 3)
+        d = (g - g_ref).abs()
+        print(f"| {it} | {t * 1e3:.3f} | {audio / t:,.0f} | {d.max().item():.3f} | {d.mean().item():.4f} |", flush=True)
+    print()
+    print("| channels | EM ms (20 it.) | MVDR ms | audio-s/s (EM+MVDR) |")
+    print("|---:|---:|---:|---:|")
+    tgt = torch.zeros(1, dtype=torch.int32).cuda()
+    ref = torch.zeros(1, dtype=torch.int32).cuda()
+    for d_sub in (2, 4, 6, 8):
+        Ys = Yd[..., :d_sub].contiguous()
+        g = gss.gss_cacgmm_em(ctx, Ys, ad, None, 20)
+        X = gss.gss_mvdr(ctx, Ys, g, tgt, ref)
+        te = _timeit(torch, lambda: gss.gss_cacgmm_em(ctx, Ys, ad, None, 20, out=g), 3)
+        tm = _timeit(torch, lambda: gss.gss_mvdr(ctx, Ys, g, tgt, ref, out=X), 3)
+        print(f"| {d_sub} | {te * 1e3:.3f} | {tm * 1e3:.3f} | {audio / (te + tm):,.0f} |", flush=True)
+    print()
+    print("| variant | classes | EM ms (20 it.) | max abs change of the speaker masks vs default |")
+    print("|---|---:|---:|---:|")
+    an = ad[:, :K - 1].contiguous()                                   # without the noise class
+    gn = gss.gss_cacgmm_em(ctx, Yd, an, None, 20)
+    tn = _timeit(torch, lambda: gss.gss_cacgmm_em(ctx, Yd, an, None, 20, out=gn), 3)
+    gu = gss.gss_cacgmm_em(ctx, Yd, ad, None, 20, 0)
+    tu = _timeit(torch, lambda: gss.gss_cacgmm_em(ctx, Yd, ad, None, 20, 0, out=gu), 3)
+    t0 = _timeit(torch, lambda: gss.gss_cacgmm_em(ctx, Yd, ad, None, 20, out=g_ref), 3)
+    print(f"| default (noise class, weights from the masks) | {K} | {t0 * 1e3:.3f} | 0 |")
+    print(f"| no noise class | {K - 1} | {tn * 1e3:.3f} | {(gn - g_ref[:, :K - 1]).abs().max().item():.3f} |")
+    print(f"| uniform class weights (weight_mode 0) | {K} | {tu * 1e3:.3f} | "
+          f"{(gu[:, :K - 1] - g_ref[:, :K - 1]).abs().max().item():.3f} |")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--meeting-s", type=float, default=300.0, help="duration of the config-4 meeting (0 = skip)")
+    ap.add_argument("--sweeps", action="store_true",
+                    help="only the parameter sweeps on config 1 (iterations, channels, noise class, weight mode)")
     a = ap.parse_args()
 
     import torch
@@ -69,6 +115,10 @@ def main():
     from . import pipeline, synth
 
     ctx = gss.Context(0)
+    if a.sweeps:
+        sweeps(torch, gss, ctx, synth)
+        ctx.close()
+        return
     print("| config | S | Tmax | D | K | iters | EM ms | MVDR ms | audio-s/s (EM+MVDR) | EM iters/s | bin-iters/s | "
           "EM TFLOP/s (alg.) | of 78.6 |")
     print("|---|---:|---:|---:|---:|---:|---:|---:|---:|---:|---:|---:|---:|")
