@@ -88,69 +88,69 @@ constexpr int kPassWaves = 4;
 constexpr int kYStride = 18;   // doubles per frame row of the y tile: 8 complex + 2 pad (16-byte units: 9 per row)
 
 
-// Channel-block pair (A, B) of phase-2 lane type eg: off-diagonal block (A < B) for eg < 6, the two
-// diagonal blocks A and B for eg = 6, 7.
-__host__ __device__ constexpr int blk_a(int eg) { return eg == 0 || eg == 1 || eg == 2 ? 0 : (eg == 3 || eg == 4 ? 1 : (eg == 5 ? 2 : (eg == 6 ? 0 : 2))); }
-__host__ __device__ constexpr int blk_b(int eg) { return eg == 0 ? 1 : (eg == 1 ? 2 : (eg == 2 ? 3 : (eg == 3 ? 2 : (eg == 4 ? 3 : (eg == 5 ? 3 : (eg == 6 ? 1 : 3)))))); }
+// Phase-2 lane type eg = channel i.  Its 8 accumulator slots: n = 0..5 are Re and Im of y_i conj(y_b),
+// b = (i + d) mod 8 for d = 1, 2, 3; n = 6, 7 are Re and Im of y_i conj(y_(i+4)) for i < 4, and the two real
+// diagonal entries |y_i|^2, |y_(i-4)|^2 for i >= 4.  The pairs at circular distance 1..4 are all 28 pairs
+// once; where b < i the slot holds the conjugate of the stored (upper-triangle) entry, i.e. its imaginary
+// part with the opposite sign.
+struct SlotEntry { int i, j, part, sign; };     // part: 0 real diagonal, 1 Re, 2 Im
+__host__ __device__ constexpr SlotEntry slot_entry(int eg, int n) {
+  if (n < 6 || eg < 4) {
+    const int d = n < 6 ? n / 2 + 1 : 4;
+    const int part = 1 + (n & 1);
+    const int a = eg, b = (eg + d) % 8;
+    if (a < b) return SlotEntry{a, b, part, 1};
+    return SlotEntry{b, a, part, part == 2 ? -1 : 1};
+  }
+  const int c = n == 6 ? eg : eg - 4;
+  return SlotEntry{c, c, 0, 1};
+}
 
 // Packed index (gss_packed_row order, matrix size D) of accumulator slot n of lane type eg, or -1 if the
 // slot lies in the zero padding.
 __host__ __device__ constexpr int slot_packed_index(int eg, int n, int D) {
-  const int cu = 2 * blk_a(eg), cv = 2 * blk_b(eg);
-  int i = 0, j = 0, part = 0;
-  if (eg < 6) {
-    i = cu + (n >> 2);
-    j = cv + ((n >> 1) & 1);
-    part = 1 + (n & 1);
-  } else {
-    const int c0 = n < 4 ? cu : cv;
-    const int m = n & 3;
-    if (m == 0) { i = c0; j = c0; part = 0; }
-    else if (m == 1) { i = c0 + 1; j = c0 + 1; part = 0; }
-    else { i = c0; j = c0 + 1; part = m - 1; }
-  }
-  if (i >= D || j >= D) return -1;
-  return part == 0 ? gss_packed_row(i, D) : gss_packed_row(i, D) + 1 + 2 * (j - i - 1) + (part - 1);
+  const SlotEntry e = slot_entry(eg, n);
+  if (e.i >= D || e.j >= D) return -1;
+  return e.part == 0 ? gss_packed_row(e.i, D) : gss_packed_row(e.i, D) + 1 + 2 * (e.j - e.i - 1) + (e.part - 1);
 }
 
-
-// slot_packed_index for every matrix size 1..8 and slot eg * 8 + n, as a table.
-struct SlotTable { short v[9][64]; };
+// slot_packed_index for every matrix size 1..8 and slot eg * 8 + n, and the slot's sign, as tables.
+struct SlotTable { short v[9][64]; signed char sign[64]; };
 constexpr SlotTable make_slot_table() {
   SlotTable t{};
   for (int d = 0; d <= 8; ++d)
     for (int sl = 0; sl < 64; ++sl) t.v[d][sl] = d == 0 ? (short)-1 : (short)slot_packed_index(sl / 8, sl % 8, d);
+  for (int sl = 0; sl < 64; ++sl) t.sign[sl] = (signed char)slot_entry(sl / 8, sl % 8).sign;
   return t;
 }
 
-// Phase 2 of a tile: lane (tg, eg) accumulates acc[n][k] += w_k[r] * P_r[entry n of block eg] over its 8
+// Phase 2 of a tile: lane (tg, eg) accumulates acc[n][k] += w_k[r] * (slot n of lane type eg)[r] over its 8
 // frames r = tg, tg + 8, ... of the 64-frame tile in LDS.  sY: [64][kYStride] doubles (8 complex channels
 // per frame, zero beyond D), sW: [64][WS] doubles (KW weights per frame).
 template <int KW, int WS, int UNROLL = 2>
 __device__ __forceinline__ void accumulate_tile(const double* __restrict__ sY, const double* __restrict__ sW,
                                                 int tg, int eg, double (&acc)[8][KW]) {
-  const int cu = 2 * blk_a(eg), cv = 2 * blk_b(eg);
+  const int c1 = 2 * ((eg + 1) & 7), c2 = 2 * ((eg + 2) & 7), c3 = 2 * ((eg + 3) & 7), c4 = 2 * ((eg + 4) & 7);
 #pragma unroll UNROLL
   for (int j = 0; j < 8; ++j) {
     const int r = tg + 8 * j;              // rows of the 8 frame groups are adjacent: distinct LDS banks
     double w[KW];
 #pragma unroll
     for (int k = 0; k < KW; ++k) w[k] = sW[r * WS + k];
-    const double2 u0 = *reinterpret_cast<const double2*>(&sY[r * kYStride + 2 * cu]);
-    const double2 u1 = *reinterpret_cast<const double2*>(&sY[r * kYStride + 2 * cu + 2]);
-    const double2 v0 = *reinterpret_cast<const double2*>(&sY[r * kYStride + 2 * cv]);
-    const double2 v1 = *reinterpret_cast<const double2*>(&sY[r * kYStride + 2 * cv + 2]);
+    const double* __restrict__ row = sY + r * kYStride;
+    const double2 x = *reinterpret_cast<const double2*>(&row[2 * eg]);
+    const double2 y1 = *reinterpret_cast<const double2*>(&row[c1]);
+    const double2 y2 = *reinterpret_cast<const double2*>(&row[c2]);
+    const double2 y3 = *reinterpret_cast<const double2*>(&row[c3]);
+    const double2 y4 = *reinterpret_cast<const double2*>(&row[c4]);
     double e[8];
-    if (eg < 6) {   // off-diagonal block: u_a conj(v_b)
-      e[0] = u0.x * v0.x + u0.y * v0.y;  e[1] = u0.y * v0.x - u0.x * v0.y;
-      e[2] = u0.x * v1.x + u0.y * v1.y;  e[3] = u0.y * v1.x - u0.x * v1.y;
-      e[4] = u1.x * v0.x + u1.y * v0.y;  e[5] = u1.y * v0.x - u1.x * v0.y;
-      e[6] = u1.x * v1.x + u1.y * v1.y;  e[7] = u1.y * v1.x - u1.x * v1.y;
-    } else {        // two diagonal blocks: |u0|^2, |u1|^2, u0 conj(u1), and the same for v
-      e[0] = u0.x * u0.x + u0.y * u0.y;  e[1] = u1.x * u1.x + u1.y * u1.y;
-      e[2] = u0.x * u1.x + u0.y * u1.y;  e[3] = u0.y * u1.x - u0.x * u1.y;
-      e[4] = v0.x * v0.x + v0.y * v0.y;  e[5] = v1.x * v1.x + v1.y * v1.y;
-      e[6] = v0.x * v1.x + v0.y * v1.y;  e[7] = v0.y * v1.x - v0.x * v1.y;
+    e[0] = x.x * y1.x + x.y * y1.y;  e[1] = x.y * y1.x - x.x * y1.y;
+    e[2] = x.x * y2.x + x.y * y2.y;  e[3] = x.y * y2.x - x.x * y2.y;
+    e[4] = x.x * y3.x + x.y * y3.y;  e[5] = x.y * y3.x - x.x * y3.y;
+    if (eg < 4) {   // the pair at distance 4
+      e[6] = x.x * y4.x + x.y * y4.y;  e[7] = x.y * y4.x - x.x * y4.y;
+    } else {        // the diagonal entries of the two channels
+      e[6] = x.x * x.x + x.y * x.y;    e[7] = y4.x * y4.x + y4.y * y4.y;
     }
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
@@ -230,7 +230,7 @@ __device__ __forceinline__ void reduce_and_store_partials(double (&acc)[8][KW], 
     for (int w = 0; w < kPassWaves; ++w) sum += red[(w * KW + k) * 64 + slot];
     static constexpr SlotTable kSlotTable = make_slot_table();
     const int pidx = kSlotTable.v[D][slot];   // slot -> packed index for matrix size D; padding slots are dropped
-    if (pidx >= 0) out[k * E + pidx] = sum;
+    if (pidx >= 0) out[k * E + pidx] = kSlotTable.sign[slot] < 0 ? -sum : sum;
   }
   if constexpr (WITH_N) {
     if (threadIdx.x < KW) {

@@ -64,10 +64,11 @@ __global__ void em_init_coef(double* __restrict__ coef, double* __restrict__ cma
 //   and the coefficients wave-uniform (scalar loads); posterior over the active classes as
 //   pi_k / det B_k * q_k^-D in (mantissa, exponent) form, fp64, no log/exp; weights w_k = gamma_k / q_k.
 //   y (as fp64) and w go to the wavefront's LDS tile.
-// Phase 2 (lane = (frame group tg, block eg), 8 x 8; frames tg, tg+8, ... of the tile): the Hermitian
-//   8 x 8 outer product is cut into 2 x 2 blocks of channels; lanes eg = 0..5 own the six off-diagonal blocks (4 complex = 8 real entries),
-//   lanes eg = 6, 7 own two diagonal blocks each (2 real diagonals + 1 complex entry per block = 8 real
-//   entries).  For its 8 frames per tile a lane reads 4 channels of y and the K weights, forms its 8
+// Phase 2 (lane = (frame group tg, channel eg), 8 x 8; frames tg, tg+8, ... of the tile): lane type eg = i
+//   owns the entries y_i conj(y_b) for b = i+1, i+2, i+3 (mod 8), and either the pair (i, i+4) (i < 4) or
+//   the real diagonal entries of channels i and i-4 (i >= 4): 8 real entries per lane, all 64 of the packed
+//   Hermitian 8 x 8 matrix over the 8 lane types, the same instructions for every lane except the last two
+//   entries.  For its 8 frames per tile a lane reads 5 channels of y and the K weights, forms its 8
 //   entries exactly and accumulates R_k[e] += w_k * P[e] in fp64.  Channels >= D are zero padding.
 //   The accumulators stay in registers across the tiles of the chunk.
 //
