@@ -33,7 +33,7 @@ FS, HOP = 16000, 256
 PEAK_TFLOPS_F64 = 78.6
 # HBM bytes per launch of the accumulating EM pass on this workload, from rocprofv3 --pmc runs
 # (FETCH_SIZE + WRITE_SIZE in KiB, each scaled by the copy-kernel calibration).
-EM_PASS_TRAFFIC_BYTES = (53265 + 1322) * 1024   # profiles/em_config1_hbm_traffic.md
+EM_PASS_TRAFFIC_BYTES = (53273 + 1322) * 1024   # profiles/em_config1_hbm_traffic.md
 
 
 def em_pass_flops(F, T, D, K):
