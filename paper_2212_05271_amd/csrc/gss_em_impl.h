@@ -209,7 +209,7 @@ __device__ __forceinline__ void pass_unit(
 #pragma unroll
     for (int k = 0; k < K; ++k) {
       a[k] = (abits[f] >> k) & 1u;
-      rq[k] = rcp_f64(fmax(q[f][k], qfloor));        // 1 / (q_k * n2c): the M-step weight is gamma_k * rq
+      rq[k] = rcp_f64_fast(fmax(q[f][k], qfloor));        // 1 / (q_k * n2c): the M-step weight is gamma_k * rq
       const double u = rq[k] * n2c;                  // 1 / q_k
       const double mu = __builtin_amdgcn_frexp_mant(u);
       const int eu = __builtin_amdgcn_frexp_exp(u);
@@ -226,7 +226,7 @@ __device__ __forceinline__ void pass_unit(
       v[k] = a[k] ? ldexp(mant[k], de) : 0.0;
       Z += v[k];
     }
-    const double rz = Z > 0.0 ? rcp_f64(Z) : 0.0;
+    const double rz = Z > 0.0 ? rcp_f64_fast(Z) : 0.0;
     if constexpr (FINAL) {
       if (t[f] < Tmax) {
 #pragma unroll
