@@ -90,6 +90,8 @@ int gss_profile_get(gss_ctx* ctx, int which, double* total_ms, int64_t* launches
  *   Y   [S][F][T][D] complex64, F = n_fft/2 + 1, T = ceil(N / hop) + 3  (must equal the T passed in)
  * Periodic Hann window of n_fft samples; the signal is zero-padded by n_fft - hop samples on both
  * sides, so frame t covers samples [(t-3)*hop, (t+1)*hop).  Only n_fft = 1024, hop = 256 is built.
+ * The first gss_stft or gss_istft call of a context allocates the context's twiddle table (4 KB) and
+ * waits for `stream` once while it is filled.
  */
 int gss_stft(gss_ctx* ctx, const float* x, int S, int D, int64_t N, int n_fft, int hop,
              float* Y, int T, void* stream);
