@@ -108,3 +108,38 @@ def test_create_without_gpu_fails_cleanly(binding):
     with pytest.raises(binding.GssError) as e:
         binding.Context(0)
     assert e.value.code < 0
+
+
+def test_header_is_plain_c_and_links(tmp_path, binding):
+    """include/gss.h compiles as C99 (no C++), and a C program that takes the address of every declared
+    entry point links against the shared library and can call the host-only ones."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    header = open(os.path.join(ROOT, "include", "gss.h")).read()
+    names = sorted(set(re.findall(r"\b(gss_[a-z_]+)\s*\(", header)))
+    src = tmp_path / "link.c"
+    refs = "\n".join(f"  p[{i}] = (fn_t)&{n};" for i, n in enumerate(names))
+    src.write_text(
+        '#include <stdio.h>\n#include <string.h>\n#include "gss.h"\n'
+        "typedef void (*fn_t)(void);\n"
+        "int main(void) {\n"
+        f"  fn_t p[{len(names)}];\n{refs}\n"
+        f"  for (int i = 0; i < {len(names)}; ++i) if (!p[i]) return 2;\n"
+        '  if (strcmp(gss_strerror(GSS_OK), "ok") != 0) return 3;\n'
+        "  int64_t f0 = 0, c0 = 0, c1 = 0, e0 = 0, e1 = 0; int32_t nf = 0;\n"
+        "  int64_t s = 1000, e = 5000;\n"
+        "  if (gss_frames_from_segments(&s, &e, 1, 16000, 512, 512, 256, &e0, &e1, &f0, &nf, &c0, &c1) != GSS_OK) return 4;\n"
+        '  printf("%s %d\\n", gss_version(), (int)nf);\n'
+        "  return 0;\n}\n")
+    exe = tmp_path / "link"
+    libdir = os.path.dirname(binding.LIB_PATH)
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), str(src),
+                        "-o", str(exe), "-L", libdir, "-l:libgss.so", f"-Wl,-rpath,{libdir}"],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
+    assert re.fullmatch(r"\d+\.\d+\.\d+ \d+\n", r.stdout)
