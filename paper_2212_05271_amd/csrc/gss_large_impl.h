@@ -399,6 +399,56 @@ __device__ __forceinline__ void gauss_jordan_large(double (*sMr)[33], double (*s
   }
 }
 
+// The same sweeps with two copies of the matrix, read from one and written to the other: one barrier per
+// sweep, and every thread keeps its own entry in registers.  (sAr, sAi) holds the input; returns 0 if the
+// inverse ends up there, 1 if it is in (sBr, sBi).
+__device__ __forceinline__ int gauss_jordan_large_2buf(double (*sAr)[33], double (*sAi)[33], double (*sBr)[33],
+                                                       double (*sBi)[33], int D, int i, int j, bool on, uint32_t* status,
+                                                       uint32_t flag, double& detm, int& dete) {
+  detm = 1.0;
+  dete = 0;
+  double mr = 0.0, mi = 0.0;
+  if (on) { mr = sAr[i][j]; mi = sAi[i][j]; }
+  int cur = 0;
+  for (int p = 0; p < D; ++p) {
+    double (*rr)[33] = cur ? sBr : sAr;
+    double (*ri)[33] = cur ? sBi : sAi;
+    double (*wr)[33] = cur ? sAr : sBr;
+    double (*wi)[33] = cur ? sAi : sBi;
+    double piv = rr[p][p];
+    if (!(piv > 1e-300)) {
+      piv = 1e-300;
+      if (threadIdx.x == 0) atomicOr(status, flag);
+    }
+    detm *= piv;
+    dete += __builtin_amdgcn_frexp_exp(detm);
+    detm = __builtin_amdgcn_frexp_mant(detm);
+    const double rp = rcp_f64(piv);
+    if (on) {
+      const double air = rr[i][p], aii = ri[i][p];
+      const double apr = rr[p][j], api = ri[p][j];
+      double nr, ni;
+      if (i == p && j == p) {
+        nr = rp; ni = 0.0;
+      } else if (i == p) {
+        nr = apr * rp; ni = api * rp;
+      } else if (j == p) {
+        nr = -air * rp; ni = -aii * rp;
+      } else {
+        nr = mr - (air * apr - aii * api) * rp;
+        ni = mi - (air * api + aii * apr) * rp;
+      }
+      mr = nr;
+      mi = ni;
+      wr[i][j] = nr;
+      wi[i][j] = ni;
+    }
+    __syncthreads();       // the sweep's writes are visible; the buffer just read may be overwritten next
+    cur ^= 1;
+  }
+  return cur;
+}
+
 // ----------------------------------------------------------------------------------------------
 // Factor kernel, 9 <= D <= 32: one workgroup per (segment, frequency, class), D*D active threads.
 // ----------------------------------------------------------------------------------------------
@@ -406,7 +456,7 @@ __global__ __launch_bounds__(1024) void em_factor_large(
     const double* __restrict__ part, const double* __restrict__ npart,
     double* __restrict__ coef, double* __restrict__ cmant, int32_t* __restrict__ cexp, uint32_t* __restrict__ status,
     int D, int K, ChunkMap cmap, int weight_mode) {
-  __shared__ double sMr[32][33], sMi[32][33];
+  __shared__ double sMr[32][33], sMi[32][33], sM2r[32][33], sM2i[32][33];
   __shared__ double sN[GSS_MAX_K];
   const int M = num_items(D);
   const long sf = blockIdx.x / K;
@@ -456,12 +506,13 @@ __global__ __launch_bounds__(1024) void em_factor_large(
   __syncthreads();
   double detm;
   int dete;
-  gauss_jordan_large(sMr, sMi, D, i, j, on, status, GSS_STATUS_NONPD_B, detm, dete);
+  const int where = gauss_jordan_large_2buf(sMr, sMi, sM2r, sM2i, D, i, j, on, status, GSS_STATUS_NONPD_B, detm, dete);
   if (on && i <= j) {
     const int m = item_index(i, j, D);
     double* c = coef + ((sf * (long)M + m) * K + k) * 2;
-    if (i == j) { c[0] = sMr[i][i]; c[1] = 0.0; }
-    else { c[0] = 2.0 * sMr[i][j]; c[1] = 2.0 * sMi[i][j]; }
+    const double ar = where ? sM2r[i][j] : sMr[i][j], ai = where ? sM2i[i][j] : sMi[i][j];
+    if (i == j) { c[0] = ar; c[1] = 0.0; }
+    else { c[0] = 2.0 * ar; c[1] = 2.0 * ai; }
   }
   if (tid == 0) {
     double pi;
