@@ -120,3 +120,41 @@ def test_super_segment_batching_reduced_meeting(env):
             xg = outs[i].cpu().numpy()
             assert np.linalg.norm(xg - xo) <= TOL_X * np.linalg.norm(xo)
         off += nf
+
+
+def test_recording_pipeline_full_hour(env):
+    """Config 4 at full size: a one-hour, 8-channel synthetic meeting with 1200 diarization segments and 7.5 s of
+    context per side through the pipeline driver (STFT of the recording once, padded batches of EM (15
+    iterations) + MVDR + iSTFT).  Every output has its segment's length and is finite; the bookkeeping matches
+    the oracle's for every segment; one interior segment is re-done end to end by the oracle, whose STFT is
+    taken over that segment's span plus the 768 samples on either side that its frames reach into."""
+    t, o, gss, synth, ctx, pipeline = (env[k] for k in ("torch", "o", "gss", "synth", "ctx", "pipeline"))
+    x, act_s, (st, en, spk) = synth.meeting(duration_s=3600.0, n_segments=1200)
+    D, N = x.shape
+    ctx_s = 120_000
+    xd = t.from_numpy(x).cuda()
+    outs, fr = pipeline.enhance_recording(ctx, xd, act_s, st, en, spk, ctx_s, ctx_s, iters=15)
+    t.cuda.synchronize()
+    assert len(outs) == 1200 and ctx.get_status() == 0
+    for i in range(len(st)):
+        assert outs[i].shape[0] == int(en[i] - st[i])
+        ref = o.segment_frames(int(st[i]), int(en[i]), N, ctx_s, ctx_s)
+        for key in ("ext_start", "ext_end", "frame0", "n_frames", "cut_start", "cut_end"):
+            assert int(fr[key][i]) == ref[key]
+    assert all(bool(t.isfinite(v).all()) for v in outs[::50])
+    # the shortest segment whose extended span stays 768 samples clear of both ends of the recording
+    inner = [i for i in range(len(st)) if fr["ext_start"][i] >= 768 and fr["ext_end"][i] + 768 <= N]
+    i = min(inner, key=lambda k: int(fr["n_frames"][k]))
+    s0, e0 = int(fr["ext_start"][i]) - 768, int(fr["ext_end"][i]) + 768
+    f0, nf = int(fr["frame0"][i]), int(fr["n_frames"][i])
+    Ysub = o.stft_channels_last(x[:, s0:e0]).astype(np.complex64)       # its frame u is recording frame u + s0 / 256
+    u0 = f0 - s0 // 256
+    assert u0 == 3 and u0 + nf <= Ysub.shape[1]
+    Ys = Ysub[:, u0:u0 + nf]
+    act = np.concatenate([o.frame_activity(act_s, f0, nf), np.ones((1, nf), np.uint8)])
+    go = o.cacgmm_em(Ys, act, 15)
+    Xo, ro, _ = o.mvdr(Ys, go, int(spk[i]))
+    xo = o.istft(Xo, (nf - 3) * 256)[int(fr["cut_start"][i]):int(fr["cut_end"][i])]
+    xg = outs[i].cpu().numpy()
+    assert int(fr["ref"][i]) == ro
+    assert np.linalg.norm(xg - xo) <= TOL_X * np.linalg.norm(xo)
