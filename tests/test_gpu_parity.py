@@ -127,6 +127,43 @@ def test_channel_and_class_counts(env, D, K):
         assert np.linalg.norm(Xg[0] - Xo) / np.linalg.norm(Xo) <= TOL_X
 
 
+@pytest.mark.parametrize("D", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_every_small_instantiation(env, D):
+    """Every (D, K) kernel instantiation for D <= 8, K = 1..8, on two problems of 10 tiles with a ragged tail:
+    few problems on many workgroup slots, so every problem is cut into chunks and the factor kernel adds
+    several partial sums."""
+    for K in range(1, 9):
+        rng = np.random.default_rng(10 * D + K)
+        F, T = 2, 600
+        Y = (_cn(rng, (F, T, D)) * np.exp(rng.standard_normal((F, T, 1)))).astype(np.complex64)
+        act = (rng.random((K, T)) < 0.5).astype(np.uint8)
+        act[K - 1] = 1
+        T_len = np.array([T - 13], dtype=np.int32)
+        g = _gpu_em(env, Y[None], act[None], T_len, 3)[0]
+        go = env["o"].cacgmm_em_batch(Y[None], act[None], T_len, 3)[0]
+        assert np.max(np.abs(g - go)) <= TOL_GAMMA, (D, K)
+        assert np.all(g[:, :, T - 13:] == 0)
+    assert env["ctx"].get_status() == 0
+
+
+@pytest.mark.parametrize("D", [10, 20, 26, 32])
+def test_every_large_instantiation(env, D):
+    """Every (class count, items-per-lane) instantiation of the large-array kernels: K = 1..8 at one channel
+    count out of each items-per-lane range, problems cut into chunks."""
+    for K in range(1, 9):
+        rng = np.random.default_rng(10 * D + K)
+        F, T = 2, 330
+        Y = (_cn(rng, (F, T, D)) * np.exp(rng.standard_normal((F, T, 1)))).astype(np.complex64)
+        act = (rng.random((K, T)) < 0.5).astype(np.uint8)
+        act[K - 1] = 1
+        T_len = np.array([T - 9], dtype=np.int32)
+        g = _gpu_em(env, Y[None], act[None], T_len, 3)[0]
+        go = env["o"].cacgmm_em_batch(Y[None], act[None], T_len, 3)[0]
+        assert np.max(np.abs(g - go)) <= TOL_GAMMA, (D, K)
+        assert np.all(g[:, :, T - 9:] == 0)
+    assert env["ctx"].get_status() == 0
+
+
 @pytest.mark.parametrize("D,K,T", [(9, 3, 100), (12, 5, 150), (16, 2, 70), (24, 5, 200), (32, 4, 130)])
 def test_large_arrays(env, D, K, T):
     """9 <= D <= 32 channels (run-time D kernels)."""
