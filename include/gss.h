@@ -47,11 +47,14 @@ typedef enum gss_status {
 /* Limits of the kernels in this build. */
 #define GSS_MAX_D 32
 #define GSS_MAX_K 8
+#define GSS_WPE_MAX_D 8  /* gss_wpe: channels                                   */
+#define GSS_WPE_MAX_N 80 /* gss_wpe: channels x taps (size of the linear system) */
 
 /* Bits of the device status word (gss_get_status). */
 #define GSS_STATUS_NONPD_B 1u        /* a class scatter matrix had a non-positive pivot; the pivot was floored */
 #define GSS_STATUS_NONPD_PHI 2u      /* the loaded background covariance had a non-positive pivot; floored     */
 #define GSS_STATUS_BAD_TARGET 4u     /* a target index was outside [0, K); it was clamped                       */
+#define GSS_STATUS_NONPD_WPE 8u      /* the loaded WPE correlation matrix had a non-positive pivot; floored     */
 
 typedef struct gss_ctx gss_ctx;
 
@@ -77,6 +80,7 @@ int64_t gss_scratch_bytes(const gss_ctx* ctx);
  * dominant kernels are bracketed with HIP events on the stream they are launched on.
  *   which = 0: the accumulating EM pass kernel (one launch per EM iteration)
  *   which = 1: the EM factor kernel (one launch per EM iteration)
+ *   which = 2: the WPE covariance kernel (one launch per WPE iteration)
  * gss_profile_get waits for the recorded launches, returns their summed duration in milliseconds and
  * their count since the last call (both host pointers), and resets both.
  */
@@ -95,6 +99,24 @@ int gss_profile_get(gss_ctx* ctx, int which, double* total_ms, int64_t* launches
  */
 int gss_stft(gss_ctx* ctx, const float* x, int S, int D, int64_t N, int n_fft, int hop,
              float* Y, int T, void* stream);
+
+/*
+ * WPE dereverberation, independent per (segment, frequency): Section 2.1 removes the late reverberation
+ * X^tail of its signal model with the weighted-prediction-error algorithm it cites (variance-normalised
+ * delayed linear prediction) before the normalisation of Eq. (2).  With ytilde_t the stack of the `taps`
+ * observations y_{t-delay}, y_{t-delay-1}, ... (D * taps components, zero before the first frame) and x = y
+ * at the start, every iteration computes lambda_t = mean_d |x_{t,d}|^2 (floored at 1e-10 of its maximum
+ * over the segment), R = sum_t ytilde_t ytilde_t^H / lambda_t, P = sum_t ytilde_t y_t^H / lambda_t,
+ * G = (R + 1e-10 tr(R)/(D taps) I)^-1 P and x_t = y_t - G^H ytilde_t.
+ *   Y      [S][F][Tmax][D] complex64
+ *   T_len  [S] int32 or NULL: frames at t >= T_len[s] do not exist (no weight, nobody's past)
+ *   taps >= 1, delay >= 1, iters >= 0 (0 copies the input); the usual setting is 10, 2, 3
+ *   X      [S][F][Tmax][D] complex64 out, must not overlap Y; exact 0 at t >= T_len[s].  A bin that is
+ *          silent, or too short for any frame to have a past, comes back unchanged.
+ * Limits: D <= GSS_WPE_MAX_D, D * taps <= GSS_WPE_MAX_N, delay <= 64.  Arithmetic: fp64 throughout.
+ */
+int gss_wpe(gss_ctx* ctx, const float* Y, const int32_t* T_len, int S, int F, int Tmax, int D,
+            int taps, int delay, int iters, float* X, void* stream);
 
 /*
  * Guided cACGMM EM, independent per (segment, frequency): Eq. (2)-(5) and the EM loop of Section 2.2.

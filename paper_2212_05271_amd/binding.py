@@ -26,7 +26,7 @@ GSS_MAX_D, GSS_MAX_K = 32, 8
 EXPORTS = (
     "gss_create", "gss_destroy", "gss_strerror", "gss_version", "gss_get_status", "gss_scratch_bytes",
     "gss_profile_enable", "gss_profile_get",
-    "gss_stft", "gss_cacgmm_em", "gss_mvdr", "gss_istft", "gss_frames_from_segments", "gss_frame_activity",
+    "gss_stft", "gss_wpe", "gss_cacgmm_em", "gss_mvdr", "gss_istft", "gss_frames_from_segments", "gss_frame_activity",
 )
 
 
@@ -63,6 +63,8 @@ def _load():
     lib.gss_stft.restype = i32
     lib.gss_cacgmm_em.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]
     lib.gss_cacgmm_em.restype = i32
+    lib.gss_wpe.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]
+    lib.gss_wpe.restype = i32
     lib.gss_mvdr.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp]
     lib.gss_mvdr.restype = i32
     lib.gss_istft.argtypes = [vp, vp, i32, i32, i32, i32, vp, i64, vp]
@@ -186,6 +188,19 @@ def gss_cacgmm_em(ctx, Y, activity, T_len=None, iters=20, weight_mode=1, out=Non
     _check(_lib.gss_cacgmm_em(ctx.handle, _ptr(Y, torch.complex64, "Y"), _ptr(activity, torch.uint8, "activity"),
                               _ptr(T_len, torch.int32, "T_len"), S, F, Tmax, D, K, int(iters), int(weight_mode),
                               _ptr(out, torch.float32, "gamma"), _stream()), "gss_cacgmm_em")
+    return out
+
+
+def gss_wpe(ctx, Y, T_len=None, taps=10, delay=2, iters=3, out=None):
+    """Y[S,F,Tmax,D] complex64 -> dereverberated X[S,F,Tmax,D] complex64 (a new tensor unless `out` is given)."""
+    import torch
+    S, F, Tmax, D = Y.shape
+    if out is None:
+        out = torch.empty((S, F, Tmax, D), dtype=torch.complex64, device=Y.device)
+    if tuple(out.shape) != (S, F, Tmax, D):
+        raise ValueError("out must be [S,F,Tmax,D]")
+    _check(_lib.gss_wpe(ctx.handle, _ptr(Y, torch.complex64, "Y"), _ptr(T_len, torch.int32, "T_len"), S, F, Tmax, D,
+                        int(taps), int(delay), int(iters), _ptr(out, torch.complex64, "X"), _stream()), "gss_wpe")
     return out
 
 

@@ -19,7 +19,7 @@
 #define GSS_EPS_SNR 1e-300      // floor on the background power in the reference-channel ratio
 
 #define GSS_PROFILE_SLOTS 64
-#define GSS_PROFILE_KERNELS 2     // 0: EM pass (accumulating), 1: EM factor
+#define GSS_PROFILE_KERNELS 3     // 0: EM pass (accumulating), 1: EM factor, 2: WPE covariance
 
 struct gss_ctx {
   int device;

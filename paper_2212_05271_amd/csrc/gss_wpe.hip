@@ -1,0 +1,464 @@
+// WPE dereverberation (arXiv 2212.05271, Section 2.1: the late reverberation X^tail of the signal model is
+// estimated with the weighted-prediction-error algorithm of the works cited there and subtracted) for gfx950.
+//
+// Per (segment, frequency), with ytilde_t the stack of the L delayed observations y_{t-Delta} .. y_{t-Delta-L+1}
+// (N = D L components, component tau*D + d = y_{t-Delta-tau, d}) and x = y at the start, each iteration is
+//
+//   power  : lambda_t = mean_d |x_{t,d}|^2, floored at 1e-10 of its maximum over the segment's frames
+//   cov    : R = sum_t ytilde_t ytilde_t^H / lambda_t  (N x N),  P = sum_t ytilde_t y_t^H / lambda_t  (N x D),
+//            fp64 partial sums per chunk of frames
+//   solve  : R += 1e-10 tr(R)/N I,  G = R^-1 P
+//   apply  : x_t = y_t - G^H ytilde_t  (and lambda for the next iteration, or the complex64 output)
+//
+// Everything up to the output is fp64: R is built from strongly correlated delayed copies of one signal and
+// the solve amplifies rounding errors of the sums by its condition number.
+#include "gss_internal.h"
+
+#include "gss_device.h"
+
+namespace {
+
+constexpr int kWpeThreads = 256;
+constexpr int kWpeTile = 64;                  // frames per LDS window of the covariance kernel
+constexpr int kWpeBlockDoubles = 32;          // a 4 x 4 complex block of R or P per lane
+constexpr double kWpeEpsPowerRel = 1e-10;
+constexpr double kWpeLoadRel = 1e-10;
+
+__device__ inline int clamp_T(const int32_t* T_len, int s, int Tmax) {
+  int T = T_len ? T_len[s] : Tmax;
+  return T < 0 ? 0 : (T > Tmax ? Tmax : T);
+}
+
+// Maximum of lam[0..T) over a workgroup (every thread gets it).  `red` holds one double per wavefront.
+__device__ inline double block_max(const double* __restrict__ lam, int T, double* red) {
+  double m = 0.0;
+  for (int t = threadIdx.x; t < T; t += blockDim.x) m = fmax(m, lam[t]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) m = fmax(m, __shfl_xor(m, o));
+  const int wave = threadIdx.x / kWave;
+  if ((threadIdx.x & (kWave - 1)) == 0) red[wave] = m;
+  __syncthreads();
+  double r = 0.0;
+  for (int w = 0; w < (int)(blockDim.x / kWave); ++w) r = fmax(r, red[w]);
+  __syncthreads();
+  return r;
+}
+
+// lambda of the observation itself (first iteration): one thread per frame.
+__global__ __launch_bounds__(kWpeThreads) void wpe_power_kernel(const float2* __restrict__ Y, const int32_t* __restrict__ T_len,
+                                                                double* __restrict__ lam, int F, int Tmax, int D,
+                                                                int blocks_per_sf) {
+  const long sf = blockIdx.x / blocks_per_sf;
+  const int t = (blockIdx.x % blocks_per_sf) * kWpeThreads + threadIdx.x;
+  const int T = clamp_T(T_len, (int)(sf / F), Tmax);
+  if (t >= Tmax) return;
+  double p = 0.0;
+  if (t < T) {
+    const float2* __restrict__ y = Y + (sf * Tmax + t) * D;
+    for (int d = 0; d < D; ++d) {
+      const double re = y[d].x, im = y[d].y;
+      p += re * re + im * im;
+    }
+    p /= (double)D;
+  }
+  lam[sf * Tmax + t] = p;
+}
+
+// Lane l of the covariance kernel owns one 4 x 4 block: the first nb(nb+1)/2 lanes the blocks (bi >= bj) of
+// the lower triangle of R (nb = ceil(N/4)), the next nb * nbd lanes the blocks of P (nbd = ceil(D/4)).
+__host__ __device__ inline void wpe_block(int l, int nb, int nbd, int& bi, int& bj, bool& is_p, bool& valid) {
+  const int nR = nb * (nb + 1) / 2;
+  valid = l < nR + nb * nbd;
+  if (l < nR) {
+    bi = 0;
+    int rem = l;
+    while (rem > bi) { rem -= bi + 1; ++bi; }
+    bj = rem;
+    is_p = false;
+  } else {
+    const int m = valid ? l - nR : 0;
+    bi = m / nbd;
+    bj = m % nbd;
+    is_p = true;
+  }
+}
+
+// Covariance accumulation.  A workgroup takes a chunk of 64-frame tiles of one (segment, frequency).  Per
+// tile the frames t0-Delta-L+1 .. t0+63 are staged in LDS in DESCENDING time order: then ytilde_t is the
+// contiguous run of N values that starts Delta frames after frame t, and the values of y_t itself sit right
+// before it, whatever D is.  Each lane keeps its 4 x 4 block in registers and adds, frame by frame,
+// (w_t a_i) conj(b_j) for its four row values a and four column values b.  Rows >= N and columns >= N (or
+// >= D) of the last blocks take whatever follows in the window; nothing ever reads them.
+// part[(wg * 32 + j) * 256 + lane]: the 32 doubles (re, im of entry [i][j'], j = (i*4 + j')*2 + {0,1}).
+__global__ __launch_bounds__(kWpeThreads) void wpe_cov_kernel(const float2* __restrict__ Y, const int32_t* __restrict__ T_len,
+                                                              const double* __restrict__ lam, double* __restrict__ part,
+                                                              int F, int Tmax, int D, int taps, int delay, ChunkMap cmap,
+                                                              int win_elems) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  float2* __restrict__ sWin = reinterpret_cast<float2*>(lds_raw);
+  double* __restrict__ sWt = reinterpret_cast<double*>(lds_raw + (size_t)win_elems * sizeof(float2));
+  double* __restrict__ sRed = sWt + kWpeTile;
+
+  long sf;
+  int chunk, tpc;
+  chunk_decode(cmap, blockIdx.x, sf, chunk, tpc);
+  const int T = clamp_T(T_len, (int)(sf / F), Tmax);
+  const int N = D * taps;
+  const int nb = (N + 3) / 4, nbd = (D + 3) / 4;
+  int bi, bj;
+  bool is_p, valid;
+  wpe_block(threadIdx.x, nb, nbd, bi, bj, is_p, valid);
+  if (!valid) { bi = 0; bj = 0; is_p = false; }
+  const int aoff = delay * D + 4 * bi;
+  const int boff = is_p ? 4 * bj : delay * D + 4 * bj;
+
+  const double* __restrict__ lrow = lam + sf * Tmax;
+  const double floor_l = kWpeEpsPowerRel * block_max(lrow, T, sRed);
+  const float2* __restrict__ Yrow = Y + sf * (long)Tmax * D;
+
+  double ar_[4][4], ai_[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { ar_[i][j] = 0.0; ai_[i][j] = 0.0; }
+
+  const int tile_end = (T + kWpeTile - 1) / kWpeTile;
+  const int tile_lo = chunk * tpc;
+  const int tile_hi = tile_lo + tpc < tile_end ? tile_lo + tpc : tile_end;
+  const int win_frames = kWpeTile + delay + taps - 1;
+  for (int tile = tile_lo; tile < tile_hi; ++tile) {
+    const int t0 = tile * kWpeTile;
+    const int tmax = t0 + kWpeTile - 1;
+    __syncthreads();                                    // the previous tile's window is no longer read
+    for (int e = threadIdx.x; e < win_elems; e += kWpeThreads) {
+      const int r = e / D, d = e - r * D;
+      const int t = tmax - r;
+      float2 v = make_float2(0.f, 0.f);
+      if (r < win_frames && t >= 0 && t < T) v = Yrow[(long)t * D + d];
+      sWin[e] = v;
+    }
+    if (threadIdx.x < kWpeTile) {
+      const int t = t0 + threadIdx.x;
+      double w = 0.0;
+      if (t < T) {
+        const double l = fmax(lrow[t], floor_l);
+        w = l > 0.0 ? 1.0 / l : 0.0;                   // all-zero bin: no weight, R = 0, bin left unchanged
+      }
+      sWt[threadIdx.x] = w;
+    }
+    __syncthreads();
+#pragma unroll 2
+    for (int tt = 0; tt < kWpeTile; ++tt) {
+      const int base = (kWpeTile - 1 - tt) * D;
+      const double w = sWt[tt];
+      double war[4], wai[4], br[4], bim[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float2 a = sWin[base + aoff + i];
+        const float2 b = sWin[base + boff + i];
+        war[i] = w * (double)a.x;
+        wai[i] = w * (double)a.y;
+        br[i] = (double)b.x;
+        bim[i] = (double)b.y;
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {                   // a conj(b)
+          ar_[i][j] = fma(war[i], br[j], fma(wai[i], bim[j], ar_[i][j]));
+          ai_[i][j] = fma(wai[i], br[j], fma(-war[i], bim[j], ai_[i][j]));
+        }
+    }
+  }
+  double* __restrict__ out = part + (size_t)blockIdx.x * kWpeBlockDoubles * kWpeThreads + threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      out[(size_t)((i * 4 + j) * 2 + 0) * kWpeThreads] = ar_[i][j];
+      out[(size_t)((i * 4 + j) * 2 + 1) * kWpeThreads] = ai_[i][j];
+    }
+}
+
+// Solve.  One workgroup per (segment, frequency): sums the chunks' blocks into the augmented matrix
+// [R | P] in LDS (row pitch `pitch` complex doubles, chosen so that a column walk is free of bank
+// conflicts), loads the diagonal, and runs Gauss-Jordan elimination without pivoting (R is Hermitian
+// positive definite) and without scaling the pivot rows: after sweep p column p is never touched again, so
+// at the end row a of the right-hand part divided by the diagonal entry is row a of G.  One barrier per
+// sweep: sweep p reads row p and column p, and writes neither.
+// Out: Gc[sf][a][d] = conj(G[a][d]), the coefficient that multiplies ytilde_a in the prediction of y_d.
+__global__ __launch_bounds__(kWpeThreads) void wpe_solve_kernel(const double* __restrict__ part, double2* __restrict__ Gc,
+                                                                uint32_t* __restrict__ status, int D, int taps,
+                                                                ChunkMap cmap, int pitch) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  double2* __restrict__ M = reinterpret_cast<double2*>(lds_raw);
+  __shared__ double sTr[kWpeThreads / kWave];
+  const long sf = blockIdx.x;
+  const int N = D * taps;
+  const int W = N + D;
+  const int nb = (N + 3) / 4, nbd = (D + 3) / 4;
+  int count;
+  const long wg0 = chunk_base(cmap, sf, count);
+
+  int bi, bj;
+  bool is_p, valid;
+  wpe_block(threadIdx.x, nb, nbd, bi, bj, is_p, valid);
+  double tr = 0.0;
+  if (valid) {
+    double v[kWpeBlockDoubles];
+#pragma unroll
+    for (int j = 0; j < kWpeBlockDoubles; ++j) v[j] = 0.0;
+    for (int c = 0; c < count; ++c) {
+      const double* __restrict__ src = part + (size_t)(wg0 + c) * kWpeBlockDoubles * kWpeThreads + threadIdx.x;
+#pragma unroll
+      for (int j = 0; j < kWpeBlockDoubles; ++j) v[j] += src[(size_t)j * kWpeThreads];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int a = 4 * bi + i;
+        const int b = 4 * bj + j;
+        const double re = v[(i * 4 + j) * 2], im = v[(i * 4 + j) * 2 + 1];
+        if (is_p) {
+          if (a < N && b < D) M[a * pitch + N + b] = make_double2(re, im);
+        } else if (a < N && b < N) {
+          if (bi != bj) {
+            M[a * pitch + b] = make_double2(re, im);
+            M[b * pitch + a] = make_double2(re, -im);
+          } else if (i > j) {                            // diagonal block: the lower part, mirrored
+            M[a * pitch + b] = make_double2(re, im);
+            M[b * pitch + a] = make_double2(re, -im);
+          } else if (i == j) {
+            M[a * pitch + a] = make_double2(re, 0.0);
+            tr += re;
+          }
+        }
+      }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) tr += __shfl_xor(tr, o);
+  if ((threadIdx.x & (kWave - 1)) == 0) sTr[threadIdx.x / kWave] = tr;
+  __syncthreads();
+  tr = 0.0;
+  for (int w = 0; w < kWpeThreads / kWave; ++w) tr += sTr[w];
+  double2* __restrict__ out = Gc + sf * (long)N * D;
+  if (!(tr > 0.0)) {                                     // no frame has a past (or silence): G = 0
+    for (int e = threadIdx.x; e < N * D; e += kWpeThreads) out[e] = make_double2(0.0, 0.0);
+    return;
+  }
+  const double load = kWpeLoadRel * tr / (double)N;
+  for (int a = threadIdx.x; a < N; a += kWpeThreads) M[a * pitch + a].x += load;
+  __syncthreads();
+
+  // thread (r, g): row r, columns p+1+g, p+1+g+G, ... with G = threads / N column groups per row
+  const int groups = kWpeThreads / N > 0 ? kWpeThreads / N : 1;
+  const int r = threadIdx.x % N;
+  const int g = threadIdx.x / N;
+  const bool worker = g < groups;
+  const double tiny = 1e-300;
+  for (int p = 0; p < N; ++p) {
+    if (worker && r != p) {
+      double piv = M[p * pitch + p].x;
+      if (!(piv > tiny)) {
+        if (r == (p == 0 ? 1 : 0) && g == 0) atomicOr(status, GSS_STATUS_NONPD_WPE);
+        piv = tiny;
+      }
+      const double inv = rcp_f64(piv);
+      const double2 mrp = M[r * pitch + p];
+      const double fr = mrp.x * inv, fi = mrp.y * inv;
+      for (int c = p + 1 + g; c < W; c += groups) {
+        const double2 pc = M[p * pitch + c];
+        double2 rc = M[r * pitch + c];
+        rc.x = fma(-fr, pc.x, fma(fi, pc.y, rc.x));      // rc -= f * pc
+        rc.y = fma(-fr, pc.y, fma(-fi, pc.x, rc.y));
+        M[r * pitch + c] = rc;
+      }
+    }
+    __syncthreads();
+  }
+  for (int e = threadIdx.x; e < N * D; e += kWpeThreads) {
+    const int a = e / D, d = e - a * D;
+    double piv = M[a * pitch + a].x;
+    piv = piv > tiny ? piv : tiny;
+    const double inv = rcp_f64(piv);
+    const double2 v = M[a * pitch + N + d];
+    out[e] = make_double2(v.x * inv, -v.y * inv);
+  }
+}
+
+// Apply: lane = frame.  The frames t0-Delta-L+1 .. t0+255 of the bin are staged in LDS (row pitch odd in
+// 8-byte units for even D, so that the lanes' rows start in different banks); every lane then subtracts
+// the prediction, walking the N components of ytilde_t while the N x D coefficients, which are the same for
+// all lanes, come through the scalar path.  FINAL: writes the complex64 output (zero at t >= T); otherwise
+// writes lambda_t of the new estimate for the next iteration.
+template <int D, bool FINAL>
+__global__ __launch_bounds__(kWpeThreads) void wpe_apply_kernel(const float2* __restrict__ Y, const int32_t* __restrict__ T_len,
+                                                                const double2* __restrict__ Gc, double* __restrict__ lam,
+                                                                float2* __restrict__ X, int F, int Tmax, int taps, int delay,
+                                                                int blocks_per_sf, int pitch) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  float2* __restrict__ sWin = reinterpret_cast<float2*>(lds_raw);
+  const long sf = blockIdx.x / blocks_per_sf;
+  const int t0 = (blockIdx.x % blocks_per_sf) * kWpeThreads;
+  const int T = clamp_T(T_len, (int)(sf / F), Tmax);
+  const int t = t0 + threadIdx.x;
+  const int N = D * taps;
+  if (t0 >= T) {                                         // nothing valid in this block
+    if (t < Tmax) {
+      if constexpr (FINAL) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) X[(sf * Tmax + t) * D + d] = make_float2(0.f, 0.f);
+      } else {
+        lam[sf * Tmax + t] = 0.0;
+      }
+    }
+    return;
+  }
+  const int past = delay + taps - 1;                     // frames before t0 that the block needs
+  const int rows = kWpeThreads + past;
+  const float2* __restrict__ Yrow = Y + sf * (long)Tmax * D;
+  for (int e = threadIdx.x; e < rows * D; e += kWpeThreads) {
+    const int r = e / D, d = e - r * D;
+    const int tt = t0 - past + r;
+    float2 v = make_float2(0.f, 0.f);
+    if (tt >= 0 && tt < T) v = Yrow[(long)tt * D + d];
+    sWin[r * pitch + d] = v;
+  }
+  __syncthreads();
+  double xr[D], xi[D];
+  const float2* __restrict__ mine = sWin + (threadIdx.x + past) * pitch;
+#pragma unroll
+  for (int d = 0; d < D; ++d) { xr[d] = (double)mine[d].x; xi[d] = (double)mine[d].y; }
+  typedef const __attribute__((address_space(4))) double* cptr_t;
+  const cptr_t g4 = (cptr_t)(uintptr_t)(Gc + sf * (long)N * D);
+  for (int tau = 0; tau < taps; ++tau) {
+    const float2* __restrict__ src = mine - (delay + tau) * pitch;
+#pragma unroll
+    for (int dp = 0; dp < D; ++dp) {
+      const float2 v = src[dp];
+      const double vr = (double)v.x, vi = (double)v.y;
+      const cptr_t c = g4 + ((long)(tau * D + dp) * D) * 2;
+#pragma unroll
+      for (int d = 0; d < D; ++d) {                      // x_d -= c[d] * v
+        const double cr = c[2 * d], ci = c[2 * d + 1];
+        xr[d] = fma(-cr, vr, fma(ci, vi, xr[d]));
+        xi[d] = fma(-cr, vi, fma(-ci, vr, xi[d]));
+      }
+    }
+  }
+  if (t >= Tmax) return;
+  if constexpr (FINAL) {
+    float2* __restrict__ o = X + (sf * Tmax + t) * D;
+#pragma unroll
+    for (int d = 0; d < D; ++d) o[d] = t < T ? make_float2((float)xr[d], (float)xi[d]) : make_float2(0.f, 0.f);
+  } else {
+    double p = 0.0;
+#pragma unroll
+    for (int d = 0; d < D; ++d) p += xr[d] * xr[d] + xi[d] * xi[d];
+    lam[sf * Tmax + t] = t < T ? p / (double)D : 0.0;
+  }
+}
+
+// iters == 0: the output is the input (zero at t >= T).
+__global__ __launch_bounds__(kWpeThreads) void wpe_copy_kernel(const float2* __restrict__ Y, const int32_t* __restrict__ T_len,
+                                                               float2* __restrict__ X, int F, int Tmax, int D, long n) {
+  const long i = (long)blockIdx.x * kWpeThreads + threadIdx.x;
+  if (i >= n) return;
+  const long frame = i / D;
+  const int t = (int)(frame % Tmax);
+  const int s = (int)(frame / Tmax / F);
+  X[i] = t < clamp_T(T_len, s, Tmax) ? Y[i] : make_float2(0.f, 0.f);
+}
+
+template <int D>
+int run_wpe(gss_ctx* ctx, const float2* Y, const int32_t* T_len, int S, int F, int Tmax, int taps, int delay, int iters,
+            float2* X, hipStream_t st) {
+  const long n_sf = (long)S * F;
+  const int N = D * taps;
+  const int W = N + D;
+  const int tiles = (Tmax + kWpeTile - 1) / kWpeTile;
+  // covariance kernel: window of 64 + delay + taps - 1 frames, plus room for the overrun of the last blocks
+  const int win_elems = (kWpeTile + delay + taps) * D + 8;
+  const int cov_lds = (int)(win_elems * sizeof(float2) + (kWpeTile + kWpeThreads / kWave) * sizeof(double));
+  int per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, wpe_cov_kernel, kWpeThreads, (size_t)cov_lds) != hipSuccess ||
+      per_cu < 1)
+    per_cu = 1;
+  const ChunkMap cmap = plan_chunk_map((long)ctx->num_cu * per_cu, n_sf, tiles, 1, 0, true);
+  const long wgs = chunk_map_wgs(cmap, n_sf);
+  const long blocks_per_sf = (Tmax + kWpeThreads - 1) / kWpeThreads;
+  if (wgs > 0x7fffffffL || n_sf * blocks_per_sf > 0x7fffffffL) return GSS_EUNSUPPORTED;
+  // solve kernel: [R | P] with a row pitch = 1 mod 8 complex doubles
+  int pitch = W;
+  while (pitch % 8 != 1) ++pitch;
+  const int solve_lds = (int)((size_t)N * pitch * sizeof(double2));
+  // apply kernel: row pitch odd for even D
+  const int apitch = D | 1;
+  const int apply_lds = (int)((size_t)(kWpeThreads + delay + taps - 1) * apitch * sizeof(float2));
+  if (solve_lds > 160 * 1024 - 1024 || apply_lds > 64 * 1024 || cov_lds > 64 * 1024) return GSS_EUNSUPPORTED;
+  if (hipFuncSetAttribute((const void*)wpe_solve_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, solve_lds) != hipSuccess)
+    return GSS_EHIP;
+
+  size_t o = 0;
+  const size_t off_lam = o;  o = gss_align_up(o + (size_t)n_sf * Tmax * sizeof(double), 256);
+  const size_t off_g = o;    o = gss_align_up(o + (size_t)n_sf * N * D * sizeof(double2), 256);
+  const size_t off_part = o; o = gss_align_up(o + (size_t)wgs * kWpeBlockDoubles * kWpeThreads * sizeof(double), 256);
+  const int rc = gss_ensure_scratch(ctx, o);
+  if (rc != GSS_OK) return rc;
+  char* base = (char*)ctx->scratch;
+  double* lam = (double*)(base + off_lam);
+  double2* Gc = (double2*)(base + off_g);
+  double* part = (double*)(base + off_part);
+
+  const dim3 block(kWpeThreads);
+  const dim3 frame_grid((unsigned)(n_sf * blocks_per_sf));
+  hipLaunchKernelGGL(wpe_power_kernel, frame_grid, block, 0, st, Y, T_len, lam, F, Tmax, D, (int)blocks_per_sf);
+  for (int it = 0; it < iters; ++it) {
+    gss_profile_begin(ctx, 2, st);
+    hipLaunchKernelGGL(wpe_cov_kernel, dim3((unsigned)wgs), block, cov_lds, st, Y, T_len, lam, part, F, Tmax, D, taps, delay,
+                       cmap, win_elems);
+    gss_profile_end(ctx, 2, st);
+    hipLaunchKernelGGL(wpe_solve_kernel, dim3((unsigned)n_sf), block, solve_lds, st, part, Gc, ctx->status, D, taps, cmap,
+                       pitch);
+    if (it + 1 < iters)
+      hipLaunchKernelGGL((wpe_apply_kernel<D, false>), frame_grid, block, apply_lds, st, Y, T_len, Gc, lam, X, F, Tmax, taps,
+                         delay, (int)blocks_per_sf, apitch);
+    else
+      hipLaunchKernelGGL((wpe_apply_kernel<D, true>), frame_grid, block, apply_lds, st, Y, T_len, Gc, lam, X, F, Tmax, taps,
+                         delay, (int)blocks_per_sf, apitch);
+  }
+  if (hipGetLastError() != hipSuccess) return GSS_EHIP;
+  return GSS_OK;
+}
+
+}  // namespace
+
+extern "C" int gss_wpe(gss_ctx* ctx, const float* Y, const int32_t* T_len, int S, int F, int Tmax, int D,
+                       int taps, int delay, int iters, float* X, void* stream) {
+  if (!ctx || !Y || !X || Y == X) return GSS_EINVAL;
+  if (S <= 0 || F <= 0 || Tmax <= 0 || D <= 0 || taps <= 0 || delay <= 0 || iters < 0) return GSS_EINVAL;
+  if (D > GSS_WPE_MAX_D || (long)D * taps > GSS_WPE_MAX_N || (long)D * taps > kWpeThreads || delay > 64) return GSS_EUNSUPPORTED;
+  {
+    const int N = D * taps, nb = (N + 3) / 4, nbd = (D + 3) / 4;
+    if (nb * (nb + 1) / 2 + nb * nbd > kWpeThreads) return GSS_EUNSUPPORTED;   // one block per lane
+  }
+  if (hipSetDevice(ctx->device) != hipSuccess) return GSS_EHIP;
+  hipStream_t st = (hipStream_t)stream;
+  const float2* Yc = (const float2*)Y;
+  float2* Xc = (float2*)X;
+  if (iters == 0) {
+    const long n = (long)S * F * Tmax * D;
+    const long blocks = (n + kWpeThreads - 1) / kWpeThreads;
+    if (blocks > 0x7fffffffL) return GSS_EUNSUPPORTED;
+    hipLaunchKernelGGL(wpe_copy_kernel, dim3((unsigned)blocks), dim3(kWpeThreads), 0, st, Yc, T_len, Xc, F, Tmax, D, n);
+    return hipGetLastError() == hipSuccess ? GSS_OK : GSS_EHIP;
+  }
+  switch (D) {
+#define GSS_CASE_D(DD) \
+  case DD: return run_wpe<DD>(ctx, Yc, T_len, S, F, Tmax, taps, delay, iters, Xc, st);
+    GSS_CASE_D(1) GSS_CASE_D(2) GSS_CASE_D(3) GSS_CASE_D(4) GSS_CASE_D(5) GSS_CASE_D(6) GSS_CASE_D(7) GSS_CASE_D(8)
+#undef GSS_CASE_D
+    default: return GSS_EUNSUPPORTED;
+  }
+}

@@ -1,0 +1,120 @@
+"""GPU parity of gss_wpe (through the C ABI) against the float64 WPE oracle on the same seeded inputs.
+Tolerance: relative L2 error of the dereverberated STFT <= 1e-4 per frequency bin (the bar of the
+beamformed STFT; both sides compute in fp64 and the output is rounded to complex64, so the measured error
+is the fp32 rounding, ~4e-8); structural zeros (t >= T_len) bit-exact."""
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+TOL_X = 1e-4
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from oracle import wpe_oracle as w
+    from paper_2212_05271_amd import binding as gss
+    from paper_2212_05271_amd import synth
+    ctx = gss.Context(0)
+    yield dict(torch=torch, w=w, gss=gss, synth=synth, ctx=ctx)
+    ctx.close()
+
+
+def _gpu_wpe(env, Y, T_len, taps, delay, iters):
+    t = env["torch"]
+    Yd = t.from_numpy(np.ascontiguousarray(Y, dtype=np.complex64)).cuda()
+    Td = None if T_len is None else t.from_numpy(np.asarray(T_len, dtype=np.int32)).cuda()
+    X = env["gss"].gss_wpe(env["ctx"], Yd, Td, taps, delay, iters)
+    t.cuda.synchronize()
+    return X.cpu().numpy()
+
+
+def _rel(a, b):
+    return np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300)
+
+
+def _check(env, Y, T_len, taps, delay, iters, fsel=None):
+    """Y [S,F,T,D] complex64; compares every (segment, selected bin) with the oracle."""
+    S, F, T, D = Y.shape
+    X = _gpu_wpe(env, Y, T_len, taps, delay, iters)
+    assert X.shape == Y.shape and X.dtype == np.complex64
+    assert np.all(np.isfinite(X.view(np.float32)))
+    fs = np.arange(F) if fsel is None else np.asarray(fsel)
+    worst = 0.0
+    for s in range(S):
+        Tv = T if T_len is None else int(T_len[s])
+        want = env["w"].wpe(Y[s][fs].astype(np.complex128), taps, delay, iters, T_valid=Tv)
+        assert np.array_equal(X[s][:, Tv:], np.zeros_like(X[s][:, Tv:]))
+        for i, f in enumerate(fs):
+            if np.linalg.norm(want[i]) == 0.0:
+                assert np.array_equal(X[s, f], np.zeros_like(X[s, f]))
+                continue
+            worst = max(worst, _rel(X[s, f], want[i]))
+    assert worst <= TOL_X, worst
+    return worst
+
+
+@pytest.mark.parametrize("D,taps,delay,T", [(4, 5, 2, 300), (8, 10, 2, 700), (3, 7, 3, 333), (1, 1, 1, 130), (2, 10, 2, 64),
+                                             (5, 16, 1, 450), (8, 3, 5, 129), (7, 11, 2, 500)])
+def test_wpe_shapes(env, D, taps, delay, T):
+    Y, _, _ = env["synth"].reverberant_stft(F=6, T=T, D=D, order=min(taps, 6), delay=delay, seed=D * 100 + taps)
+    _check(env, Y[None], None, taps, delay, 3)
+
+
+def test_wpe_iterations_and_actual_dereverberation(env):
+    Y, S_dry, _ = env["synth"].reverberant_stft(F=8, T=1200, D=4, order=5, delay=2, seed=3)
+    for iters in (0, 1, 2, 5):
+        _check(env, Y[None], None, 5, 2, iters)
+    X = _gpu_wpe(env, Y[None], None, 5, 2, 3)[0]
+    n = np.linalg.norm
+    assert n(X - S_dry) < 0.4 * n(Y - S_dry)            # the output is much closer to the dry signal than the input
+
+
+def test_wpe_ragged_batch(env):
+    rng = np.random.default_rng(0)
+    S, F, T, D = 3, 5, 520, 8
+    Y = np.stack([env["synth"].reverberant_stft(F=F, T=T, D=D, seed=10 + s)[0] for s in range(S)])
+    T_len = np.array([520, 301, 77], dtype=np.int32)
+    for s in range(S):                                   # garbage in the padding must not matter
+        Y[s, :, T_len[s]:] = (rng.standard_normal((F, T - T_len[s], D)) * 50).astype(np.complex64)
+    _check(env, Y, T_len, 10, 2, 3)
+
+
+def test_wpe_degenerate(env):
+    rng = np.random.default_rng(1)
+    F, T, D = 4, 200, 4
+    Y = ((rng.standard_normal((1, F, T, D)) + 1j * rng.standard_normal((1, F, T, D))) * 0.5).astype(np.complex64)
+    Y[0, 1] = 0.0                                        # a silent bin
+    Y[0, 2, :, :] = 0.0
+    Y[0, 2, 17] = 1.0                                    # one non-zero frame: the variance floor at work
+    _check(env, Y, None, 6, 2, 3)
+    _check(env, Y[:, :, :2], None, 6, 2, 3)              # no frame has a past: unchanged
+    X = _gpu_wpe(env, Y[:, :, :2], None, 6, 2, 3)
+    assert np.array_equal(X, Y[:, :, :2])
+    _check(env, Y, np.array([0], dtype=np.int32), 6, 2, 3)   # empty segment
+    st = env["ctx"].get_status() if hasattr(env["ctx"], "get_status") else 0
+    assert st == 0
+
+
+def test_wpe_rejects_unsupported_shapes(env):
+    t = env["torch"]
+    gss = env["gss"]
+    Y = t.zeros((1, 2, 50, 9), dtype=t.complex64).cuda()
+    with pytest.raises(Exception):
+        gss.gss_wpe(env["ctx"], Y, None, 2, 2, 1)        # more than 8 channels
+    Y = t.zeros((1, 2, 50, 8), dtype=t.complex64).cuda()
+    with pytest.raises(Exception):
+        gss.gss_wpe(env["ctx"], Y, None, 11, 2, 1)       # 8 x 11 > 80
+    with pytest.raises(Exception):
+        gss.gss_wpe(env["ctx"], Y, None, 10, 0, 1)       # delay must be positive
+    with pytest.raises(Exception):
+        gss.gss_wpe(env["ctx"], Y, None, 10, 2, 1, out=Y)   # in place is not allowed
+
+
+def test_wpe_full_size_sampled_bins(env):
+    """The configuration that is timed (513 x 1560 x 8, 10 taps, delay 2, 3 iterations): all bins on the
+    GPU, a sample of them on the oracle."""
+    Y, _, _ = env["synth"].reverberant_stft(F=513, T=1560, D=8, seed=0)
+    _check(env, Y[None], None, 10, 2, 3, fsel=[0, 1, 100, 255, 256, 511, 512])
