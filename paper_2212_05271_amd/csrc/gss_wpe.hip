@@ -180,18 +180,12 @@ __global__ __launch_bounds__(kWpeThreads) void wpe_cov_kernel(const float2* __re
     }
 }
 
-// Solve.  One workgroup per (segment, frequency): sums the chunks' blocks into the augmented matrix
-// [R | P] in LDS (row pitch `pitch` complex doubles, chosen so that a column walk is free of bank
-// conflicts), loads the diagonal, and runs Gauss-Jordan elimination without pivoting (R is Hermitian
-// positive definite) and without scaling the pivot rows: after sweep p column p is never touched again, so
-// at the end row a of the right-hand part divided by the diagonal entry is row a of G.  One barrier per
-// sweep: sweep p reads row p and column p, and writes neither.
-// Out: Gc[sf][a][d] = conj(G[a][d]), the coefficient that multiplies ytilde_a in the prediction of y_d.
-__global__ __launch_bounds__(kWpeThreads) void wpe_solve_kernel(const double* __restrict__ part, double2* __restrict__ Gc,
-                                                                uint32_t* __restrict__ status, int D, int taps,
-                                                                ChunkMap cmap, int pitch) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  double2* __restrict__ M = reinterpret_cast<double2*>(lds_raw);
+// Assemble.  One workgroup per (segment, frequency): lane l sums its block over the chunks and writes the
+// entries, with the Hermitian mirror image, into the augmented matrix A[sf] = [R | P] (N rows of N + D
+// complex doubles) in global memory; the trace of R goes to trace[sf].
+__global__ __launch_bounds__(kWpeThreads) void wpe_assemble_kernel(const double* __restrict__ part, double2* __restrict__ A,
+                                                                   double* __restrict__ trace, int D, int taps,
+                                                                   ChunkMap cmap) {
   __shared__ double sTr[kWpeThreads / kWave];
   const long sf = blockIdx.x;
   const int N = D * taps;
@@ -199,6 +193,7 @@ __global__ __launch_bounds__(kWpeThreads) void wpe_solve_kernel(const double* __
   const int nb = (N + 3) / 4, nbd = (D + 3) / 4;
   int count;
   const long wg0 = chunk_base(cmap, sf, count);
+  double2* __restrict__ M = A + sf * (long)N * W;
 
   int bi, bj;
   bool is_p, valid;
@@ -221,16 +216,13 @@ __global__ __launch_bounds__(kWpeThreads) void wpe_solve_kernel(const double* __
         const int b = 4 * bj + j;
         const double re = v[(i * 4 + j) * 2], im = v[(i * 4 + j) * 2 + 1];
         if (is_p) {
-          if (a < N && b < D) M[a * pitch + N + b] = make_double2(re, im);
+          if (a < N && b < D) M[a * W + N + b] = make_double2(re, im);
         } else if (a < N && b < N) {
-          if (bi != bj) {
-            M[a * pitch + b] = make_double2(re, im);
-            M[b * pitch + a] = make_double2(re, -im);
-          } else if (i > j) {                            // diagonal block: the lower part, mirrored
-            M[a * pitch + b] = make_double2(re, im);
-            M[b * pitch + a] = make_double2(re, -im);
+          if (bi != bj || i > j) {                       // below the diagonal: the entry and its mirror image
+            M[a * W + b] = make_double2(re, im);
+            M[b * W + a] = make_double2(re, -im);
           } else if (i == j) {
-            M[a * pitch + a] = make_double2(re, 0.0);
+            M[a * W + a] = make_double2(re, 0.0);
             tr += re;
           }
         }
@@ -240,50 +232,125 @@ __global__ __launch_bounds__(kWpeThreads) void wpe_solve_kernel(const double* __
   for (int o = 32; o > 0; o >>= 1) tr += __shfl_xor(tr, o);
   if ((threadIdx.x & (kWave - 1)) == 0) sTr[threadIdx.x / kWave] = tr;
   __syncthreads();
-  tr = 0.0;
-  for (int w = 0; w < kWpeThreads / kWave; ++w) tr += sTr[w];
+  if (threadIdx.x == 0) {
+    double t = 0.0;
+    for (int w = 0; w < kWpeThreads / kWave; ++w) t += sTr[w];
+    trace[sf] = t;
+  }
+}
+
+// Solve.  One workgroup of 16 x 32 threads per (segment, frequency) keeps the whole augmented matrix in
+// registers: thread (i, j) owns rows i, i+16, ... and columns j, j+32, j+64.  Gauss-Jordan elimination without
+// pivoting (R + loading is Hermitian positive definite) and without scaling the pivot rows: after sweep p
+// column p is never touched again, so at the end row a of the right-hand part divided by pivot a is row a of
+// G.  Per sweep the owners publish the pivot row and the pivot column of the NEXT sweep in LDS (two
+// buffers, one barrier per sweep); every thread reads the values for its rows and columns from there.
+// Out: Gc[sf][a][d] = conj(G[a][d]), the coefficient that multiplies ytilde_a in the prediction of y_d.
+constexpr int kSolveTR = 16, kSolveTC = 32;
+constexpr int kSolveThreads = kSolveTR * kSolveTC;
+constexpr int kSolveKR = (GSS_WPE_MAX_N + kSolveTR - 1) / kSolveTR;                      // rows per thread
+constexpr int kSolveMC = (GSS_WPE_MAX_N + GSS_WPE_MAX_D + kSolveTC - 1) / kSolveTC;      // columns per thread
+constexpr int kSolveRowBuf = kSolveMC * kSolveTC, kSolveColBuf = kSolveKR * kSolveTR;
+
+__global__ __launch_bounds__(kSolveThreads) void wpe_solve_kernel(const double2* __restrict__ A, const double* __restrict__ trace,
+                                                                double2* __restrict__ Gc, uint32_t* __restrict__ status,
+                                                                int D, int taps) {
+  __shared__ double2 sRow[2][kSolveRowBuf];
+  __shared__ double2 sCol[2][kSolveColBuf];
+  __shared__ double sPiv[kSolveColBuf];
+  const long sf = blockIdx.x;
+  const int N = D * taps;
+  const int W = N + D;
+  const int j = threadIdx.x % kSolveTC, i = threadIdx.x / kSolveTC;
   double2* __restrict__ out = Gc + sf * (long)N * D;
+  const double tr = trace[sf];
   if (!(tr > 0.0)) {                                     // no frame has a past (or silence): G = 0
-    for (int e = threadIdx.x; e < N * D; e += kWpeThreads) out[e] = make_double2(0.0, 0.0);
+    for (int e = threadIdx.x; e < N * D; e += kSolveThreads) out[e] = make_double2(0.0, 0.0);
     return;
   }
   const double load = kWpeLoadRel * tr / (double)N;
-  for (int a = threadIdx.x; a < N; a += kWpeThreads) M[a * pitch + a].x += load;
+  const double2* __restrict__ M = A + sf * (long)N * W;
+  double tre[kSolveKR][kSolveMC], tim[kSolveKR][kSolveMC];
+#pragma unroll
+  for (int k = 0; k < kSolveKR; ++k)
+#pragma unroll
+    for (int m = 0; m < kSolveMC; ++m) {
+      const int r = i + kSolveTR * k, c = j + kSolveTC * m;
+      double2 v = make_double2(0.0, 0.0);
+      if (r < N && c < W) v = M[r * W + c];
+      if (r == c) v.x += load;
+      tre[k][m] = v.x;
+      tim[k][m] = v.y;
+    }
+  // Row q lives in register row q / TR of the threads with i == q % TR, column q in register column q / TC
+  // of the threads with j == q % TC: the register index is the same for the whole workgroup, so it is
+  // picked with scalar branches and only the lane test is a vector operation.
+  auto publish = [&](int q, int buf) {                   // row q and column q of the current matrix
+    const int kq = q / kSolveTR, mq = q / kSolveTC;
+    const bool row_owner = i == q % kSolveTR, col_owner = j == q % kSolveTC;
+#pragma unroll
+    for (int k = 0; k < kSolveKR; ++k)
+      if (k == kq && row_owner) {
+#pragma unroll
+        for (int m = 0; m < kSolveMC; ++m) sRow[buf][j + kSolveTC * m] = make_double2(tre[k][m], tim[k][m]);
+      }
+#pragma unroll
+    for (int m = 0; m < kSolveMC; ++m)
+      if (m == mq && col_owner) {
+#pragma unroll
+        for (int k = 0; k < kSolveKR; ++k) sCol[buf][i + kSolveTR * k] = make_double2(tre[k][m], tim[k][m]);
+      }
+  };
+  publish(0, 0);
   __syncthreads();
-
-  // thread (r, g): row r, columns p+1+g, p+1+g+G, ... with G = threads / N column groups per row
-  const int groups = kWpeThreads / N > 0 ? kWpeThreads / N : 1;
-  const int r = threadIdx.x % N;
-  const int g = threadIdx.x / N;
-  const bool worker = g < groups;
   const double tiny = 1e-300;
   for (int p = 0; p < N; ++p) {
-    if (worker && r != p) {
-      double piv = M[p * pitch + p].x;
-      if (!(piv > tiny)) {
-        if (r == (p == 0 ? 1 : 0) && g == 0) atomicOr(status, GSS_STATUS_NONPD_WPE);
-        piv = tiny;
-      }
-      const double inv = rcp_f64(piv);
-      const double2 mrp = M[r * pitch + p];
-      const double fr = mrp.x * inv, fi = mrp.y * inv;
-      for (int c = p + 1 + g; c < W; c += groups) {
-        const double2 pc = M[p * pitch + c];
-        double2 rc = M[r * pitch + c];
-        rc.x = fma(-fr, pc.x, fma(fi, pc.y, rc.x));      // rc -= f * pc
-        rc.y = fma(-fr, pc.y, fma(-fi, pc.x, rc.y));
-        M[r * pitch + c] = rc;
+    const int buf = p & 1;
+    double piv = sRow[buf][p].x;
+    if (!(piv > tiny)) {
+      if (threadIdx.x == 0) atomicOr(status, GSS_STATUS_NONPD_WPE);
+      piv = tiny;
+    }
+    if (threadIdx.x == 0) sPiv[p] = piv;
+    const double inv = rcp_f64(piv);
+    double fr[kSolveKR], fi[kSolveKR];
+    const int kp = p / kSolveTR;
+    const double keep = i == p % kSolveTR ? 0.0 : inv;   // the pivot row itself stays
+#pragma unroll
+    for (int k = 0; k < kSolveKR; ++k) {
+      const double2 v = sCol[buf][i + kSolveTR * k];     // rows >= N hold zeros, and so does their column entry
+      const double sc = k == kp ? keep : inv;
+      fr[k] = v.x * sc;
+      fi[k] = v.y * sc;
+    }
+#pragma unroll
+    for (int m = 0; m < kSolveMC; ++m) {
+      const int c = j + kSolveTC * m;
+      if (c > p && c < W) {
+        const double2 pc = sRow[buf][c];
+#pragma unroll
+        for (int k = 0; k < kSolveKR; ++k) {             // row r -= f_r * row p
+          tre[k][m] = fma(-fr[k], pc.x, fma(fi[k], pc.y, tre[k][m]));
+          tim[k][m] = fma(-fr[k], pc.y, fma(-fi[k], pc.x, tim[k][m]));
+        }
       }
     }
+    if (p + 1 < N) publish(p + 1, buf ^ 1);
     __syncthreads();
   }
-  for (int e = threadIdx.x; e < N * D; e += kWpeThreads) {
-    const int a = e / D, d = e - a * D;
-    double piv = M[a * pitch + a].x;
-    piv = piv > tiny ? piv : tiny;
-    const double inv = rcp_f64(piv);
-    const double2 v = M[a * pitch + N + d];
-    out[e] = make_double2(v.x * inv, -v.y * inv);
+#pragma unroll
+  for (int m = 0; m < kSolveMC; ++m) {
+    const int c = j + kSolveTC * m;
+    if (c >= N && c < W) {
+#pragma unroll
+      for (int k = 0; k < kSolveKR; ++k) {
+        const int r = i + kSolveTR * k;
+        if (r < N) {
+          const double inv = rcp_f64(sPiv[r]);
+          out[r * D + (c - N)] = make_double2(tre[k][m] * inv, -tim[k][m] * inv);
+        }
+      }
+    }
   }
 }
 
@@ -389,27 +456,25 @@ int run_wpe(gss_ctx* ctx, const float2* Y, const int32_t* T_len, int S, int F, i
   const long wgs = chunk_map_wgs(cmap, n_sf);
   const long blocks_per_sf = (Tmax + kWpeThreads - 1) / kWpeThreads;
   if (wgs > 0x7fffffffL || n_sf * blocks_per_sf > 0x7fffffffL) return GSS_EUNSUPPORTED;
-  // solve kernel: [R | P] with a row pitch = 1 mod 8 complex doubles
-  int pitch = W;
-  while (pitch % 8 != 1) ++pitch;
-  const int solve_lds = (int)((size_t)N * pitch * sizeof(double2));
   // apply kernel: row pitch odd for even D
   const int apitch = D | 1;
   const int apply_lds = (int)((size_t)(kWpeThreads + delay + taps - 1) * apitch * sizeof(float2));
-  if (solve_lds > 160 * 1024 - 1024 || apply_lds > 64 * 1024 || cov_lds > 64 * 1024) return GSS_EUNSUPPORTED;
-  if (hipFuncSetAttribute((const void*)wpe_solve_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, solve_lds) != hipSuccess)
-    return GSS_EHIP;
+  if (apply_lds > 64 * 1024 || cov_lds > 64 * 1024) return GSS_EUNSUPPORTED;
 
   size_t o = 0;
   const size_t off_lam = o;  o = gss_align_up(o + (size_t)n_sf * Tmax * sizeof(double), 256);
   const size_t off_g = o;    o = gss_align_up(o + (size_t)n_sf * N * D * sizeof(double2), 256);
   const size_t off_part = o; o = gss_align_up(o + (size_t)wgs * kWpeBlockDoubles * kWpeThreads * sizeof(double), 256);
+  const size_t off_a = o;    o = gss_align_up(o + (size_t)n_sf * N * W * sizeof(double2), 256);
+  const size_t off_tr = o;   o = gss_align_up(o + (size_t)n_sf * sizeof(double), 256);
   const int rc = gss_ensure_scratch(ctx, o);
   if (rc != GSS_OK) return rc;
   char* base = (char*)ctx->scratch;
   double* lam = (double*)(base + off_lam);
   double2* Gc = (double2*)(base + off_g);
   double* part = (double*)(base + off_part);
+  double2* A = (double2*)(base + off_a);
+  double* trace = (double*)(base + off_tr);
 
   const dim3 block(kWpeThreads);
   const dim3 frame_grid((unsigned)(n_sf * blocks_per_sf));
@@ -419,8 +484,8 @@ int run_wpe(gss_ctx* ctx, const float2* Y, const int32_t* T_len, int S, int F, i
     hipLaunchKernelGGL(wpe_cov_kernel, dim3((unsigned)wgs), block, cov_lds, st, Y, T_len, lam, part, F, Tmax, D, taps, delay,
                        cmap, win_elems);
     gss_profile_end(ctx, 2, st);
-    hipLaunchKernelGGL(wpe_solve_kernel, dim3((unsigned)n_sf), block, solve_lds, st, part, Gc, ctx->status, D, taps, cmap,
-                       pitch);
+    hipLaunchKernelGGL(wpe_assemble_kernel, dim3((unsigned)n_sf), block, 0, st, part, A, trace, D, taps, cmap);
+    hipLaunchKernelGGL(wpe_solve_kernel, dim3((unsigned)n_sf), dim3(kSolveThreads), 0, st, A, trace, Gc, ctx->status, D, taps);
     if (it + 1 < iters)
       hipLaunchKernelGGL((wpe_apply_kernel<D, false>), frame_grid, block, apply_lds, st, Y, T_len, Gc, lam, X, F, Tmax, taps,
                          delay, (int)blocks_per_sf, apitch);
