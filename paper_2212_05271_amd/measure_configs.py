@@ -103,11 +103,37 @@ def sweeps(torch, gss, ctx, synth):
           f"{(gu[:, :K - 1] - g_ref[:, :K - 1]).abs().max().item():.3f} |")
 
 
+def wpe_rows(torch, gss, ctx, synth):
+    """gss_wpe on a reverberant stand-in of config 1's shape (513 x 1560 x 8), 10 taps, delay 2: time per
+    call, audio seconds per second, and the algorithmic fp64 rate of the covariance kernel
+    (8 flops per complex multiply-add, N(N+1)/2 + N D entries per frame, N = D taps)."""
+    Y, _, _ = synth.reverberant_stft(F=513, T=1560, D=8, seed=0)
+    F, T, D = Y.shape
+    taps, delay = 10, 2
+    N = D * taps
+    Yd = torch.from_numpy(Y[None]).cuda()
+    X = gss.gss_wpe(ctx, Yd, None, taps, delay, 3)
+    audio = T * HOP / FS
+    print("| WPE iterations | ms | audio-s/s | covariance kernel: launches, mean us, TFLOP/s (alg.), of 78.6 |")
+    print("|---:|---:|---:|---|")
+    for it in (1, 2, 3):
+        t = _timeit(torch, lambda: gss.gss_wpe(ctx, Yd, None, taps, delay, it, out=X), 5)
+        ctx.profile_enable(True)
+        gss.gss_wpe(ctx, Yd, None, taps, delay, it, out=X)
+        ms, n = ctx.profile_get(2)
+        ctx.profile_enable(False)
+        flops = (N * (N + 1) // 2 + N * D) * 8 * F * T
+        tf = flops / (ms / n * 1e-3) / 1e12
+        print(f"| {it} | {t * 1e3:.3f} | {audio / t:,.0f} | {n}, {ms / n * 1e3:.1f}, {tf:.1f}, {100 * tf / PEAK_TFLOPS_F64:.0f} % |",
+              flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--meeting-s", type=float, default=300.0, help="duration of the config-4 meeting (0 = skip)")
     ap.add_argument("--sweeps", action="store_true",
                     help="only the parameter sweeps on config 1 (iterations, channels, noise class, weight mode)")
+    ap.add_argument("--wpe", action="store_true", help="only the dereverberation timing (config 1's shape)")
     a = ap.parse_args()
 
     import torch
@@ -117,6 +143,10 @@ def main():
     ctx = gss.Context(0)
     if a.sweeps:
         sweeps(torch, gss, ctx, synth)
+        ctx.close()
+        return
+    if a.wpe:
+        wpe_rows(torch, gss, ctx, synth)
         ctx.close()
         return
     print("| config | S | Tmax | D | K | iters | EM ms | MVDR ms | audio-s/s (EM+MVDR) | EM iters/s | bin-iters/s | "

@@ -39,12 +39,14 @@ def plan_batches(n_frames, max_batch_frames=200_000, max_segments=64):
 
 
 def enhance_recording(ctx, x, act_samples, seg_start, seg_end, seg_spk, ctx_left, ctx_right, iters=15,
-                      weight_mode=1, max_batch_frames=200_000, Yrec=None):
+                      weight_mode=1, max_batch_frames=200_000, Yrec=None, wpe_taps=0, wpe_delay=2, wpe_iters=3):
     """x[D, N] float32 CUDA tensor, act_samples[n_spk, N] uint8 (host), segments (host arrays).
 
     Classes per segment: the n_spk speakers in recording order plus a noise class that is always active
-    (K = n_spk + 1); the target class is the segment's speaker.  Returns a list of 1-D float32 CUDA
-    tensors (the enhanced target region of every segment) and a dict of bookkeeping arrays.
+    (K = n_spk + 1); the target class is the segment's speaker.  wpe_taps > 0 dereverberates every
+    segment's STFT (context included) with gss_wpe before the masks are estimated; masks and beamformer then
+    work on the dereverberated signal (Section 2.1).  Returns a list of 1-D float32 CUDA tensors (the
+    enhanced target region of every segment) and a dict of bookkeeping arrays.
     """
     import torch
 
@@ -74,6 +76,8 @@ def enhance_recording(ctx, x, act_samples, seg_start, seg_end, seg_spk, ctx_left
         T_d = torch.from_numpy(T_len).to(x.device)
         tgt = torch.from_numpy(np.asarray([seg_spk[i] for i in batch], dtype=np.int32)).to(x.device)
         ref = torch.full((S,), -1, dtype=torch.int32, device=x.device)
+        if wpe_taps > 0:
+            Y = gss.gss_wpe(ctx, Y, T_d, wpe_taps, wpe_delay, wpe_iters)
         gamma = gss.gss_cacgmm_em(ctx, Y, act_d, T_d, iters, weight_mode)
         X = gss.gss_mvdr(ctx, Y, gamma, tgt, ref, T_d)
         xh = gss.gss_istft(ctx, X, (Tmax - 3) * HOP)
@@ -131,7 +135,8 @@ def super_segment_pieces(members, seg_start, seg_end, n_samples, ctx_left, ctx_r
 
 
 def enhance_recording_super(ctx, x, act_samples, seg_start, seg_end, seg_spk, ctx_left, ctx_right,
-                            max_batch_s=50.0, iters=15, weight_mode=1, max_batch_frames=200_000, Yrec=None):
+                            max_batch_s=50.0, iters=15, weight_mode=1, max_batch_frames=200_000, Yrec=None,
+                            wpe_taps=0, wpe_delay=2, wpe_iters=3):
     """Super-segment batching.  Arguments as enhance_recording; max_batch_s bounds the summed member
     duration of a super-segment (seconds at 16 kHz).
 
@@ -178,6 +183,8 @@ def enhance_recording_super(ctx, x, act_samples, seg_start, seg_end, seg_spk, ct
         T_d = torch.from_numpy(T_len).to(x.device)
         tgt = torch.from_numpy(np.asarray([seg_spk[plans[b]["members"][0]] for b in batch], dtype=np.int32)).to(x.device)
         ref = torch.full((S,), -1, dtype=torch.int32, device=x.device)
+        if wpe_taps > 0:                                  # the concatenation is dereverberated as one segment
+            Y = gss.gss_wpe(ctx, Y, T_d, wpe_taps, wpe_delay, wpe_iters)
         gamma = gss.gss_cacgmm_em(ctx, Y, torch.from_numpy(act).to(x.device), T_d, iters, weight_mode)
         X = gss.gss_mvdr(ctx, Y, gamma, tgt, ref, T_d)
         ref_h = ref.cpu().numpy()

@@ -83,6 +83,33 @@ def test_recording_pipeline_reduced_meeting(env):
         assert np.linalg.norm(xg - xo) <= TOL_X * np.linalg.norm(xo)
 
 
+def test_recording_pipeline_with_wpe(env):
+    """The 60 s meeting with dereverberation switched on (10 taps, delay 2, 3 iterations): WPE -> EM -> MVDR ->
+    iSTFT of the shortest segment re-done end to end by the oracles (the dereverberated STFT rounded to
+    complex64, the precision in which the stages hand it over)."""
+    from oracle import wpe_oracle as w
+    t, o, gss, synth, ctx, pipeline = (env[k] for k in ("torch", "o", "gss", "synth", "ctx", "pipeline"))
+    x, act_s, (st, en, spk) = synth.meeting(duration_s=60.0, n_segments=16)
+    D, N = x.shape
+    ctx_s = 48_000
+    xd = t.from_numpy(x).cuda()
+    outs, fr = pipeline.enhance_recording(ctx, xd, act_s, st, en, spk, ctx_s, ctx_s, iters=15, wpe_taps=10)
+    t.cuda.synchronize()
+    plain, _ = pipeline.enhance_recording(ctx, xd, act_s, st, en, spk, ctx_s, ctx_s, iters=15)
+    Yrec = o.stft_channels_last(x).astype(np.complex64)
+    i = int(np.argsort(fr["n_frames"])[0])
+    f0, nf = int(fr["frame0"][i]), int(fr["n_frames"][i])
+    Ys = w.wpe(Yrec[:, f0:f0 + nf].astype(np.complex128), 10, 2, 3).astype(np.complex64)
+    act = np.concatenate([o.frame_activity(act_s, f0, nf), np.ones((1, nf), np.uint8)])
+    go = o.cacgmm_em(Ys, act, 15)
+    Xo, ro, _ = o.mvdr(Ys, go, int(spk[i]))
+    xo = o.istft(Xo, (nf - 3) * 256)[int(fr["cut_start"][i]):int(fr["cut_end"][i])]
+    xg = outs[i].cpu().numpy()
+    assert int(fr["ref"][i]) == ro
+    assert np.linalg.norm(xg - xo) <= TOL_X * np.linalg.norm(xo)
+    assert np.linalg.norm(xg - plain[i].cpu().numpy()) > 1e-2 * np.linalg.norm(xo)   # and it does change the output
+
+
 def test_super_segment_batching_reduced_meeting(env):
     """Super-segment batching (Section 3, "Segment batching") on the 60 s meeting: same-speaker segments
     concatenated along time with one context window per super-segment, shared statistics, every member
