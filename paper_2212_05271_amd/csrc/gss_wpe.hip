@@ -95,8 +95,8 @@ __global__ __launch_bounds__(kWpeThreads) void wpe_cov_kernel(const float2* __re
                                                               int F, int Tmax, int D, int taps, int delay, ChunkMap cmap,
                                                               int win_elems) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  float2* __restrict__ sWin = reinterpret_cast<float2*>(lds_raw);
-  double* __restrict__ sWt = reinterpret_cast<double*>(lds_raw + (size_t)win_elems * sizeof(float2));
+  double2* __restrict__ sWin = reinterpret_cast<double2*>(lds_raw);
+  double* __restrict__ sWt = reinterpret_cast<double*>(lds_raw + (size_t)win_elems * sizeof(double2));
   double* __restrict__ sRed = sWt + kWpeTile;
 
   long sf;
@@ -135,7 +135,7 @@ __global__ __launch_bounds__(kWpeThreads) void wpe_cov_kernel(const float2* __re
       const int t = tmax - r;
       float2 v = make_float2(0.f, 0.f);
       if (r < win_frames && t >= 0 && t < T) v = Yrow[(long)t * D + d];
-      sWin[e] = v;
+      sWin[e] = make_double2((double)v.x, (double)v.y);  // converted once here, not at every use
     }
     if (threadIdx.x < kWpeTile) {
       const int t = t0 + threadIdx.x;
@@ -154,12 +154,12 @@ __global__ __launch_bounds__(kWpeThreads) void wpe_cov_kernel(const float2* __re
       double war[4], wai[4], br[4], bim[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float2 a = sWin[base + aoff + i];
-        const float2 b = sWin[base + boff + i];
-        war[i] = w * (double)a.x;
-        wai[i] = w * (double)a.y;
-        br[i] = (double)b.x;
-        bim[i] = (double)b.y;
+        const double2 a = sWin[base + aoff + i];
+        const double2 b = sWin[base + boff + i];
+        war[i] = w * a.x;
+        wai[i] = w * a.y;
+        br[i] = b.x;
+        bim[i] = b.y;
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i)
@@ -447,7 +447,7 @@ int run_wpe(gss_ctx* ctx, const float2* Y, const int32_t* T_len, int S, int F, i
   const int tiles = (Tmax + kWpeTile - 1) / kWpeTile;
   // covariance kernel: window of 64 + delay + taps - 1 frames, plus room for the overrun of the last blocks
   const int win_elems = (kWpeTile + delay + taps) * D + 8;
-  const int cov_lds = (int)(win_elems * sizeof(float2) + (kWpeTile + kWpeThreads / kWave) * sizeof(double));
+  const int cov_lds = (int)(win_elems * sizeof(double2) + (kWpeTile + kWpeThreads / kWave) * sizeof(double));
   int per_cu = 0;
   if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, wpe_cov_kernel, kWpeThreads, (size_t)cov_lds) != hipSuccess ||
       per_cu < 1)
