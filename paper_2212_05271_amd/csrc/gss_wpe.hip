@@ -69,11 +69,11 @@ __global__ __launch_bounds__(kWpeThreads) void wpe_power_kernel(const float2* __
 __host__ __device__ inline void wpe_block(int l, int nb, int nbd, int& bi, int& bj, bool& is_p, bool& valid) {
   const int nR = nb * (nb + 1) / 2;
   valid = l < nR + nb * nbd;
-  if (l < nR) {
-    bi = 0;
-    int rem = l;
-    while (rem > bi) { rem -= bi + 1; ++bi; }
-    bj = rem;
+  if (l < nR) {                                          // row bi of the triangle holds bi + 1 blocks
+    bi = (int)((sqrtf(8.f * (float)l + 1.f) - 1.f) * 0.5f);
+    while (bi * (bi + 1) / 2 > l) --bi;
+    while ((bi + 1) * (bi + 2) / 2 <= l) ++bi;
+    bj = l - bi * (bi + 1) / 2;
     is_p = false;
   } else {
     const int m = valid ? l - nR : 0;
