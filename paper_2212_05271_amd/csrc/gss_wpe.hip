@@ -180,14 +180,15 @@ __global__ __launch_bounds__(kWpeThreads) void wpe_cov_kernel(const float2* __re
     }
 }
 
-// Assemble.  One workgroup per (segment, frequency): lane l sums its block over the chunks and writes the
-// entries, with the Hermitian mirror image, into the augmented matrix A[sf] = [R | P] (N rows of N + D
-// complex doubles) in global memory; the trace of R goes to trace[sf].
+// Assemble.  Four workgroups per (segment, frequency), one per row of the 4 x 4 blocks: lane l sums row
+// blockIdx % 4 of its block over the chunks and writes the four entries, with the Hermitian mirror image,
+// into the augmented matrix A[sf] = [R | P] (N rows of N + D complex doubles) in global memory.  (Little
+// work per thread on purpose: the kernel is a gather and scatter that wants many wavefronts in flight; one
+// workgroup per bin took 85 us on 513 bins, four take 42 us, eight 47 us.)
 __global__ __launch_bounds__(kWpeThreads) void wpe_assemble_kernel(const double* __restrict__ part, double2* __restrict__ A,
-                                                                   double* __restrict__ trace, int D, int taps,
-                                                                   ChunkMap cmap) {
-  __shared__ double sTr[kWpeThreads / kWave];
-  const long sf = blockIdx.x;
+                                                                   int D, int taps, ChunkMap cmap) {
+  const long sf = blockIdx.x >> 2;
+  const int i = blockIdx.x & 3;
   const int N = D * taps;
   const int W = N + D;
   const int nb = (N + 3) / 4, nbd = (D + 3) / 4;
@@ -198,44 +199,31 @@ __global__ __launch_bounds__(kWpeThreads) void wpe_assemble_kernel(const double*
   int bi, bj;
   bool is_p, valid;
   wpe_block(threadIdx.x, nb, nbd, bi, bj, is_p, valid);
-  double tr = 0.0;
-  if (valid) {
-    double v[kWpeBlockDoubles];
+  if (!valid) return;
+  double v[8];
 #pragma unroll
-    for (int j = 0; j < kWpeBlockDoubles; ++j) v[j] = 0.0;
-    for (int c = 0; c < count; ++c) {
-      const double* __restrict__ src = part + (size_t)(wg0 + c) * kWpeBlockDoubles * kWpeThreads + threadIdx.x;
+  for (int q = 0; q < 8; ++q) v[q] = 0.0;
+  for (int c = 0; c < count; ++c) {
+    const double* __restrict__ src =
+        part + ((size_t)(wg0 + c) * kWpeBlockDoubles + (size_t)i * 8) * kWpeThreads + threadIdx.x;
 #pragma unroll
-      for (int j = 0; j < kWpeBlockDoubles; ++j) v[j] += src[(size_t)j * kWpeThreads];
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int a = 4 * bi + i;
-        const int b = 4 * bj + j;
-        const double re = v[(i * 4 + j) * 2], im = v[(i * 4 + j) * 2 + 1];
-        if (is_p) {
-          if (a < N && b < D) M[a * W + N + b] = make_double2(re, im);
-        } else if (a < N && b < N) {
-          if (bi != bj || i > j) {                       // below the diagonal: the entry and its mirror image
-            M[a * W + b] = make_double2(re, im);
-            M[b * W + a] = make_double2(re, -im);
-          } else if (i == j) {
-            M[a * W + a] = make_double2(re, 0.0);
-            tr += re;
-          }
-        }
-      }
+    for (int q = 0; q < 8; ++q) v[q] += src[(size_t)q * kWpeThreads];
   }
+  const int a = 4 * bi + i;
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) tr += __shfl_xor(tr, o);
-  if ((threadIdx.x & (kWave - 1)) == 0) sTr[threadIdx.x / kWave] = tr;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    double t = 0.0;
-    for (int w = 0; w < kWpeThreads / kWave; ++w) t += sTr[w];
-    trace[sf] = t;
+  for (int j = 0; j < 4; ++j) {
+    const int b = 4 * bj + j;
+    const double re = v[2 * j], im = v[2 * j + 1];
+    if (is_p) {
+      if (a < N && b < D) M[a * W + N + b] = make_double2(re, im);
+    } else if (a < N && b < N) {
+      if (bi != bj || i > j) {                           // below the diagonal: the entry and its mirror image
+        M[a * W + b] = make_double2(re, im);
+        M[b * W + a] = make_double2(re, -im);
+      } else if (i == j) {
+        M[a * W + a] = make_double2(re, 0.0);
+      }
+    }
   }
 }
 
@@ -252,9 +240,8 @@ constexpr int kSolveKR = (GSS_WPE_MAX_N + kSolveTR - 1) / kSolveTR;             
 constexpr int kSolveMC = (GSS_WPE_MAX_N + GSS_WPE_MAX_D + kSolveTC - 1) / kSolveTC;      // columns per thread
 constexpr int kSolveRowBuf = kSolveMC * kSolveTC, kSolveColBuf = kSolveKR * kSolveTR;
 
-__global__ __launch_bounds__(kSolveThreads) void wpe_solve_kernel(const double2* __restrict__ A, const double* __restrict__ trace,
-                                                                double2* __restrict__ Gc, uint32_t* __restrict__ status,
-                                                                int D, int taps) {
+__global__ __launch_bounds__(kSolveThreads) void wpe_solve_kernel(const double2* __restrict__ A, double2* __restrict__ Gc,
+                                                                uint32_t* __restrict__ status, int D, int taps) {
   __shared__ double2 sRow[2][kSolveRowBuf];
   __shared__ double2 sCol[2][kSolveColBuf];
   __shared__ double sPiv[kSolveColBuf];
@@ -263,14 +250,9 @@ __global__ __launch_bounds__(kSolveThreads) void wpe_solve_kernel(const double2*
   const int W = N + D;
   const int j = threadIdx.x % kSolveTC, i = threadIdx.x / kSolveTC;
   double2* __restrict__ out = Gc + sf * (long)N * D;
-  const double tr = trace[sf];
-  if (!(tr > 0.0)) {                                     // no frame has a past (or silence): G = 0
-    for (int e = threadIdx.x; e < N * D; e += kSolveThreads) out[e] = make_double2(0.0, 0.0);
-    return;
-  }
-  const double load = kWpeLoadRel * tr / (double)N;
   const double2* __restrict__ M = A + sf * (long)N * W;
   double tre[kSolveKR][kSolveMC], tim[kSolveKR][kSolveMC];
+  double tr = 0.0;
 #pragma unroll
   for (int k = 0; k < kSolveKR; ++k)
 #pragma unroll
@@ -278,10 +260,28 @@ __global__ __launch_bounds__(kSolveThreads) void wpe_solve_kernel(const double2*
       const int r = i + kSolveTR * k, c = j + kSolveTC * m;
       double2 v = make_double2(0.0, 0.0);
       if (r < N && c < W) v = M[r * W + c];
-      if (r == c) v.x += load;
+      if (r == c && r < N) tr += v.x;
       tre[k][m] = v.x;
       tim[k][m] = v.y;
     }
+  // trace of R: every diagonal entry is held by exactly one thread
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) tr += __shfl_xor(tr, o);
+  if ((threadIdx.x & (kWave - 1)) == 0) sPiv[threadIdx.x / kWave] = tr;
+  __syncthreads();
+  tr = 0.0;
+  for (int w = 0; w < kSolveThreads / kWave; ++w) tr += sPiv[w];
+  __syncthreads();                                       // sPiv is reused for the pivots
+  if (!(tr > 0.0)) {                                     // no frame has a past (or silence): G = 0
+    for (int e = threadIdx.x; e < N * D; e += kSolveThreads) out[e] = make_double2(0.0, 0.0);
+    return;
+  }
+  const double load = kWpeLoadRel * tr / (double)N;
+#pragma unroll
+  for (int k = 0; k < kSolveKR; ++k)
+#pragma unroll
+    for (int m = 0; m < kSolveMC; ++m)
+      if (i + kSolveTR * k == j + kSolveTC * m) tre[k][m] += load;
   // Row q lives in register row q / TR of the threads with i == q % TR, column q in register column q / TC
   // of the threads with j == q % TC: the register index is the same for the whole workgroup, so it is
   // picked with scalar branches and only the lane test is a vector operation.
@@ -455,7 +455,7 @@ int run_wpe(gss_ctx* ctx, const float2* Y, const int32_t* T_len, int S, int F, i
   const ChunkMap cmap = plan_chunk_map((long)ctx->num_cu * per_cu, n_sf, tiles, 1, 0, true);
   const long wgs = chunk_map_wgs(cmap, n_sf);
   const long blocks_per_sf = (Tmax + kWpeThreads - 1) / kWpeThreads;
-  if (wgs > 0x7fffffffL || n_sf * blocks_per_sf > 0x7fffffffL) return GSS_EUNSUPPORTED;
+  if (wgs > 0x7fffffffL || n_sf * blocks_per_sf > 0x7fffffffL || n_sf * 4 > 0x7fffffffL) return GSS_EUNSUPPORTED;
   // apply kernel: row pitch odd for even D
   const int apitch = D | 1;
   const int apply_lds = (int)((size_t)(kWpeThreads + delay + taps - 1) * apitch * sizeof(float2));
@@ -466,7 +466,6 @@ int run_wpe(gss_ctx* ctx, const float2* Y, const int32_t* T_len, int S, int F, i
   const size_t off_g = o;    o = gss_align_up(o + (size_t)n_sf * N * D * sizeof(double2), 256);
   const size_t off_part = o; o = gss_align_up(o + (size_t)wgs * kWpeBlockDoubles * kWpeThreads * sizeof(double), 256);
   const size_t off_a = o;    o = gss_align_up(o + (size_t)n_sf * N * W * sizeof(double2), 256);
-  const size_t off_tr = o;   o = gss_align_up(o + (size_t)n_sf * sizeof(double), 256);
   const int rc = gss_ensure_scratch(ctx, o);
   if (rc != GSS_OK) return rc;
   char* base = (char*)ctx->scratch;
@@ -474,7 +473,6 @@ int run_wpe(gss_ctx* ctx, const float2* Y, const int32_t* T_len, int S, int F, i
   double2* Gc = (double2*)(base + off_g);
   double* part = (double*)(base + off_part);
   double2* A = (double2*)(base + off_a);
-  double* trace = (double*)(base + off_tr);
 
   const dim3 block(kWpeThreads);
   const dim3 frame_grid((unsigned)(n_sf * blocks_per_sf));
@@ -484,8 +482,8 @@ int run_wpe(gss_ctx* ctx, const float2* Y, const int32_t* T_len, int S, int F, i
     hipLaunchKernelGGL(wpe_cov_kernel, dim3((unsigned)wgs), block, cov_lds, st, Y, T_len, lam, part, F, Tmax, D, taps, delay,
                        cmap, win_elems);
     gss_profile_end(ctx, 2, st);
-    hipLaunchKernelGGL(wpe_assemble_kernel, dim3((unsigned)n_sf), block, 0, st, part, A, trace, D, taps, cmap);
-    hipLaunchKernelGGL(wpe_solve_kernel, dim3((unsigned)n_sf), dim3(kSolveThreads), 0, st, A, trace, Gc, ctx->status, D, taps);
+    hipLaunchKernelGGL(wpe_assemble_kernel, dim3((unsigned)(n_sf * 4)), block, 0, st, part, A, D, taps, cmap);
+    hipLaunchKernelGGL(wpe_solve_kernel, dim3((unsigned)n_sf), dim3(kSolveThreads), 0, st, A, Gc, ctx->status, D, taps);
     if (it + 1 < iters)
       hipLaunchKernelGGL((wpe_apply_kernel<D, false>), frame_grid, block, apply_lds, st, Y, T_len, Gc, lam, X, F, Tmax, taps,
                          delay, (int)blocks_per_sf, apitch);
