@@ -101,6 +101,39 @@ def sweeps(torch, gss, ctx, synth):
     print(f"| no noise class | {K - 1} | {tn * 1e3:.3f} | {(gn - g_ref[:, :K - 1]).abs().max().item():.3f} |")
     print(f"| uniform class weights (weight_mode 0) | {K} | {tu * 1e3:.3f} | "
           f"{(gu[:, :K - 1] - g_ref[:, :K - 1]).abs().max().item():.3f} |")
+    print()
+    # context duration and dereverberation on/off, on a 10-minute meeting through the super-segment pipeline
+    from . import pipeline
+    dur = 600.0
+    x, act_s, (st, en, spk) = synth.meeting(duration_s=dur, n_segments=200)
+    xd = torch.from_numpy(x).cuda()
+    print("| context per side (s) | WPE | ms (10-minute meeting, super-segments, 15 it.) | audio processed (s) | recording-s/s | "
+          "relative change of the enhanced segments vs 15 s, no WPE |")
+    print("|---:|---|---:|---:|---:|---:|")
+    base_out = None
+    rows = []
+    for c_s, taps in ((15.0, 0), (5.0, 0), (10.0, 0), (20.0, 0), (15.0, 10)):
+        c = int(c_s * FS)
+
+        def run():
+            return pipeline.enhance_recording_super(ctx, xd, act_s, st, en, spk, c, c, max_batch_s=50.0, iters=15,
+                                                    wpe_taps=taps)
+
+        run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        outs, info = run()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        flat = torch.cat(outs)
+        if base_out is None:
+            base_out = flat
+        rel = ((flat - base_out).norm() / base_out.norm()).item()
+        proc = float(np.sum(info["T"])) * HOP / FS
+        rows.append((c_s, taps, dt, proc, rel))
+    for c_s, taps, dt, proc, rel in sorted(rows, key=lambda r: (r[1], r[0])):
+        print(f"| {c_s:.0f} | {'10 taps, delay 2, 3 it.' if taps else 'off'} | {dt * 1e3:.1f} | {proc:.0f} | {dur / dt:,.0f} | {rel:.3f} |",
+              flush=True)
 
 
 def wpe_rows(torch, gss, ctx, synth):
