@@ -399,18 +399,71 @@ __global__ __launch_bounds__(kWpeThreads) void wpe_apply_kernel(const float2* __
   for (int d = 0; d < D; ++d) { xr[d] = (double)mine[d].x; xi[d] = (double)mine[d].y; }
   typedef const __attribute__((address_space(4))) double* cptr_t;
   const cptr_t g4 = (cptr_t)(uintptr_t)(Gc + sf * (long)N * D);
-  for (int tau = 0; tau < taps; ++tau) {
-    const float2* __restrict__ src = mine - (delay + tau) * pitch;
+  if constexpr (D % 2 == 0) {
+    // The D coefficients of one component of ytilde are wave-uniform and come through the scalar path; two
+    // such rows are resident in SGPRs and the loads of the next row are issued during the arithmetic of the
+    // current one (the empty asm statements fix that order: the next row's offset becomes known after the
+    // first product of the current row, and every sum passes a fence at the end of the row).  LDS and scalar
+    // loads share one counter, so the frame values of the next tap are fetched from LDS along with the first
+    // coefficient row of the current tap, one tap ahead.  The pipeline fetches one row past the last one
+    // it uses; the coefficient array is followed by padding so that this load stays in bounds.
+    double cA[2 * D], cB[2 * D];
+    auto fetch = [&](double (&c)[2 * D], int off) {
+      const cptr_t cg = g4 + off;
 #pragma unroll
-    for (int dp = 0; dp < D; ++dp) {
-      const float2 v = src[dp];
-      const double vr = (double)v.x, vi = (double)v.y;
-      const cptr_t c = g4 + ((long)(tau * D + dp) * D) * 2;
+      for (int x = 0; x < 2 * D; ++x) c[x] = cg[x];
+    };
+    float2 vcur[D], vnxt[D];
+    {
+      const float2* __restrict__ src = mine - delay * pitch;
 #pragma unroll
-      for (int d = 0; d < D; ++d) {                      // x_d -= c[d] * v
-        const double cr = c[2 * d], ci = c[2 * d + 1];
-        xr[d] = fma(-cr, vr, fma(ci, vi, xr[d]));
-        xi[d] = fma(-cr, vi, fma(-ci, vr, xi[d]));
+      for (int dp = 0; dp < D; ++dp) vcur[dp] = src[dp];
+      int off0 = 0;
+      asm volatile("" : "+s"(off0));                    // opaque offset: keeps the loads inside this kernel's loop
+      fetch(cA, off0);
+    }
+    for (int tau = 0; tau < taps; ++tau) {
+      const int tn = tau + 1 < taps ? tau + 1 : tau;     // the last tap re-reads its own row (stays in bounds)
+      const float2* __restrict__ srcn = mine - (delay + tn) * pitch;
+#pragma unroll
+      for (int dp = 0; dp < D; ++dp) {
+        const double vr = (double)vcur[dp].x, vi = (double)vcur[dp].y;
+        double (&cur)[2 * D] = (dp & 1) ? cB : cA;
+        double (&nxt)[2 * D] = (dp & 1) ? cA : cB;
+        xr[0] = fma(-cur[0], vr, fma(cur[1], vi, xr[0]));  // first use of this row: the wait for its loads lands here
+        int noff = (tau * D + dp + 1) * 2 * D;
+        asm volatile("" : "+s"(noff), "+v"(xr[0]));
+        fetch(nxt, noff);
+        if (dp == 0) {
+#pragma unroll
+          for (int q = 0; q < D; ++q) vnxt[q] = srcn[q];
+        }
+        xi[0] = fma(-cur[0], vi, fma(-cur[1], vr, xi[0]));
+#pragma unroll
+        for (int d = 1; d < D; ++d) {                    // x_d -= c[d] * v
+          xr[d] = fma(-cur[2 * d], vr, fma(cur[2 * d + 1], vi, xr[d]));
+          xi[d] = fma(-cur[2 * d], vi, fma(-cur[2 * d + 1], vr, xi[d]));
+        }
+#pragma unroll
+        for (int d = 0; d < D; ++d) asm volatile("" : "+v"(xr[d]), "+v"(xi[d]));
+      }
+#pragma unroll
+      for (int q = 0; q < D; ++q) vcur[q] = vnxt[q];
+    }
+  } else {
+    for (int tau = 0; tau < taps; ++tau) {
+      const float2* __restrict__ src = mine - (delay + tau) * pitch;
+#pragma unroll
+      for (int dp = 0; dp < D; ++dp) {
+        const float2 v = src[dp];
+        const double vr = (double)v.x, vi = (double)v.y;
+        const cptr_t c = g4 + ((long)(tau * D + dp) * D) * 2;
+#pragma unroll
+        for (int d = 0; d < D; ++d) {                    // x_d -= c[d] * v
+          const double cr = c[2 * d], ci = c[2 * d + 1];
+          xr[d] = fma(-cr, vr, fma(ci, vi, xr[d]));
+          xi[d] = fma(-cr, vi, fma(-ci, vr, xi[d]));
+        }
       }
     }
   }
@@ -463,7 +516,7 @@ int run_wpe(gss_ctx* ctx, const float2* Y, const int32_t* T_len, int S, int F, i
 
   size_t o = 0;
   const size_t off_lam = o;  o = gss_align_up(o + (size_t)n_sf * Tmax * sizeof(double), 256);
-  const size_t off_g = o;    o = gss_align_up(o + (size_t)n_sf * N * D * sizeof(double2), 256);
+  const size_t off_g = o;    o = gss_align_up(o + (size_t)n_sf * N * D * sizeof(double2) + 256, 256);   // + read-ahead padding
   const size_t off_part = o; o = gss_align_up(o + (size_t)wgs * kWpeBlockDoubles * kWpeThreads * sizeof(double), 256);
   const size_t off_a = o;    o = gss_align_up(o + (size_t)n_sf * N * W * sizeof(double2), 256);
   const int rc = gss_ensure_scratch(ctx, o);

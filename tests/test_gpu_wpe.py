@@ -57,7 +57,7 @@ def _check(env, Y, T_len, taps, delay, iters, fsel=None):
 
 
 @pytest.mark.parametrize("D,taps,delay,T", [(4, 5, 2, 300), (8, 10, 2, 700), (3, 7, 3, 333), (1, 1, 1, 130), (2, 10, 2, 64),
-                                             (5, 16, 1, 450), (8, 3, 5, 129), (7, 11, 2, 500)])
+                                             (5, 16, 1, 450), (8, 3, 5, 129), (7, 11, 2, 500), (6, 13, 2, 260)])
 def test_wpe_shapes(env, D, taps, delay, T):
     Y, _, _ = env["synth"].reverberant_stft(F=6, T=T, D=D, order=min(taps, 6), delay=delay, seed=D * 100 + taps)
     _check(env, Y[None], None, taps, delay, 3)
