@@ -123,6 +123,43 @@ def test_sliced_recording_stft_reconstructs_span():
     assert np.allclose(xs[r["cut_start"]:r["cut_end"]], x[3100:5200])
 
 
+def test_frame_activity_reads_the_sample_the_window_weighs_most():
+    """Independent pin of the frame -> sample rule: a unit impulse at sample c is sent through the oracle's
+    STFT; for every frame the sample whose impulse gives that frame the most energy is the sample the frame's
+    analysis window weighs most (its centre, or the nearest sample of the recording when the centre falls
+    outside).  frame_activity must read exactly that sample: an activity that is on at that sample only
+    lights the frame, and an activity that is off at that sample only leaves it dark."""
+    n_fft, hop = 16, 4
+    for N in (37, 40, 9):
+        T = o.stft_num_frames(N, hop)
+        energy = np.zeros((N, T))
+        for c in range(N):
+            x = np.zeros(N)
+            x[c] = 1.0
+            energy[c] = np.sum(np.abs(o.stft(x, n_fft, hop)) ** 2, axis=0)
+        for t in range(T):
+            if energy[:, t].max() == 0.0:                   # the frame's support touches the recording only where
+                continue                                    # the window is zero: nothing to read
+            best = np.flatnonzero(energy[:, t] >= energy[:, t].max() * (1 - 1e-12))
+            assert len(best) == 1, (N, t, best)             # the heaviest sample is unique
+            c = int(best[0])
+            only = np.zeros(N, np.uint8)
+            only[c] = 1
+            assert o.frame_activity(only, 0, T, hop)[t] == 1, (N, t, c)
+            assert o.frame_activity(1 - only, 0, T, hop)[t] == 0, (N, t, c)
+            # the same frame addressed through a frame range that starts later
+            if t >= 2:
+                assert o.frame_activity(only, t - 2, 3, hop).tolist()[2] == 1
+        # an impulse on a window centre lights one frame only; one in between lights none (nearest-centre sampling
+        # of a one-sample event), so every interior sample is read by at most one frame
+        reads = np.zeros(N, int)
+        for c in range(N):
+            only = np.zeros(N, np.uint8)
+            only[c] = 1
+            reads[c] = int(o.frame_activity(only, 0, T, hop).sum())
+        assert np.all(reads[1:N - 1] <= 1) and reads.sum() == T
+
+
 def test_frame_activity_samples_window_centre():
     hop = 4
     act = np.zeros(40, np.uint8)
