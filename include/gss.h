@@ -55,6 +55,9 @@ typedef enum gss_status {
 #define GSS_STATUS_NONPD_PHI 2u      /* the loaded background covariance had a non-positive pivot; floored     */
 #define GSS_STATUS_BAD_TARGET 4u     /* a target index was outside [0, K); it was clamped                       */
 #define GSS_STATUS_NONPD_WPE 8u      /* the loaded WPE correlation matrix had a non-positive pivot; floored     */
+#define GSS_STATUS_ZERO_FRAME 16u    /* gss_cacgmm_em met a frame t < T_len[s] with ||y||^2 < 1e-20 (Eq. (2) is
+                                        0/0 there): it was normalised to the zero vector, its q clamped        */
+#define GSS_STATUS_BAD_REF 32u       /* a reference channel >= D was passed to gss_mvdr; it was chosen instead  */
 
 typedef struct gss_ctx gss_ctx;
 
@@ -139,9 +142,10 @@ int gss_cacgmm_em(gss_ctx* ctx, const float* Y, const uint8_t* activity, const i
  *   gamma  [S][K][F][Tmax] float32 masks
  *   target [S] int32: index of the class to extract, 0 <= target[s] < K (a value outside is clamped and
  *          raises GSS_STATUS_BAD_TARGET in the status word)
- *   ref    [S] int32 in/out: >= 0 = use this reference channel; < 0 = choose the channel with the
- *          largest ratio of beamformed target power to beamformed background power summed over
- *          frequency (lowest index on ties); on return holds the channel used
+ *   ref    [S] int32 in/out: 0 <= ref[s] < D = use this reference channel; < 0 = choose the channel with
+ *          the largest ratio of beamformed target power to beamformed background power summed over
+ *          frequency (lowest index on ties); >= D is treated like < 0 and raises GSS_STATUS_BAD_REF; on
+ *          return holds the channel used
  *   X      [S][F][Tmax] complex64 out: h(f)^H y_{t,f}; exact 0 at t >= T_len[s]
  */
 int gss_mvdr(gss_ctx* ctx, const float* Y, const float* gamma, const int32_t* T_len,

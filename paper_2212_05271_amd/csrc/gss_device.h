@@ -249,6 +249,18 @@ __device__ __forceinline__ void reduce_and_store_partials(double (&acc)[8][KW], 
   }
 }
 
+// Workgroups of `threads` threads of kernel `kern` that one compute unit holds at a time (`dflt` if the
+// runtime cannot say).
+template <typename Kern>
+inline int resident_wgs(Kern kern, int threads, int dflt, size_t lds_bytes = 0) {
+  int n = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kern, threads, lds_bytes) != hipSuccess || n < 1) {
+    (void)hipGetLastError();
+    n = dflt;
+  }
+  return n;
+}
+
 // How the (segment, frequency) problems are cut into workgroups.  The first n_main problems get c_main
 // chunks of tpc_main tiles each; the remaining ones (the tail that would otherwise run alone on an almost
 // empty chip after the last full round of workgroups) are cut finer, into c_tail chunks of tpc_tail tiles.

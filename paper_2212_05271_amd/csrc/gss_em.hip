@@ -19,7 +19,9 @@
 // fp64 from the RAW fp32 observations (products of fp32 numbers are exact in fp64); the unit
 // normalisation of Eq. (2) is applied to q afterwards (q is homogeneous of degree 2 in y) and cancels
 // in the M-step weight.  On this chip fp64 FMA issues at the same rate as unpacked fp32 FMA, so this
-// costs registers, not time.  The posterior itself (log, exp, normalisation over K) is fp32.
+// costs registers, not time.  The posterior is fp64 as well, evaluated as pi_k / det B_k * q_k^-D in
+// mantissa / exponent form (no logarithm, no exponential); only the gamma that leaves the library is
+// rounded to fp32.
 #include "gss_internal.h"
 
 #define GSS_DECL_D(DD)                                                                                           \

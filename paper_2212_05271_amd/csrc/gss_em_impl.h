@@ -19,14 +19,14 @@
 // fp64 from the RAW fp32 observations (products of fp32 numbers are exact in fp64); the unit
 // normalisation of Eq. (2) is applied to q afterwards (q is homogeneous of degree 2 in y) and cancels
 // in the M-step weight.  On this chip fp64 FMA issues at the same rate as unpacked fp32 FMA, so this
-// costs registers, not time.  The posterior itself (log, exp, normalisation over K) is fp32.
+// costs registers, not time.  The posterior is fp64 as well, evaluated as pi_k / det B_k * q_k^-D in
+// mantissa / exponent form (no logarithm, no exponential); only the gamma that leaves the library is
+// rounded to fp32.
 #pragma once
 
 #include "gss_internal.h"
 
 #include "gss_device.h"
-
-#include <cstdlib>
 
 namespace {
 
@@ -91,7 +91,8 @@ template <int D, int K, int NF, bool FINAL>
 __device__ __forceinline__ void pass_unit(
     const float2* __restrict__ Yrow, const uint8_t* __restrict__ arow, const double* __restrict__ cf,
     const double* __restrict__ cm, const int32_t* __restrict__ ce, float* __restrict__ gamma_row /* + k*F*Tmax */,
-    long gamma_kstride, int T, int Tmax, int t0, int lane, double* __restrict__ sY, double* __restrict__ sW,
+    uint32_t* __restrict__ status, long gamma_kstride, int T, int Tmax, int t0, int lane, double* __restrict__ sY,
+    double* __restrict__ sW,
     double (&acc)[8][K], double (&nacc)[K]) {
   constexpr int E = D * D;
   constexpr int WS = K | 1;
@@ -228,6 +229,7 @@ __device__ __forceinline__ void pass_unit(
     }
     const double rz = Z > 0.0 ? rcp_f64_fast(Z) : 0.0;
     if constexpr (FINAL) {
+      if (valid[f] && !(n2[f] >= GSS_EPS_NORM_SQ)) atomicOr(status, GSS_STATUS_ZERO_FRAME);
       if (t[f] < Tmax) {
 #pragma unroll
         for (int k = 0; k < K; ++k) gamma_row[k * gamma_kstride + t[f]] = (float)(v[k] * rz);
@@ -260,7 +262,7 @@ template <int D, int K, bool FINAL>
 __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
     const float2* __restrict__ Y, const uint8_t* __restrict__ act, const int32_t* __restrict__ T_len,
     const double* __restrict__ coef, const double* __restrict__ cmant, const int32_t* __restrict__ cexp,
-    double* __restrict__ part, double* __restrict__ npart, float* __restrict__ gamma,
+    double* __restrict__ part, double* __restrict__ npart, float* __restrict__ gamma, uint32_t* __restrict__ status,
     int F, int Tmax, ChunkMap cmap) {
   constexpr int E = D * D;
   constexpr int WS = K | 1;
@@ -311,10 +313,10 @@ __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
   const int n_units = n_big + (n_tiles - n_big * kNF);
   for (int u = wave; u < n_units; u += kPassWaves) {
     if (u < n_big) {
-      pass_unit<D, K, kNF, FINAL>(Yrow, arow, cf, cm, ce, gamma_row, gamma_kstride, T, Tmax,
+      pass_unit<D, K, kNF, FINAL>(Yrow, arow, cf, cm, ce, gamma_row, status, gamma_kstride, T, Tmax,
                                   (tile_lo + u * kNF) * kWave, lane, sY, sW, acc, nacc);
     } else {
-      pass_unit<D, K, 1, FINAL>(Yrow, arow, cf, cm, ce, gamma_row, gamma_kstride, T, Tmax,
+      pass_unit<D, K, 1, FINAL>(Yrow, arow, cf, cm, ce, gamma_row, status, gamma_kstride, T, Tmax,
                                 (tile_lo + n_big * kNF + (u - n_big)) * kWave, lane, sY, sW, acc, nacc);
     }
   }
@@ -459,22 +461,12 @@ struct EmPlan {
   size_t off_coef, off_cm, off_ce, off_part, off_npart, total;
 };
 
-int env_int(const char* name, int dflt) {
-  if (const char* e = getenv(name)) {
-    const int v = atoi(e);
-    if (v > 0) return v;
-  }
-  return dflt;
-}
-
 EmPlan make_plan(const gss_ctx* ctx, long n_sf, int Tmax, int D, int K, int wgs_per_cu, int wgs_per_cu_fin) {
   EmPlan p;
   const int tiles = (Tmax + kWave - 1) / kWave;
   const int round_up = kPassWaves * kNF;               // a chunk is a whole number of rounds of units
-  // GSS_EM_TPC overrides the tiles per chunk of the main part, GSS_EM_NOTAIL switches the tail cut off
-  // (tuning aids).
   const long slots = (long)ctx->num_cu * wgs_per_cu;
-  p.acc = plan_chunk_map(slots, n_sf, tiles, round_up, env_int("GSS_EM_TPC", 0), env_int("GSS_EM_NOTAIL", 0) == 0);
+  p.acc = plan_chunk_map(slots, n_sf, tiles, round_up, 0, true);
   p.wgs_acc = chunk_map_wgs(p.acc, n_sf);
   p.fin = plan_chunk_map((long)ctx->num_cu * wgs_per_cu_fin, n_sf, tiles, round_up, 0, true);
   p.wgs_fin = chunk_map_wgs(p.fin, n_sf);
@@ -493,14 +485,9 @@ template <int D, int K>
 int run_small(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_t* T_len, int S, int F, int Tmax,
               int iters, int weight_mode, float* gamma, hipStream_t st) {
   const long n_sf = (long)S * F;
-  int wgs_per_cu = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&wgs_per_cu, em_pass_small<D, K, false>, kWave * kPassWaves, 0) !=
-          hipSuccess || wgs_per_cu < 1)
-    wgs_per_cu = 2;
-  int wgs_per_cu_fin = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&wgs_per_cu_fin, em_pass_small<D, K, true>, kWave * kPassWaves, 0) !=
-          hipSuccess || wgs_per_cu_fin < 1)
-    wgs_per_cu_fin = 2;
+  // resident workgroups per compute unit of the two pass kernels: asked once per instantiation
+  static const int wgs_per_cu = resident_wgs(em_pass_small<D, K, false>, kWave * kPassWaves, 2);
+  static const int wgs_per_cu_fin = resident_wgs(em_pass_small<D, K, true>, kWave * kPassWaves, 2);
   const EmPlan p = make_plan(ctx, n_sf, Tmax, D, K, wgs_per_cu, wgs_per_cu_fin);
   int rc = gss_ensure_scratch(ctx, p.total);
   if (rc != GSS_OK) return rc;
@@ -517,7 +504,7 @@ int run_small(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_t* 
   for (int it = 0; it < iters; ++it) {
     gss_profile_begin(ctx, 0, st);
     hipLaunchKernelGGL((em_pass_small<D, K, false>), dim3((unsigned)p.wgs_acc), block, 0, st, Y, act, T_len, coef, cm, ce,
-                       part, npart, (float*)nullptr, F, Tmax, p.acc);
+                       part, npart, (float*)nullptr, ctx->status, F, Tmax, p.acc);
     gss_profile_end(ctx, 0, st);
     gss_profile_begin(ctx, 1, st);
     hipLaunchKernelGGL((em_factor_small<D, K>), dim3((unsigned)n_sf), dim3(kWave * K), 0, st, part, npart, coef, cm, ce,
@@ -525,7 +512,7 @@ int run_small(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_t* 
     gss_profile_end(ctx, 1, st);
   }
   hipLaunchKernelGGL((em_pass_small<D, K, true>), dim3((unsigned)p.wgs_fin), block, 0, st, Y, act, T_len, coef, cm, ce,
-                     (double*)nullptr, (double*)nullptr, gamma, F, Tmax, p.fin);
+                     (double*)nullptr, (double*)nullptr, gamma, ctx->status, F, Tmax, p.fin);
   if (hipGetLastError() != hipSuccess) return GSS_EHIP;
   return GSS_OK;
 }

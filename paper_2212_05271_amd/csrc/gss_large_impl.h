@@ -145,7 +145,7 @@ template <int K, int NR, bool FINAL>
 __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
     const float2* __restrict__ Y, const uint8_t* __restrict__ act, const int32_t* __restrict__ T_len,
     const double* __restrict__ coef, const double* __restrict__ cmant, const int32_t* __restrict__ cexp,
-    double* __restrict__ part, double* __restrict__ npart, float* __restrict__ gamma,
+    double* __restrict__ part, double* __restrict__ npart, float* __restrict__ gamma, uint32_t* __restrict__ status,
     int F, int Tmax, int D, ChunkMap cmap, int RS, int tile_bytes) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   constexpr int WS = K | 1;
@@ -320,6 +320,7 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
     }
     const double rz = Z > 0.0 ? rcp_f64(Z) : 0.0;
     if (FINAL) {
+      if (valid && !(n2 >= GSS_EPS_NORM_SQ)) atomicOr(status, GSS_STATUS_ZERO_FRAME);
       if (t < Tmax) {
 #pragma unroll
         for (int k = 0; k < K; ++k) gamma[(((long)s * K + k) * F + f) * Tmax + t] = (float)(v[k] * rz);
@@ -773,7 +774,7 @@ int run_em_large(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_
   for (int it = 0; it < iters; ++it) {
     gss_profile_begin(ctx, 0, st);
     hipLaunchKernelGGL((em_pass_large<K, NR, false>), dim3((unsigned)wgs_acc), block, p.lds_bytes, st, Y, act, T_len, coef,
-                       cm, ce, part, npart, (float*)nullptr, F, Tmax, D, acc_map, p.RS, p.tile_bytes);
+                       cm, ce, part, npart, (float*)nullptr, ctx->status, F, Tmax, D, acc_map, p.RS, p.tile_bytes);
     gss_profile_end(ctx, 0, st);
     gss_profile_begin(ctx, 1, st);
     hipLaunchKernelGGL(em_factor_large, dim3((unsigned)(n_sf * K)), dim3(fthreads), 0, st, part, npart, coef, cm, ce,
@@ -781,7 +782,7 @@ int run_em_large(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_
     gss_profile_end(ctx, 1, st);
   }
   hipLaunchKernelGGL((em_pass_large<K, NR, true>), dim3((unsigned)wgs_fin), block, p.lds_bytes, st, Y, act, T_len, coef, cm,
-                     ce, (double*)nullptr, (double*)nullptr, gamma, F, Tmax, D, fin_map, p.RS, p.tile_bytes);
+                     ce, (double*)nullptr, (double*)nullptr, gamma, ctx->status, F, Tmax, D, fin_map, p.RS, p.tile_bytes);
   if (hipGetLastError() != hipSuccess) return GSS_EHIP;
   return GSS_OK;
 }
@@ -823,7 +824,7 @@ int run_mvdr_large(gss_ctx* ctx, const float2* Y, const float* gamma, const int3
                      target, part, ctx->status, F, Tmax, D, K, cmap, p.RS, p.tile_bytes);
   const int sthreads = (D * D + 63) / 64 * 64;
   hipLaunchKernelGGL(mvdr_solve_large, dim3((unsigned)n_sf), dim3(sthreads), 0, st, part, H, pw, ctx->status, D, cmap);
-  gss_launch_mvdr_ref(pw, ref, S, F, D, st);
+  gss_launch_mvdr_ref(pw, ref, ctx->status, S, F, D, st);
   const int fpc = 1024;
   const int CA = (Tmax + fpc - 1) / fpc;
   if (n_sf * CA > 0x7fffffffL) return GSS_EUNSUPPORTED;

@@ -21,8 +21,8 @@ namespace {
 // ----------------------------------------------------------------------------------------------
 // Covariance accumulation for D <= 8.  Same tile machinery as the EM pass: a workgroup of kPassWaves
 // wavefronts per (segment, frequency, chunk); per tile, lane = frame loads y and the two weights into the
-// wavefront's LDS region, then lane = (frame group, 2 x 2 channel block) accumulates the two weighted
-// outer products.  Output: part[sf][chunk][2][E] packed (0: target, 1: background).
+// wavefront's LDS region, then lane = (frame group, channel i) accumulates the two weighted outer products
+// (lane type i owns y_i conj(y_b) at circular channel distance 1..4 plus its share of the diagonal).  Output: part[sf][chunk][2][E] packed (0: target, 1: background).
 // ----------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(kWave * kPassWaves) void mvdr_cov_small(
@@ -239,9 +239,10 @@ __global__ __launch_bounds__(kWave) void mvdr_solve_small(
 // Reference channel per segment: one workgroup of 1024 threads per segment; thread (r, j) sums candidate
 // r's powers over the frequencies f = j, j + 32, ..., the 32 partial sums per candidate are added in a
 // fixed order (deterministic), then thread 0 takes the arg-max (lowest index on ties).
-// ref_io[s] >= 0 on entry is kept.
+// 0 <= ref_io[s] < D on entry is kept; a value >= D is flagged in the status word and replaced by the choice.
 // ----------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void mvdr_ref(const double* __restrict__ pw, int32_t* __restrict__ ref_io, int F, int D) {
+__global__ __launch_bounds__(1024) void mvdr_ref(const double* __restrict__ pw, int32_t* __restrict__ ref_io,
+                                                 uint32_t* __restrict__ status, int F, int D) {
   __shared__ double snum[32][33], sden[32][33];
   __shared__ double score[GSS_MAX_D];
   const int s = blockIdx.x;
@@ -264,6 +265,7 @@ __global__ __launch_bounds__(1024) void mvdr_ref(const double* __restrict__ pw, 
   __syncthreads();
   if (threadIdx.x == 0) {
     int cur = ref_io[s];
+    if (cur >= D) atomicOr(status, GSS_STATUS_BAD_REF);
     if (cur < 0 || cur >= D) {
       int best = 0;
       for (int c = 1; c < D; ++c)
@@ -323,10 +325,7 @@ int run_mvdr_small(gss_ctx* ctx, const float2* Y, const float* gamma, const int3
   const int tiles = (Tmax + kWave - 1) / kWave;
   // Chunks per problem: as many as fit the resident workgroup slots in one round (the wavefronts of a
   // workgroup take the chunk's tiles round-robin, so a chunk may hold any number of tiles).
-  int wgs_per_cu = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&wgs_per_cu, mvdr_cov_small<D>, kWave * kPassWaves, 0) != hipSuccess ||
-      wgs_per_cu < 1)
-    wgs_per_cu = 2;
+  static const int wgs_per_cu = resident_wgs(mvdr_cov_small<D>, kWave * kPassWaves, 2);
   long c_target = ((long)ctx->num_cu * wgs_per_cu) / n_sf;
   if (c_target < 1) c_target = 1;
   if (c_target > tiles) c_target = tiles;
@@ -348,7 +347,7 @@ int run_mvdr_small(gss_ctx* ctx, const float2* Y, const float* gamma, const int3
   hipLaunchKernelGGL((mvdr_cov_small<D>), dim3((unsigned)(n_sf * C)), dim3(kWave * kPassWaves), 0, st, Y, gamma, T_len,
                      target, part, ctx->status, F, Tmax, K, C, tpc);
   hipLaunchKernelGGL((mvdr_solve_small<D>), dim3((unsigned)n_sf), dim3(kWave), 0, st, part, H, pw, ctx->status, C);
-  gss_launch_mvdr_ref(pw, ref, S, F, D, st);
+  gss_launch_mvdr_ref(pw, ref, ctx->status, S, F, D, st);
   const int fpc = 1024;
   const int CA = (Tmax + fpc - 1) / fpc;
   if (n_sf * CA > 0x7fffffffL) return GSS_EUNSUPPORTED;
@@ -360,8 +359,8 @@ int run_mvdr_small(gss_ctx* ctx, const float2* Y, const float* gamma, const int3
 
 }  // namespace
 
-void gss_launch_mvdr_ref(const double* pw, int32_t* ref, int S, int F, int D, hipStream_t st) {
-  hipLaunchKernelGGL(mvdr_ref, dim3((unsigned)S), dim3(1024), 0, st, pw, ref, F, D);
+void gss_launch_mvdr_ref(const double* pw, int32_t* ref, uint32_t* status, int S, int F, int D, hipStream_t st) {
+  hipLaunchKernelGGL(mvdr_ref, dim3((unsigned)S), dim3(1024), 0, st, pw, ref, status, F, D);
 }
 
 extern "C" int gss_mvdr(gss_ctx* ctx, const float* Y, const float* gamma, const int32_t* T_len,

@@ -92,8 +92,8 @@ def enhance_recording(ctx, x, act_samples, seg_start, seg_end, seg_spk, ctx_left
 def plan_super_segments(seg_start, seg_end, seg_spk, max_batch_samples):
     """Packs the segments of each speaker, in time order, into super-segments: a super-segment takes the
     speaker's next segment as long as the summed duration of its members stays within max_batch_samples
-    (a segment longer than that forms a super-segment alone; max_batch_samples <= 0 puts every segment alone:
-    the "at most one segment per batch" option).  Returns a list of index lists, ordered by the start of
+    (a segment longer than that forms a super-segment alone; max_batch_samples <= 0 makes every segment a
+    super-segment of its own: the option for non-stationary speakers of Section 3, segment batching).  Returns a list of index lists, ordered by the start of
     their first member."""
     seg_start = np.asarray(seg_start, dtype=np.int64)
     seg_end = np.asarray(seg_end, dtype=np.int64)

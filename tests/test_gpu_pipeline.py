@@ -23,12 +23,13 @@ def env():
 
 def test_config2_full_size_batch(env):
     """64 segments, T in [125, 1875], 1-4 speakers + noise (K padded to 5), 15 iterations, bucketed by length
-    into 4 padded batches: the launch configuration of the batched workload.  The oracle checks one segment per
-    bucket on four frequency bins (segments and bins are independent)."""
+    into 4 padded batches: the launch configuration of the batched workload.  The oracle checks the shortest,
+    the longest and one middle segment of every bucket on six frequency bins, the first and the last included
+    (segments and bins are independent)."""
     t, o, gss, synth, ctx = env["torch"], env["o"], env["gss"], env["synth"], env["ctx"]
     T, ns = synth.config2_plan()
     buckets = synth.buckets_by_length(T, 4)
-    bins = np.array([5, 130, 300, 500])
+    bins = np.array([0, 5, 130, 300, 500, 512])
     for bi, idx in enumerate(buckets):
         segs = [synth.config2_segment(i, T[i], ns[i]) for i in idx]
         Y, act, T_len, target = synth.pad_batch(segs)
@@ -38,17 +39,18 @@ def test_config2_full_size_batch(env):
         ref = t.zeros(len(idx), dtype=t.int32).cuda()
         X = gss.gss_mvdr(ctx, Yd, g, t.from_numpy(target).cuda(), ref, Td)
         t.cuda.synchronize()
-        pick = len(idx) // 2 + (bi % 3)
-        seg = segs[pick]
-        Ts = seg.Y.shape[1]
-        go = o.cacgmm_em(seg.Y[bins], seg.activity, 15)
-        gg = g[pick].cpu().numpy()
-        assert np.max(np.abs(gg[:, bins, :Ts] - go)) <= TOL_GAMMA
-        assert np.all(gg[:, :, Ts:] == 0)
-        Xo, _, _ = o.mvdr(seg.Y[bins], gg[:, bins, :Ts].astype(np.float64), 0, ref=0)
-        Xg = X[pick].cpu().numpy()
-        assert np.linalg.norm(Xg[bins, :Ts] - Xo) <= TOL_X * np.linalg.norm(Xo)
-        assert np.all(Xg[:, Ts:] == 0)
+        by_len = np.argsort([sg.Y.shape[1] for sg in segs], kind="stable")
+        for pick in sorted({int(by_len[0]), int(by_len[-1]), len(idx) // 2 + (bi % 3)}):
+            seg = segs[pick]
+            Ts = seg.Y.shape[1]
+            go = o.cacgmm_em(seg.Y[bins], seg.activity, 15)
+            gg = g[pick].cpu().numpy()
+            assert np.max(np.abs(gg[:, bins, :Ts] - go)) <= TOL_GAMMA
+            assert np.all(gg[:, :, Ts:] == 0)
+            Xo, _, _ = o.mvdr(seg.Y[bins], gg[:, bins, :Ts].astype(np.float64), 0, ref=0)
+            Xg = X[pick].cpu().numpy()
+            assert np.linalg.norm(Xg[bins, :Ts] - Xo) <= TOL_X * np.linalg.norm(Xo)
+            assert np.all(Xg[:, Ts:] == 0)
         del Yd, g, X
 
 
