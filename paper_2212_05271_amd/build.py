@@ -34,21 +34,23 @@ HIP_FLAGS = [
 # Sources that are compiled several times, once per value of a macro, so that their template
 # instantiations build in parallel.
 MULTI = {
-    "gss_em_inst.hip": [("GSS_INST_D", d) for d in range(1, 9)],
-    "gss_large_inst.hip": [("GSS_INST_K", k) for k in range(1, 9)],
+    "gss_em_inst.hip": [(("GSS_INST_D", d), ("GSS_INST_K", k)) for d in range(8, 0, -1) for k in range(8, 0, -1)],
+    "gss_large_inst.hip": [(("GSS_INST_K", k),) for k in range(1, 9)],
 }
 
 
 def sources():
-    """List of (source path, object name, extra flags)."""
+    """List of (source path, object name, extra flags), the slowest translation units first."""
     jobs = []
-    for f in sorted(os.listdir(CSRC)):
+    names = sorted(os.listdir(CSRC), key=lambda n: (n not in MULTI, n))
+    for f in names:
         if not f.endswith(".hip"):
             continue
         src = os.path.join(CSRC, f)
         if f in MULTI:
-            for macro, val in MULTI[f]:
-                jobs.append((src, f"{f}.{macro}_{val}.o", [f"-D{macro}={val}"]))
+            for macros in MULTI[f]:
+                tag = ".".join(f"{m}_{v}" for m, v in macros)
+                jobs.append((src, f"{f}.{tag}.o", [f"-D{m}={v}" for m, v in macros]))
         else:
             jobs.append((src, f + ".o", []))
     return jobs

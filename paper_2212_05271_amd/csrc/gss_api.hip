@@ -1,7 +1,34 @@
 // Context management, error strings and the host-side integer helpers of libgss.
 #include "gss_internal.h"
 
+#include <mutex>
 #include <new>
+
+// Working memory of gss_cacgmm_em_noalloc: one copy per GPU, held until the process ends.  In host code this
+// name is only a handle for hipGetSymbolAddress; kernels and copies get the device address looked up below.
+static __device__ __align__(256) unsigned char scratch[GSS_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+void* g_static_ptr[kMaxDevices] = {nullptr};
+
+// Device address of `scratch` on `device` (which must be current), looked up once per device.
+int static_scratch_address(int device, void** out) {
+  if (device < 0 || device >= kMaxDevices) return GSS_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  if (!g_static_ptr[device]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return GSS_EHIP;
+    }
+    g_static_ptr[device] = p;
+  }
+  *out = g_static_ptr[device];
+  return GSS_OK;
+}
+}  // namespace
 
 extern "C" {
 
@@ -14,6 +41,7 @@ const char* gss_strerror(int code) {
     case GSS_EUNSUPPORTED: return "shape not supported by this build";
     case GSS_ENOMEM: return "out of device memory";
     case GSS_EHIP: return "HIP runtime error";
+    case GSS_ETOOBIG: return "problem exceeds the static scratch buffer of the no-allocation entry point";
     default: return "unknown error";
   }
 }
@@ -28,6 +56,8 @@ int gss_create(gss_ctx** out, int device_id) {
   c->device = device_id;
   c->scratch = nullptr;
   c->scratch_cap = 0;
+  c->scratch_fixed = 0;
+  c->static_scratch = nullptr;
   c->status = nullptr;
   c->num_cu = 256;
   c->twiddles = nullptr;
@@ -41,6 +71,13 @@ int gss_create(gss_ctx** out, int device_id) {
   hipDeviceProp_t prop;
   if (hipGetDeviceProperties(&prop, device_id) == hipSuccess && prop.multiProcessorCount > 0)
     c->num_cu = prop.multiProcessorCount;
+  {
+    const int rc = static_scratch_address(device_id, &c->static_scratch);
+    if (rc != GSS_OK) {
+      delete c;
+      return rc;
+    }
+  }
   if (hipMalloc((void**)&c->status, sizeof(uint32_t)) != hipSuccess) {
     delete c;
     return GSS_ENOMEM;
@@ -78,6 +115,24 @@ int gss_get_status(gss_ctx* ctx, uint32_t* host_out, void* stream) {
   GSS_HIP_CHECK(hipMemcpyAsync(ctx->status, &zero, sizeof(uint32_t), hipMemcpyHostToDevice, st));
   GSS_HIP_CHECK(hipStreamSynchronize(st));
   return GSS_OK;
+}
+
+int gss_cacgmm_em_noalloc(gss_ctx* ctx, const float* Y, const uint8_t* activity, const int32_t* T_len,
+                          int S, int F, int Tmax, int D, int K, int iters, int weight_mode,
+                          float* gamma, void* stream) {
+  if (!ctx || !ctx->static_scratch) return GSS_EINVAL;
+  // The kernels of gss_cacgmm_em take their working memory from ctx->scratch; for the duration of this call
+  // that is the static array (by its device address), and growing it is refused.
+  void* const saved = ctx->scratch;
+  const size_t saved_cap = ctx->scratch_cap;
+  ctx->scratch = ctx->static_scratch;
+  ctx->scratch_cap = GSS_STATIC_SCRATCH_BYTES;
+  ctx->scratch_fixed = 1;
+  const int rc = gss_cacgmm_em(ctx, Y, activity, T_len, S, F, Tmax, D, K, iters, weight_mode, gamma, stream);
+  ctx->scratch = saved;
+  ctx->scratch_cap = saved_cap;
+  ctx->scratch_fixed = 0;
+  return rc;
 }
 
 int64_t gss_scratch_bytes(const gss_ctx* ctx) { return ctx ? (int64_t)ctx->scratch_cap : 0; }
@@ -183,6 +238,7 @@ void gss_profile_end(gss_ctx* ctx, int which, hipStream_t st) {
 
 int gss_ensure_scratch(gss_ctx* ctx, size_t bytes) {
   if (bytes <= ctx->scratch_cap) return GSS_OK;
+  if (ctx->scratch_fixed) return GSS_ETOOBIG;
   if (hipDeviceSynchronize() != hipSuccess) return GSS_EHIP;
   if (ctx->scratch) {
     (void)hipFree(ctx->scratch);

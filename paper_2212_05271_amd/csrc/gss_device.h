@@ -167,6 +167,64 @@ __device__ __forceinline__ void accumulate_tile(const double* __restrict__ sY, c
   }
 }
 
+// The same for the classes of `mask` only (wave-uniform): the weights of the other classes are zero in every
+// frame of the tile (their columns of sW hold stale values that are read and never used).  One frame per
+// step: its entries are formed, the row and weights of the next frame are requested from LDS, and then each
+// class of the mask adds its 8 products under one uniform branch, so the LDS latency is covered by the
+// previous frame's arithmetic.
+template <int KW, int WS>
+__device__ __forceinline__ void accumulate_tile_masked(const double* __restrict__ sY, const double* __restrict__ sW,
+                                                       int tg, int eg, unsigned mask, double (&acc)[8][KW]) {
+  // five row pointers and one weight pointer per lane; every access below is one of them plus a constant
+  // (the constant goes into the offset field of the LDS instruction)
+  const double* __restrict__ p0 = sY + tg * kYStride + 2 * eg;
+  const double* __restrict__ p1 = sY + tg * kYStride + 2 * ((eg + 1) & 7);
+  const double* __restrict__ p2 = sY + tg * kYStride + 2 * ((eg + 2) & 7);
+  const double* __restrict__ p3 = sY + tg * kYStride + 2 * ((eg + 3) & 7);
+  const double* __restrict__ p4 = sY + tg * kYStride + 2 * ((eg + 4) & 7);
+  const double* __restrict__ pw = sW + tg * WS;
+  double2 y[5];
+  double w[KW];
+  auto fetch = [&](auto JF) {
+    constexpr int o = 8 * JF.value * kYStride;     // rows of the 8 frame groups are adjacent: distinct LDS banks
+    y[0] = *reinterpret_cast<const double2*>(p0 + o);
+    y[1] = *reinterpret_cast<const double2*>(p1 + o);
+    y[2] = *reinterpret_cast<const double2*>(p2 + o);
+    y[3] = *reinterpret_cast<const double2*>(p3 + o);
+    y[4] = *reinterpret_cast<const double2*>(p4 + o);
+#pragma unroll
+    for (int k = 0; k < KW; ++k) w[k] = pw[8 * JF.value * WS + k];
+  };
+  fetch(std::integral_constant<int, 0>{});
+  static_for<0, 8>([&](auto JI) {
+    constexpr int j = JI.value;
+    double e[8], wc[KW];
+    {
+      const double2 x = y[0], y1 = y[1], y2 = y[2], y3 = y[3], y4 = y[4];
+      e[0] = x.x * y1.x + x.y * y1.y;  e[1] = x.y * y1.x - x.x * y1.y;
+      e[2] = x.x * y2.x + x.y * y2.y;  e[3] = x.y * y2.x - x.x * y2.y;
+      e[4] = x.x * y3.x + x.y * y3.y;  e[5] = x.y * y3.x - x.x * y3.y;
+      if (eg < 4) {   // the pair at distance 4
+        e[6] = x.x * y4.x + x.y * y4.y;  e[7] = x.y * y4.x - x.x * y4.y;
+      } else {        // the diagonal entries of the two channels
+        e[6] = x.x * x.x + x.y * x.y;    e[7] = y4.x * y4.x + y4.y * y4.y;
+      }
+#pragma unroll
+      for (int k = 0; k < KW; ++k) wc[k] = w[k];
+    }
+    if constexpr (j < 7) fetch(std::integral_constant<int, j + 1>{});
+    static_for<0, KW>([&](auto KI) {
+      constexpr int k = KI.value;
+      unsigned m = mask;
+      asm volatile("" : "+s"(m));           // re-test the one mask register instead of keeping KW booleans
+      if ((m >> k) & 1u) {
+#pragma unroll
+        for (int n = 0; n < 8; ++n) acc[n][k] = fma(wc[k], e[n], acc[n][k]);
+      }
+    });
+  });
+}
+
 // Reduction of the per-lane accumulators of a workgroup of kPassWaves wavefronts into packed partial
 // sums: out[k * E + packed index] for k < KW, matrix size D.  Sums are taken in a fixed order (frame
 // groups ascending, then wavefronts ascending).

@@ -24,11 +24,23 @@
 // rounded to fp32.
 #include "gss_internal.h"
 
-#define GSS_DECL_D(DD)                                                                                           \
-  int gss_em_small_d##DD(gss_ctx* ctx, const float* Y, const uint8_t* activity, const int32_t* T_len, int S, int F, \
-                         int Tmax, int K, int iters, int weight_mode, float* gamma, hipStream_t st);
-GSS_DECL_D(1) GSS_DECL_D(2) GSS_DECL_D(3) GSS_DECL_D(4) GSS_DECL_D(5) GSS_DECL_D(6) GSS_DECL_D(7) GSS_DECL_D(8)
-#undef GSS_DECL_D
+typedef int (*em_small_fn)(gss_ctx*, const float*, const uint8_t*, const int32_t*, int, int, int, int, int, float*,
+                           hipStream_t);
+#define GSS_DECL(DD, KK)                                                                                          \
+  int gss_em_small_d##DD##_k##KK(gss_ctx* ctx, const float* Y, const uint8_t* activity, const int32_t* T_len, int S, \
+                                 int F, int Tmax, int iters, int weight_mode, float* gamma, hipStream_t st);
+#define GSS_DECL_ROW(DD) \
+  GSS_DECL(DD, 1) GSS_DECL(DD, 2) GSS_DECL(DD, 3) GSS_DECL(DD, 4) GSS_DECL(DD, 5) GSS_DECL(DD, 6) GSS_DECL(DD, 7) GSS_DECL(DD, 8)
+GSS_DECL_ROW(1) GSS_DECL_ROW(2) GSS_DECL_ROW(3) GSS_DECL_ROW(4) GSS_DECL_ROW(5) GSS_DECL_ROW(6) GSS_DECL_ROW(7) GSS_DECL_ROW(8)
+#undef GSS_DECL_ROW
+#undef GSS_DECL
+
+#define GSS_ROW(DD)                                                                                               \
+  { gss_em_small_d##DD##_k1, gss_em_small_d##DD##_k2, gss_em_small_d##DD##_k3, gss_em_small_d##DD##_k4,          \
+    gss_em_small_d##DD##_k5, gss_em_small_d##DD##_k6, gss_em_small_d##DD##_k7, gss_em_small_d##DD##_k8 }
+static const em_small_fn kEmSmall[8][8] = {GSS_ROW(1), GSS_ROW(2), GSS_ROW(3), GSS_ROW(4),
+                                           GSS_ROW(5), GSS_ROW(6), GSS_ROW(7), GSS_ROW(8)};
+#undef GSS_ROW
 
 extern "C" int gss_cacgmm_em(gss_ctx* ctx, const float* Y, const uint8_t* activity, const int32_t* T_len,
                              int S, int F, int Tmax, int D, int K, int iters, int weight_mode,
@@ -39,11 +51,6 @@ extern "C" int gss_cacgmm_em(gss_ctx* ctx, const float* Y, const uint8_t* activi
   if (D > GSS_MAX_D || K > GSS_MAX_K) return GSS_EUNSUPPORTED;
   if (hipSetDevice(ctx->device) != hipSuccess) return GSS_EHIP;
   hipStream_t st = (hipStream_t)stream;
-  switch (D) {
-#define GSS_CASE_D(DD) \
-  case DD: return gss_em_small_d##DD(ctx, Y, activity, T_len, S, F, Tmax, K, iters, weight_mode, gamma, st);
-    GSS_CASE_D(1) GSS_CASE_D(2) GSS_CASE_D(3) GSS_CASE_D(4) GSS_CASE_D(5) GSS_CASE_D(6) GSS_CASE_D(7) GSS_CASE_D(8)
-#undef GSS_CASE_D
-    default: return gss_em_large(ctx, Y, activity, T_len, S, F, Tmax, D, K, iters, weight_mode, gamma, st);
-  }
+  if (D <= 8) return kEmSmall[D - 1][K - 1](ctx, Y, activity, T_len, S, F, Tmax, iters, weight_mode, gamma, st);
+  return gss_em_large(ctx, Y, activity, T_len, S, F, Tmax, D, K, iters, weight_mode, gamma, st);
 }

@@ -19,24 +19,31 @@
 // fp64 from the RAW fp32 observations (products of fp32 numbers are exact in fp64); the unit
 // normalisation of Eq. (2) is applied to q afterwards (q is homogeneous of degree 2 in y) and cancels
 // in the M-step weight.  On this chip fp64 FMA issues at the same rate as unpacked fp32 FMA, so this
-// costs registers, not time.  The posterior is fp64 as well, evaluated as pi_k / det B_k * q_k^-D in
-// mantissa / exponent form (no logarithm, no exponential); only the gamma that leaves the library is
-// rounded to fp32.
+// costs registers, not time.  The posterior is fp64 as well, evaluated as pi_k / det B_k * q_k^-D and
+// normalised over the classes (no logarithm, no exponential; for D <= 8 every term is a normal double);
+// only the gamma that leaves the library is rounded to fp32.
 #pragma once
 
 #include "gss_internal.h"
 
 #include "gss_device.h"
 
+#ifdef GSS_DEV_TIMING
+__device__ long long g_dev_times[4 * 16 * 8];
+__device__ int g_dev_count[4];
+#define DEV_STAMP(slot) do { if (dev_on && lane == 0) g_dev_times[(dev_wave * 16 + dev_unit) * 8 + (slot)] = clock64(); } while (0)
+#else
+#define DEV_STAMP(slot) do { } while (0)
+#endif
+
 namespace {
 
 // ----------------------------------------------------------------------------------------------
 // Coefficient initialisation: B = I, log-term 0  (pass 0).
-// coef[sf][k][E] packed as gss_packed_row(); the class constant pi_k / det B_k is kept as
-// cmant * 2^cexp with cmant in [0.5, 1).
+// coef[sf][k][E] packed as gss_packed_row(); cconst[sf][k] = pi_k / det B_k (any common factor cancels in
+// the posterior).
 // ----------------------------------------------------------------------------------------------
-__global__ void em_init_coef(double* __restrict__ coef, double* __restrict__ cmant, int32_t* __restrict__ cexp,
-                             int D, int K, long n_sf) {
+__global__ void em_init_coef(double* __restrict__ coef, double* __restrict__ cconst, int D, int K, long n_sf) {
   const int E = D * D;
   long total = n_sf * (long)K * E;
   for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
@@ -49,231 +56,250 @@ __global__ void em_init_coef(double* __restrict__ coef, double* __restrict__ cma
   }
   long nl = n_sf * (long)K;
   for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nl; i += (long)gridDim.x * blockDim.x) {
-    cmant[i] = 0.5;
-    cexp[i] = 1;
+    cconst[i] = 1.0;
   }
 }
 
 // ----------------------------------------------------------------------------------------------
-// Pass kernel for D <= 8.  Workgroup = kPassWaves wavefronts that all work on the same
-// (segment, frequency), so that the class coefficients they stream through the scalar cache are shared;
-// every wavefront owns whole tiles of 64 frames and a private LDS region, and there is no workgroup
-// barrier inside the tile loop.
+// Pass kernel for D <= 8.  Workgroup = kPassWaves wavefronts on the same (segment, frequency); every
+// wavefront owns a contiguous range of tiles of 64 frames and a private LDS region, and there is no
+// workgroup barrier inside the tile loop.
 //
-// Phase 1 (lane = frame): q_k = <coef_k, y y^H> with the outer product generated entry by entry in fp64
-//   and the coefficients wave-uniform (scalar loads); posterior over the active classes as
-//   pi_k / det B_k * q_k^-D in (mantissa, exponent) form, fp64, no log/exp; weights w_k = gamma_k / q_k.
-//   y (as fp64) and w go to the wavefront's LDS tile.
+// Class coefficients.  The packed coefficients of B_k^-1 (D * D reals per class) are the same for every
+// frame.  They live in vector registers for the whole kernel, 16 per register: lane l of every row of 16
+// lanes holds entry 16 r + (l mod 16) of register r, and the FMAs of phase 1 read them with the
+// row-broadcast lane selector of the double-precision vector FMA (v_fmac_f64 ... row_newbcast:n takes its
+// first factor from lane n of the executing lane's row).  No scalar loads and no LDS traffic in the inner
+// loop; D = 8, K = 5 needs 20 register pairs.  When K * ceil(D*D/16) exceeds kResidentRegs the registers
+// of one 16-entry block are fetched from an LDS copy of the coefficients at the start of the block instead.
+//
+// Classes that are not active anywhere in a tile (activity mask, Eq. (5)) have posterior 0 in all of its
+// frames and add nothing to any sum: the tile's arithmetic for them is skipped under wave-uniform branches.
+//
+// Phase 1 (lane = frame): the Hermitian outer product is generated 16 entries at a time in fp64, and
+//   q_k = <coef_k, y y^H> takes 16 row-broadcast FMAs per live class and block; posterior over the active
+//   classes; weights w_k = gamma_k / q_k.  y (as fp64) and w go to the wavefront's LDS tile.
 // Phase 2 (lane = (frame group tg, channel eg), 8 x 8; frames tg, tg+8, ... of the tile): lane type eg = i
 //   owns the entries y_i conj(y_b) for b = i+1, i+2, i+3 (mod 8), and either the pair (i, i+4) (i < 4) or
 //   the real diagonal entries of channels i and i-4 (i >= 4): 8 real entries per lane, all 64 of the packed
 //   Hermitian 8 x 8 matrix over the 8 lane types, the same instructions for every lane except the last two
-//   entries.  For its 8 frames per tile a lane reads 5 channels of y and the K weights, forms its 8
+//   entries.  For its 8 frames per tile a lane reads 5 channels of y and the weights, forms its 8
 //   entries exactly and accumulates R_k[e] += w_k * P[e] in fp64.  Channels >= D are zero padding.
 //   The accumulators stay in registers across the tiles of the chunk.
 //
-// Grid: blockIdx.x = chunk + C * (f + F * s).  A chunk is `tiles_per_chunk` tiles of 64 frames, dealt to
-// the wavefronts round-robin.
+// Grid: blockIdx.x = chunk + C * (f + F * s).  A chunk is `tiles_per_chunk` tiles of 64 frames.
 // ----------------------------------------------------------------------------------------------
 
+// Activity in the form the pass kernels read: abyte[s][t] has bit k set when class k may be active in frame t
+// (a_{t,k} of Eq. (5); 0 at t >= T_len[s]), tmask[s][tile] is the OR of the bytes of the tile's 64 frames.
+// Grid: one wavefront per (segment, tile).
+__global__ __launch_bounds__(kWave) void em_pack_activity(
+    const uint8_t* __restrict__ act, const int32_t* __restrict__ T_len, uint8_t* __restrict__ abyte,
+    uint32_t* __restrict__ tmask, int K, int Tmax, int tiles) {
+  const int s = blockIdx.x / tiles, tile = blockIdx.x % tiles;
+  const int lane = threadIdx.x;
+  int T = T_len ? T_len[s] : Tmax;
+  T = T < 0 ? 0 : (T > Tmax ? Tmax : T);
+  const int t = tile * kWave + lane;
+  unsigned b = 0;
+  if (t < T)
+    for (int k = 0; k < K; ++k) b |= (act[((long)s * K + k) * Tmax + t] != 0 ? 1u : 0u) << k;
+  if (t < Tmax) abyte[(long)s * Tmax + t] = (uint8_t)b;
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) b |= (unsigned)__shfl_xor((int)b, off, kWave);
+  if (lane == 0) tmask[(long)s * tiles + tile] = b;
+}
 
-// Entries of the packed outer product per group of scalar coefficient loads (2 or 4 doubles per class);
-// two groups are in SGPRs at a time, 2 * K * G * 2 registers of the 100 or so there are.
-__host__ __device__ constexpr int coef_group(int K) { return K <= 5 ? 4 : 2; }
+// Doubles per frame row of the weight tile in LDS (odd: spreads the rows over the banks).
+__host__ __device__ constexpr int weight_stride(int K) { return K | 1; }
 
-// Frames per lane in phase 1.  Every class coefficient that comes through the scalar path is applied to
-// kNF frames; the scalar data path returns about one dword per clock per pair of compute units, so
-// at kNF = 1 it is as busy as the vector ALUs.
-constexpr int kNF = 2;
+// Registers (pairs) of 16 coefficients per class, and how many of them a wavefront keeps resident.
+__host__ __device__ constexpr int coef_regs(int D) { return (D * D + 15) / 16; }
+constexpr int kResidentRegs = 20;
 
-// One unit of work of a wavefront: NF consecutive tiles of 64 frames starting at frame t0.
-template <int D, int K, int NF, bool FINAL>
-__device__ __forceinline__ void pass_unit(
-    const float2* __restrict__ Yrow, const uint8_t* __restrict__ arow, const double* __restrict__ cf,
-    const double* __restrict__ cm, const int32_t* __restrict__ ce, float* __restrict__ gamma_row /* + k*F*Tmax */,
-    uint32_t* __restrict__ status, long gamma_kstride, int T, int Tmax, int t0, int lane, double* __restrict__ sY,
-    double* __restrict__ sW,
-    double (&acc)[8][K], double (&nacc)[K]) {
+// acc += c[lane N of the row] * p: the double-precision FMA with the row-broadcast selector on its first
+// factor.  Every lane of the wavefront must be active (the selector reads other lanes).  The instruction is
+// written as an asm statement, which hides it from the compiler's hazard handling: a lane-selecting
+// instruction must not issue within two wait states of a vector instruction that writes one of its
+// registers, so the first FMA of a run (SETTLE) is preceded by the two idle states itself.
+template <int N, bool SETTLE>
+__device__ __forceinline__ void fma_bcast(double& acc, double c, double p) {
+  static_assert(N >= 0 && N < 16, "row_newbcast selects one of the 16 lanes of a row");
+  if constexpr (SETTLE)
+    asm("s_nop 1\n\tv_fmac_f64_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+        : "+v"(acc) : "v"(c), "v"(p), "n"(N));
+  else
+    asm("v_fmac_f64_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(c), "v"(p), "n"(N));
+}
+
+// Wave-uniform test of bit k of `mask`, re-evaluated from the one scalar register that holds the mask at every
+// use (the empty asm statement keeps the compiler from caching the K booleans in scalar register pairs).
+__device__ __forceinline__ bool class_on(unsigned mask, int k) {
+  asm volatile("" : "+s"(mask));
+  return (mask >> k) & 1u;
+}
+
+// One tile of 64 frames starting at frame t0.  `tmask` (wave-uniform) is the tile's activity mask.
+//   creg : the resident coefficient registers [K * coef_regs(D)] (used when RESIDENT)
+//   sC   : LDS copy of the coefficients, [K * coef_regs(D)][16] doubles (used otherwise)
+//   cc   : class constants pi_k / det B_k (wave-uniform)
+template <int D, int K, bool FINAL, bool RESIDENT>
+__device__ __forceinline__ void pass_tile(
+    const float2* __restrict__ Yrow, const uint8_t* __restrict__ abrow, const double (&creg)[RESIDENT ? K * coef_regs(D) : 1],
+    const double* __restrict__ sC, const double (&cc)[K], float* __restrict__ gamma_row /* + k*F*Tmax */,
+    uint32_t* __restrict__ status, long gamma_kstride, int T, int Tmax, int t0, int lane, unsigned tmask,
+    double* __restrict__ sY, double* __restrict__ sW, double (&acc)[8][K], double (&nacc)[K]
+#ifdef GSS_DEV_TIMING
+    , bool dev_on, int dev_wave, int dev_unit
+#endif
+    ) {
   constexpr int E = D * D;
-  constexpr int WS = K | 1;
+  constexpr int R = coef_regs(D);
+  constexpr int WS = weight_stride(K);
   const int tg = lane >> 3, eg = lane & 7;
+  DEV_STAMP(0);
+  tmask &= (1u << K) - 1u;
+  const int t = t0 + lane;
+  if constexpr (FINAL) {
+    // the classes that are not live anywhere in the tile: their zeros
+    static_for<0, K>([&](auto KI) {
+      constexpr int k = KI.value;
+      if (!class_on(tmask, k)) {
+        if (t < Tmax) gamma_row[k * gamma_kstride + t] = 0.f;
+      }
+    });
+  }
+  if (tmask == 0u) return;                    // no frame of the tile has an active class
 
   // ---- phase 1: load y ----
   // A lane whose frame lies beyond T reads frame 0 instead (it exists whenever a tile is processed at all, or is
-  // padding in the final pass); its activity bits are forced to zero, so its posterior and weights are zero.
-  int t[NF];
-  bool valid[NF];
-  double yr[NF][D], yi[NF][D];
+  // padding in the final pass); its activity bits are zero, so its posterior and weights are zero.
+  const bool valid = t < T;
+  double yr[D], yi[D];
 #pragma unroll
-  for (int f = 0; f < NF; ++f) {
-    t[f] = t0 + f * kWave + lane;
-    valid[f] = t[f] < T;
-#pragma unroll
-    for (int d = 0; d < D; ++d) {
-      const float2 v = Yrow[(long)(valid[f] ? t[f] : 0) * D + d];
-      yr[f][d] = (double)v.x;
-      yi[f][d] = (double)v.y;
-    }
+  for (int d = 0; d < D; ++d) {
+    const float2 v = Yrow[(long)(valid ? t : 0) * D + d];
+    yr[d] = (double)v.x;
+    yi[d] = (double)v.y;
   }
-  // activity bits of the lane's frames, fetched here so that the loads overlap the q loop
-  unsigned abits[NF];
-#pragma unroll
-  for (int f = 0; f < NF; ++f) {
-    unsigned b = 0;
-#pragma unroll
-    for (int k = 0; k < K; ++k) b |= (arow[(long)k * Tmax + (valid[f] ? t[f] : 0)] != 0 ? 1u : 0u) << k;
-    abits[f] = valid[f] ? b : 0u;
-    asm volatile("" : "+v"(abits[f]));
-  }
+  unsigned abits = abrow[valid ? t : 0];
+  abits = valid ? abits : 0u;
+#ifdef GSS_DEV_TIMING
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  DEV_STAMP(1);
+#endif
 
-  // ---- q_k = <coef_k, y y^H> ----
-  // The coefficients are wave-uniform and come through the scalar path straight into the FMAs as SGPR
-  // operands, one group of G packed entries (K*G doubles) at a time, two groups in registers: the loads of
-  // group g + 1 are issued during the arithmetic of group g.  Left alone, the compiler either hoists all
-  // K*E loads out of the tile loop and spills them, or puts every load directly in front of its first use.
-  // The empty asm statements steer it: the offset of group g + 1 comes into existence only after the first
-  // product of group g (which is where the wait for group g's loads lands, with nothing else outstanding:
-  // scalar loads may return out of order, so that wait is always for all of them), and every partial sum
-  // passes through a fence at the end of its group, which keeps the group's arithmetic in place.
-  double q[NF][K];
-  double n2[NF];
+  // ---- q_k = <coef_k, y y^H>, 16 entries of the outer product at a time; three partial sums per class (an FMA
+  // does not wait for the one before it) ----
+  double q[K][3];
+  double n2 = 0.0;
 #pragma unroll
-  for (int f = 0; f < NF; ++f) {
-    n2[f] = 0.0;
+  for (int k = 0; k < K; ++k) { q[k][0] = 0.0; q[k][1] = 0.0; q[k][2] = 0.0; }
+  static_for<0, R>([&](auto RI) {
+    constexpr int r = RI.value;
+    constexpr int ng = (E - 16 * r) < 16 ? (E - 16 * r) : 16;
+    double c[K];
+    if constexpr (!RESIDENT) {
+      // this block's coefficient registers, from the LDS copy (requested before the products are formed)
 #pragma unroll
-    for (int k = 0; k < K; ++k) q[f][k] = 0.0;
-  }
-  constexpr int G = coef_group(K);
-  constexpr int NG = (E + G - 1) / G;
-  typedef const __attribute__((address_space(4))) double* const_ptr_t;
-  const const_ptr_t cf4 = (const_ptr_t)(uintptr_t)cf;
-  double ccur[K][G], cnxt[K][G];
-  {
-    int off0 = 0;
-    asm volatile("" : "+s"(off0));            // opaque (uniform) offset: keeps the loads inside this unit
-    const const_ptr_t c0 = cf4 + off0;
-#pragma unroll
-    for (int k = 0; k < K; ++k)
-#pragma unroll
-      for (int e = 0; e < G; ++e) ccur[k][e] = (e < E) ? c0[k * E + e] : 0.0;
-  }
-  static_for<0, NG>([&](auto GI) {
-    constexpr int g = GI.value * G;
-    constexpr int ng = (E - g) < G ? (E - g) : G;
-    double Pg[NF][ng];
-#pragma unroll
-    for (int f = 0; f < NF; ++f) {
-      static_for<0, ng>([&](auto EI) {
-        constexpr int e = EI.value;
-        Pg[f][e] = packed_entry<D, g + e>(yr[f], yi[f]);
-        if constexpr (packed_part(g + e, D) == 0) n2[f] += Pg[f][e];
-      });
+      for (int k = 0; k < K; ++k) c[k] = sC[(k * R + r) * 16 + (lane & 15)];
     }
-    q[0][0] = fma(ccur[0][0], Pg[0][0], q[0][0]);      // first use of this group: waits for its loads
-    if constexpr (g + G < E) {
-      int noff = g + G;
-      asm volatile("" : "+s"(noff), "+v"(q[0][0]));   // the next group's offset exists only from here on
-      const const_ptr_t cn = cf4 + noff;
-#pragma unroll
-      for (int k = 0; k < K; ++k)
-#pragma unroll
-        for (int e = 0; e < G; ++e) cnxt[k][e] = (g + G + e < E) ? cn[k * E + e] : 0.0;
-    }
-#pragma unroll
-    for (int k = 0; k < K; ++k) {
-#pragma unroll
-      for (int e = 0; e < ng; ++e) {
-#pragma unroll
-        for (int f = 0; f < NF; ++f)
-          if (!(k == 0 && e == 0 && f == 0)) q[f][k] = fma(ccur[k][e], Pg[f][e], q[f][k]);
+    double P[ng];
+    static_for<0, ng>([&](auto EI) {
+      constexpr int e = EI.value;
+      P[e] = packed_entry<D, 16 * r + e>(yr, yi);
+      if constexpr (packed_part(16 * r + e, D) == 0) n2 += P[e];
+    });
+    static_for<0, K>([&](auto KI) {
+      constexpr int k = KI.value;
+      if (class_on(tmask, k)) {
+        double ck;
+        if constexpr (RESIDENT) ck = creg[k * R + r]; else ck = c[k];
+        static_for<0, ng>([&](auto EI) {
+          constexpr int e = EI.value;
+          fma_bcast<e, e == 0>(q[k][e % 3], ck, P[e]);
+        });
       }
-    }
-#pragma unroll
-    for (int f = 0; f < NF; ++f)
-#pragma unroll
-      for (int k = 0; k < K; ++k) asm volatile("" : "+v"(q[f][k]));
-#pragma unroll
-    for (int k = 0; k < K; ++k)
-#pragma unroll
-      for (int e = 0; e < G; ++e) ccur[k][e] = cnxt[k][e];
+    });
   });
+  DEV_STAMP(7);
 
-#pragma unroll
-  for (int f = 0; f < NF; ++f) {
-    // posterior over the active classes: pi_k / det B_k * q_k^-D with q_k = max(qraw_k / n2c, eps_q)
-    const double n2c = fmax(n2[f], GSS_EPS_NORM_SQ);
-    const double qfloor = GSS_EPS_Q * n2c;
-    double rq[K], mant[K];
-    int ex[K];
-    bool a[K];
-    int emax = -(1 << 28);
-#pragma unroll
-    for (int k = 0; k < K; ++k) {
-      a[k] = (abits[f] >> k) & 1u;
-      rq[k] = rcp_f64_fast(fmax(q[f][k], qfloor));        // 1 / (q_k * n2c): the M-step weight is gamma_k * rq
-      const double u = rq[k] * n2c;                  // 1 / q_k
-      const double mu = __builtin_amdgcn_frexp_mant(u);
-      const int eu = __builtin_amdgcn_frexp_exp(u);
-      const double pw = ipow<D>(mu);                 // in [2^-D, 1)
-      mant[k] = cm[k] * __builtin_amdgcn_frexp_mant(pw);
-      ex[k] = a[k] ? ce[k] + eu * D + __builtin_amdgcn_frexp_exp(pw) : -(1 << 28);
-      emax = ex[k] > emax ? ex[k] : emax;
-    }
-    double v[K], Z = 0.0;
-#pragma unroll
-    for (int k = 0; k < K; ++k) {
-      int de = ex[k] - emax;
-      de = de < -1100 ? -1100 : de;
-      v[k] = a[k] ? ldexp(mant[k], de) : 0.0;
+  // ---- posterior over the active classes: v_k = pi_k / det B_k * q_k^-D with q_k = max(qraw_k / n2c, eps_q),
+  // normalised over k.  For D <= 8 this needs no scaling: B has trace D and eigenvalues >= 1e-6, so
+  // 1e-6 <= q <= 1e6 on unit vectors (floored at 1e-10), q^-D lies in [1e-48, 1e80], 1 / det B in
+  // [1, 1e42] and pi in [1e-30, 1]: every v_k is a normal double.
+  const double n2c = fmax(n2, GSS_EPS_NORM_SQ);
+  const double qfloor = GSS_EPS_Q * n2c;
+  double rq[K], v[K], Z = 0.0;
+  static_for<0, K>([&](auto KI) {
+    constexpr int k = KI.value;
+    rq[k] = 0.0;
+    v[k] = 0.0;
+    if (class_on(tmask, k)) {
+      rq[k] = rcp_f64_fast(fmax(q[k][0] + q[k][1] + q[k][2], qfloor));   // 1 / (q * n2c): the M-step weight is gamma * rq
+      const double u = rq[k] * n2c;                             // 1 / q
+      const double p = cc[k] * ipow<D>(u);
+      v[k] = ((abits >> k) & 1u) ? p : 0.0;
       Z += v[k];
     }
-    const double rz = Z > 0.0 ? rcp_f64_fast(Z) : 0.0;
-    if constexpr (FINAL) {
-      if (valid[f] && !(n2[f] >= GSS_EPS_NORM_SQ)) atomicOr(status, GSS_STATUS_ZERO_FRAME);
-      if (t[f] < Tmax) {
-#pragma unroll
-        for (int k = 0; k < K; ++k) gamma_row[k * gamma_kstride + t[f]] = (float)(v[k] * rz);
+  });
+  const double rz = Z > 0.0 ? rcp_f64_fast(Z) : 0.0;
+  if constexpr (FINAL) {
+    if (valid && !(n2 >= GSS_EPS_NORM_SQ)) atomicOr(status, GSS_STATUS_ZERO_FRAME);
+    static_for<0, K>([&](auto KI) {
+      constexpr int k = KI.value;
+      if (class_on(tmask, k)) {
+        if (t < Tmax) gamma_row[k * gamma_kstride + t] = (float)(v[k] * rz);
       }
-    } else {
-      // this tile's y and weights go to LDS, then phase 2 runs over it
-      if (t0 + f * kWave >= T) break;              // uniform: nothing valid in this tile
+    });
+  } else {
+    // this tile's y and weights go to LDS, then phase 2 runs over it
 #pragma unroll
-      for (int d = 0; d < 8; ++d) {
-        double2 yv = make_double2(0.0, 0.0);
-        if (d < D) yv = make_double2(yr[f][d < D ? d : 0], yi[f][d < D ? d : 0]);
-        *reinterpret_cast<double2*>(&sY[lane * kYStride + 2 * d]) = yv;
-      }
-#pragma unroll
-      for (int k = 0; k < K; ++k) {
+    for (int d = 0; d < 8; ++d) {
+      double2 yv = make_double2(0.0, 0.0);
+      if (d < D) yv = make_double2(yr[d < D ? d : 0], yi[d < D ? d : 0]);
+      *reinterpret_cast<double2*>(&sY[lane * kYStride + 2 * d]) = yv;
+    }
+    static_for<0, K>([&](auto KI) {
+      constexpr int k = KI.value;
+      if (class_on(tmask, k)) {
         const double g = v[k] * rz;
         nacc[k] += g;
         sW[lane * WS + k] = g * rq[k];
       }
-      wave_lds_sync();
+    });
+    DEV_STAMP(2);
+    wave_lds_sync();
+    DEV_STAMP(3);
 
-      // ---- phase 2 ----
-      accumulate_tile<K, K | 1>(sY, sW, tg, eg, acc);
-      wave_lds_sync();
-    }
+    // ---- phase 2 ----
+    accumulate_tile_masked<K, WS>(sY, sW, tg, eg, tmask, acc);
+    wave_lds_sync();
+    DEV_STAMP(4);
   }
 }
 
 template <int D, int K, bool FINAL>
 __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
-    const float2* __restrict__ Y, const uint8_t* __restrict__ act, const int32_t* __restrict__ T_len,
-    const double* __restrict__ coef, const double* __restrict__ cmant, const int32_t* __restrict__ cexp,
+    const float2* __restrict__ Y, const uint8_t* __restrict__ abyte, const uint32_t* __restrict__ tmask,
+    const int32_t* __restrict__ T_len,
+    const double* __restrict__ coef, const double* __restrict__ cconst,
     double* __restrict__ part, double* __restrict__ npart, float* __restrict__ gamma, uint32_t* __restrict__ status,
     int F, int Tmax, ChunkMap cmap) {
   constexpr int E = D * D;
-  constexpr int WS = K | 1;
+  constexpr int R = coef_regs(D);
+  constexpr bool RESIDENT = K * R <= kResidentRegs;
+  constexpr int WS = weight_stride(K);
   constexpr int kTileDoubles = kWave * kYStride + kWave * WS;
-  // per-wavefront tiles; reused at the end for the cross-wavefront reduction (needs kPassWaves*(64*K+K))
+  constexpr int kCoefDoubles = RESIDENT ? 0 : K * R * 16;
+  // per-wavefront tiles (+ the coefficient copy); the tiles are reused at the end for the cross-wavefront
+  // reduction (needs kPassWaves * (64 * K + K))
   constexpr int kRedDoubles = kPassWaves * (64 * K + K);
-  constexpr int kLdsDoubles = FINAL ? 1 : (kPassWaves * kTileDoubles > kRedDoubles ? kPassWaves * kTileDoubles : kRedDoubles);
-  __shared__ __attribute__((aligned(16))) double lds[kLdsDoubles];
+  constexpr int kTilesDoubles = FINAL ? 2 : (kPassWaves * kTileDoubles > kRedDoubles ? kPassWaves * kTileDoubles : kRedDoubles);
+  __shared__ __attribute__((aligned(16))) double lds[kTilesDoubles + kCoefDoubles];
 
   const int lane = threadIdx.x & (kWave - 1);
-  const int wave = threadIdx.x / kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   long sf;
   int chunk, tiles_per_chunk;
   chunk_decode(cmap, blockIdx.x, sf, chunk, tiles_per_chunk);
@@ -284,10 +310,38 @@ __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
   const int t_end = FINAL ? Tmax : T;       // the final pass also writes the zero padding
 
   const double* __restrict__ cf = coef + sf * (long)(K * E);
-  const double* __restrict__ cm = cmant + sf * K;
-  const int32_t* __restrict__ ce = cexp + sf * K;
   double* __restrict__ sY = lds + (FINAL ? 0 : wave * kTileDoubles);
   double* __restrict__ sW = sY + (FINAL ? 0 : kWave * kYStride);
+  double* __restrict__ sC = lds + kTilesDoubles;
+
+  // The class coefficients: register r of class k holds entries 16 r .. 16 r + 15 of its packed coefficients,
+  // entry 16 r + (lane mod 16) in every lane (a lane past the end of the class reads the last entry of the
+  // array instead: its value is never used).
+  double creg[RESIDENT ? K * R : 1];
+  if constexpr (RESIDENT) {
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const int e = 16 * r + (lane & 15);
+        creg[k * R + r] = cf[k * E + (e < E ? e : E - 1)];
+      }
+  } else {
+    creg[0] = 0.0;
+    for (int x = threadIdx.x; x < K * R * 16; x += kWave * kPassWaves) {
+      const int k = x / (R * 16), e = x % (R * 16);
+      sC[x] = cf[k * E + (e < E ? e : E - 1)];
+    }
+    __syncthreads();
+  }
+  // class constants pi_k / det B_k (wave-uniform, read through the scalar path)
+  double cc[K];
+  {
+    typedef const __attribute__((address_space(4))) double* cc_ptr_t;
+    const cc_ptr_t ccp = (cc_ptr_t)(uintptr_t)(cconst + sf * K);
+#pragma unroll
+    for (int k = 0; k < K; ++k) cc[k] = ccp[k];
+  }
 
   double acc[8][K];
   double nacc[K];
@@ -298,33 +352,42 @@ __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
     for (int n = 0; n < 8; ++n) acc[n][k] = 0.0;
   }
   const float2* __restrict__ Yrow = Y + sf * (long)Tmax * D;
-  const uint8_t* __restrict__ arow = act + (long)s * K * Tmax;
+  const uint8_t* __restrict__ abrow = abyte + (long)s * Tmax;
+  const int tiles_total = (Tmax + kWave - 1) / kWave;
+  // the tile masks are read through the scalar path (they were written by an earlier kernel)
+  typedef const __attribute__((address_space(4))) uint32_t* mask_ptr_t;
+  const mask_ptr_t tmrow = (mask_ptr_t)(uintptr_t)(tmask + (long)s * tiles_total);
   float* __restrict__ gamma_row = FINAL ? gamma + ((long)s * K * F + f) * Tmax : nullptr;
   const long gamma_kstride = (long)F * Tmax;
 
-  // The chunk's tiles, as units of kNF tiles followed by single tiles, dealt to the wavefronts round-robin.
+  // The chunk's tiles are split into one contiguous range per wavefront (lengths differ by at most one); the
+  // assignment depends only on the tile count, so the sums are bitwise reproducible.
   const int tile_lo = chunk * tiles_per_chunk;
   int tile_hi = tile_lo + tiles_per_chunk;
   const int tile_end = (t_end + kWave - 1) / kWave;
   tile_hi = tile_hi < tile_end ? tile_hi : tile_end;
   const int n_tiles = tile_hi > tile_lo ? tile_hi - tile_lo : 0;
-  // a chunk with no more tiles than wavefronts is dealt out tile by tile
-  const int n_big = n_tiles <= kPassWaves ? 0 : n_tiles / kNF;
-  const int n_units = n_big + (n_tiles - n_big * kNF);
-  for (int u = wave; u < n_units; u += kPassWaves) {
-    if (u < n_big) {
-      pass_unit<D, K, kNF, FINAL>(Yrow, arow, cf, cm, ce, gamma_row, status, gamma_kstride, T, Tmax,
-                                  (tile_lo + u * kNF) * kWave, lane, sY, sW, acc, nacc);
-    } else {
-      pass_unit<D, K, 1, FINAL>(Yrow, arow, cf, cm, ce, gamma_row, status, gamma_kstride, T, Tmax,
-                                (tile_lo + n_big * kNF + (u - n_big)) * kWave, lane, sY, sW, acc, nacc);
-    }
+  const int my_lo = tile_lo + (n_tiles * wave) / kPassWaves;
+  const int my_hi = tile_lo + (n_tiles * (wave + 1)) / kPassWaves;
+  for (int tile = my_lo; tile < my_hi; ++tile) {
+    pass_tile<D, K, FINAL, RESIDENT>(Yrow, abrow, creg, sC, cc, gamma_row, status, gamma_kstride, T, Tmax, tile * kWave,
+                                     lane, tmrow[tile], sY, sW, acc, nacc
+#ifdef GSS_DEV_TIMING
+                                     , blockIdx.x == 100 && !FINAL, wave, (tile - my_lo) < 15 ? tile - my_lo : 14
+#endif
+                                     );
   }
   if (FINAL) return;
+#ifdef GSS_DEV_TIMING
+  if (blockIdx.x == 100 && lane == 0) { g_dev_times[(wave * 16 + 15) * 8 + 0] = clock64(); }
+#endif
 
   // Reduce over the 8 frame groups and over the wavefronts; write the chunk's packed partial sums and counts.
   reduce_and_store_partials<D, K, true>(acc, nacc, sY, lds, part + (long)blockIdx.x * (K * E),
                                         npart + (long)blockIdx.x * K, lane, wave);
+#ifdef GSS_DEV_TIMING
+  if (blockIdx.x == 100 && lane == 0) { g_dev_times[(wave * 16 + 15) * 8 + 1] = clock64(); }
+#endif
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -337,7 +400,7 @@ __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
 template <int D, int K>
 __global__ __launch_bounds__(kWave * K) void em_factor_small(
     const double* __restrict__ part, const double* __restrict__ npart,
-    double* __restrict__ coef, double* __restrict__ cmant, int32_t* __restrict__ cexp, uint32_t* __restrict__ status,
+    double* __restrict__ coef, double* __restrict__ cconst, uint32_t* __restrict__ status,
     ChunkMap cmap, int weight_mode) {
   constexpr int E = D * D;
   __shared__ double sR[K][E];
@@ -446,8 +509,7 @@ __global__ __launch_bounds__(kWave * K) void em_factor_small(
       pi = 1.0 / (double)K;
     }
     const double c = fmax(pi, GSS_EPS_PI) / detm;            // pi_k / det B_k = c * 2^-dete
-    cmant[sf * K + k] = __builtin_amdgcn_frexp_mant(c);
-    cexp[sf * K + k] = __builtin_amdgcn_frexp_exp(c) - dete;
+    cconst[sf * K + k] = ldexp(c, -dete);
   }
 }
 
@@ -458,13 +520,13 @@ struct EmPlan {
   ChunkMap acc;          // chunking of the accumulating passes
   ChunkMap fin;          // chunking of the final pass
   long wgs_acc, wgs_fin;
-  size_t off_coef, off_cm, off_ce, off_part, off_npart, total;
+  size_t off_coef, off_cc, off_part, off_npart, off_abyte, off_tmask, total;
 };
 
-EmPlan make_plan(const gss_ctx* ctx, long n_sf, int Tmax, int D, int K, int wgs_per_cu, int wgs_per_cu_fin) {
+EmPlan make_plan(const gss_ctx* ctx, long n_sf, int S, int Tmax, int D, int K, int wgs_per_cu, int wgs_per_cu_fin) {
   EmPlan p;
   const int tiles = (Tmax + kWave - 1) / kWave;
-  const int round_up = kPassWaves * kNF;               // a chunk is a whole number of rounds of units
+  const int round_up = kPassWaves;                     // a chunk is a whole number of rounds of tiles
   const long slots = (long)ctx->num_cu * wgs_per_cu;
   p.acc = plan_chunk_map(slots, n_sf, tiles, round_up, 0, true);
   p.wgs_acc = chunk_map_wgs(p.acc, n_sf);
@@ -473,10 +535,11 @@ EmPlan make_plan(const gss_ctx* ctx, long n_sf, int Tmax, int D, int K, int wgs_
   const size_t E = (size_t)D * D;
   size_t o = 0;
   p.off_coef = o;  o = gss_align_up(o + (size_t)n_sf * K * E * sizeof(double) + 64, 256);
-  p.off_cm = o;    o = gss_align_up(o + (size_t)n_sf * K * sizeof(double), 256);
-  p.off_ce = o;    o = gss_align_up(o + (size_t)n_sf * K * sizeof(int32_t), 256);
+  p.off_cc = o;    o = gss_align_up(o + (size_t)n_sf * K * sizeof(double), 256);
   p.off_part = o;  o = gss_align_up(o + (size_t)p.wgs_acc * K * E * sizeof(double), 256);
   p.off_npart = o; o = gss_align_up(o + (size_t)p.wgs_acc * K * sizeof(double), 256);
+  p.off_abyte = o; o = gss_align_up(o + (size_t)S * Tmax, 256);
+  p.off_tmask = o; o = gss_align_up(o + (size_t)S * tiles * sizeof(uint32_t), 256);
   p.total = o;
   return p;
 }
@@ -488,45 +551,38 @@ int run_small(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_t* 
   // resident workgroups per compute unit of the two pass kernels: asked once per instantiation
   static const int wgs_per_cu = resident_wgs(em_pass_small<D, K, false>, kWave * kPassWaves, 2);
   static const int wgs_per_cu_fin = resident_wgs(em_pass_small<D, K, true>, kWave * kPassWaves, 2);
-  const EmPlan p = make_plan(ctx, n_sf, Tmax, D, K, wgs_per_cu, wgs_per_cu_fin);
+  const EmPlan p = make_plan(ctx, n_sf, S, Tmax, D, K, wgs_per_cu, wgs_per_cu_fin);
   int rc = gss_ensure_scratch(ctx, p.total);
   if (rc != GSS_OK) return rc;
   char* base = (char*)ctx->scratch;
   double* coef = (double*)(base + p.off_coef);
-  double* cm = (double*)(base + p.off_cm);
-  int32_t* ce = (int32_t*)(base + p.off_ce);
+  double* cc = (double*)(base + p.off_cc);
   double* part = (double*)(base + p.off_part);
   double* npart = (double*)(base + p.off_npart);
+  uint8_t* abyte = (uint8_t*)(base + p.off_abyte);
+  uint32_t* tmask = (uint32_t*)(base + p.off_tmask);
+  const int tiles = (Tmax + kWave - 1) / kWave;
 
+  if ((long)S * tiles > 0x7fffffffL) return GSS_EUNSUPPORTED;
   if (p.wgs_acc > 0x7fffffffL || p.wgs_fin > 0x7fffffffL) return GSS_EUNSUPPORTED;
   const dim3 block(kWave * kPassWaves);
-  hipLaunchKernelGGL(em_init_coef, dim3(1024), dim3(256), 0, st, coef, cm, ce, D, K, n_sf);
+  hipLaunchKernelGGL(em_init_coef, dim3(1024), dim3(256), 0, st, coef, cc, D, K, n_sf);
+  hipLaunchKernelGGL(em_pack_activity, dim3((unsigned)(S * tiles)), dim3(kWave), 0, st, act, T_len, abyte, tmask, K, Tmax,
+                     tiles);
   for (int it = 0; it < iters; ++it) {
     gss_profile_begin(ctx, 0, st);
-    hipLaunchKernelGGL((em_pass_small<D, K, false>), dim3((unsigned)p.wgs_acc), block, 0, st, Y, act, T_len, coef, cm, ce,
-                       part, npart, (float*)nullptr, ctx->status, F, Tmax, p.acc);
+    hipLaunchKernelGGL((em_pass_small<D, K, false>), dim3((unsigned)p.wgs_acc), block, 0, st, Y, abyte, tmask, T_len, coef,
+                       cc, part, npart, (float*)nullptr, ctx->status, F, Tmax, p.acc);
     gss_profile_end(ctx, 0, st);
     gss_profile_begin(ctx, 1, st);
-    hipLaunchKernelGGL((em_factor_small<D, K>), dim3((unsigned)n_sf), dim3(kWave * K), 0, st, part, npart, coef, cm, ce,
+    hipLaunchKernelGGL((em_factor_small<D, K>), dim3((unsigned)n_sf), dim3(kWave * K), 0, st, part, npart, coef, cc,
                        ctx->status, p.acc, weight_mode);
     gss_profile_end(ctx, 1, st);
   }
-  hipLaunchKernelGGL((em_pass_small<D, K, true>), dim3((unsigned)p.wgs_fin), block, 0, st, Y, act, T_len, coef, cm, ce,
+  hipLaunchKernelGGL((em_pass_small<D, K, true>), dim3((unsigned)p.wgs_fin), block, 0, st, Y, abyte, tmask, T_len, coef, cc,
                      (double*)nullptr, (double*)nullptr, gamma, ctx->status, F, Tmax, p.fin);
   if (hipGetLastError() != hipSuccess) return GSS_EHIP;
   return GSS_OK;
-}
-
-template <int D>
-int dispatch_k(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_t* T_len, int S, int F, int Tmax,
-               int K, int iters, int weight_mode, float* gamma, hipStream_t st) {
-  switch (K) {
-#define GSS_CASE_K(KK) \
-  case KK: return run_small<D, KK>(ctx, Y, act, T_len, S, F, Tmax, iters, weight_mode, gamma, st);
-    GSS_CASE_K(1) GSS_CASE_K(2) GSS_CASE_K(3) GSS_CASE_K(4) GSS_CASE_K(5) GSS_CASE_K(6) GSS_CASE_K(7) GSS_CASE_K(8)
-#undef GSS_CASE_K
-    default: return GSS_EUNSUPPORTED;
-  }
 }
 
 }  // namespace

@@ -1,16 +1,23 @@
-// One translation unit per channel count D (compiled once for every GSS_INST_D = 1..8 by build.py, so
-// that the template instantiations over (D, K) compile in parallel).
+// One translation unit per (channel count D, class count K): compiled once for every GSS_INST_D = 1..8 and
+// GSS_INST_K = 1..8 by build.py, so that the template instantiations compile in parallel.
 #include "gss_em_impl.h"
 
-#ifndef GSS_INST_D
-#error "compile with -DGSS_INST_D=<channels>"
+#if !defined(GSS_INST_D) || !defined(GSS_INST_K)
+#error "compile with -DGSS_INST_D=<channels> -DGSS_INST_K=<classes>"
 #endif
 
-#define GSS_CAT2(a, b) a##b
-#define GSS_CAT(a, b) GSS_CAT2(a, b)
+#define GSS_CAT4(a, b, c, d) a##b##c##d
+#define GSS_NAME(a, b, c, d) GSS_CAT4(a, b, c, d)
 
-int GSS_CAT(gss_em_small_d, GSS_INST_D)(gss_ctx* ctx, const float* Y, const uint8_t* activity, const int32_t* T_len,
-                                        int S, int F, int Tmax, int K, int iters, int weight_mode, float* gamma,
-                                        hipStream_t st) {
-  return dispatch_k<GSS_INST_D>(ctx, (const float2*)Y, activity, T_len, S, F, Tmax, K, iters, weight_mode, gamma, st);
+int GSS_NAME(gss_em_small_d, GSS_INST_D, _k, GSS_INST_K)(gss_ctx* ctx, const float* Y, const uint8_t* activity,
+                                                          const int32_t* T_len, int S, int F, int Tmax, int iters,
+                                                          int weight_mode, float* gamma, hipStream_t st) {
+  return run_small<GSS_INST_D, GSS_INST_K>(ctx, (const float2*)Y, activity, T_len, S, F, Tmax, iters, weight_mode, gamma,
+                                           st);
 }
+
+#ifdef GSS_DEV_TIMING
+extern "C" int gss_dev_read_times(long long* out) {
+  return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_dev_times), sizeof(long long) * 4 * 16 * 8) == hipSuccess ? 0 : -1;
+}
+#endif

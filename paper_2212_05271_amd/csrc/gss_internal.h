@@ -25,6 +25,9 @@ struct gss_ctx {
   int device;
   void* scratch;          // device
   size_t scratch_cap;
+  int scratch_fixed;      // non-zero while a no-allocation entry point runs: `scratch` is then this device's static
+                          // array and gss_ensure_scratch refuses to grow it
+  void* static_scratch;   // device address of the library's static scratch array on this context's device
   uint32_t* status;       // device, one word
   int num_cu;
   void* twiddles;         // device: exp(-2 pi i k / 1024), k = 0..512 (float2), filled by the first STFT/iSTFT call
@@ -49,7 +52,8 @@ int gss_mvdr_large(gss_ctx* ctx, const float* Y, const float* gamma, const int32
 void gss_launch_mvdr_ref(const double* pw, int32_t* ref, uint32_t* status, int S, int F, int D, hipStream_t st);
 
 // Makes sure ctx->scratch holds at least `bytes`.  Growing synchronises the device (the old block may
-// still be in use by kernels already enqueued) and reallocates.
+// still be in use by kernels already enqueued) and reallocates.  While ctx->scratch_fixed is set nothing is
+// allocated: a request beyond the capacity returns GSS_ETOOBIG.
 int gss_ensure_scratch(gss_ctx* ctx, size_t bytes);
 
 static inline size_t gss_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
