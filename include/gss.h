@@ -41,7 +41,9 @@ typedef enum gss_status {
   GSS_EINVAL = -1,       /* null pointer, non-positive size, out-of-range argument   */
   GSS_EUNSUPPORTED = -2, /* shape outside what the kernels are built for             */
   GSS_ENOMEM = -3,       /* scratch allocation failed                                */
-  GSS_EHIP = -4          /* the HIP runtime reported an error (launch, device, ...)  */
+  GSS_EHIP = -4,         /* the HIP runtime reported an error (launch, device, ...)  */
+  GSS_ETOOBIG = -5       /* the problem needs more scratch than the fixed static buffer of a
+                            no-allocation entry point holds (GSS_STATIC_SCRATCH_BYTES)          */
 } gss_status;
 
 /* Limits of the kernels in this build. */
@@ -49,6 +51,7 @@ typedef enum gss_status {
 #define GSS_MAX_K 8
 #define GSS_WPE_MAX_D 8  /* gss_wpe: channels                                   */
 #define GSS_WPE_MAX_N 80 /* gss_wpe: channels x taps (size of the linear system) */
+#define GSS_STATIC_SCRATCH_BYTES (64u << 20) /* gss_cacgmm_em_noalloc: size of the static scratch array per GPU */
 
 /* Bits of the device status word (gss_get_status). */
 #define GSS_STATUS_NONPD_B 1u        /* a class scatter matrix had a non-positive pivot; the pivot was floored */
@@ -135,6 +138,24 @@ int gss_wpe(gss_ctx* ctx, const float* Y, const int32_t* T_len, int S, int F, in
 int gss_cacgmm_em(gss_ctx* ctx, const float* Y, const uint8_t* activity, const int32_t* T_len,
                   int S, int F, int Tmax, int D, int K, int iters, int weight_mode,
                   float* gamma, void* stream);
+
+/*
+ * gss_cacgmm_em for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc).  Same arguments, same kernels and same results as gss_cacgmm_em,
+ * but the working memory (class coefficients and the partial sums of the M-step) lives in a static device
+ * array of GSS_STATIC_SCRATCH_BYTES that the library holds once per GPU until the process ends; the call
+ * makes no hipMalloc / hipFree and no other allocating call.
+ *   - A problem whose working memory exceeds the array is rejected with GSS_ETOOBIG and nothing is written.
+ *     The need is about 16 * S * F * K * D * D bytes (+ the partial sums of problems split over several
+ *     workgroups when S * F is small): S * F * K * D * D <= 3.5 million always fits (e.g. 21 segments of
+ *     513 bins at D = 8, K = 5).
+ *   - Every call on one GPU, from any context, uses the same array: calls that overlap in time on one GPU
+ *     race.  Order them on one stream or with events.  Nothing in the array has to survive between calls;
+ *     each call initialises what it reads.
+ */
+int gss_cacgmm_em_noalloc(gss_ctx* ctx, const float* Y, const uint8_t* activity, const int32_t* T_len,
+                          int S, int F, int Tmax, int D, int K, int iters, int weight_mode,
+                          float* gamma, void* stream);
 
 /*
  * Mask-based MVDR (Souden form), Eq. (6)-(9) of Section 2.3, per segment and frequency.

@@ -20,13 +20,14 @@ import torch  # noqa: F401
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgss.so")
 
-GSS_OK, GSS_EINVAL, GSS_EUNSUPPORTED, GSS_ENOMEM, GSS_EHIP = 0, -1, -2, -3, -4
+GSS_OK, GSS_EINVAL, GSS_EUNSUPPORTED, GSS_ENOMEM, GSS_EHIP, GSS_ETOOBIG = 0, -1, -2, -3, -4, -5
+GSS_STATIC_SCRATCH_BYTES = 64 << 20
 GSS_MAX_D, GSS_MAX_K = 32, 8
 
 EXPORTS = (
     "gss_create", "gss_destroy", "gss_strerror", "gss_version", "gss_get_status", "gss_scratch_bytes",
     "gss_profile_enable", "gss_profile_get",
-    "gss_stft", "gss_wpe", "gss_cacgmm_em", "gss_mvdr", "gss_istft", "gss_frames_from_segments", "gss_frame_activity",
+    "gss_stft", "gss_wpe", "gss_cacgmm_em", "gss_cacgmm_em_noalloc", "gss_mvdr", "gss_istft", "gss_frames_from_segments", "gss_frame_activity",
 )
 
 
@@ -63,6 +64,8 @@ def _load():
     lib.gss_stft.restype = i32
     lib.gss_cacgmm_em.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]
     lib.gss_cacgmm_em.restype = i32
+    lib.gss_cacgmm_em_noalloc.argtypes = lib.gss_cacgmm_em.argtypes
+    lib.gss_cacgmm_em_noalloc.restype = i32
     lib.gss_wpe.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]
     lib.gss_wpe.restype = i32
     lib.gss_mvdr.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp]
@@ -174,7 +177,7 @@ def gss_stft(ctx, x, n_fft=1024, hop=256, out=None):
     return out
 
 
-def gss_cacgmm_em(ctx, Y, activity, T_len=None, iters=20, weight_mode=1, out=None):
+def gss_cacgmm_em(ctx, Y, activity, T_len=None, iters=20, weight_mode=1, out=None, _entry="gss_cacgmm_em"):
     """Y[S,F,Tmax,D] complex64, activity[S,K,Tmax] uint8, T_len[S] int32|None -> gamma[S,K,F,Tmax] float32."""
     import torch
     S, F, Tmax, D = Y.shape
@@ -185,10 +188,17 @@ def gss_cacgmm_em(ctx, Y, activity, T_len=None, iters=20, weight_mode=1, out=Non
         raise ValueError("T_len must be [S]")
     if out is None:
         out = torch.empty((S, K, F, Tmax), dtype=torch.float32, device=Y.device)
-    _check(_lib.gss_cacgmm_em(ctx.handle, _ptr(Y, torch.complex64, "Y"), _ptr(activity, torch.uint8, "activity"),
-                              _ptr(T_len, torch.int32, "T_len"), S, F, Tmax, D, K, int(iters), int(weight_mode),
-                              _ptr(out, torch.float32, "gamma"), _stream()), "gss_cacgmm_em")
+    _check(getattr(_lib, _entry)(ctx.handle, _ptr(Y, torch.complex64, "Y"), _ptr(activity, torch.uint8, "activity"),
+                                 _ptr(T_len, torch.int32, "T_len"), S, F, Tmax, D, K, int(iters), int(weight_mode),
+                                 _ptr(out, torch.float32, "gamma"), _stream()), _entry)
     return out
+
+
+def gss_cacgmm_em_noalloc(ctx, Y, activity, T_len=None, iters=20, weight_mode=1, *, out):
+    """gss_cacgmm_em with the library's static scratch array as working memory (no device allocation inside the
+    call; `out` must be supplied by the caller for the same reason).  Raises GssError(GSS_ETOOBIG) when the problem
+    does not fit GSS_STATIC_SCRATCH_BYTES."""
+    return gss_cacgmm_em(ctx, Y, activity, T_len, iters, weight_mode, out=out, _entry="gss_cacgmm_em_noalloc")
 
 
 def gss_wpe(ctx, Y, T_len=None, taps=10, delay=2, iters=3, out=None):
