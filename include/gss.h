@@ -140,6 +140,22 @@ int gss_cacgmm_em(gss_ctx* ctx, const float* Y, const uint8_t* activity, const i
                   float* gamma, void* stream);
 
 /*
+ * gss_cacgmm_em on segments that are frame ranges of ONE recording's STFT (Section 2.2: a target segment is
+ * processed together with a context window around it; Section 3, "Segment batching": the segments of a
+ * recording are processed in batches).  Nothing is copied: segment s is the frames frame0[s] ..
+ * frame0[s] + T_len[s] - 1 of the recording.
+ *   Yrec   [F][Trec][D] complex64: STFT of the whole recording (gss_stft with S = 1)
+ *   frame0 [S] int64 (device): first frame of every segment, 0 <= frame0[s] <= Trec
+ *   T_len  [S] int32 (device) or NULL (= Tmax): frames of every segment; clipped to Tmax and to the frames the
+ *          recording holds from frame0[s] on
+ *   activity [S][K][Tmax], gamma [S][K][F][Tmax]: as for gss_cacgmm_em (indexed by the frame within the segment)
+ * Everything else as for gss_cacgmm_em.
+ */
+int gss_cacgmm_em_frames(gss_ctx* ctx, const float* Yrec, int64_t Trec, const int64_t* frame0,
+                         const uint8_t* activity, const int32_t* T_len, int S, int F, int Tmax, int D, int K,
+                         int iters, int weight_mode, float* gamma, void* stream);
+
+/*
  * gss_cacgmm_em for callers that cannot allocate device memory (code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc).  Same arguments, same kernels and same results as gss_cacgmm_em,
  * but the working memory (class coefficients and the partial sums of the M-step) lives in a static device
@@ -172,6 +188,14 @@ int gss_cacgmm_em_noalloc(gss_ctx* ctx, const float* Y, const uint8_t* activity,
 int gss_mvdr(gss_ctx* ctx, const float* Y, const float* gamma, const int32_t* T_len,
              int S, int F, int Tmax, int D, int K, const int32_t* target, int32_t* ref,
              float* X, void* stream);
+
+/*
+ * gss_mvdr on segments that are frame ranges of one recording's STFT; Yrec, Trec, frame0, T_len as for
+ * gss_cacgmm_em_frames, everything else as for gss_mvdr (Section 2.3, Eq. (6)-(9)).  X [S][F][Tmax].
+ */
+int gss_mvdr_frames(gss_ctx* ctx, const float* Yrec, int64_t Trec, const int64_t* frame0, const float* gamma,
+                    const int32_t* T_len, int S, int F, int Tmax, int D, int K, const int32_t* target,
+                    int32_t* ref, float* X, void* stream);
 
 /*
  * Inverse STFT matching gss_stft: inverse real FFT, synthesis window w / sum_shifts(w^2), overlap-add,

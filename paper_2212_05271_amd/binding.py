@@ -27,7 +27,8 @@ GSS_MAX_D, GSS_MAX_K = 32, 8
 EXPORTS = (
     "gss_create", "gss_destroy", "gss_strerror", "gss_version", "gss_get_status", "gss_scratch_bytes",
     "gss_profile_enable", "gss_profile_get",
-    "gss_stft", "gss_wpe", "gss_cacgmm_em", "gss_cacgmm_em_noalloc", "gss_mvdr", "gss_istft", "gss_frames_from_segments", "gss_frame_activity",
+    "gss_stft", "gss_wpe", "gss_cacgmm_em", "gss_cacgmm_em_noalloc", "gss_cacgmm_em_frames", "gss_mvdr",
+    "gss_mvdr_frames", "gss_istft", "gss_frames_from_segments", "gss_frame_activity",
 )
 
 
@@ -66,6 +67,10 @@ def _load():
     lib.gss_cacgmm_em.restype = i32
     lib.gss_cacgmm_em_noalloc.argtypes = lib.gss_cacgmm_em.argtypes
     lib.gss_cacgmm_em_noalloc.restype = i32
+    lib.gss_cacgmm_em_frames.argtypes = [vp, vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]
+    lib.gss_cacgmm_em_frames.restype = i32
+    lib.gss_mvdr_frames.argtypes = [vp, vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp]
+    lib.gss_mvdr_frames.restype = i32
     lib.gss_wpe.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]
     lib.gss_wpe.restype = i32
     lib.gss_mvdr.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp]
@@ -199,6 +204,41 @@ def gss_cacgmm_em_noalloc(ctx, Y, activity, T_len=None, iters=20, weight_mode=1,
     call; `out` must be supplied by the caller for the same reason).  Raises GssError(GSS_ETOOBIG) when the problem
     does not fit GSS_STATIC_SCRATCH_BYTES."""
     return gss_cacgmm_em(ctx, Y, activity, T_len, iters, weight_mode, out=out, _entry="gss_cacgmm_em_noalloc")
+
+
+def gss_cacgmm_em_frames(ctx, Yrec, frame0, activity, T_len, iters=20, weight_mode=1, out=None):
+    """Yrec[F,Trec,D] complex64 (the recording's STFT), frame0[S] int64, activity[S,K,Tmax] uint8, T_len[S] int32
+    -> gamma[S,K,F,Tmax] float32; segment s is frames frame0[s] .. frame0[s] + T_len[s] - 1 of the recording."""
+    import torch
+    F, Trec, D = Yrec.shape
+    S, K, Tmax = activity.shape
+    if tuple(frame0.shape) != (S,) or (T_len is not None and tuple(T_len.shape) != (S,)):
+        raise ValueError("frame0 and T_len must be [S]")
+    if out is None:
+        out = torch.empty((S, K, F, Tmax), dtype=torch.float32, device=Yrec.device)
+    _check(_lib.gss_cacgmm_em_frames(ctx.handle, _ptr(Yrec, torch.complex64, "Yrec"), Trec, _ptr(frame0, torch.int64, "frame0"),
+                                     _ptr(activity, torch.uint8, "activity"), _ptr(T_len, torch.int32, "T_len"),
+                                     S, F, Tmax, D, K, int(iters), int(weight_mode),
+                                     _ptr(out, torch.float32, "gamma"), _stream()), "gss_cacgmm_em_frames")
+    return out
+
+
+def gss_mvdr_frames(ctx, Yrec, frame0, gamma, target, ref, T_len, out=None):
+    """Yrec[F,Trec,D], frame0[S] int64, gamma[S,K,F,Tmax], target[S], ref[S] (in/out), T_len[S] -> X[S,F,Tmax]."""
+    import torch
+    F, Trec, D = Yrec.shape
+    S, K, F2, Tmax = gamma.shape
+    if F2 != F:
+        raise ValueError("gamma must be [S,K,F,Tmax]")
+    if tuple(frame0.shape) != (S,) or tuple(target.shape) != (S,) or tuple(ref.shape) != (S,):
+        raise ValueError("frame0, target and ref must be [S]")
+    if out is None:
+        out = torch.empty((S, F, Tmax), dtype=torch.complex64, device=Yrec.device)
+    _check(_lib.gss_mvdr_frames(ctx.handle, _ptr(Yrec, torch.complex64, "Yrec"), Trec, _ptr(frame0, torch.int64, "frame0"),
+                                _ptr(gamma, torch.float32, "gamma"), _ptr(T_len, torch.int32, "T_len"), S, F, Tmax, D, K,
+                                _ptr(target, torch.int32, "target"), _ptr(ref, torch.int32, "ref"),
+                                _ptr(out, torch.complex64, "X"), _stream()), "gss_mvdr_frames")
+    return out
 
 
 def gss_wpe(ctx, Y, T_len=None, taps=10, delay=2, iters=3, out=None):

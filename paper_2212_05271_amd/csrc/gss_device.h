@@ -80,6 +80,25 @@ __device__ __forceinline__ double packed_entry(const double (&yr)[D], const doub
   else return yi[i] * yr[j] - yr[i] * yi[j];                            // Im(y_i conj(y_j))
 }
 
+// First frame of (segment s, frequency f) in the view and the number T of valid frames of the segment:
+// T_len[s] (all Tmax frames if T_len is NULL) clipped to [0, Tmax] and to what the underlying array holds
+// behind the segment's first frame.
+__device__ __forceinline__ const float2* y_row(const gss_yview& v, const int32_t* __restrict__ T_len, int s, int f,
+                                               int D, int Tmax, int& T) {
+  long off = v.frame0 ? (long)v.frame0[s] : 0;
+  off = off < 0 ? 0 : (off > v.t_limit ? v.t_limit : off);
+  int t = T_len ? T_len[s] : Tmax;
+  t = t < 0 ? 0 : (t > Tmax ? Tmax : t);
+  const long room = v.t_limit - off;
+  T = (long)t > room ? (int)room : t;
+  return v.base + (long)s * v.s_stride + (long)f * v.f_stride + off * D;
+}
+__device__ __forceinline__ int y_frames(const gss_yview& v, const int32_t* __restrict__ T_len, int s, int Tmax) {
+  int T;
+  (void)y_row(v, T_len, s, 0, 1, Tmax, T);
+  return T;
+}
+
 // Orders this wavefront's LDS traffic: everything written before is visible to every lane of the
 // wavefront after.  (The LDS executes one wavefront's instructions in order; this only has to stop the
 // compiler from moving accesses across and make it wait for outstanding ones.)

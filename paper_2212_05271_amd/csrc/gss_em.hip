@@ -24,10 +24,10 @@
 // rounded to fp32.
 #include "gss_internal.h"
 
-typedef int (*em_small_fn)(gss_ctx*, const float*, const uint8_t*, const int32_t*, int, int, int, int, int, float*,
+typedef int (*em_small_fn)(gss_ctx*, const gss_yview&, const uint8_t*, const int32_t*, int, int, int, int, int, float*,
                            hipStream_t);
 #define GSS_DECL(DD, KK)                                                                                          \
-  int gss_em_small_d##DD##_k##KK(gss_ctx* ctx, const float* Y, const uint8_t* activity, const int32_t* T_len, int S, \
+  int gss_em_small_d##DD##_k##KK(gss_ctx* ctx, const gss_yview& Y, const uint8_t* activity, const int32_t* T_len, int S, \
                                  int F, int Tmax, int iters, int weight_mode, float* gamma, hipStream_t st);
 #define GSS_DECL_ROW(DD) \
   GSS_DECL(DD, 1) GSS_DECL(DD, 2) GSS_DECL(DD, 3) GSS_DECL(DD, 4) GSS_DECL(DD, 5) GSS_DECL(DD, 6) GSS_DECL(DD, 7) GSS_DECL(DD, 8)
@@ -42,15 +42,31 @@ static const em_small_fn kEmSmall[8][8] = {GSS_ROW(1), GSS_ROW(2), GSS_ROW(3), G
                                            GSS_ROW(5), GSS_ROW(6), GSS_ROW(7), GSS_ROW(8)};
 #undef GSS_ROW
 
-extern "C" int gss_cacgmm_em(gss_ctx* ctx, const float* Y, const uint8_t* activity, const int32_t* T_len,
-                             int S, int F, int Tmax, int D, int K, int iters, int weight_mode,
-                             float* gamma, void* stream) {
-  if (!ctx || !Y || !activity || !gamma) return GSS_EINVAL;
+static int em_dispatch(gss_ctx* ctx, const gss_yview& yv, const uint8_t* activity, const int32_t* T_len, int S, int F,
+                       int Tmax, int D, int K, int iters, int weight_mode, float* gamma, void* stream) {
   if (S <= 0 || F <= 0 || Tmax <= 0 || D <= 0 || K <= 0 || iters < 0) return GSS_EINVAL;
   if (weight_mode != 0 && weight_mode != 1) return GSS_EINVAL;
   if (D > GSS_MAX_D || K > GSS_MAX_K) return GSS_EUNSUPPORTED;
   if (hipSetDevice(ctx->device) != hipSuccess) return GSS_EHIP;
   hipStream_t st = (hipStream_t)stream;
-  if (D <= 8) return kEmSmall[D - 1][K - 1](ctx, Y, activity, T_len, S, F, Tmax, iters, weight_mode, gamma, st);
-  return gss_em_large(ctx, Y, activity, T_len, S, F, Tmax, D, K, iters, weight_mode, gamma, st);
+  if (D <= 8) return kEmSmall[D - 1][K - 1](ctx, yv, activity, T_len, S, F, Tmax, iters, weight_mode, gamma, st);
+  return gss_em_large(ctx, yv, activity, T_len, S, F, Tmax, D, K, iters, weight_mode, gamma, st);
+}
+
+extern "C" int gss_cacgmm_em(gss_ctx* ctx, const float* Y, const uint8_t* activity, const int32_t* T_len,
+                             int S, int F, int Tmax, int D, int K, int iters, int weight_mode,
+                             float* gamma, void* stream) {
+  if (!ctx || !Y || !activity || !gamma) return GSS_EINVAL;
+  if (F <= 0 || Tmax <= 0 || D <= 0) return GSS_EINVAL;
+  return em_dispatch(ctx, gss_dense_view(Y, F, Tmax, D), activity, T_len, S, F, Tmax, D, K, iters, weight_mode, gamma,
+                     stream);
+}
+
+extern "C" int gss_cacgmm_em_frames(gss_ctx* ctx, const float* Yrec, int64_t Trec, const int64_t* frame0,
+                                    const uint8_t* activity, const int32_t* T_len, int S, int F, int Tmax, int D,
+                                    int K, int iters, int weight_mode, float* gamma, void* stream) {
+  if (!ctx || !Yrec || !frame0 || !activity || !gamma) return GSS_EINVAL;
+  if (Trec <= 0 || D <= 0) return GSS_EINVAL;
+  return em_dispatch(ctx, gss_frames_view(Yrec, Trec, frame0, D), activity, T_len, S, F, Tmax, D, K, iters, weight_mode,
+                     gamma, stream);
 }

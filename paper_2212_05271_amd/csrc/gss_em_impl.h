@@ -94,12 +94,11 @@ __global__ void em_init_coef(double* __restrict__ coef, double* __restrict__ cco
 // (a_{t,k} of Eq. (5); 0 at t >= T_len[s]), tmask[s][tile] is the OR of the bytes of the tile's 64 frames.
 // Grid: one wavefront per (segment, tile).
 __global__ __launch_bounds__(kWave) void em_pack_activity(
-    const uint8_t* __restrict__ act, const int32_t* __restrict__ T_len, uint8_t* __restrict__ abyte,
+    gss_yview yv, const uint8_t* __restrict__ act, const int32_t* __restrict__ T_len, uint8_t* __restrict__ abyte,
     uint32_t* __restrict__ tmask, int K, int Tmax, int tiles) {
   const int s = blockIdx.x / tiles, tile = blockIdx.x % tiles;
   const int lane = threadIdx.x;
-  int T = T_len ? T_len[s] : Tmax;
-  T = T < 0 ? 0 : (T > Tmax ? Tmax : T);
+  const int T = y_frames(yv, T_len, s, Tmax);
   const int t = tile * kWave + lane;
   unsigned b = 0;
   if (t < T)
@@ -281,7 +280,7 @@ __device__ __forceinline__ void pass_tile(
 
 template <int D, int K, bool FINAL>
 __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
-    const float2* __restrict__ Y, const uint8_t* __restrict__ abyte, const uint32_t* __restrict__ tmask,
+    gss_yview yv, const uint8_t* __restrict__ abyte, const uint32_t* __restrict__ tmask,
     const int32_t* __restrict__ T_len,
     const double* __restrict__ coef, const double* __restrict__ cconst,
     double* __restrict__ part, double* __restrict__ npart, float* __restrict__ gamma, uint32_t* __restrict__ status,
@@ -305,8 +304,8 @@ __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
   chunk_decode(cmap, blockIdx.x, sf, chunk, tiles_per_chunk);
   const int s = (int)((unsigned)sf / (unsigned)F);
   const int f = (int)((unsigned)sf % (unsigned)F);
-  int T = T_len ? T_len[s] : Tmax;
-  T = T < 0 ? 0 : (T > Tmax ? Tmax : T);
+  int T;
+  const float2* __restrict__ Yrow = y_row(yv, T_len, s, f, D, Tmax, T);
   const int t_end = FINAL ? Tmax : T;       // the final pass also writes the zero padding
 
   const double* __restrict__ cf = coef + sf * (long)(K * E);
@@ -351,7 +350,6 @@ __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
 #pragma unroll
     for (int n = 0; n < 8; ++n) acc[n][k] = 0.0;
   }
-  const float2* __restrict__ Yrow = Y + sf * (long)Tmax * D;
   const uint8_t* __restrict__ abrow = abyte + (long)s * Tmax;
   const int tiles_total = (Tmax + kWave - 1) / kWave;
   // the tile masks are read through the scalar path (they were written by an earlier kernel)
@@ -545,7 +543,7 @@ EmPlan make_plan(const gss_ctx* ctx, long n_sf, int S, int Tmax, int D, int K, i
 }
 
 template <int D, int K>
-int run_small(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_t* T_len, int S, int F, int Tmax,
+int run_small(gss_ctx* ctx, const gss_yview& Y, const uint8_t* act, const int32_t* T_len, int S, int F, int Tmax,
               int iters, int weight_mode, float* gamma, hipStream_t st) {
   const long n_sf = (long)S * F;
   // resident workgroups per compute unit of the two pass kernels: asked once per instantiation
@@ -567,7 +565,8 @@ int run_small(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_t* 
   if (p.wgs_acc > 0x7fffffffL || p.wgs_fin > 0x7fffffffL) return GSS_EUNSUPPORTED;
   const dim3 block(kWave * kPassWaves);
   hipLaunchKernelGGL(em_init_coef, dim3(1024), dim3(256), 0, st, coef, cc, D, K, n_sf);
-  hipLaunchKernelGGL(em_pack_activity, dim3((unsigned)(S * tiles)), dim3(kWave), 0, st, act, T_len, abyte, tmask, K, Tmax,
+  hipLaunchKernelGGL(em_pack_activity, dim3((unsigned)(S * tiles)), dim3(kWave), 0, st, Y, act, T_len, abyte, tmask, K,
+                     Tmax,
                      tiles);
   for (int it = 0; it < iters; ++it) {
     gss_profile_begin(ctx, 0, st);

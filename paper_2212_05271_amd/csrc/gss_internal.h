@@ -39,14 +39,45 @@ struct gss_ctx {
   int64_t prof_launches[GSS_PROFILE_KERNELS];
 };
 
+// Where the observations of a batch live.  Frame t, channel d of (segment s, frequency f) is the complex number
+//   base[s * s_stride + f * f_stride + ((frame0 ? frame0[s] : 0) + t) * D + d].
+// A dense batch [S][F][Tmax][D] has s_stride = F * Tmax * D, f_stride = Tmax * D, frame0 = NULL; segments
+// that are frame ranges of one recording STFT [F][Trec][D] have s_stride = 0, f_stride = Trec * D and
+// frame0[s] (device) = first frame of segment s.  t_limit = frames per (segment, frequency) row of the
+// underlying array (Tmax or Trec): the kernels never read at or beyond it.
+struct gss_yview {
+  const float2* base;
+  long s_stride, f_stride;
+  const int64_t* frame0;
+  long t_limit;
+};
+static inline gss_yview gss_dense_view(const float* Y, int F, int Tmax, int D) {
+  gss_yview v;
+  v.base = (const float2*)Y;
+  v.s_stride = (long)F * Tmax * D;
+  v.f_stride = (long)Tmax * D;
+  v.frame0 = nullptr;
+  v.t_limit = Tmax;
+  return v;
+}
+static inline gss_yview gss_frames_view(const float* Yrec, int64_t Trec, const int64_t* frame0, int D) {
+  gss_yview v;
+  v.base = (const float2*)Yrec;
+  v.s_stride = 0;
+  v.f_stride = (long)Trec * D;
+  v.frame0 = frame0;
+  v.t_limit = (long)Trec;
+  return v;
+}
+
 // Brackets one kernel launch with HIP events on `st` when profiling is on.
 void gss_profile_begin(gss_ctx* ctx, int which, hipStream_t st);
 void gss_profile_end(gss_ctx* ctx, int which, hipStream_t st);
 
 // Kernels for 9 <= D <= GSS_MAX_D channels (gss_large.hip), called by the entry points after validation.
-int gss_em_large(gss_ctx* ctx, const float* Y, const uint8_t* activity, const int32_t* T_len, int S, int F, int Tmax,
+int gss_em_large(gss_ctx* ctx, const gss_yview& Y, const uint8_t* activity, const int32_t* T_len, int S, int F, int Tmax,
                  int D, int K, int iters, int weight_mode, float* gamma, hipStream_t st);
-int gss_mvdr_large(gss_ctx* ctx, const float* Y, const float* gamma, const int32_t* T_len, int S, int F, int Tmax,
+int gss_mvdr_large(gss_ctx* ctx, const gss_yview& Y, const float* gamma, const int32_t* T_len, int S, int F, int Tmax,
                    int D, int K, const int32_t* target, int32_t* ref, float* X, hipStream_t st);
 // Reference-channel kernel shared by the small- and large-D MVDR paths (gss_mvdr.hip).
 void gss_launch_mvdr_ref(const double* pw, int32_t* ref, uint32_t* status, int S, int F, int D, hipStream_t st);

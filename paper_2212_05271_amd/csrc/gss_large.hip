@@ -15,12 +15,12 @@
 #include "gss_large_impl.h"
 
 #define GSS_DECL_K(KK)                                                                                           \
-  int gss_em_large_k##KK(gss_ctx* ctx, const float* Y, const uint8_t* activity, const int32_t* T_len, int S, int F, \
+  int gss_em_large_k##KK(gss_ctx* ctx, const gss_yview& Y, const uint8_t* activity, const int32_t* T_len, int S, int F, \
                          int Tmax, int D, int iters, int weight_mode, float* gamma, hipStream_t st);
 GSS_DECL_K(1) GSS_DECL_K(2) GSS_DECL_K(3) GSS_DECL_K(4) GSS_DECL_K(5) GSS_DECL_K(6) GSS_DECL_K(7) GSS_DECL_K(8)
 #undef GSS_DECL_K
 
-int gss_em_large(gss_ctx* ctx, const float* Y, const uint8_t* activity, const int32_t* T_len, int S, int F, int Tmax,
+int gss_em_large(gss_ctx* ctx, const gss_yview& Y, const uint8_t* activity, const int32_t* T_len, int S, int F, int Tmax,
                  int D, int K, int iters, int weight_mode, float* gamma, hipStream_t st) {
   switch (K) {
 #define GSS_CASE_K(KK) \
@@ -31,9 +31,9 @@ int gss_em_large(gss_ctx* ctx, const float* Y, const uint8_t* activity, const in
   }
 }
 
-int gss_mvdr_large(gss_ctx* ctx, const float* Y, const float* gamma, const int32_t* T_len, int S, int F, int Tmax,
+int gss_mvdr_large(gss_ctx* ctx, const gss_yview& Y, const float* gamma, const int32_t* T_len, int S, int F, int Tmax,
                    int D, int K, const int32_t* target, int32_t* ref, float* X, hipStream_t st) {
-  const float2* Yc = (const float2*)Y;
+  const gss_yview& Yc = Y;
   float2* Xc = (float2*)X;
   const int nr = (num_items(D) + kWave - 1) / kWave;
   if (nr <= 3) return run_mvdr_large<3>(ctx, Yc, gamma, T_len, S, F, Tmax, D, K, target, ref, Xc, st);

@@ -143,7 +143,7 @@ constexpr int kCoefPadDoubles = 4 * 2 * 2 * GSS_MAX_K;
 
 template <int K, int NR, bool FINAL>
 __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
-    const float2* __restrict__ Y, const uint8_t* __restrict__ act, const int32_t* __restrict__ T_len,
+    gss_yview yv, const uint8_t* __restrict__ act, const int32_t* __restrict__ T_len,
     const double* __restrict__ coef, const double* __restrict__ cmant, const int32_t* __restrict__ cexp,
     double* __restrict__ part, double* __restrict__ npart, float* __restrict__ gamma, uint32_t* __restrict__ status,
     int F, int Tmax, int D, ChunkMap cmap, int RS, int tile_bytes) {
@@ -157,8 +157,8 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
   chunk_decode(cmap, blockIdx.x, sf, chunk, tiles_per_chunk);
   const int s = (int)(sf / F);
   const int f = (int)(sf % F);
-  int T = T_len ? T_len[s] : Tmax;
-  T = T < 0 ? 0 : (T > Tmax ? Tmax : T);
+  int T;
+  const float2* __restrict__ Yrow = y_row(yv, T_len, s, f, D, Tmax, T);
   const int t_end = FINAL ? Tmax : T;
 
   float2* __restrict__ sY = reinterpret_cast<float2*>(lds_raw + (size_t)wave * tile_bytes);
@@ -167,7 +167,6 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
   const double* __restrict__ cf = coef + sf * (long)M * K * 2;
   const double* __restrict__ cm = cmant + sf * K;
   const int32_t* __restrict__ ce = cexp + sf * K;
-  const float2* __restrict__ Yrow = Y + sf * (long)Tmax * D;
   const uint8_t* __restrict__ arow = act + (long)s * K * Tmax;
 
   int oi[NR], oj[NR];
@@ -535,7 +534,7 @@ __global__ __launch_bounds__(1024) void em_factor_large(
 // ----------------------------------------------------------------------------------------------
 template <int NR>
 __global__ __launch_bounds__(kWave * kLargeWaves) void mvdr_cov_large(
-    const float2* __restrict__ Y, const float* __restrict__ gamma, const int32_t* __restrict__ T_len,
+    gss_yview yv, const float* __restrict__ gamma, const int32_t* __restrict__ T_len,
     const int32_t* __restrict__ target, double* __restrict__ part, uint32_t* __restrict__ status,
     int F, int Tmax, int D, int K, ChunkMap cmap, int RS, int tile_bytes) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
@@ -548,8 +547,8 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void mvdr_cov_large(
   chunk_decode(cmap, blockIdx.x, sf, chunk, tiles_per_chunk);
   const int s = (int)(sf / F);
   const int f = (int)(sf % F);
-  int T = T_len ? T_len[s] : Tmax;
-  T = T < 0 ? 0 : (T > Tmax ? Tmax : T);
+  int T;
+  const float2* __restrict__ Yrow = y_row(yv, T_len, s, f, D, Tmax, T);
   int tgt = target[s];
   if (tgt < 0 || tgt >= K) {
     if (threadIdx.x == 0 && chunk == 0 && f == 0) atomicOr(status, GSS_STATUS_BAD_TARGET);
@@ -557,7 +556,6 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void mvdr_cov_large(
   }
   float2* __restrict__ sY = reinterpret_cast<float2*>(lds_raw + (size_t)wave * tile_bytes);
   double* __restrict__ sW = reinterpret_cast<double*>(lds_raw + (size_t)wave * tile_bytes + (size_t)kWave * RS * sizeof(float2));
-  const float2* __restrict__ Yrow = Y + sf * (long)Tmax * D;
   const float* __restrict__ grow = gamma + ((long)s * K * F + f) * Tmax;
   const long gk = (long)F * Tmax;
 
@@ -679,19 +677,18 @@ __global__ __launch_bounds__(1024) void mvdr_solve_large(
 }
 
 __global__ __launch_bounds__(256) void mvdr_apply_large(
-    const float2* __restrict__ Y, const double2* __restrict__ H, const int32_t* __restrict__ ref,
+    gss_yview yv, const double2* __restrict__ H, const int32_t* __restrict__ ref,
     const int32_t* __restrict__ T_len, float2* __restrict__ X, int F, int Tmax, int D, int C, int frames_per_chunk) {
   __shared__ double2 sh[GSS_MAX_D];
   const int chunk = blockIdx.x % C;
   const long sf = blockIdx.x / C;
   const int s = (int)(sf / F);
-  int T = T_len ? T_len[s] : Tmax;
-  T = T < 0 ? 0 : (T > Tmax ? Tmax : T);
+  int T;
+  const float2* __restrict__ Yrow = y_row(yv, T_len, s, (int)(sf % F), D, Tmax, T);
   int r = ref[s];
   r = r < 0 ? 0 : (r >= D ? D - 1 : r);
   if (threadIdx.x < D) sh[threadIdx.x] = H[(sf * D + r) * D + threadIdx.x];
   __syncthreads();
-  const float2* __restrict__ Yrow = Y + sf * (long)Tmax * D;
   float2* __restrict__ Xrow = X + sf * (long)Tmax;
   const int t_lo = chunk * frames_per_chunk;
   int t_hi = t_lo + frames_per_chunk;
@@ -737,7 +734,7 @@ long large_slots(const gss_ctx* ctx, Kern kern, int lds_bytes) {
 }
 
 template <int K, int NR>
-int run_em_large(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_t* T_len, int S, int F, int Tmax,
+int run_em_large(gss_ctx* ctx, const gss_yview& Y, const uint8_t* act, const int32_t* T_len, int S, int F, int Tmax,
                  int D, int iters, int weight_mode, float* gamma, hipStream_t st) {
   const long n_sf = (long)S * F;
   const int M = num_items(D);
@@ -788,7 +785,7 @@ int run_em_large(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_
 }
 
 template <int K>
-int dispatch_nr(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_t* T_len, int S, int F, int Tmax,
+int dispatch_nr(gss_ctx* ctx, const gss_yview& Y, const uint8_t* act, const int32_t* T_len, int S, int F, int Tmax,
                 int D, int iters, int weight_mode, float* gamma, hipStream_t st) {
   const int nr = (num_items(D) + kWave - 1) / kWave;       // 1 .. 9
   if (nr <= 3) return run_em_large<K, 3>(ctx, Y, act, T_len, S, F, Tmax, D, iters, weight_mode, gamma, st);
@@ -798,7 +795,7 @@ int dispatch_nr(gss_ctx* ctx, const float2* Y, const uint8_t* act, const int32_t
 }
 
 template <int NR>
-int run_mvdr_large(gss_ctx* ctx, const float2* Y, const float* gamma, const int32_t* T_len, int S, int F, int Tmax,
+int run_mvdr_large(gss_ctx* ctx, const gss_yview& Y, const float* gamma, const int32_t* T_len, int S, int F, int Tmax,
                    int D, int K, const int32_t* target, int32_t* ref, float2* X, hipStream_t st) {
   const long n_sf = (long)S * F;
   const int M = num_items(D);

@@ -26,7 +26,7 @@ namespace {
 // ----------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(kWave * kPassWaves) void mvdr_cov_small(
-    const float2* __restrict__ Y, const float* __restrict__ gamma, const int32_t* __restrict__ T_len,
+    gss_yview yv, const float* __restrict__ gamma, const int32_t* __restrict__ T_len,
     const int32_t* __restrict__ target, double* __restrict__ part, uint32_t* __restrict__ status,
     int F, int Tmax, int K, int C, int tiles_per_chunk) {
   constexpr int E = D * D;
@@ -42,8 +42,8 @@ __global__ __launch_bounds__(kWave * kPassWaves) void mvdr_cov_small(
   const long sf = blockIdx.x / C;
   const int s = (int)(sf / F);
   const int f = (int)(sf % F);
-  int T = T_len ? T_len[s] : Tmax;
-  T = T < 0 ? 0 : (T > Tmax ? Tmax : T);
+  int T;
+  const float2* __restrict__ Yrow = y_row(yv, T_len, s, f, D, Tmax, T);
   int tgt = target[s];
   if (tgt < 0 || tgt >= K) {                        // out of range: flagged, then clamped
     if (threadIdx.x == 0 && chunk == 0 && f == 0) atomicOr(status, GSS_STATUS_BAD_TARGET);
@@ -57,7 +57,6 @@ __global__ __launch_bounds__(kWave * kPassWaves) void mvdr_cov_small(
   for (int n = 0; n < 8; ++n) { acc[n][0] = 0.0; acc[n][1] = 0.0; }
   const int tg = lane >> 3, eg = lane & 7;
 
-  const float2* __restrict__ Yrow = Y + sf * (long)Tmax * D;
   const float* __restrict__ grow = gamma + ((long)s * K * F + f) * Tmax;   // + k * F * Tmax + t
   const long gk = (long)F * Tmax;
 
@@ -67,13 +66,13 @@ __global__ __launch_bounds__(kWave * kPassWaves) void mvdr_cov_small(
   tile_hi = tile_hi < tile_end ? tile_hi : tile_end;
   // One tile of 64 frames per step; the loads of the wavefront's next tile are issued before the arithmetic
   // of the current one.  A lane beyond T reads frame 0 (its weights are forced to zero).
-  float2 yv[D];
+  float2 yraw[D];
   float gv[GSS_MAX_K];
   auto load_tile = [&](int tile) {
     const int t = tile * kWave + lane;
     const long tc = t < T ? t : 0;
 #pragma unroll
-    for (int d = 0; d < D; ++d) yv[d] = Yrow[tc * D + d];
+    for (int d = 0; d < D; ++d) yraw[d] = Yrow[tc * D + d];
 #pragma unroll
     for (int k = 0; k < GSS_MAX_K; ++k) gv[k] = k < K ? grow[k * gk + tc] : 0.f;
   };
@@ -84,7 +83,7 @@ __global__ __launch_bounds__(kWave * kPassWaves) void mvdr_cov_small(
 #pragma unroll
     for (int d = 0; d < 8; ++d) {
       double2 v = make_double2(0.0, 0.0);
-      if (d < D) v = make_double2((double)yv[d < D ? d : 0].x, (double)yv[d < D ? d : 0].y);
+      if (d < D) v = make_double2((double)yraw[d < D ? d : 0].x, (double)yraw[d < D ? d : 0].y);
       *reinterpret_cast<double2*>(&sY[lane * kYStride + 2 * d]) = v;
     }
     double wt = 0.0, wb = 0.0;
@@ -282,13 +281,13 @@ __global__ __launch_bounds__(1024) void mvdr_ref(const double* __restrict__ pw, 
 // ----------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256) void mvdr_apply_small(
-    const float2* __restrict__ Y, const double2* __restrict__ H, const int32_t* __restrict__ ref,
+    gss_yview yv, const double2* __restrict__ H, const int32_t* __restrict__ ref,
     const int32_t* __restrict__ T_len, float2* __restrict__ X, int F, int Tmax, int C, int frames_per_chunk) {
   const int chunk = blockIdx.x % C;
   const long sf = blockIdx.x / C;
   const int s = (int)(sf / F);
-  int T = T_len ? T_len[s] : Tmax;
-  T = T < 0 ? 0 : (T > Tmax ? Tmax : T);
+  int T;
+  const float2* __restrict__ Yrow = y_row(yv, T_len, s, (int)(sf % F), D, Tmax, T);
   int r = ref[s];
   r = r < 0 ? 0 : (r >= D ? D - 1 : r);
   double hr[D], hi[D];
@@ -298,7 +297,6 @@ __global__ __launch_bounds__(256) void mvdr_apply_small(
     hr[d] = h.x;
     hi[d] = h.y;
   }
-  const float2* __restrict__ Yrow = Y + sf * (long)Tmax * D;
   float2* __restrict__ Xrow = X + sf * (long)Tmax;
   const int t_lo = chunk * frames_per_chunk;
   int t_hi = t_lo + frames_per_chunk;
@@ -318,7 +316,7 @@ __global__ __launch_bounds__(256) void mvdr_apply_small(
 }
 
 template <int D>
-int run_mvdr_small(gss_ctx* ctx, const float2* Y, const float* gamma, const int32_t* T_len, int S, int F, int Tmax,
+int run_mvdr_small(gss_ctx* ctx, const gss_yview& Y, const float* gamma, const int32_t* T_len, int S, int F, int Tmax,
                    int K, const int32_t* target, int32_t* ref, float2* X, hipStream_t st) {
   const long n_sf = (long)S * F;
   constexpr int E = D * D;
@@ -363,21 +361,35 @@ void gss_launch_mvdr_ref(const double* pw, int32_t* ref, uint32_t* status, int S
   hipLaunchKernelGGL(mvdr_ref, dim3((unsigned)S), dim3(1024), 0, st, pw, ref, status, F, D);
 }
 
-extern "C" int gss_mvdr(gss_ctx* ctx, const float* Y, const float* gamma, const int32_t* T_len,
-                        int S, int F, int Tmax, int D, int K, const int32_t* target, int32_t* ref,
-                        float* X, void* stream) {
-  if (!ctx || !Y || !gamma || !target || !ref || !X) return GSS_EINVAL;
+static int mvdr_dispatch(gss_ctx* ctx, const gss_yview& yv, const float* gamma, const int32_t* T_len, int S, int F,
+                         int Tmax, int D, int K, const int32_t* target, int32_t* ref, float* X, void* stream) {
   if (S <= 0 || F <= 0 || Tmax <= 0 || D <= 0 || K <= 0) return GSS_EINVAL;
   if (D > GSS_MAX_D || K > GSS_MAX_K) return GSS_EUNSUPPORTED;
   if (hipSetDevice(ctx->device) != hipSuccess) return GSS_EHIP;
   hipStream_t st = (hipStream_t)stream;
-  const float2* Yc = (const float2*)Y;
   float2* Xc = (float2*)X;
   switch (D) {
 #define GSS_CASE_D(DD) \
-  case DD: return run_mvdr_small<DD>(ctx, Yc, gamma, T_len, S, F, Tmax, K, target, ref, Xc, st);
+  case DD: return run_mvdr_small<DD>(ctx, yv, gamma, T_len, S, F, Tmax, K, target, ref, Xc, st);
     GSS_CASE_D(1) GSS_CASE_D(2) GSS_CASE_D(3) GSS_CASE_D(4) GSS_CASE_D(5) GSS_CASE_D(6) GSS_CASE_D(7) GSS_CASE_D(8)
 #undef GSS_CASE_D
-    default: return gss_mvdr_large(ctx, Y, gamma, T_len, S, F, Tmax, D, K, target, ref, X, st);
+    default: return gss_mvdr_large(ctx, yv, gamma, T_len, S, F, Tmax, D, K, target, ref, X, st);
   }
+}
+
+extern "C" int gss_mvdr(gss_ctx* ctx, const float* Y, const float* gamma, const int32_t* T_len,
+                        int S, int F, int Tmax, int D, int K, const int32_t* target, int32_t* ref,
+                        float* X, void* stream) {
+  if (!ctx || !Y || !gamma || !target || !ref || !X) return GSS_EINVAL;
+  if (F <= 0 || Tmax <= 0 || D <= 0) return GSS_EINVAL;
+  return mvdr_dispatch(ctx, gss_dense_view(Y, F, Tmax, D), gamma, T_len, S, F, Tmax, D, K, target, ref, X, stream);
+}
+
+extern "C" int gss_mvdr_frames(gss_ctx* ctx, const float* Yrec, int64_t Trec, const int64_t* frame0, const float* gamma,
+                               const int32_t* T_len, int S, int F, int Tmax, int D, int K, const int32_t* target,
+                               int32_t* ref, float* X, void* stream) {
+  if (!ctx || !Yrec || !frame0 || !gamma || !target || !ref || !X) return GSS_EINVAL;
+  if (Trec <= 0 || D <= 0) return GSS_EINVAL;
+  return mvdr_dispatch(ctx, gss_frames_view(Yrec, Trec, frame0, D), gamma, T_len, S, F, Tmax, D, K, target, ref, X,
+                       stream);
 }

@@ -43,10 +43,12 @@ def enhance_recording(ctx, x, act_samples, seg_start, seg_end, seg_spk, ctx_left
     """x[D, N] float32 CUDA tensor, act_samples[n_spk, N] uint8 (host), segments (host arrays).
 
     Classes per segment: the n_spk speakers in recording order plus a noise class that is always active
-    (K = n_spk + 1); the target class is the segment's speaker.  wpe_taps > 0 dereverberates every
-    segment's STFT (context included) with gss_wpe before the masks are estimated; masks and beamformer then
-    work on the dereverberated signal (Section 2.1).  Returns a list of 1-D float32 CUDA tensors (the
-    enhanced target region of every segment) and a dict of bookkeeping arrays.
+    (K = n_spk + 1); the target class is the segment's speaker.  The recording is transformed once; a segment
+    (with its context) is a frame range of that STFT and is handed to the library as such
+    (gss_cacgmm_em_frames / gss_mvdr_frames): nothing is copied or padded on the way in.  wpe_taps > 0
+    dereverberates every segment's STFT (context included) with gss_wpe before the masks are estimated; masks
+    and beamformer then work on the dereverberated copy (Section 2.1).  Returns a list of 1-D float32 CUDA
+    tensors (the enhanced target region of every segment) and a dict of bookkeeping arrays.
     """
     import torch
 
@@ -55,36 +57,49 @@ def enhance_recording(ctx, x, act_samples, seg_start, seg_end, seg_spk, ctx_left
     K = n_spk + 1
     if Yrec is None:
         Yrec = gss.gss_stft(ctx, x.reshape(1, D, N).contiguous())          # [1, F, Trec, D]
-    F = Yrec.shape[1]
+    Yr = Yrec[0]
+    F = Yr.shape[0]
     fr = gss.gss_frames_from_segments(seg_start, seg_end, N, ctx_left, ctx_right, HOP)
     n_seg = len(seg_start)
     outputs = [None] * n_seg
-    refs = np.zeros(n_seg, dtype=np.int32)
-    for batch in plan_batches(fr["n_frames"], max_batch_frames):
+    # frame-level activity of the whole recording once; a segment's rows are a slice of it
+    act_rec = gss.gss_frame_activity(act_samples, 0, Yr.shape[1], HOP)
+    batches = plan_batches(fr["n_frames"], max_batch_frames)
+    ref_all = torch.full((n_seg,), -1, dtype=torch.int32, device=x.device)
+    order = np.concatenate([np.asarray(b, dtype=np.int64) for b in batches]) if batches else np.zeros(0, np.int64)
+    frame0_d = torch.from_numpy(np.ascontiguousarray(fr["frame0"][order])).to(x.device)
+    tlen_d = torch.from_numpy(np.ascontiguousarray(fr["n_frames"][order])).to(x.device)
+    tgt_d = torch.from_numpy(np.ascontiguousarray(np.asarray(seg_spk, dtype=np.int32)[order])).to(x.device)
+    pos = 0
+    for batch in batches:
         S = len(batch)
         Tmax = int(max(fr["n_frames"][i] for i in batch))
-        Y = torch.zeros((S, F, Tmax, D), dtype=torch.complex64, device=x.device)
         act = np.zeros((S, K, Tmax), dtype=np.uint8)
-        T_len = np.zeros(S, dtype=np.int32)
         for b, i in enumerate(batch):
             f0, nf = int(fr["frame0"][i]), int(fr["n_frames"][i])
-            Y[b, :, :nf] = Yrec[0, :, f0:f0 + nf]
-            act[b, :n_spk, :nf] = gss.gss_frame_activity(act_samples, f0, nf, HOP)
+            act[b, :n_spk, :nf] = act_rec[:, f0:f0 + nf]
             act[b, n_spk, :nf] = 1
-            T_len[b] = nf
         act_d = torch.from_numpy(act).to(x.device)
-        T_d = torch.from_numpy(T_len).to(x.device)
-        tgt = torch.from_numpy(np.asarray([seg_spk[i] for i in batch], dtype=np.int32)).to(x.device)
+        f0_d, T_d, tgt = frame0_d[pos:pos + S], tlen_d[pos:pos + S], tgt_d[pos:pos + S]
         ref = torch.full((S,), -1, dtype=torch.int32, device=x.device)
         if wpe_taps > 0:
+            Y = torch.zeros((S, F, Tmax, D), dtype=torch.complex64, device=x.device)
+            for b, i in enumerate(batch):
+                f0, nf = int(fr["frame0"][i]), int(fr["n_frames"][i])
+                Y[b, :, :nf] = Yr[:, f0:f0 + nf]
             Y = gss.gss_wpe(ctx, Y, T_d, wpe_taps, wpe_delay, wpe_iters)
-        gamma = gss.gss_cacgmm_em(ctx, Y, act_d, T_d, iters, weight_mode)
-        X = gss.gss_mvdr(ctx, Y, gamma, tgt, ref, T_d)
+            gamma = gss.gss_cacgmm_em(ctx, Y, act_d, T_d, iters, weight_mode)
+            X = gss.gss_mvdr(ctx, Y, gamma, tgt, ref, T_d)
+        else:
+            gamma = gss.gss_cacgmm_em_frames(ctx, Yr, f0_d, act_d, T_d, iters, weight_mode)
+            X = gss.gss_mvdr_frames(ctx, Yr, f0_d, gamma, tgt, ref, T_d)
         xh = gss.gss_istft(ctx, X, (Tmax - 3) * HOP)
-        ref_h = ref.cpu().numpy()
+        ref_all[pos:pos + S] = ref
         for b, i in enumerate(batch):
             outputs[i] = xh[b, int(fr["cut_start"][i]):int(fr["cut_end"][i])]
-            refs[i] = ref_h[b]
+        pos += S
+    refs = np.zeros(n_seg, dtype=np.int32)
+    refs[order] = ref_all.cpu().numpy()
     fr["ref"] = refs
     return outputs, fr
 

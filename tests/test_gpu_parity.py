@@ -418,3 +418,49 @@ def test_argument_errors(env):
     D = Y.shape[-1]
     gss.gss_mvdr(ctx, Y, g, t.zeros(1, dtype=t.int32).cuda(), ref)
     assert ctx.get_status() & 32 and 0 <= int(ref.item()) < D
+
+
+# ---------------------------------------------------------------------------------------------
+# segments as frame ranges of one recording's STFT
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("D", [4, 8, 12])
+def test_frames_entry_points(env, D):
+    """gss_cacgmm_em_frames / gss_mvdr_frames read segments in place out of a recording's STFT: the same bits
+    as the dense entry points on copies of those frame ranges, and the oracle's values; a range that runs past
+    the end of the recording is clipped, never read."""
+    t, gss, ctx, o = env["torch"], env["gss"], env["ctx"], env["o"]
+    rng = np.random.default_rng(900 + D)
+    F, Trec, K, iters = 7, 700, 3, 5
+    Yrec = (_cn(rng, (F, Trec, D)) * np.exp(rng.standard_normal((F, Trec, 1)))).astype(np.complex64)
+    frame0 = np.array([0, 130, 417, 600], dtype=np.int64)
+    T_len = np.array([200, 77, 283, 150], dtype=np.int32)          # the last one would end at frame 750 > Trec
+    S, Tmax = len(frame0), 283
+    act = (rng.random((S, K, Tmax)) < 0.6).astype(np.uint8)
+    act[:, K - 1] = 1
+    for s in range(S):
+        act[s, :, T_len[s]:] = 0
+    Yd = t.from_numpy(Yrec).cuda()
+    f0d, Td, ad = t.from_numpy(frame0).cuda(), t.from_numpy(T_len).cuda(), t.from_numpy(act).cuda()
+    g = gss.gss_cacgmm_em_frames(ctx, Yd, f0d, ad, Td, iters)
+    tgt = t.zeros(S, dtype=t.int32).cuda()
+    ref = t.full((S,), -1, dtype=t.int32).cuda()
+    X = gss.gss_mvdr_frames(ctx, Yd, f0d, g, tgt, ref, Td)
+    t.cuda.synchronize()
+    # dense copies (the clipped length of the last segment is what the recording holds: 100 frames)
+    T_eff = np.minimum(T_len, Trec - frame0).astype(np.int32)
+    Yp = np.zeros((S, F, Tmax, D), np.complex64)
+    for s in range(S):
+        Yp[s, :, :T_eff[s]] = Yrec[:, frame0[s]:frame0[s] + T_eff[s]]
+    gd = gss.gss_cacgmm_em(ctx, t.from_numpy(Yp).cuda(), ad, t.from_numpy(T_eff).cuda(), iters)
+    ref2 = t.full((S,), -1, dtype=t.int32).cuda()
+    Xd = gss.gss_mvdr(ctx, t.from_numpy(Yp).cuda(), gd, tgt, ref2, t.from_numpy(T_eff).cuda())
+    t.cuda.synchronize()
+    assert t.equal(g, gd) and t.equal(X, Xd) and t.equal(ref, ref2)
+    gn = g.cpu().numpy()
+    for s in range(S):
+        go = o.cacgmm_em(Yp[s, :, :T_eff[s]], act[s, :, :T_eff[s]], iters)
+        assert np.max(np.abs(gn[s, :, :, :T_eff[s]] - go)) <= TOL_GAMMA
+        assert np.all(gn[s, :, :, T_eff[s]:] == 0)
+        Xo, ro, _ = o.mvdr(Yp[s, :, :T_eff[s]], go, 0)
+        Xg, rg = _gpu_mvdr(env, Yp[s:s + 1, :, :T_eff[s]], go[None], None, [0], [ro])
+        assert np.linalg.norm(Xg[0] - Xo) <= TOL_X * np.linalg.norm(Xo)
