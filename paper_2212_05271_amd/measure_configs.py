@@ -59,6 +59,39 @@ def row(r):
             f"{r['bins_iters'] / (r['em_ms'] * 1e-3):.3g} | {tf:.1f} | {100 * tf / PEAK_TFLOPS_F64:.0f} % |")
 
 
+def sub_records(torch, gss, ctx, synth):
+    """EM + MVDR stream time of configurations 0-3 (config 2 per length bucket and in total) as a list of dicts:
+    the sub-records of bench.py's JSON line."""
+    recs = []
+
+    def rec(r):
+        tf = r["flops"] / (r["em_ms"] * 1e-3) / 1e12
+        t = (r["em_ms"] + r["mvdr_ms"]) * 1e-3
+        return dict(config=r["name"], S=r["S"], Tmax=r["T"], D=r["D"], K=r["K"], em_iters=r["iters"],
+                    em_ms=round(r["em_ms"], 3), mvdr_ms=round(r["mvdr_ms"], 3), audio_s_per_s=round(r["audio_s"] / t, 1),
+                    em_iters_per_s=round(r["S"] * r["iters"] / (r["em_ms"] * 1e-3), 1),
+                    em_alg_tflops=round(tf, 2), em_frac_of_fp64_peak=round(tf / PEAK_TFLOPS_F64, 4))
+
+    for name, seg in (("c0", synth.config0()), ("c1", synth.config1()), ("c3", synth.config3())):
+        recs.append(rec(measure_batch(torch, gss, ctx, name, seg.Y[None], seg.activity[None], None, seg.iters)))
+    T, ns = synth.config2_plan()
+    tot = None
+    for bi, idx in enumerate(synth.buckets_by_length(T, 4)):
+        segs = [synth.config2_segment(i, T[i], ns[i]) for i in idx]
+        Y, act, T_len, target = synth.pad_batch(segs)
+        r = measure_batch(torch, gss, ctx, f"c2 bucket {bi}", Y, act, T_len, 15, target)
+        recs.append(rec(r))
+        if tot is None:
+            tot = dict(r, name="c2 all 64 segments")
+        else:
+            for k in ("S", "frames", "em_ms", "mvdr_ms", "audio_s", "flops", "bins_iters"):
+                tot[k] += r[k]
+            tot["T"] = max(tot["T"], r["T"])
+        del Y, act
+    recs.append(rec(tot))
+    return recs
+
+
 def sweeps(torch, gss, ctx, synth):
     """The axes of the paper's ablations (Section 5.3) as speed and mask-change sweeps on config 1: EM
     iterations, number of channels, noise class on/off, class-weight mode.  No recognition scores: the
