@@ -82,6 +82,17 @@ int gss_get_status(gss_ctx* ctx, uint32_t* host_out, void* stream);
 int64_t gss_scratch_bytes(const gss_ctx* ctx);
 
 /*
+ * Tuning options of a context (host call, no device work).  Returns GSS_EINVAL for an unknown option.
+ *   GSS_OPT_EM_WHOLE_MIN_PROBLEMS: gss_cacgmm_em* runs a batch with at least this many (segment, frequency)
+ *     problems (and D <= 8) in its one-wavefront-per-problem kernel, smaller batches in the kernels that cut a
+ *     problem over several workgroups.  value < 0 restores the default (three problems per resident
+ *     wavefront of the GPU); 0 always takes the one-wavefront-per-problem kernel.  Both give the same masks
+ *     up to the order of the floating-point sums.
+ */
+#define GSS_OPT_EM_WHOLE_MIN_PROBLEMS 1
+int gss_set_option(gss_ctx* ctx, int option, int64_t value);
+
+/*
  * Per-kernel timing for measurements (not part of the method): when enabled, the launches of the
  * dominant kernels are bracketed with HIP events on the stream they are launched on.
  *   which = 0: the accumulating EM pass kernel (one launch per EM iteration)

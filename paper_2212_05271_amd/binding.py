@@ -22,11 +22,12 @@ LIB_PATH = os.path.join(_HERE, "libgss.so")
 
 GSS_OK, GSS_EINVAL, GSS_EUNSUPPORTED, GSS_ENOMEM, GSS_EHIP, GSS_ETOOBIG = 0, -1, -2, -3, -4, -5
 GSS_STATIC_SCRATCH_BYTES = 64 << 20
+GSS_OPT_EM_WHOLE_MIN_PROBLEMS = 1
 GSS_MAX_D, GSS_MAX_K = 32, 8
 
 EXPORTS = (
     "gss_create", "gss_destroy", "gss_strerror", "gss_version", "gss_get_status", "gss_scratch_bytes",
-    "gss_profile_enable", "gss_profile_get",
+    "gss_profile_enable", "gss_profile_get", "gss_set_option",
     "gss_stft", "gss_wpe", "gss_cacgmm_em", "gss_cacgmm_em_noalloc", "gss_cacgmm_em_frames", "gss_mvdr",
     "gss_mvdr_frames", "gss_istft", "gss_frames_from_segments", "gss_frame_activity",
 )
@@ -57,6 +58,8 @@ def _load():
     lib.gss_get_status.restype = i32
     lib.gss_scratch_bytes.argtypes = [vp]
     lib.gss_scratch_bytes.restype = i64
+    lib.gss_set_option.argtypes = [vp, i32, i64]
+    lib.gss_set_option.restype = i32
     lib.gss_profile_enable.argtypes = [vp, i32]
     lib.gss_profile_enable.restype = i32
     lib.gss_profile_get.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
@@ -155,6 +158,9 @@ class Context:
         out = C.c_uint32(0)
         _check(_lib.gss_get_status(self.handle, C.byref(out), _stream()), "gss_get_status")
         return int(out.value)
+
+    def set_option(self, option, value):
+        _check(_lib.gss_set_option(self.handle, int(option), int(value)), "gss_set_option")
 
     def scratch_bytes(self):
         return int(_lib.gss_scratch_bytes(self.handle))

@@ -60,6 +60,7 @@ int gss_create(gss_ctx** out, int device_id) {
   c->static_scratch = nullptr;
   c->status = nullptr;
   c->num_cu = 256;
+  c->em_whole_min_problems = -1;
   c->twiddles = nullptr;
   c->profile = 0;
   for (int k = 0; k < GSS_PROFILE_KERNELS; ++k) {
@@ -133,6 +134,17 @@ int gss_cacgmm_em_noalloc(gss_ctx* ctx, const float* Y, const uint8_t* activity,
   ctx->scratch_cap = saved_cap;
   ctx->scratch_fixed = 0;
   return rc;
+}
+
+int gss_set_option(gss_ctx* ctx, int option, int64_t value) {
+  if (!ctx) return GSS_EINVAL;
+  switch (option) {
+    case GSS_OPT_EM_WHOLE_MIN_PROBLEMS:
+      ctx->em_whole_min_problems = value;
+      return GSS_OK;
+    default:
+      return GSS_EINVAL;
+  }
 }
 
 int64_t gss_scratch_bytes(const gss_ctx* ctx) { return ctx ? (int64_t)ctx->scratch_cap : 0; }

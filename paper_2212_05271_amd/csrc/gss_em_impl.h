@@ -512,8 +512,265 @@ __global__ __launch_bounds__(kWave * K) void em_factor_small(
 }
 
 // ----------------------------------------------------------------------------------------------
+// Whole-EM kernel for batches with many problems (segments x frequencies >> resident wavefronts): ONE
+// wavefront owns one (segment, frequency) for all iterations.  Per iteration it walks the problem's tiles
+// (pass_tile above), sums its accumulators over the 8 frame groups through LDS, and factorises the K class
+// matrices itself, so that the coefficients of the next iteration go from LDS straight back into its
+// registers: no partial sums in memory, no second kernel, no launch per iteration, nothing shared between
+// wavefronts (a workgroup is one wavefront), and the same fixed summation order on every run.
+//
+// Factorisation in the wavefront: lane (k, i) = (lane / 8, lane % 8) holds row i of the matrix of class k
+// (8 complex numbers) in registers.  B_k = D R_k / N_k is Hermitised by construction (packed sums), scaled
+// to trace D and loaded with delta I (identity for a class without data); in-place Gauss-Jordan sweeps
+// without pivoting (the pivots of a Hermitian positive-definite matrix are positive; their product is
+// det B): the owner of pivot row p publishes it in LDS, the 8 lanes of the class read it back.
+// ----------------------------------------------------------------------------------------------
+template <int D, int K>
+__global__ __launch_bounds__(kWave, 2) void em_whole_small(
+    gss_yview yv, const uint8_t* __restrict__ abyte, const uint32_t* __restrict__ tmask,
+    const int32_t* __restrict__ T_len, float* __restrict__ gamma, uint32_t* __restrict__ status,
+    int F, int Tmax, int iters, int weight_mode) {
+  constexpr int E = D * D;
+  constexpr int R = coef_regs(D);
+  constexpr bool RESIDENT = K * R <= kResidentRegs;
+  constexpr int WS = weight_stride(K);
+  constexpr int kTileDoubles = kWave * kYStride + kWave * WS;
+  constexpr int kCoefDoubles = K * R * 16;             // packed coefficients, padded to whole registers
+  constexpr int kRowDoubles = K * 16;                  // one published pivot row (8 complex) per class
+  __shared__ __attribute__((aligned(16))) double lds[kTileDoubles + kCoefDoubles + K * E + kRowDoubles + 3 * K + 8];
+  double* __restrict__ sY = lds;
+  double* __restrict__ sW = sY + kWave * kYStride;
+  double* __restrict__ sC = lds + kTileDoubles;        // [K][R * 16] coefficients of B^-1 for the next pass
+  double* __restrict__ sR = sC + kCoefDoubles;         // [K][E] packed weighted scatter sums
+  double* __restrict__ sP = sR + K * E;                // [K][16] published pivot rows
+  double* __restrict__ sN = sP + kRowDoubles;          // [K] class counts
+  double* __restrict__ sCC = sN + K;                   // [K] class constants pi / det B
+  double* __restrict__ sT = sCC + K;                   // [K] traces
+
+  const int lane = threadIdx.x;
+  const long sf = blockIdx.x;
+  const int s = (int)((unsigned)sf / (unsigned)F);
+  const int f = (int)((unsigned)sf % (unsigned)F);
+  int T;
+  const float2* __restrict__ Yrow = y_row(yv, T_len, s, f, D, Tmax, T);
+  const uint8_t* __restrict__ abrow = abyte + (long)s * Tmax;
+  const int tiles_total = (Tmax + kWave - 1) / kWave;
+  typedef const __attribute__((address_space(4))) uint32_t* mask_ptr_t;
+  const mask_ptr_t tmrow = (mask_ptr_t)(uintptr_t)(tmask + (long)s * tiles_total);
+  float* __restrict__ gamma_row = gamma + ((long)s * K * F + f) * Tmax;
+  const long gamma_kstride = (long)F * Tmax;
+  const int tiles = (T + kWave - 1) / kWave;
+
+  // pass 0: B = I, uniform weights
+  double creg[RESIDENT ? K * R : 1];
+  double cc[K];
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    cc[k] = 1.0;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int e = 16 * r + (lane & 15);
+      double v = 0.0;
+#pragma unroll
+      for (int d = 0; d < D; ++d)
+        if (e == gss_packed_row(d, D)) v = 1.0;
+      if constexpr (RESIDENT) creg[k * R + r] = v;
+      else if (lane < 16) sC[(k * R + r) * 16 + lane] = v;
+    }
+  }
+  if constexpr (!RESIDENT) {
+    creg[0] = 0.0;
+    wave_lds_sync();
+  }
+
+  const int fk = lane >> 3, fi = lane & 7;              // factorisation: class and row of this lane
+  for (int it = 0; it < iters; ++it) {
+    double acc[8][K];
+    double nacc[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      nacc[k] = 0.0;
+#pragma unroll
+      for (int n = 0; n < 8; ++n) acc[n][k] = 0.0;
+    }
+    for (int tile = 0; tile < tiles; ++tile)
+      pass_tile<D, K, false, RESIDENT>(Yrow, abrow, creg, sC, cc, nullptr, status, gamma_kstride, T, Tmax, tile * kWave,
+                                       lane, tmrow[tile], sY, sW, acc, nacc
+#ifdef GSS_DEV_TIMING
+                                       , false, 0, 0
+#endif
+                                       );
+
+    // ---- sums over the 8 frame groups -> packed sR[k][e]; class counts over the lanes -> sN[k] ----
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      double nv = nacc[k];
+#pragma unroll
+      for (int off = 1; off < kWave; off <<= 1) nv += __shfl_xor(nv, off, kWave);
+      if (lane == 0) sN[k] = nv;
+    }
+    static constexpr SlotTable kSlots = make_slot_table();
+    const int slot = (lane & 7) * 8 + (lane >> 3);     // lane o = 8 n + eg reads back slot (eg, n)
+    const int pidx = kSlots.v[D][slot];
+    const double sgn = kSlots.sign[slot] < 0 ? -1.0 : 1.0;
+#pragma unroll
+    for (int k0 = 0; k0 < K; k0 += 2) {
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+        if (k0 + c < K) {
+#pragma unroll
+          for (int n = 0; n < 8; ++n) sY[(c * 8 + n) * kReduceRow + lane] = acc[n][k0 + c];
+        }
+      wave_lds_sync();
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+        if (k0 + c < K) {
+          double sum = 0.0;
+#pragma unroll
+          for (int tg = 0; tg < 8; ++tg) sum += sY[(c * 8 + (lane >> 3)) * kReduceRow + tg * 8 + (lane & 7)];
+          if (pidx >= 0) sR[(k0 + c) * E + pidx] = sgn * sum;
+        }
+      wave_lds_sync();
+    }
+
+    // ---- M-step: B_k from (R_k, N_k), regularised, inverted; coefficients and class constants ----
+    const bool on = fk < K && fi < D;
+    double ar[8], ai[8];                                  // row fi of class fk
+    double tr = 0.0;
+    if (fk < K) {
+#pragma unroll
+      for (int d = 0; d < D; ++d) tr += sR[fk * E + gss_packed_row(d, D)];
+    }
+    const double Nk = fk < K ? sN[fk] : 1.0;
+    double Ntot = 0.0;
+#pragma unroll
+    for (int k = 0; k < K; ++k) Ntot += sN[k];
+    // B = D R / max(N, eps); dead if its trace <= eps; else rescaled to trace D (= R * D / tr R)
+    const bool dead = !((double)D * tr / fmax(Nk, GSS_EPS_N) > GSS_EPS_N);
+    const double sc = dead ? 0.0 : (double)D / tr;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      ar[j] = 0.0;
+      ai[j] = 0.0;
+      if (on && j < D) {
+        if (j == fi) {
+          ar[j] = (dead ? 1.0 : sR[fk * E + gss_packed_row(fi, D)] * sc) + GSS_DELTA;
+        } else if (!dead) {
+          const int lo = fi < j ? fi : j, hi = fi < j ? j : fi;
+          const int p = gss_packed_row(lo, D) + 1 + 2 * (hi - lo - 1);
+          ar[j] = sR[fk * E + p] * sc;
+          ai[j] = sR[fk * E + p + 1] * sc;
+          if (fi > j) ai[j] = -ai[j];                    // lower triangle = conjugate
+        }
+      }
+    }
+    double det = 1.0;
+#pragma unroll
+    for (int p = 0; p < D; ++p) {
+      if (on && fi == p) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) *reinterpret_cast<double2*>(&sP[fk * 16 + 2 * j]) = make_double2(ar[j], ai[j]);
+      }
+      wave_lds_sync();
+      if (on) {
+        double pr[8], pi[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const double2 v = *reinterpret_cast<const double2*>(&sP[fk * 16 + 2 * j]);
+          pr[j] = v.x;
+          pi[j] = v.y;
+        }
+        double piv = pr[p];
+        if (!(piv > 1e-300)) {
+          piv = 1e-300;
+          if (fi == 0) atomicOr(status, GSS_STATUS_NONPD_B);
+        }
+        det *= piv;
+        const double rp = rcp_f64(piv);
+        if (fi == p) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            ar[j] = pr[j] * rp;
+            ai[j] = pi[j] * rp;
+          }
+          ar[p] = rp;
+          ai[p] = 0.0;
+        } else {
+          const double fr = ar[p] * rp, fim = ai[p] * rp;    // M_ip / pivot
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            if (j != p) {
+              ar[j] -= fr * pr[j] - fim * pi[j];
+              ai[j] -= fr * pi[j] + fim * pr[j];
+            }
+          }
+          ar[p] = -fr;
+          ai[p] = -fim;
+        }
+      }
+      wave_lds_sync();
+    }
+    // packed coefficients of q = sum_i A_ii P_ii + 2 sum_{i<j} (Re A_ij Re P_ij + Im A_ij Im P_ij), A = B^-1
+    if (on) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        if (j < D && j >= fi) {
+          if (j == fi) {
+            sC[fk * (R * 16) + gss_packed_row(fi, D)] = ar[j];
+          } else {
+            const int p = gss_packed_row(fi, D) + 1 + 2 * (j - fi - 1);
+            sC[fk * (R * 16) + p] = 2.0 * ar[j];
+            sC[fk * (R * 16) + p + 1] = 2.0 * ai[j];
+          }
+        }
+      }
+      if (fi == 0) {
+        const double pi_k = weight_mode == 1 ? Nk / fmax(Ntot, GSS_EPS_N) : 1.0 / (double)K;
+        sCC[fk] = fmax(pi_k, GSS_EPS_PI) / det;
+      }
+    }
+    wave_lds_sync();
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      cc[k] = sCC[k];
+      if constexpr (RESIDENT) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          const int e = 16 * r + (lane & 15);
+          creg[k * R + r] = sC[k * (R * 16) + (e < E ? e : E - 1)];
+        }
+      }
+    }
+    wave_lds_sync();
+  }
+
+  // final pass: the posteriors = the masks, zero padding included
+  {
+    double acc[8][K];
+    double nacc[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      nacc[k] = 0.0;
+#pragma unroll
+      for (int n = 0; n < 8; ++n) acc[n][k] = 0.0;
+    }
+    for (int tile = 0; tile < tiles_total; ++tile)
+      pass_tile<D, K, true, RESIDENT>(Yrow, abrow, creg, sC, cc, gamma_row, status, gamma_kstride, T, Tmax, tile * kWave,
+                                      lane, tmrow[tile], sY, sW, acc, nacc
+#ifdef GSS_DEV_TIMING
+                                      , false, 0, 0
+#endif
+                                      );
+  }
+}
+
+// ----------------------------------------------------------------------------------------------
 // Host-side plan and dispatch
 // ----------------------------------------------------------------------------------------------
+// The whole-EM kernel is used when the batch holds at least this many problems per resident wavefront (so that
+// the last, partly filled round of wavefronts is a small part of the run).
+constexpr int kWholeMinRounds = 3;
+
 struct EmPlan {
   ChunkMap acc;          // chunking of the accumulating passes
   ChunkMap fin;          // chunking of the final pass
@@ -564,10 +821,23 @@ int run_small(gss_ctx* ctx, const gss_yview& Y, const uint8_t* act, const int32_
   if ((long)S * tiles > 0x7fffffffL) return GSS_EUNSUPPORTED;
   if (p.wgs_acc > 0x7fffffffL || p.wgs_fin > 0x7fffffffL) return GSS_EUNSUPPORTED;
   const dim3 block(kWave * kPassWaves);
-  hipLaunchKernelGGL(em_init_coef, dim3(1024), dim3(256), 0, st, coef, cc, D, K, n_sf);
   hipLaunchKernelGGL(em_pack_activity, dim3((unsigned)(S * tiles)), dim3(kWave), 0, st, Y, act, T_len, abyte, tmask, K,
-                     Tmax,
-                     tiles);
+                     Tmax, tiles);
+  // Many problems per resident wavefront: one wavefront runs the whole EM of a problem (no partial sums, no
+  // factor launches).  Few problems: each one is cut into chunks over several workgroups, one pass and one
+  // factor launch per iteration.
+  static const int waves_per_cu = resident_wgs(em_whole_small<D, K>, kWave, 8);
+  const long whole_min = ctx->em_whole_min_problems >= 0 ? (long)ctx->em_whole_min_problems
+                                                         : (long)kWholeMinRounds * ctx->num_cu * waves_per_cu;
+  if (iters > 0 && n_sf >= whole_min && n_sf <= 0x7fffffffL) {
+    gss_profile_begin(ctx, 0, st);
+    hipLaunchKernelGGL((em_whole_small<D, K>), dim3((unsigned)n_sf), dim3(kWave), 0, st, Y, abyte, tmask, T_len, gamma,
+                       ctx->status, F, Tmax, iters, weight_mode);
+    gss_profile_end(ctx, 0, st);
+    if (hipGetLastError() != hipSuccess) return GSS_EHIP;
+    return GSS_OK;
+  }
+  hipLaunchKernelGGL(em_init_coef, dim3(1024), dim3(256), 0, st, coef, cc, D, K, n_sf);
   for (int it = 0; it < iters; ++it) {
     gss_profile_begin(ctx, 0, st);
     hipLaunchKernelGGL((em_pass_small<D, K, false>), dim3((unsigned)p.wgs_acc), block, 0, st, Y, abyte, tmask, T_len, coef,

@@ -30,6 +30,7 @@ struct gss_ctx {
   void* static_scratch;   // device address of the library's static scratch array on this context's device
   uint32_t* status;       // device, one word
   int num_cu;
+  int64_t em_whole_min_problems;   // GSS_OPT_EM_WHOLE_MIN_PROBLEMS (< 0: default)
   void* twiddles;         // device: exp(-2 pi i k / 1024), k = 0..512 (float2), filled by the first STFT/iSTFT call
   // optional per-kernel timing with HIP events (gss_profile_enable / gss_profile_get)
   int profile;

@@ -146,6 +146,37 @@ def test_every_small_instantiation(env, D):
     assert env["ctx"].get_status() == 0
 
 
+@pytest.mark.parametrize("D", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_every_whole_em_instantiation(env, D):
+    """The one-wavefront-per-problem kernel (whole EM of a problem in one wavefront, factorisation included),
+    forced through the context option, for every (D, K): a ragged batch of three segments with weights from the
+    masks and uniform, degenerate frames included; and the same bits on a second run."""
+    gss, ctx = env["gss"], env["ctx"]
+    ctx.set_option(gss.GSS_OPT_EM_WHOLE_MIN_PROBLEMS, 0)
+    try:
+        for K in range(1, 9):
+            rng = np.random.default_rng(50 * D + K)
+            S, F, T = 3, 3, 333
+            Y = (_cn(rng, (S, F, T, D)) * np.exp(rng.standard_normal((S, F, T, 1)))).astype(np.complex64)
+            Y[1, :, 40] = 0                                              # a zero-energy frame
+            act = (rng.random((S, K, T)) < 0.5).astype(np.uint8)
+            act[:, K - 1] = 1
+            act[2, :, 100:110] = 0                                       # frames without any active class
+            if K > 1:
+                act[0, 0] = 0                                            # a class that is never active
+            T_len = np.array([T, 150, T - 13], dtype=np.int32)
+            for wm in (1, 0):
+                g = _gpu_em(env, Y, act, T_len, 4, wm)
+                go = env["o"].cacgmm_em_batch(Y, act, T_len, 4, wm)
+                assert np.max(np.abs(g - go)) <= TOL_GAMMA, (D, K, wm)
+                for s_ in range(S):
+                    assert np.all(g[s_, :, :, T_len[s_]:] == 0)
+            assert np.array_equal(g, _gpu_em(env, Y, act, T_len, 4, 0))
+        assert env["ctx"].get_status() == 16                            # the zero-energy frame, nothing else
+    finally:
+        ctx.set_option(gss.GSS_OPT_EM_WHOLE_MIN_PROBLEMS, -1)
+
+
 @pytest.mark.parametrize("D", [10, 20, 26, 32])
 def test_every_large_instantiation(env, D):
     """Every (class count, items-per-lane) instantiation of the large-array kernels: K = 1..8 at one channel
