@@ -49,6 +49,16 @@ definition, not numerical noise):
       clipped to the recording; frame activity is sampled at the sample nearest
       the window centre.
   R13 A fixed number of iterations, no early exit.
+  R16 Reference channel per frequency (speakers that move; Section 3, "Segment
+      batching", says one reference channel suits a recording only when the
+      speakers are stationary): the channel r maximising, for that frequency
+      alone, Re(h_r^H Phi_k h_r) / Re(h_r^H Phi_bg h_r), lowest index on ties.
+  R17 Block-wise processing for speakers that move (Section 1 cites block-online
+      GSS; the paper gives no formula): a segment is cut into consecutive blocks
+      of `block` samples (the last one shorter); block b is enhanced from the
+      span [block start - history, block end) only, i.e. as a segment of its own
+      with left context `history` and no right context, with its own masks,
+      filter and reference channel.  Nothing after the block's last frame is used.
 """
 
 from __future__ import annotations
@@ -241,6 +251,35 @@ def reference_channel_scores(H, phi_k, phi_bg_loaded):
     return num / np.maximum(den, EPS_SNR)
 
 
+def reference_channel_scores_per_frequency(H, phi_k, phi_bg_loaded):
+    """score[f, r] = Re(h_r^H Phi_k h_r) / Re(h_r^H Phi_bg h_r) at frequency f   (R16)."""
+    num = np.einsum("fir,fij,fjr->fr", H.conj(), phi_k, H).real
+    den = np.einsum("fir,fij,fjr->fr", H.conj(), phi_bg_loaded, H).real
+    return num / np.maximum(den, EPS_SNR)
+
+
+def mvdr_per_frequency_ref(Y, gamma, target, ref=None):
+    """Mask-based Souden MVDR with one reference channel per frequency (R16).
+
+    Y[F,T,D], gamma[K,F,T], target class index, ref[F] channels (None = choose all; an entry < 0 = choose
+    that frequency's).  Returns X[F,T] complex128, ref[F] (int), h[F,D].
+    """
+    Y = np.asarray(Y, dtype=np.complex128)
+    F = Y.shape[0]
+    phi_k, phi_bg = masked_covariances(Y, gamma, target)
+    phi_bg_l = load_background(phi_bg)
+    H = souden_filters(phi_k, phi_bg_l)
+    chosen = np.argmax(reference_channel_scores_per_frequency(H, phi_k, phi_bg_l), axis=1)   # lowest index on ties
+    if ref is None:
+        ref_f = chosen
+    else:
+        ref_f = np.where(np.asarray(ref) < 0, chosen, np.asarray(ref))
+    ref_f = ref_f.astype(np.int64)
+    h = H[np.arange(F), :, ref_f]
+    X = np.einsum("fd,ftd->ft", h.conj(), Y)
+    return X, ref_f, h
+
+
 def mvdr(Y, gamma, target, ref=None):
     """Mask-based Souden MVDR for one segment.
 
@@ -359,3 +398,36 @@ def frame_activity(act_samples, frame0, n_frames, hop=256):
         c = min(max(c, 0), N - 1)
         out[..., i] = (act[..., c] != 0)
     return out
+
+
+# ---------------------------------------------------------------------------
+# Block-wise processing of a segment (R17).  The bookkeeping is integers only.
+# ---------------------------------------------------------------------------
+def block_spans(seg_start, seg_end, block):
+    """Consecutive blocks [b0, b1) of `block` samples that tile the segment [seg_start, seg_end)."""
+    s, e, n = int(seg_start), int(seg_end), int(block)
+    return [(b, min(b + n, e)) for b in range(s, e, n)]
+
+
+def enhance_blocks(x, act_samples, seg_start, seg_end, target, block, history, iters, weight_mode=1, hop=256):
+    """One segment of the recording x[D, N], block by block (R17): every block is its own segment with left
+    context `history` samples and no right context: STFT of the recording, the block's frames, EM, MVDR with
+    the block's own reference channel, inverse STFT, cut to the block.  act_samples[n_spk, N]; the classes are
+    the speakers plus a noise class that is always active.  Returns the enhanced segment (float64) and the
+    list of (block start, block end, reference channel)."""
+    x = np.asarray(x, dtype=np.float64)
+    N = x.shape[1]
+    Yrec = stft_channels_last(x).astype(np.complex64)       # the precision in which the stages hand it over
+    out = np.zeros(int(seg_end) - int(seg_start))
+    info = []
+    for b0, b1 in block_spans(seg_start, seg_end, block):
+        fr = segment_frames(b0, b1, N, history, 0, hop)
+        f0, nf = fr["frame0"], fr["n_frames"]
+        Ys = Yrec[:, f0:f0 + nf]
+        act = np.concatenate([frame_activity(act_samples, f0, nf, hop), np.ones((1, nf), np.uint8)])
+        g = cacgmm_em(Ys, act, iters, weight_mode)
+        X, ref, _ = mvdr(Ys, g, target)
+        xb = istft(X, (nf - 3) * hop, 4 * hop, hop)[fr["cut_start"]:fr["cut_end"]]
+        out[b0 - int(seg_start):b1 - int(seg_start)] = xb
+        info.append((b0, b1, ref))
+    return out, info

@@ -770,6 +770,7 @@ __global__ __launch_bounds__(kWave, 2) void em_whole_small(
 // The whole-EM kernel is used when the batch holds at least this many problems per resident wavefront (so that
 // the last, partly filled round of wavefronts is a small part of the run).
 constexpr int kWholeMinRounds = 3;
+constexpr int kWholeMaxTilesAlways = 5;
 
 struct EmPlan {
   ChunkMap acc;          // chunking of the accumulating passes
@@ -829,7 +830,10 @@ int run_small(gss_ctx* ctx, const gss_yview& Y, const uint8_t* act, const int32_
   static const int waves_per_cu = resident_wgs(em_whole_small<D, K>, kWave, 8);
   const long whole_min = ctx->em_whole_min_problems >= 0 ? (long)ctx->em_whole_min_problems
                                                          : (long)kWholeMinRounds * ctx->num_cu * waves_per_cu;
-  if (iters > 0 && n_sf >= whole_min && n_sf <= 0x7fffffffL) {
+  // (Problems of a few tiles also go there whatever their number: two launches per iteration cost more than
+  // the whole EM of such a problem in one wavefront.)
+  const bool whole = n_sf >= whole_min || (ctx->em_whole_min_problems < 0 && tiles <= kWholeMaxTilesAlways);
+  if (iters > 0 && whole && n_sf <= 0x7fffffffL) {
     gss_profile_begin(ctx, 0, st);
     hipLaunchKernelGGL((em_whole_small<D, K>), dim3((unsigned)n_sf), dim3(kWave), 0, st, Y, abyte, tmask, T_len, gamma,
                        ctx->status, F, Tmax, iters, weight_mode);

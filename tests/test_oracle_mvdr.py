@@ -159,3 +159,62 @@ def test_batch_wrapper():
     X, ref = o.mvdr_batch(Y, g, np.array([12, 7]), np.array([0, 1]), np.array([-1, 1]))
     X1, r1, _ = o.mvdr(Y[1, :, :7], g[1, :, :, :7], 1, 1)
     assert np.allclose(X[1, :, :7], X1) and np.all(X[1, :, 7:] == 0) and ref[1] == 1
+
+
+# ---------------------------------------------------------------- reference channel per frequency (R16)
+def test_per_frequency_reference_by_loops():
+    """The per-frequency choice written out with loops; where every frequency prefers the same channel it is
+    the per-segment choice; a fixed reference channel is used as given."""
+    rng = np.random.default_rng(21)
+    F, T, D, K = 6, 40, 4, 3
+    Y = _cn(rng, (F, T, D))
+    g = rng.random((K, F, T))
+    g /= g.sum(0, keepdims=True)
+    X, ref_f, h = o.mvdr_per_frequency_ref(Y, g, 1)
+    pk, pb = o.masked_covariances(Y, g, 1)
+    pbl = o.load_background(pb)
+    H = o.souden_filters(pk, pbl)
+    for f in range(F):
+        best, best_score = 0, -1.0
+        for r in range(D):
+            hr = H[f, :, r]
+            sc = np.vdot(hr, pk[f] @ hr).real / np.vdot(hr, pbl[f] @ hr).real
+            if sc > best_score:
+                best, best_score = r, sc
+        assert ref_f[f] == best
+        assert np.allclose(h[f], H[f, :, best])
+        for t in range(T):
+            assert abs(X[f, t] - np.vdot(H[f, :, best], Y[f, t])) < 1e-12
+    # forcing every frequency to the per-segment channel reproduces the per-segment beamformer
+    Xs, ref_s, _ = o.mvdr(Y, g, 1)
+    Xf, rf, _ = o.mvdr_per_frequency_ref(Y, g, 1, ref=np.full(F, ref_s))
+    assert np.all(rf == ref_s) and np.allclose(Xf, Xs)
+    # mixed: negative entries are chosen, the others kept
+    given = np.array([2, -1, 0, -1, 3, 1])
+    _, rmix, _ = o.mvdr_per_frequency_ref(Y, g, 1, ref=given)
+    assert np.all(rmix[given >= 0] == given[given >= 0]) and np.all(rmix[given < 0] == ref_f[given < 0])
+
+
+def test_per_frequency_reference_follows_a_microphone_that_is_dead_in_a_band():
+    """Two-source toy: microphone 0 hears the target in the lower half of the band only, microphone 1 in the
+    upper half only.  One channel per segment has to give up half of the band; one per frequency picks the
+    live microphone in each half and is distortionless there (h^H v = v_ref)."""
+    rng = np.random.default_rng(22)
+    F, T, D = 8, 400, 3
+    v = _cn(rng, (F, D))
+    v[:4, 1] = 0.0                                   # mic 1 dead below, mic 0 dead above
+    v[4:, 0] = 0.0
+    v[:, 2] *= 0.05                                  # mic 2 hears the target only faintly
+    s = _cn(rng, (F, T))
+    n = 0.3 * _cn(rng, (F, T, D))
+    Y = s[:, :, None] * v[:, None, :] + n
+    g = np.zeros((2, F, T))
+    g[0] = 0.9
+    g[1] = 0.1
+    _, ref_f, h = o.mvdr_per_frequency_ref(Y, g, 0)
+    assert np.all(ref_f[:4] == 0) and np.all(ref_f[4:] == 1)
+    phi_k = np.einsum("fi,fj->fij", v, v.conj())
+    H = o.souden_filters(phi_k, o.load_background(np.einsum("fti,ftj->fij", n, n.conj())))
+    for f in range(F):
+        r = ref_f[f]
+        assert abs(np.vdot(H[f, :, r], v[f]) - v[f, r]) < 1e-9

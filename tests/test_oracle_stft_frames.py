@@ -169,3 +169,54 @@ def test_frame_activity_samples_window_centre():
     assert fa.tolist() == expect
     fa2 = o.frame_activity(np.stack([act, 1 - act]), 2, 5, hop)
     assert fa2.shape == (2, 5) and fa2[0].tolist() == expect[2:7] and np.all(fa2[0] + fa2[1] == 1)
+
+
+# ---------------------------------------------------------------- block-wise processing (R17)
+def test_block_spans_tile_the_segment():
+    for s, e, n in ((0, 10, 3), (5, 6, 4), (7, 39, 8), (100, 164, 64), (3, 20, 100)):
+        spans = o.block_spans(s, e, n)
+        covered = np.zeros(e - s, int)
+        for b0, b1 in spans:
+            assert s <= b0 < b1 <= e and b1 - b0 <= n
+            covered[b0 - s:b1 - s] += 1
+        assert np.all(covered == 1)
+        assert all(b1 - b0 == n for b0, b1 in spans[:-1])
+
+
+def test_block_processing_is_causal_and_reduces_to_the_segment():
+    """(i) One block that spans the whole segment, with the left context as history, is the ordinary
+    per-segment result with no right context.  (ii) Causality: audio that comes after a block's last frame
+    does not change that block's output (here: everything from 768 samples after the block's end on is
+    replaced), while audio inside its history does."""
+    rng = np.random.default_rng(31)
+    D, N = 3, 12000
+    act = np.zeros((2, N), np.uint8)
+    act[0, 1000:9000] = 1
+    act[1, 5000:12000] = 1
+    src = rng.standard_normal((2, N)) * act
+    A = rng.standard_normal((D, 2))
+    x = A @ src + 0.05 * rng.standard_normal((D, N))
+    s0, s1, hist, iters = 2048, 9216, 1536, 4
+    # (i)
+    whole, info = o.enhance_blocks(x, act, s0, s1, 0, s1 - s0, hist, iters)
+    assert len(info) == 1
+    fr = o.segment_frames(s0, s1, N, hist, 0)
+    Ys = o.stft_channels_last(x).astype(np.complex64)[:, fr["frame0"]:fr["frame0"] + fr["n_frames"]]
+    a = np.concatenate([o.frame_activity(act, fr["frame0"], fr["n_frames"]), np.ones((1, fr["n_frames"]), np.uint8)])
+    X, ref, _ = o.mvdr(Ys, o.cacgmm_em(Ys, a, iters), 0)
+    direct = o.istft(X, (fr["n_frames"] - 3) * 256)[fr["cut_start"]:fr["cut_end"]]
+    assert info[0][2] == ref and np.max(np.abs(whole - direct)) < 1e-12
+    # (ii)
+    block = 2560
+    base, binfo = o.enhance_blocks(x, act, s0, s1, 0, block, hist, iters)
+    assert [b[:2] for b in binfo] == o.block_spans(s0, s1, block) and len(binfo) == 3
+    b0, b1, _ = binfo[0]
+    x2 = x.copy()
+    x2[:, b1 + 768:] = rng.standard_normal((D, N - b1 - 768))        # beyond the reach of the block's last frame
+    changed, _ = o.enhance_blocks(x2, act, s0, s1, 0, block, hist, iters)
+    assert np.max(np.abs(changed[:b1 - s0] - base[:b1 - s0])) < 1e-12
+    assert np.max(np.abs(changed[b1 - s0:] - base[b1 - s0:])) > 1e-3
+    x3 = x.copy()
+    x3[:, b0 - hist:b0 - hist + 512] *= 3.0                           # inside the first block's history
+    changed3, _ = o.enhance_blocks(x3, act, s0, s1, 0, block, hist, iters)
+    assert np.max(np.abs(changed3[:b1 - s0] - base[:b1 - s0])) > 1e-6
