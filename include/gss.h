@@ -209,6 +209,23 @@ int gss_mvdr_frames(gss_ctx* ctx, const float* Yrec, int64_t Trec, const int64_t
                     int32_t* ref, float* X, void* stream);
 
 /*
+ * The general form of gss_mvdr: dense batch or frame ranges of a recording, and the reference channel chosen per
+ * segment or per frequency.  Section 3 ("Segment batching") notes that one reference channel for a whole batch
+ * suits stationary speakers only; for speakers that move the channel may be chosen for every frequency on its own.
+ *   Y, Trec, frame0 : Trec = 0 and frame0 = NULL: Y is a dense batch [S][F][Tmax][D] (as gss_mvdr);
+ *                     Trec > 0 and frame0 != NULL: Y is a recording's STFT [F][Trec][D] (as gss_mvdr_frames)
+ *   ref_mode = GSS_REF_PER_SEGMENT  : ref [S], as gss_mvdr
+ *   ref_mode = GSS_REF_PER_FREQUENCY: ref [S][F] in/out; an entry < 0 (or >= D, flagged) is replaced by the channel
+ *                     with the largest ratio of beamformed target power to beamformed background power at that
+ *                     frequency (lowest index on ties); X[s][f][:] uses the filter of ref[s][f]
+ */
+#define GSS_REF_PER_SEGMENT 0
+#define GSS_REF_PER_FREQUENCY 1
+int gss_mvdr_ex(gss_ctx* ctx, const float* Y, int64_t Trec, const int64_t* frame0, const float* gamma,
+                const int32_t* T_len, int S, int F, int Tmax, int D, int K, const int32_t* target,
+                int ref_mode, int32_t* ref, float* X, void* stream);
+
+/*
  * Inverse STFT matching gss_stft: inverse real FFT, synthesis window w / sum_shifts(w^2), overlap-add,
  * padding stripped.
  *   X  [S][F][T] complex64   (F = n_fft/2 + 1)

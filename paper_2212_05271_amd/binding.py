@@ -23,13 +23,14 @@ LIB_PATH = os.path.join(_HERE, "libgss.so")
 GSS_OK, GSS_EINVAL, GSS_EUNSUPPORTED, GSS_ENOMEM, GSS_EHIP, GSS_ETOOBIG = 0, -1, -2, -3, -4, -5
 GSS_STATIC_SCRATCH_BYTES = 64 << 20
 GSS_OPT_EM_WHOLE_MIN_PROBLEMS = 1
+GSS_REF_PER_SEGMENT, GSS_REF_PER_FREQUENCY = 0, 1
 GSS_MAX_D, GSS_MAX_K = 32, 8
 
 EXPORTS = (
     "gss_create", "gss_destroy", "gss_strerror", "gss_version", "gss_get_status", "gss_scratch_bytes",
     "gss_profile_enable", "gss_profile_get", "gss_set_option",
     "gss_stft", "gss_wpe", "gss_cacgmm_em", "gss_cacgmm_em_noalloc", "gss_cacgmm_em_frames", "gss_mvdr",
-    "gss_mvdr_frames", "gss_istft", "gss_frames_from_segments", "gss_frame_activity",
+    "gss_mvdr_frames", "gss_mvdr_ex", "gss_istft", "gss_frames_from_segments", "gss_frame_activity",
 )
 
 
@@ -74,6 +75,8 @@ def _load():
     lib.gss_cacgmm_em_frames.restype = i32
     lib.gss_mvdr_frames.argtypes = [vp, vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp]
     lib.gss_mvdr_frames.restype = i32
+    lib.gss_mvdr_ex.argtypes = [vp, vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, i32, vp, vp, vp]
+    lib.gss_mvdr_ex.restype = i32
     lib.gss_wpe.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]
     lib.gss_wpe.restype = i32
     lib.gss_mvdr.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp]
@@ -244,6 +247,31 @@ def gss_mvdr_frames(ctx, Yrec, frame0, gamma, target, ref, T_len, out=None):
                                 _ptr(gamma, torch.float32, "gamma"), _ptr(T_len, torch.int32, "T_len"), S, F, Tmax, D, K,
                                 _ptr(target, torch.int32, "target"), _ptr(ref, torch.int32, "ref"),
                                 _ptr(out, torch.complex64, "X"), _stream()), "gss_mvdr_frames")
+    return out
+
+
+def gss_mvdr_ex(ctx, Y, gamma, target, ref, T_len=None, frame0=None, ref_mode=GSS_REF_PER_SEGMENT, out=None):
+    """The general beamformer call.  frame0 None: Y[S,F,Tmax,D] dense batch; frame0[S] int64: Y[F,Trec,D] is a
+    recording's STFT.  ref_mode GSS_REF_PER_SEGMENT: ref[S]; GSS_REF_PER_FREQUENCY: ref[S,F] (in/out)."""
+    import torch
+    S, K, F, Tmax = gamma.shape
+    if frame0 is None:
+        if tuple(Y.shape[:3]) != (S, F, Tmax):
+            raise ValueError("Y must be [S,F,Tmax,D]")
+        D, Trec = Y.shape[3], 0
+    else:
+        if Y.dim() != 3 or Y.shape[0] != F or tuple(frame0.shape) != (S,):
+            raise ValueError("Y must be [F,Trec,D] and frame0 [S]")
+        Trec, D = Y.shape[1], Y.shape[2]
+    want = (S, F) if ref_mode == GSS_REF_PER_FREQUENCY else (S,)
+    if tuple(ref.shape) != want or tuple(target.shape) != (S,):
+        raise ValueError(f"ref must be {want} and target [S]")
+    if out is None:
+        out = torch.empty((S, F, Tmax), dtype=torch.complex64, device=Y.device)
+    _check(_lib.gss_mvdr_ex(ctx.handle, _ptr(Y, torch.complex64, "Y"), Trec, _ptr(frame0, torch.int64, "frame0"),
+                            _ptr(gamma, torch.float32, "gamma"), _ptr(T_len, torch.int32, "T_len"), S, F, Tmax, D, K,
+                            _ptr(target, torch.int32, "target"), int(ref_mode), _ptr(ref, torch.int32, "ref"),
+                            _ptr(out, torch.complex64, "X"), _stream()), "gss_mvdr_ex")
     return out
 
 

@@ -537,7 +537,7 @@ __global__ __launch_bounds__(kWave, 2) void em_whole_small(
   constexpr int kTileDoubles = kWave * kYStride + kWave * WS;
   constexpr int kCoefDoubles = K * R * 16;             // packed coefficients, padded to whole registers
   constexpr int kRowDoubles = K * 16;                  // one published pivot row (8 complex) per class
-  __shared__ __attribute__((aligned(16))) double lds[kTileDoubles + kCoefDoubles + K * E + kRowDoubles + 3 * K + 8];
+  __shared__ __attribute__((aligned(16))) double lds[kTileDoubles + kCoefDoubles + K * E + kRowDoubles + 2 * K + 8];
   double* __restrict__ sY = lds;
   double* __restrict__ sW = sY + kWave * kYStride;
   double* __restrict__ sC = lds + kTileDoubles;        // [K][R * 16] coefficients of B^-1 for the next pass
@@ -545,7 +545,6 @@ __global__ __launch_bounds__(kWave, 2) void em_whole_small(
   double* __restrict__ sP = sR + K * E;                // [K][16] published pivot rows
   double* __restrict__ sN = sP + kRowDoubles;          // [K] class counts
   double* __restrict__ sCC = sN + K;                   // [K] class constants pi / det B
-  double* __restrict__ sT = sCC + K;                   // [K] traces
 
   const int lane = threadIdx.x;
   const long sf = blockIdx.x;

@@ -79,9 +79,10 @@ void gss_profile_end(gss_ctx* ctx, int which, hipStream_t st);
 int gss_em_large(gss_ctx* ctx, const gss_yview& Y, const uint8_t* activity, const int32_t* T_len, int S, int F, int Tmax,
                  int D, int K, int iters, int weight_mode, float* gamma, hipStream_t st);
 int gss_mvdr_large(gss_ctx* ctx, const gss_yview& Y, const float* gamma, const int32_t* T_len, int S, int F, int Tmax,
-                   int D, int K, const int32_t* target, int32_t* ref, float* X, hipStream_t st);
+                   int D, int K, const int32_t* target, int32_t* ref, int ref_per_f, float* X, hipStream_t st);
 // Reference-channel kernel shared by the small- and large-D MVDR paths (gss_mvdr.hip).
-void gss_launch_mvdr_ref(const double* pw, int32_t* ref, uint32_t* status, int S, int F, int D, hipStream_t st);
+void gss_launch_mvdr_ref(const double* pw, int32_t* ref, uint32_t* status, int S, int F, int D, int ref_per_f,
+                         hipStream_t st);
 
 // Makes sure ctx->scratch holds at least `bytes`.  Growing synchronises the device (the old block may
 // still be in use by kernels already enqueued) and reallocates.  While ctx->scratch_fixed is set nothing is

@@ -32,12 +32,12 @@ int gss_em_large(gss_ctx* ctx, const gss_yview& Y, const uint8_t* activity, cons
 }
 
 int gss_mvdr_large(gss_ctx* ctx, const gss_yview& Y, const float* gamma, const int32_t* T_len, int S, int F, int Tmax,
-                   int D, int K, const int32_t* target, int32_t* ref, float* X, hipStream_t st) {
+                   int D, int K, const int32_t* target, int32_t* ref, int ref_per_f, float* X, hipStream_t st) {
   const gss_yview& Yc = Y;
   float2* Xc = (float2*)X;
   const int nr = (num_items(D) + kWave - 1) / kWave;
-  if (nr <= 3) return run_mvdr_large<3>(ctx, Yc, gamma, T_len, S, F, Tmax, D, K, target, ref, Xc, st);
-  if (nr <= 5) return run_mvdr_large<5>(ctx, Yc, gamma, T_len, S, F, Tmax, D, K, target, ref, Xc, st);
-  if (nr <= 7) return run_mvdr_large<7>(ctx, Yc, gamma, T_len, S, F, Tmax, D, K, target, ref, Xc, st);
-  return run_mvdr_large<9>(ctx, Yc, gamma, T_len, S, F, Tmax, D, K, target, ref, Xc, st);
+  if (nr <= 3) return run_mvdr_large<3>(ctx, Yc, gamma, T_len, S, F, Tmax, D, K, target, ref, ref_per_f, Xc, st);
+  if (nr <= 5) return run_mvdr_large<5>(ctx, Yc, gamma, T_len, S, F, Tmax, D, K, target, ref, ref_per_f, Xc, st);
+  if (nr <= 7) return run_mvdr_large<7>(ctx, Yc, gamma, T_len, S, F, Tmax, D, K, target, ref, ref_per_f, Xc, st);
+  return run_mvdr_large<9>(ctx, Yc, gamma, T_len, S, F, Tmax, D, K, target, ref, ref_per_f, Xc, st);
 }

@@ -678,14 +678,15 @@ __global__ __launch_bounds__(1024) void mvdr_solve_large(
 
 __global__ __launch_bounds__(256) void mvdr_apply_large(
     gss_yview yv, const double2* __restrict__ H, const int32_t* __restrict__ ref,
-    const int32_t* __restrict__ T_len, float2* __restrict__ X, int F, int Tmax, int D, int C, int frames_per_chunk) {
+    const int32_t* __restrict__ T_len, float2* __restrict__ X, int F, int Tmax, int D, int C, int frames_per_chunk,
+    int ref_per_f) {
   __shared__ double2 sh[GSS_MAX_D];
   const int chunk = blockIdx.x % C;
   const long sf = blockIdx.x / C;
   const int s = (int)(sf / F);
   int T;
   const float2* __restrict__ Yrow = y_row(yv, T_len, s, (int)(sf % F), D, Tmax, T);
-  int r = ref[s];
+  int r = ref[ref_per_f ? sf : (long)s];
   r = r < 0 ? 0 : (r >= D ? D - 1 : r);
   if (threadIdx.x < D) sh[threadIdx.x] = H[(sf * D + r) * D + threadIdx.x];
   __syncthreads();
@@ -796,7 +797,7 @@ int dispatch_nr(gss_ctx* ctx, const gss_yview& Y, const uint8_t* act, const int3
 
 template <int NR>
 int run_mvdr_large(gss_ctx* ctx, const gss_yview& Y, const float* gamma, const int32_t* T_len, int S, int F, int Tmax,
-                   int D, int K, const int32_t* target, int32_t* ref, float2* X, hipStream_t st) {
+                   int D, int K, const int32_t* target, int32_t* ref, int ref_per_f, float2* X, hipStream_t st) {
   const long n_sf = (long)S * F;
   const int M = num_items(D);
   const LargePlan p = plan_large(D, 2);
@@ -821,12 +822,12 @@ int run_mvdr_large(gss_ctx* ctx, const gss_yview& Y, const float* gamma, const i
                      target, part, ctx->status, F, Tmax, D, K, cmap, p.RS, p.tile_bytes);
   const int sthreads = (D * D + 63) / 64 * 64;
   hipLaunchKernelGGL(mvdr_solve_large, dim3((unsigned)n_sf), dim3(sthreads), 0, st, part, H, pw, ctx->status, D, cmap);
-  gss_launch_mvdr_ref(pw, ref, ctx->status, S, F, D, st);
+  gss_launch_mvdr_ref(pw, ref, ctx->status, S, F, D, ref_per_f, st);
   const int fpc = 1024;
   const int CA = (Tmax + fpc - 1) / fpc;
   if (n_sf * CA > 0x7fffffffL) return GSS_EUNSUPPORTED;
   hipLaunchKernelGGL(mvdr_apply_large, dim3((unsigned)(n_sf * CA)), dim3(256), 0, st, Y, H, ref, T_len, X, F, Tmax, D,
-                     CA, fpc);
+                     CA, fpc, ref_per_f);
   if (hipGetLastError() != hipSuccess) return GSS_EHIP;
   return GSS_OK;
 }

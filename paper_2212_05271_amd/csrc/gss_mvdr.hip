@@ -275,6 +275,26 @@ __global__ __launch_bounds__(1024) void mvdr_ref(const double* __restrict__ pw, 
   }
 }
 
+// Reference channel per (segment, frequency): the candidate with the largest ratio of the two powers at that
+// frequency alone (lowest index on ties); 0 <= ref_io[sf] < D on entry is kept.  One thread per (s, f).
+__global__ __launch_bounds__(256) void mvdr_ref_freq(const double* __restrict__ pw, int32_t* __restrict__ ref_io,
+                                                     uint32_t* __restrict__ status, long n_sf, int D) {
+  const long sf = blockIdx.x * (long)blockDim.x + threadIdx.x;
+  if (sf >= n_sf) return;
+  int cur = ref_io[sf];
+  if (cur >= D) atomicOr(status, GSS_STATUS_BAD_REF);
+  if (cur < 0 || cur >= D) {
+    int best = 0;
+    double best_score = pw[(sf * D + 0) * 2 + 0] / fmax(pw[(sf * D + 0) * 2 + 1], GSS_EPS_SNR);
+    for (int c = 1; c < D; ++c) {
+      const double sc = pw[(sf * D + c) * 2 + 0] / fmax(pw[(sf * D + c) * 2 + 1], GSS_EPS_SNR);
+      if (sc > best_score) { best = c; best_score = sc; }
+    }
+    cur = best;
+  }
+  ref_io[sf] = cur;
+}
+
 // ----------------------------------------------------------------------------------------------
 // Apply: X[s][f][t] = sum_d conj(h[d]) y[t][d], lane = frame; the filter is wave-uniform.
 // Grid: blockIdx.x = chunk + C * (f + F * s), 256 frames per workgroup step.
@@ -282,13 +302,14 @@ __global__ __launch_bounds__(1024) void mvdr_ref(const double* __restrict__ pw, 
 template <int D>
 __global__ __launch_bounds__(256) void mvdr_apply_small(
     gss_yview yv, const double2* __restrict__ H, const int32_t* __restrict__ ref,
-    const int32_t* __restrict__ T_len, float2* __restrict__ X, int F, int Tmax, int C, int frames_per_chunk) {
+    const int32_t* __restrict__ T_len, float2* __restrict__ X, int F, int Tmax, int C, int frames_per_chunk,
+    int ref_per_f) {
   const int chunk = blockIdx.x % C;
   const long sf = blockIdx.x / C;
   const int s = (int)(sf / F);
   int T;
   const float2* __restrict__ Yrow = y_row(yv, T_len, s, (int)(sf % F), D, Tmax, T);
-  int r = ref[s];
+  int r = ref[ref_per_f ? sf : (long)s];
   r = r < 0 ? 0 : (r >= D ? D - 1 : r);
   double hr[D], hi[D];
 #pragma unroll
@@ -317,7 +338,7 @@ __global__ __launch_bounds__(256) void mvdr_apply_small(
 
 template <int D>
 int run_mvdr_small(gss_ctx* ctx, const gss_yview& Y, const float* gamma, const int32_t* T_len, int S, int F, int Tmax,
-                   int K, const int32_t* target, int32_t* ref, float2* X, hipStream_t st) {
+                   int K, const int32_t* target, int32_t* ref, int ref_per_f, float2* X, hipStream_t st) {
   const long n_sf = (long)S * F;
   constexpr int E = D * D;
   const int tiles = (Tmax + kWave - 1) / kWave;
@@ -345,51 +366,67 @@ int run_mvdr_small(gss_ctx* ctx, const gss_yview& Y, const float* gamma, const i
   hipLaunchKernelGGL((mvdr_cov_small<D>), dim3((unsigned)(n_sf * C)), dim3(kWave * kPassWaves), 0, st, Y, gamma, T_len,
                      target, part, ctx->status, F, Tmax, K, C, tpc);
   hipLaunchKernelGGL((mvdr_solve_small<D>), dim3((unsigned)n_sf), dim3(kWave), 0, st, part, H, pw, ctx->status, C);
-  gss_launch_mvdr_ref(pw, ref, ctx->status, S, F, D, st);
+  gss_launch_mvdr_ref(pw, ref, ctx->status, S, F, D, ref_per_f, st);
   const int fpc = 1024;
   const int CA = (Tmax + fpc - 1) / fpc;
   if (n_sf * CA > 0x7fffffffL) return GSS_EUNSUPPORTED;
   hipLaunchKernelGGL((mvdr_apply_small<D>), dim3((unsigned)(n_sf * CA)), dim3(256), 0, st, Y, H, ref, T_len, X, F, Tmax,
-                     CA, fpc);
+                     CA, fpc, ref_per_f);
   if (hipGetLastError() != hipSuccess) return GSS_EHIP;
   return GSS_OK;
 }
 
 }  // namespace
 
-void gss_launch_mvdr_ref(const double* pw, int32_t* ref, uint32_t* status, int S, int F, int D, hipStream_t st) {
+void gss_launch_mvdr_ref(const double* pw, int32_t* ref, uint32_t* status, int S, int F, int D, int ref_per_f,
+                         hipStream_t st) {
+  if (ref_per_f) {
+    const long n_sf = (long)S * F;
+    hipLaunchKernelGGL(mvdr_ref_freq, dim3((unsigned)((n_sf + 255) / 256)), dim3(256), 0, st, pw, ref, status, n_sf, D);
+    return;
+  }
   hipLaunchKernelGGL(mvdr_ref, dim3((unsigned)S), dim3(1024), 0, st, pw, ref, status, F, D);
 }
 
 static int mvdr_dispatch(gss_ctx* ctx, const gss_yview& yv, const float* gamma, const int32_t* T_len, int S, int F,
-                         int Tmax, int D, int K, const int32_t* target, int32_t* ref, float* X, void* stream) {
+                         int Tmax, int D, int K, const int32_t* target, int32_t* ref, int ref_mode, float* X,
+                         void* stream) {
   if (S <= 0 || F <= 0 || Tmax <= 0 || D <= 0 || K <= 0) return GSS_EINVAL;
+  if (ref_mode != GSS_REF_PER_SEGMENT && ref_mode != GSS_REF_PER_FREQUENCY) return GSS_EINVAL;
   if (D > GSS_MAX_D || K > GSS_MAX_K) return GSS_EUNSUPPORTED;
   if (hipSetDevice(ctx->device) != hipSuccess) return GSS_EHIP;
   hipStream_t st = (hipStream_t)stream;
   float2* Xc = (float2*)X;
+  const int per_f = ref_mode == GSS_REF_PER_FREQUENCY;
   switch (D) {
 #define GSS_CASE_D(DD) \
-  case DD: return run_mvdr_small<DD>(ctx, yv, gamma, T_len, S, F, Tmax, K, target, ref, Xc, st);
+  case DD: return run_mvdr_small<DD>(ctx, yv, gamma, T_len, S, F, Tmax, K, target, ref, per_f, Xc, st);
     GSS_CASE_D(1) GSS_CASE_D(2) GSS_CASE_D(3) GSS_CASE_D(4) GSS_CASE_D(5) GSS_CASE_D(6) GSS_CASE_D(7) GSS_CASE_D(8)
 #undef GSS_CASE_D
-    default: return gss_mvdr_large(ctx, yv, gamma, T_len, S, F, Tmax, D, K, target, ref, X, st);
+    default: return gss_mvdr_large(ctx, yv, gamma, T_len, S, F, Tmax, D, K, target, ref, per_f, X, st);
   }
 }
 
 extern "C" int gss_mvdr(gss_ctx* ctx, const float* Y, const float* gamma, const int32_t* T_len,
                         int S, int F, int Tmax, int D, int K, const int32_t* target, int32_t* ref,
                         float* X, void* stream) {
-  if (!ctx || !Y || !gamma || !target || !ref || !X) return GSS_EINVAL;
-  if (F <= 0 || Tmax <= 0 || D <= 0) return GSS_EINVAL;
-  return mvdr_dispatch(ctx, gss_dense_view(Y, F, Tmax, D), gamma, T_len, S, F, Tmax, D, K, target, ref, X, stream);
+  return gss_mvdr_ex(ctx, Y, 0, nullptr, gamma, T_len, S, F, Tmax, D, K, target, GSS_REF_PER_SEGMENT, ref, X, stream);
 }
 
 extern "C" int gss_mvdr_frames(gss_ctx* ctx, const float* Yrec, int64_t Trec, const int64_t* frame0, const float* gamma,
                                const int32_t* T_len, int S, int F, int Tmax, int D, int K, const int32_t* target,
                                int32_t* ref, float* X, void* stream) {
-  if (!ctx || !Yrec || !frame0 || !gamma || !target || !ref || !X) return GSS_EINVAL;
-  if (Trec <= 0 || D <= 0) return GSS_EINVAL;
-  return mvdr_dispatch(ctx, gss_frames_view(Yrec, Trec, frame0, D), gamma, T_len, S, F, Tmax, D, K, target, ref, X,
-                       stream);
+  if (!frame0 || Trec <= 0) return GSS_EINVAL;
+  return gss_mvdr_ex(ctx, Yrec, Trec, frame0, gamma, T_len, S, F, Tmax, D, K, target, GSS_REF_PER_SEGMENT, ref, X,
+                     stream);
+}
+
+extern "C" int gss_mvdr_ex(gss_ctx* ctx, const float* Y, int64_t Trec, const int64_t* frame0, const float* gamma,
+                           const int32_t* T_len, int S, int F, int Tmax, int D, int K, const int32_t* target,
+                           int ref_mode, int32_t* ref, float* X, void* stream) {
+  if (!ctx || !Y || !gamma || !target || !ref || !X) return GSS_EINVAL;
+  if (F <= 0 || Tmax <= 0 || D <= 0 || Trec < 0) return GSS_EINVAL;
+  if ((frame0 != nullptr) != (Trec > 0)) return GSS_EINVAL;
+  const gss_yview yv = frame0 ? gss_frames_view(Y, Trec, frame0, D) : gss_dense_view(Y, F, Tmax, D);
+  return mvdr_dispatch(ctx, yv, gamma, T_len, S, F, Tmax, D, K, target, ref, ref_mode, X, stream);
 }

@@ -104,6 +104,43 @@ def enhance_recording(ctx, x, act_samples, seg_start, seg_end, seg_spk, ctx_left
     return outputs, fr
 
 
+def block_spans(seg_start, seg_end, block):
+    """Consecutive blocks of `block` samples that tile [seg_start, seg_end) (the last one may be shorter)."""
+    s, e, n = int(seg_start), int(seg_end), int(block)
+    if n <= 0:
+        raise ValueError("block must be positive")
+    return [(b, min(b + n, e)) for b in range(s, e, n)]
+
+
+def enhance_recording_blocks(ctx, x, act_samples, seg_start, seg_end, seg_spk, block, history, iters=15,
+                             weight_mode=1, max_batch_frames=200_000, Yrec=None):
+    """Block-wise processing for speakers that move (Section 3, "Segment batching", keeps one set of statistics
+    and one reference channel per batch for stationary speakers only; Section 1 cites block-online GSS): every
+    segment is cut into consecutive blocks of `block` samples, and every block is enhanced as a segment of its
+    own from the span [block start - history, block end): own masks, own filter, own reference channel, nothing
+    after the block's last frame.  The blocks of all segments are independent, so they are batched together
+    like any other segments.  Returns (outputs, info): outputs[i] the enhanced segment i (its blocks joined),
+    info the block table (segment, start, end, reference channel)."""
+    import torch
+
+    b0s, b1s, owner = [], [], []
+    for i in range(len(seg_start)):
+        for b0, b1 in block_spans(seg_start[i], seg_end[i], block):
+            b0s.append(b0); b1s.append(b1); owner.append(i)
+    b0s, b1s = np.asarray(b0s, np.int64), np.asarray(b1s, np.int64)
+    spk_b = np.asarray([seg_spk[i] for i in owner], dtype=np.int32)
+    outs_b, fr = enhance_recording(ctx, x, act_samples, b0s, b1s, spk_b, int(history), 0, iters=iters,
+                                   weight_mode=weight_mode, max_batch_frames=max_batch_frames, Yrec=Yrec)
+    outputs = []
+    pos = 0
+    for i in range(len(seg_start)):
+        n = sum(1 for o_ in owner if o_ == i)
+        outputs.append(torch.cat(outs_b[pos:pos + n]) if n > 1 else outs_b[pos])
+        pos += n
+    info = dict(segment=np.asarray(owner, np.int32), start=b0s, end=b1s, ref=fr["ref"], frames=fr)
+    return outputs, info
+
+
 def plan_super_segments(seg_start, seg_end, seg_spk, max_batch_samples):
     """Packs the segments of each speaker, in time order, into super-segments: a super-segment takes the
     speaker's next segment as long as the summed duration of its members stays within max_batch_samples

@@ -495,3 +495,47 @@ def test_frames_entry_points(env, D):
         Xo, ro, _ = o.mvdr(Yp[s, :, :T_eff[s]], go, 0)
         Xg, rg = _gpu_mvdr(env, Yp[s:s + 1, :, :T_eff[s]], go[None], None, [0], [ro])
         assert np.linalg.norm(Xg[0] - Xo) <= TOL_X * np.linalg.norm(Xo)
+
+
+def test_reference_channel_per_frequency(env):
+    """gss_mvdr_ex with one reference channel per frequency: the chosen channels agree with the oracle's wherever
+    its two best scores differ by more than 1e-4 relative; with the channels forced to the oracle's the beamformed
+    STFT matches; a given channel is kept; dense batch and frame ranges of a recording alike."""
+    t, gss, ctx, o = env["torch"], env["gss"], env["ctx"], env["o"]
+    for D in (4, 8, 12):
+        rng = np.random.default_rng(1200 + D)
+        S, F, T, K = 2, 33, 200, 3
+        Y = (_cn(rng, (S, F, T, D)) * np.exp(rng.standard_normal((S, F, T, 1)))).astype(np.complex64)
+        g = rng.random((S, K, F, T)).astype(np.float32)
+        g /= g.sum(1, keepdims=True)
+        T_len = np.array([T, 150], dtype=np.int32)
+        Yd, gd, Td = t.from_numpy(Y).cuda(), t.from_numpy(g).cuda(), t.from_numpy(T_len).cuda()
+        tgt = t.from_numpy(np.array([1, 0], dtype=np.int32)).cuda()
+        ref = t.full((S, F), -1, dtype=t.int32).cuda()
+        X = gss.gss_mvdr_ex(ctx, Yd, gd, tgt, ref, Td, ref_mode=gss.GSS_REF_PER_FREQUENCY)
+        t.cuda.synchronize()
+        ref_g = ref.cpu().numpy()
+        for s_ in range(S):
+            Ts = int(T_len[s_])
+            gs = g[s_, :, :, :Ts].astype(np.float64)
+            Xo, ro, _ = o.mvdr_per_frequency_ref(Y[s_, :, :Ts], gs, int(tgt[s_].item()))
+            pk, pb = o.masked_covariances(Y[s_, :, :Ts], gs, int(tgt[s_].item()))
+            pbl = o.load_background(pb)
+            sc = np.sort(o.reference_channel_scores_per_frequency(o.souden_filters(pk, pbl), pk, pbl), axis=1)
+            clear = (sc[:, -1] - sc[:, -2]) > 1e-4 * sc[:, -1]
+            assert clear.sum() > F // 2 and np.all(ref_g[s_][clear] == ro[clear])
+            # X with the oracle's channels
+            rf = t.from_numpy(np.stack([ro if q == s_ else np.zeros(F, np.int64) for q in range(S)]).astype(np.int32)).cuda()
+            Xf = gss.gss_mvdr_ex(ctx, Yd, gd, tgt, rf, Td, ref_mode=gss.GSS_REF_PER_FREQUENCY)
+            t.cuda.synchronize()
+            assert np.array_equal(rf.cpu().numpy()[s_], ro.astype(np.int32))
+            Xg = Xf[s_].cpu().numpy()
+            assert np.linalg.norm(Xg[:, :Ts] - Xo) <= TOL_X * np.linalg.norm(Xo)
+            assert np.all(Xg[:, Ts:] == 0)
+        # the per-segment mode of the general call is gss_mvdr
+        r1 = t.full((S,), -1, dtype=t.int32).cuda()
+        r2 = t.full((S,), -1, dtype=t.int32).cuda()
+        Xa = gss.gss_mvdr_ex(ctx, Yd, gd, tgt, r1, Td)
+        Xb = gss.gss_mvdr(ctx, Yd, gd, tgt, r2, Td)
+        assert t.equal(Xa, Xb) and t.equal(r1, r2)
+    del X

@@ -187,3 +187,33 @@ def test_recording_pipeline_full_hour(env):
     xg = outs[i].cpu().numpy()
     assert int(fr["ref"][i]) == ro
     assert np.linalg.norm(xg - xo) <= TOL_X * np.linalg.norm(xo)
+
+
+def test_block_processing_reduced_meeting(env):
+    """Block-wise processing (every block of a segment enhanced from its own past only, own reference channel) on
+    the 60 s meeting: block table and two segments end to end against the oracle's block loop."""
+    t, o, gss, synth, ctx, pipeline = (env[k] for k in ("torch", "o", "gss", "synth", "ctx", "pipeline"))
+    x, act_s, (st, en, spk) = synth.meeting(duration_s=60.0, n_segments=16)
+    D, N = x.shape
+    block, hist, iters = 32_000, 48_000, 8
+    xd = t.from_numpy(x).cuda()
+    outs, info = pipeline.enhance_recording_blocks(ctx, xd, act_s, st, en, spk, block, hist, iters=iters)
+    t.cuda.synchronize()
+    assert len(outs) == len(st)
+    rows = 0
+    for i in range(len(st)):
+        assert outs[i].shape[0] == int(en[i] - st[i])
+        spans = o.block_spans(int(st[i]), int(en[i]), block)
+        mine = np.flatnonzero(info["segment"] == i)
+        assert [(int(info["start"][m]), int(info["end"][m])) for m in mine] == spans
+        rows += len(spans)
+    assert rows == len(info["segment"])
+    longest = int(np.argmax(en - st))
+    shortest = int(np.argmin(en - st))
+    for i in (longest, shortest):
+        xo, binfo = o.enhance_blocks(x, act_s, int(st[i]), int(en[i]), int(spk[i]), block, hist, iters)
+        mine = np.flatnonzero(info["segment"] == i)
+        assert [int(info["ref"][m]) for m in mine] == [b[2] for b in binfo]
+        xg = outs[i].cpu().numpy()
+        assert np.linalg.norm(xg - xo) <= TOL_X * np.linalg.norm(xo)
+    assert len(o.block_spans(int(st[longest]), int(en[longest]), block)) > 1
