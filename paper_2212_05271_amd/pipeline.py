@@ -186,18 +186,43 @@ def super_segment_pieces(members, seg_start, seg_end, n_samples, ctx_left, ctx_r
     return np.asarray(starts, np.int64), np.asarray(ends, np.int64), member_of
 
 
+def merge_runs(ext_start, ext_end, hop=HOP):
+    """Hop-snapped spans in time order -> runs of consecutive frames.  Spans that touch or overlap are merged
+    (a span that starts at or before the end of the run so far extends it), so that every frame of the recording
+    appears at most once per run.  Returns a list of (first frame, number of frames, indices of the spans in the
+    run); a run of samples [a, b) is covered by the frames a / hop .. b / hop + 2."""
+    runs = []
+    cur_a = cur_b = None
+    idx = []
+    for p, (a, b) in enumerate(zip(ext_start, ext_end)):
+        a, b = int(a), int(b)
+        if cur_a is not None and a <= cur_b:
+            cur_b = max(cur_b, b)
+            idx.append(p)
+        else:
+            if cur_a is not None:
+                runs.append((cur_a // hop, (cur_b - cur_a) // hop + 3, idx))
+            cur_a, cur_b, idx = a, b, [p]
+    if cur_a is not None:
+        runs.append((cur_a // hop, (cur_b - cur_a) // hop + 3, idx))
+    return runs
+
+
 def enhance_recording_super(ctx, x, act_samples, seg_start, seg_end, seg_spk, ctx_left, ctx_right,
                             max_batch_s=50.0, iters=15, weight_mode=1, max_batch_frames=200_000, Yrec=None,
                             wpe_taps=0, wpe_delay=2, wpe_iters=3):
     """Super-segment batching.  Arguments as enhance_recording; max_batch_s bounds the summed member
     duration of a super-segment (seconds at 16 kHz).
 
-    Every span of a super-segment (context, members, context) becomes the frame range that covers it (the
-    same bookkeeping as for a stand-alone segment without context); the ranges are concatenated along time,
-    the EM and the beamformer see the concatenation as one segment (one set of class parameters, one filter
-    and one reference channel per frequency), and every member's slice of the beamformed STFT is inverted on
-    its own and cut to the member.  Returns (outputs, info) with outputs[i] the enhanced segment i and info
-    holding the super-segment membership, lengths and reference channels.
+    Every span of a super-segment (context, members, context) is snapped to the frame range that covers it
+    (the bookkeeping of a stand-alone segment without context).  Spans that touch or overlap in time (the
+    context before the first member and that member, back-to-back members, ...) are merged into one run of
+    frames, so that no recording frame enters the statistics twice and the frames of a run are consecutive in
+    time; the runs are concatenated along time, the EM and the beamformer see the concatenation as one
+    segment (one set of class parameters, one filter and one reference channel), and every member's own
+    frames (a slice of its run) of the beamformed STFT are inverted on their own and cut to the member.
+    Returns (outputs, info) with outputs[i] the enhanced segment i and info holding the super-segment
+    membership, lengths, runs and reference channels.
     """
     import torch
 
@@ -213,7 +238,9 @@ def enhance_recording_super(ctx, x, act_samples, seg_start, seg_end, seg_spk, ct
     for members in supers:
         ps, pe, member_of = super_segment_pieces(members, seg_start, seg_end, N, ctx_left, ctx_right)
         fr = gss.gss_frames_from_segments(ps, pe, N, 0, 0, HOP)
-        plans.append(dict(members=members, member_of=member_of, fr=fr, T=int(fr["n_frames"].sum())))
+        runs = merge_runs(fr["ext_start"], fr["ext_end"], HOP)
+        plans.append(dict(members=members, member_of=member_of, fr=fr, runs=runs,
+                          T=int(sum(r[1] for r in runs))))
     outputs = [None] * n_seg
     super_ref = np.zeros(len(supers), dtype=np.int32)
     member_X = []                                   # (segment index, X slice [F, n], cut_start, cut_end)
@@ -224,9 +251,8 @@ def enhance_recording_super(ctx, x, act_samples, seg_start, seg_end, seg_spk, ct
         act = np.zeros((S, K, Tmax), dtype=np.uint8)
         T_len = np.zeros(S, dtype=np.int32)
         for bi, b in enumerate(batch):
-            fr, off = plans[b]["fr"], 0
-            for f0, nf in zip(fr["frame0"], fr["n_frames"]):
-                f0, nf = int(f0), int(nf)
+            off = 0
+            for f0, nf, _ in plans[b]["runs"]:
                 Y[bi, :, off:off + nf] = Yrec[0, :, f0:f0 + nf]
                 act[bi, :n_spk, off:off + nf] = gss.gss_frame_activity(act_samples, f0, nf, HOP)
                 off += nf
@@ -242,12 +268,16 @@ def enhance_recording_super(ctx, x, act_samples, seg_start, seg_end, seg_spk, ct
         ref_h = ref.cpu().numpy()
         for bi, b in enumerate(batch):
             super_ref[b] = ref_h[bi]
-            fr, off = plans[b]["fr"], 0
+            fr, runs = plans[b]["fr"], plans[b]["runs"]
+            run_off = np.concatenate([[0], np.cumsum([r[1] for r in runs])])
             for p, i in enumerate(plans[b]["member_of"]):
-                nf = int(fr["n_frames"][p])
-                if i >= 0:
-                    member_X.append((i, X[bi, :, off:off + nf], int(fr["cut_start"][p]), int(fr["cut_end"][p])))
-                off += nf
+                if i < 0:
+                    continue
+                # the member's own frames: a slice of the run that holds its span
+                f0, nf = int(fr["frame0"][p]), int(fr["n_frames"][p])
+                r = next(q for q, run in enumerate(runs) if p in run[2])
+                off = int(run_off[r]) + f0 - runs[r][0]
+                member_X.append((i, X[bi, :, off:off + nf], int(fr["cut_start"][p]), int(fr["cut_end"][p])))
     # every member's slice is inverted on its own, in padded batches of similar length
     for batch in plan_batches([m[1].shape[1] for m in member_X], max_batch_frames):
         Tm = max(member_X[b][1].shape[1] for b in batch)
@@ -259,5 +289,5 @@ def enhance_recording_super(ctx, x, act_samples, seg_start, seg_end, seg_spk, ct
             i, _, c0, c1 = member_X[b]
             outputs[i] = xh[bi, c0:c1]
     info = dict(supers=supers, T=np.asarray([p["T"] for p in plans], dtype=np.int32), ref=super_ref,
-                pieces=[(p["member_of"], p["fr"]) for p in plans])
+                pieces=[(p["member_of"], p["fr"]) for p in plans], runs=[p["runs"] for p in plans])
     return outputs, info

@@ -134,22 +134,37 @@ def test_super_segment_batching_reduced_meeting(env):
     ps, pe, member_of = pipeline.super_segment_pieces(members, st, en, N, ctx_s, ctx_s)
     Yrec = o.stft_channels_last(x).astype(np.complex64)
     frames = [o.segment_frames(int(s), int(e), N, 0, 0) for s, e in zip(ps, pe)]
-    Ys = np.concatenate([Yrec[:, f["frame0"]:f["frame0"] + f["n_frames"]] for f in frames], axis=1)
-    act = np.concatenate([o.frame_activity(act_s, f["frame0"], f["n_frames"]) for f in frames], axis=1)
+    # spans that touch in time form one run of consecutive frames: no recording frame is used twice
+    used = set()
+    run_list = []                                       # [first frame, last frame + 1]
+    for f in frames:
+        fa, fb = f["frame0"], f["frame0"] + f["n_frames"]
+        if run_list and f["ext_start"] <= run_list[-1][2]:
+            run_list[-1][1] = max(run_list[-1][1], fb)
+            run_list[-1][2] = max(run_list[-1][2], f["ext_end"])
+        else:
+            run_list.append([fa, fb, f["ext_end"]])
+    for fa, fb, _ in run_list:
+        for q in range(fa, fb):
+            used.add(q)
+    assert len(used) == sum(fb - fa for fa, fb, _ in run_list)   # no frame twice, unless members overlap in time
+    Ys = np.concatenate([Yrec[:, fa:fb] for fa, fb, _ in run_list], axis=1)
+    act = np.concatenate([o.frame_activity(act_s, fa, fb - fa) for fa, fb, _ in run_list], axis=1)
     act = np.concatenate([act, np.ones((1, act.shape[1]), np.uint8)])
     assert Ys.shape[1] == int(info["T"][b])
+    assert len(run_list) < len(frames), "the context and the first member must have merged"
     go = o.cacgmm_em(Ys, act, 15)
     Xo, ro, _ = o.mvdr(Ys, go, int(spk[members[0]]))
     assert int(info["ref"][b]) == ro
-    off = 0
+    starts = np.concatenate([[0], np.cumsum([r[1] - r[0] for r in run_list])])
     for f, i in zip(frames, member_of):
         nf = f["n_frames"]
         if i >= 0:
+            r = next(q for q, (fa, fb, _) in enumerate(run_list) if fa <= f["frame0"] and f["frame0"] + nf <= fb)
+            off = int(starts[r]) + f["frame0"] - run_list[r][0]
             xo = o.istft(Xo[:, off:off + nf], (nf - 3) * 256)[f["cut_start"]:f["cut_end"]]
             xg = outs[i].cpu().numpy()
             assert np.linalg.norm(xg - xo) <= TOL_X * np.linalg.norm(xo)
-        off += nf
-
 
 def test_recording_pipeline_full_hour(env):
     """Config 4 at full size: a one-hour, 8-channel synthetic meeting with 1200 diarization segments and 7.5 s of

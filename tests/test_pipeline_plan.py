@@ -54,3 +54,19 @@ def test_super_segment_pieces_context_once_and_clipped():
     assert pe.tolist() == [16000, 48000, 120000, 230000, 240000]               # right context clipped at N
     ps, pe, member_of = pipeline.super_segment_pieces([1], st, en, N, 0, 0)
     assert member_of == [1] and ps.tolist() == [80000] and pe.tolist() == [120000]
+
+
+def test_merge_runs_no_frame_twice():
+    from paper_2212_05271_amd.pipeline import merge_runs
+    hop = 256
+    # context | member (touching), a gap, two back-to-back members, an isolated span
+    es = np.array([0, 2560, 10240, 12800, 30720]) 
+    ee = np.array([2560, 5120, 12800, 15360, 33280])
+    runs = merge_runs(es, ee, hop)
+    assert [r[2] for r in runs] == [[0, 1], [2, 3], [4]]
+    assert runs[0][:2] == (0, 5120 // hop + 3) and runs[1][:2] == (10240 // hop, (15360 - 10240) // hop + 3)
+    for f0, nf, idx in runs:
+        for p in idx:                                   # every span's own frames lie inside its run
+            assert f0 <= es[p] // hop and ee[p] // hop + 3 <= f0 + nf
+    assert sum(r[1] for r in runs) < sum((e - s) // hop + 3 for s, e in zip(es, ee))
+    assert merge_runs([], [], hop) == []
