@@ -32,9 +32,10 @@ if ROOT not in sys.path:
 FS, HOP = 16000, 256
 # Published MI355X vector peak for the arithmetic type of the EM kernels (fp64 FMA): 78.6 TFLOP/s.
 PEAK_TFLOPS_F64 = 78.6
-# HBM bytes per launch of the dominant kernel, written by `python -m paper_2212_05271_amd.profile_summary` from
-# rocprofv3 --pmc runs of this script (FETCH_SIZE / WRITE_SIZE, scaled by the copy-kernel calibration).
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "em_pass_hbm_traffic.json")
+# HBM bytes per launch of the dominant kernel on the one-hour meeting, written by
+# `python -m paper_2212_05271_amd.profile_summary traffic` from rocprofv3 --pmc runs of this script (FETCH_SIZE /
+# WRITE_SIZE, scaled by the copy-kernel calibration).
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "em_pass_hbm_traffic.md")
 
 
 def em_pass_flops_per_bin(D, K):
@@ -164,17 +165,18 @@ def main():
     flops_total = em_pass_flops_per_bin(D, K) * F * frames * iters * a.steps
     achieved = flops_total / (pass_ms * 1e-3) / 1e12
     traffic = None
-    if os.path.exists(TRAFFIC_FILE):
-        with open(TRAFFIC_FILE) as f:
-            tr = json.load(f)
-        if abs(tr.get("meeting_s", 0.0) - a.meeting_s) < 1e-6:
-            traffic = tr.get("bytes_per_launch")
-    roofline = dict(bound="alu", kernel="em_pass_small<8,5,false> (accumulating EM pass: one launch per EM iteration and "
-                    "batch of segments)", achieved=round(achieved, 3), peak=PEAK_TFLOPS_F64, unit="TFLOP/s",
+    if os.path.exists(TRAFFIC_FILE) and abs(a.meeting_s - 3600.0) < 1e-6:
+        import re
+        m = re.search(r"^bytes per launch \(FETCH_SIZE \+ WRITE_SIZE, calibrated\): (\d+)", open(TRAFFIC_FILE).read(), re.M)
+        if m:
+            traffic = int(m.group(1))
+    roofline = dict(bound="alu", kernel="em_whole_small<8,5> (all EM iterations of a batch of segments in one launch: one "
+                    "wavefront per segment and frequency)", achieved=round(achieved, 3), peak=PEAK_TFLOPS_F64, unit="TFLOP/s",
                     frac=round(achieved / PEAK_TFLOPS_F64, 4), traffic=traffic,
                     flops_per_launch=round(flops_total / max(pass_n, 1)), avg_launch_us=round(pass_ms / max(pass_n, 1) * 1e3, 2),
                     launches=pass_n,
-                    note="algorithmic flops ((3 + 4K) D^2 + 3D + 30K per time-frequency bin and iteration, K = 5 classes) "
+                    note="algorithmic flops ((3 + 4K) D^2 + 3D + 30K per time-frequency bin and iteration, K = 5 classes, "
+                         "15 iterations; the final mask pass and the factorisations inside the kernel are not counted) "
                          "over the summed duration of the launches; fp64 vector FMA peak (the kernel's arithmetic; packed "
                          "fp32 is switched off for this library).  The kernel skips the classes that are inactive in a "
                          "whole 64-frame tile, so it executes fewer flops than the formula counts.")
@@ -201,7 +203,7 @@ def main():
         "recording_s_per_s": round(a.meeting_s * a.steps / elapsed, 1),
         "em_iters_per_s": round(n_seg * iters * a.steps / elapsed, 1),
         "tf_bin_iters_per_s": round(F * frames * iters * a.steps / elapsed, 1),
-        "em_kernel_ms_per_step": {"pass": round(pass_ms / a.steps, 2), "factor": round(fac_ms / a.steps, 2),
+        "em_kernel_ms_per_step": {"em": round(pass_ms / a.steps, 2), "separate_factor_launches": round(fac_ms / a.steps, 2),
                                   "note": "from the second, event-instrumented run of the same steps"},
         "peak_device_memory_gb": round(peak_gb, 2),
         "status_word": status,

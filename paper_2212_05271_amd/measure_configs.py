@@ -200,6 +200,8 @@ def main():
     ap.add_argument("--sweeps", action="store_true",
                     help="only the parameter sweeps on config 1 (iterations, channels, noise class, weight mode)")
     ap.add_argument("--wpe", action="store_true", help="only the dereverberation timing (config 1's shape)")
+    ap.add_argument("--config", choices=("c0", "c1", "c2", "c3"), default=None,
+                    help="only this configuration (for a kernel trace of its own)")
     a = ap.parse_args()
 
     import torch
@@ -218,11 +220,13 @@ def main():
     print("| config | S | Tmax | D | K | iters | EM ms | MVDR ms | audio-s/s (EM+MVDR) | EM iters/s | bin-iters/s | "
           "EM TFLOP/s (alg.) | of 78.6 |")
     print("|---|---:|---:|---:|---:|---:|---:|---:|---:|---:|---:|---:|---:|")
-    for name, seg in (("c0", synth.config0()), ("c1", synth.config1()), ("c3", synth.config3())):
-        print(row(measure_batch(torch, gss, ctx, name, seg.Y[None], seg.activity[None], None, seg.iters)), flush=True)
+    for name, make in (("c0", synth.config0), ("c1", synth.config1), ("c3", synth.config3)):
+        if a.config in (None, name):
+            seg = make()
+            print(row(measure_batch(torch, gss, ctx, name, seg.Y[None], seg.activity[None], None, seg.iters)), flush=True)
     T, ns = synth.config2_plan()
     tot = None
-    for bi, idx in enumerate(synth.buckets_by_length(T, 4)):
+    for bi, idx in enumerate(synth.buckets_by_length(T, 4) if a.config in (None, "c2") else []):
         segs = [synth.config2_segment(i, T[i], ns[i]) for i in idx]
         Y, act, T_len, target = synth.pad_batch(segs)
         r = measure_batch(torch, gss, ctx, f"c2 bucket {bi}", Y, act, T_len, 15, target)
@@ -234,9 +238,10 @@ def main():
                 tot[k] += r[k]
             tot["T"] = max(tot["T"], r["T"])
         del Y, act
-    print(row(tot), flush=True)
+    if tot is not None:
+        print(row(tot), flush=True)
 
-    if a.meeting_s > 0:
+    if a.meeting_s > 0 and a.config is None:
         n_seg = max(4, int(round(1200 * a.meeting_s / 3600.0)))
         x, act_s, (st, en, spk) = synth.meeting(duration_s=a.meeting_s, n_segments=n_seg)
         xd = torch.from_numpy(x).cuda()
