@@ -108,6 +108,49 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// A class whose bit is clear in a tile's activity mask has posterior 0 in every frame of the tile and adds nothing
+// to any sum: the pass kernels skip its arithmetic for the whole tile under wave-uniform branches.
+// Activity in the form the pass kernels read: abyte[s][t] has bit k set when class k may be active in frame t
+// (a_{t,k} of Eq. (5); 0 at t >= T_len[s]), tmask[s][tile] is the OR of the bytes of the tile's 64 frames.
+// Grid: one wavefront per (segment, tile).
+__global__ __launch_bounds__(kWave) void em_pack_activity(
+    gss_yview yv, const uint8_t* __restrict__ act, const int32_t* __restrict__ T_len, uint8_t* __restrict__ abyte,
+    uint32_t* __restrict__ tmask, int K, int Tmax, int tiles) {
+  const int s = blockIdx.x / tiles, tile = blockIdx.x % tiles;
+  const int lane = threadIdx.x;
+  const int T = y_frames(yv, T_len, s, Tmax);
+  const int t = tile * kWave + lane;
+  unsigned b = 0;
+  if (t < T)
+    for (int k = 0; k < K; ++k) b |= (act[((long)s * K + k) * Tmax + t] != 0 ? 1u : 0u) << k;
+  if (t < Tmax) abyte[(long)s * Tmax + t] = (uint8_t)b;
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) b |= (unsigned)__shfl_xor((int)b, off, kWave);
+  if (lane == 0) tmask[(long)s * tiles + tile] = b;
+}
+
+// acc += c[lane N of the row] * p: the double-precision FMA with the row-broadcast selector on its first
+// factor.  Every lane of the wavefront must be active (the selector reads other lanes).  The instruction is
+// written as an asm statement, which hides it from the compiler's hazard handling: a lane-selecting
+// instruction must not issue within two wait states of a vector instruction that writes one of its
+// registers, so the first FMA of a run (SETTLE) is preceded by the two idle states itself.
+template <int N, bool SETTLE>
+__device__ __forceinline__ void fma_bcast(double& acc, double c, double p) {
+  static_assert(N >= 0 && N < 16, "row_newbcast selects one of the 16 lanes of a row");
+  if constexpr (SETTLE)
+    asm("s_nop 1\n\tv_fmac_f64_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+        : "+v"(acc) : "v"(c), "v"(p), "n"(N));
+  else
+    asm("v_fmac_f64_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(c), "v"(p), "n"(N));
+}
+
+// Wave-uniform test of bit k of `mask`, re-evaluated from the one scalar register that holds the mask at every
+// use (the empty asm statement keeps the compiler from caching the K booleans in scalar register pairs).
+__device__ __forceinline__ bool class_on(unsigned mask, int k) {
+  asm volatile("" : "+s"(mask));
+  return (mask >> k) & 1u;
+}
+
 // Tile geometry shared by the kernels that accumulate weighted outer products: a workgroup is
 // kPassWaves wavefronts, each wavefront owns whole tiles of 64 frames and a private LDS region.
 constexpr int kPassWaves = 4;

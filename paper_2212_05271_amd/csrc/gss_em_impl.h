@@ -28,13 +28,6 @@
 
 #include "gss_device.h"
 
-#ifdef GSS_DEV_TIMING
-__device__ long long g_dev_times[4 * 16 * 8];
-__device__ int g_dev_count[4];
-#define DEV_STAMP(slot) do { if (dev_on && lane == 0) g_dev_times[(dev_wave * 16 + dev_unit) * 8 + (slot)] = clock64(); } while (0)
-#else
-#define DEV_STAMP(slot) do { } while (0)
-#endif
 
 namespace {
 
@@ -90,53 +83,12 @@ __global__ void em_init_coef(double* __restrict__ coef, double* __restrict__ cco
 // Grid: blockIdx.x = chunk + C * (f + F * s).  A chunk is `tiles_per_chunk` tiles of 64 frames.
 // ----------------------------------------------------------------------------------------------
 
-// Activity in the form the pass kernels read: abyte[s][t] has bit k set when class k may be active in frame t
-// (a_{t,k} of Eq. (5); 0 at t >= T_len[s]), tmask[s][tile] is the OR of the bytes of the tile's 64 frames.
-// Grid: one wavefront per (segment, tile).
-__global__ __launch_bounds__(kWave) void em_pack_activity(
-    gss_yview yv, const uint8_t* __restrict__ act, const int32_t* __restrict__ T_len, uint8_t* __restrict__ abyte,
-    uint32_t* __restrict__ tmask, int K, int Tmax, int tiles) {
-  const int s = blockIdx.x / tiles, tile = blockIdx.x % tiles;
-  const int lane = threadIdx.x;
-  const int T = y_frames(yv, T_len, s, Tmax);
-  const int t = tile * kWave + lane;
-  unsigned b = 0;
-  if (t < T)
-    for (int k = 0; k < K; ++k) b |= (act[((long)s * K + k) * Tmax + t] != 0 ? 1u : 0u) << k;
-  if (t < Tmax) abyte[(long)s * Tmax + t] = (uint8_t)b;
-#pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) b |= (unsigned)__shfl_xor((int)b, off, kWave);
-  if (lane == 0) tmask[(long)s * tiles + tile] = b;
-}
-
 // Doubles per frame row of the weight tile in LDS (odd: spreads the rows over the banks).
 __host__ __device__ constexpr int weight_stride(int K) { return K | 1; }
 
 // Registers (pairs) of 16 coefficients per class, and how many of them a wavefront keeps resident.
 __host__ __device__ constexpr int coef_regs(int D) { return (D * D + 15) / 16; }
 constexpr int kResidentRegs = 20;
-
-// acc += c[lane N of the row] * p: the double-precision FMA with the row-broadcast selector on its first
-// factor.  Every lane of the wavefront must be active (the selector reads other lanes).  The instruction is
-// written as an asm statement, which hides it from the compiler's hazard handling: a lane-selecting
-// instruction must not issue within two wait states of a vector instruction that writes one of its
-// registers, so the first FMA of a run (SETTLE) is preceded by the two idle states itself.
-template <int N, bool SETTLE>
-__device__ __forceinline__ void fma_bcast(double& acc, double c, double p) {
-  static_assert(N >= 0 && N < 16, "row_newbcast selects one of the 16 lanes of a row");
-  if constexpr (SETTLE)
-    asm("s_nop 1\n\tv_fmac_f64_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
-        : "+v"(acc) : "v"(c), "v"(p), "n"(N));
-  else
-    asm("v_fmac_f64_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(c), "v"(p), "n"(N));
-}
-
-// Wave-uniform test of bit k of `mask`, re-evaluated from the one scalar register that holds the mask at every
-// use (the empty asm statement keeps the compiler from caching the K booleans in scalar register pairs).
-__device__ __forceinline__ bool class_on(unsigned mask, int k) {
-  asm volatile("" : "+s"(mask));
-  return (mask >> k) & 1u;
-}
 
 // One tile of 64 frames starting at frame t0.  `tmask` (wave-uniform) is the tile's activity mask.
 //   creg : the resident coefficient registers [K * coef_regs(D)] (used when RESIDENT)
@@ -148,15 +100,11 @@ __device__ __forceinline__ void pass_tile(
     const double* __restrict__ sC, const double (&cc)[K], float* __restrict__ gamma_row /* + k*F*Tmax */,
     uint32_t* __restrict__ status, long gamma_kstride, int T, int Tmax, int t0, int lane, unsigned tmask,
     double* __restrict__ sY, double* __restrict__ sW, double (&acc)[8][K], double (&nacc)[K]
-#ifdef GSS_DEV_TIMING
-    , bool dev_on, int dev_wave, int dev_unit
-#endif
     ) {
   constexpr int E = D * D;
   constexpr int R = coef_regs(D);
   constexpr int WS = weight_stride(K);
   const int tg = lane >> 3, eg = lane & 7;
-  DEV_STAMP(0);
   tmask &= (1u << K) - 1u;
   const int t = t0 + lane;
   if constexpr (FINAL) {
@@ -183,10 +131,6 @@ __device__ __forceinline__ void pass_tile(
   }
   unsigned abits = abrow[valid ? t : 0];
   abits = valid ? abits : 0u;
-#ifdef GSS_DEV_TIMING
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  DEV_STAMP(1);
-#endif
 
   // ---- q_k = <coef_k, y y^H>, 16 entries of the outer product at a time; three partial sums per class (an FMA
   // does not wait for the one before it) ----
@@ -221,7 +165,6 @@ __device__ __forceinline__ void pass_tile(
       }
     });
   });
-  DEV_STAMP(7);
 
   // ---- posterior over the active classes: v_k = pi_k / det B_k * q_k^-D with q_k = max(qraw_k / n2c, eps_q),
   // normalised over k.  For D <= 8 this needs no scaling: B has trace D and eigenvalues >= 1e-6, so
@@ -267,14 +210,11 @@ __device__ __forceinline__ void pass_tile(
         sW[lane * WS + k] = g * rq[k];
       }
     });
-    DEV_STAMP(2);
     wave_lds_sync();
-    DEV_STAMP(3);
 
     // ---- phase 2 ----
     accumulate_tile_masked<K, WS>(sY, sW, tg, eg, tmask, acc);
     wave_lds_sync();
-    DEV_STAMP(4);
   }
 }
 
@@ -370,22 +310,13 @@ __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
   for (int tile = my_lo; tile < my_hi; ++tile) {
     pass_tile<D, K, FINAL, RESIDENT>(Yrow, abrow, creg, sC, cc, gamma_row, status, gamma_kstride, T, Tmax, tile * kWave,
                                      lane, tmrow[tile], sY, sW, acc, nacc
-#ifdef GSS_DEV_TIMING
-                                     , blockIdx.x == 100 && !FINAL, wave, (tile - my_lo) < 15 ? tile - my_lo : 14
-#endif
                                      );
   }
   if (FINAL) return;
-#ifdef GSS_DEV_TIMING
-  if (blockIdx.x == 100 && lane == 0) { g_dev_times[(wave * 16 + 15) * 8 + 0] = clock64(); }
-#endif
 
   // Reduce over the 8 frame groups and over the wavefronts; write the chunk's packed partial sums and counts.
   reduce_and_store_partials<D, K, true>(acc, nacc, sY, lds, part + (long)blockIdx.x * (K * E),
                                         npart + (long)blockIdx.x * K, lane, wave);
-#ifdef GSS_DEV_TIMING
-  if (blockIdx.x == 100 && lane == 0) { g_dev_times[(wave * 16 + 15) * 8 + 1] = clock64(); }
-#endif
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -595,9 +526,6 @@ __global__ __launch_bounds__(kWave, 2) void em_whole_small(
     for (int tile = 0; tile < tiles; ++tile)
       pass_tile<D, K, false, RESIDENT>(Yrow, abrow, creg, sC, cc, nullptr, status, gamma_kstride, T, Tmax, tile * kWave,
                                        lane, tmrow[tile], sY, sW, acc, nacc
-#ifdef GSS_DEV_TIMING
-                                       , false, 0, 0
-#endif
                                        );
 
     // ---- sums over the 8 frame groups -> packed sR[k][e]; class counts over the lanes -> sN[k] ----
@@ -756,9 +684,6 @@ __global__ __launch_bounds__(kWave, 2) void em_whole_small(
     for (int tile = 0; tile < tiles_total; ++tile)
       pass_tile<D, K, true, RESIDENT>(Yrow, abrow, creg, sC, cc, gamma_row, status, gamma_kstride, T, Tmax, tile * kWave,
                                       lane, tmrow[tile], sY, sW, acc, nacc
-#ifdef GSS_DEV_TIMING
-                                      , false, 0, 0
-#endif
                                       );
   }
 }

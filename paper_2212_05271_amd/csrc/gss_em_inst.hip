@@ -15,9 +15,3 @@ int GSS_NAME(gss_em_small_d, GSS_INST_D, _k, GSS_INST_K)(gss_ctx* ctx, const gss
   return run_small<GSS_INST_D, GSS_INST_K>(ctx, Y, activity, T_len, S, F, Tmax, iters, weight_mode, gamma,
                                            st);
 }
-
-#ifdef GSS_DEV_TIMING
-extern "C" int gss_dev_read_times(long long* out) {
-  return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_dev_times), sizeof(long long) * 4 * 16 * 8) == hipSuccess ? 0 : -1;
-}
-#endif

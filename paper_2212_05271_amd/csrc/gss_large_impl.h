@@ -3,15 +3,17 @@
 // kernels (arXiv 2212.05271, Section 2.2 and 2.3); what changes is the mapping:
 //
 //   * D is a run-time value; the Hermitian outer product has M = D (D + 1) / 2 "items" (i <= j), each a
-//     real diagonal entry or a complex off-diagonal one.  All per-class data is laid out per item:
-//     coef[sf][m][k][2] (the two real coefficients that multiply Re and Im of item m), partial sums
-//     part[sf][chunk][m][k][2].
+//     real diagonal entry or a complex off-diagonal one.  Coefficients are class-major, coef[sf][k][CP]
+//     (entries 2 m and 2 m + 1 multiply Re and Im of item m; CP = 2 M rounded up to whole groups of 16,
+//     zero padding); partial sums are item-major, part[workgroup][m][k][2].
 //   * The frames of a tile sit in LDS as fp32 (exactly as they came), because D * 16 bytes of fp64 per
 //     frame would not leave room for two workgroups per compute unit.
-//   * Phase 1 (lane = frame) walks the items in a run-time loop, reading y_i, y_j of its own frame from
-//     LDS and the class coefficients through the scalar path.
+//   * Phase 1 (lane = frame) walks the items 8 at a time in a run-time loop, reading y_i, y_j of its own
+//     frame from LDS; the 16 coefficients of a group sit in one register pair per class and reach the FMAs
+//     through the row-broadcast operand selector.
 //   * Phase 2 (lane = a few items, frames in sequence): each lane owns NR items m = lane, lane + 64, ...,
 //     forms them for every frame of the tile from LDS and accumulates K weighted sums per real part.
+//   * Classes that are inactive in all 64 frames of a tile are skipped in both phases.
 #pragma once
 
 #include "gss_internal.h"
@@ -43,21 +45,24 @@ __device__ __forceinline__ double ipow_rt(double x, int n) {   // x^n, n >= 1
   return r;
 }
 
+// Coefficient layout for 9 <= D <= 32: class-major, coef[sf][k][CP] with entry 2 m (2 m + 1) the coefficient of
+// Re (Im) of item m and CP = 2 M rounded up to whole groups of 16 (the padding is zero).
+__host__ __device__ inline int coef_pitch(int D) { return (2 * num_items(D) + 15) / 16 * 16; }
+
 __global__ void em_init_coef_large(double* __restrict__ coef, double* __restrict__ cmant, int32_t* __restrict__ cexp,
-                                   int D, int K, long n_sf, int pad) {
-  const int M = num_items(D);
-  const long per = (long)M * K * 2;
-  const long total = n_sf * per;
+                                   int D, int K, long n_sf) {
+  const int CP = coef_pitch(D);
+  const long total = n_sf * K * CP;
   for (long x = blockIdx.x * (long)blockDim.x + threadIdx.x; x < total; x += (long)gridDim.x * blockDim.x) {
-    const long r = x % per;
-    const int m = (int)(r / (2 * K));
-    const int part = (int)(r & 1);
-    int i, j;
-    item_ij(m, D, i, j);
-    coef[x] = (i == j && part == 0) ? 1.0 : 0.0;
+    const int c = (int)(x % CP);
+    double v = 0.0;
+    if (c < 2 * num_items(D) && (c & 1) == 0) {
+      int i, j;
+      item_ij(c >> 1, D, i, j);
+      v = (i == j) ? 1.0 : 0.0;
+    }
+    coef[x] = v;
   }
-  for (long x = blockIdx.x * (long)blockDim.x + threadIdx.x; x < pad; x += (long)gridDim.x * blockDim.x)
-    coef[total + x] = 0.0;
   const long nl = n_sf * K;
   for (long x = blockIdx.x * (long)blockDim.x + threadIdx.x; x < nl; x += (long)gridDim.x * blockDim.x) {
     cmant[x] = 0.5;
@@ -77,29 +82,36 @@ __device__ __forceinline__ void load_tile(const float2* __restrict__ Yrow, int t
   }
 }
 
-// Phase 2 for the lane's NR items over the 64 frames of the tile.
+// Phase 2 for the lane's NR items over the 64 frames of the tile, for the classes of `mask` (wave-uniform; the
+// weights of the other classes are zero in every frame of the tile).
 template <int KW, int NR>
 __device__ __forceinline__ void accumulate_items(const float2* __restrict__ sY, const double* __restrict__ sW, int RS,
-                                                 int WS, const int (&oi)[NR], const int (&oj)[NR],
+                                                 int WS, const int (&oi)[NR], const int (&oj)[NR], unsigned mask,
                                                  double (&acc)[NR][2][KW]) {
-#pragma unroll 2
+#pragma unroll 1
   for (int r = 0; r < kWave; ++r) {
     double w[KW];
 #pragma unroll
     for (int k = 0; k < KW; ++k) w[k] = sW[r * WS + k];
+    double re[NR], im[NR];
 #pragma unroll
     for (int n = 0; n < NR; ++n) {
       const float2 a = sY[r * RS + oi[n]];
       const float2 b = sY[r * RS + oj[n]];
       const double ar = a.x, ai = a.y, br = b.x, bi = b.y;
-      const double re = ar * br + ai * bi;          // Re(y_i conj(y_j)); |y_i|^2 on the diagonal
-      const double im = ai * br - ar * bi;          // Im(y_i conj(y_j)); 0 on the diagonal
-#pragma unroll
-      for (int k = 0; k < KW; ++k) {
-        acc[n][0][k] = fma(w[k], re, acc[n][0][k]);
-        acc[n][1][k] = fma(w[k], im, acc[n][1][k]);
-      }
+      re[n] = ar * br + ai * bi;          // Re(y_i conj(y_j)); |y_i|^2 on the diagonal
+      im[n] = ai * br - ar * bi;          // Im(y_i conj(y_j)); 0 on the diagonal
     }
+    static_for<0, KW>([&](auto KI) {
+      constexpr int k = KI.value;
+      if (class_on(mask, k)) {
+#pragma unroll
+        for (int n = 0; n < NR; ++n) {
+          acc[n][0][k] = fma(w[k], re[n], acc[n][0][k]);
+          acc[n][1][k] = fma(w[k], im[n], acc[n][1][k]);
+        }
+      }
+    });
   }
 }
 
@@ -134,24 +146,25 @@ __device__ __forceinline__ void reduce_items(double (&acc)[NR][2][KW], double* _
 // EM pass, 9 <= D <= 32.  Grid: blockIdx.x = chunk + C * (f + F * s); the chunk's tiles are dealt to the
 // wavefronts round-robin.  Dynamic LDS: kLargeWaves * (64 * RS float2 + 64 * WS doubles), reused for the
 // final reduction (needs M * K * 2 doubles).
+//
+// Phase 1 (lane = frame) walks the items 8 at a time.  The 16 class coefficients of such a group (Re and Im
+// of 8 items) sit in one register pair, entry lane mod 16 in every lane, fetched from memory one group ahead
+// (a coalesced 128-byte read that the four rows of the wavefront share); the FMAs take them through the
+// row-broadcast selector of the fp64 FMA.  Classes outside the tile's activity mask are skipped.
 // ----------------------------------------------------------------------------------------------
-// Items per group of scalar coefficient loads in phase 1 (2 * K doubles per item, two groups resident).
-template <int K>
-constexpr int kLargeGroup = K <= 5 ? 2 : 1;
-// Zeroed doubles behind the coefficient array: the pipeline reads up to four groups past the last item.
-constexpr int kCoefPadDoubles = 4 * 2 * 2 * GSS_MAX_K;
-
 template <int K, int NR, bool FINAL>
 __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
-    gss_yview yv, const uint8_t* __restrict__ act, const int32_t* __restrict__ T_len,
+    gss_yview yv, const uint8_t* __restrict__ abyte, const uint32_t* __restrict__ tmask,
+    const int32_t* __restrict__ T_len,
     const double* __restrict__ coef, const double* __restrict__ cmant, const int32_t* __restrict__ cexp,
     double* __restrict__ part, double* __restrict__ npart, float* __restrict__ gamma, uint32_t* __restrict__ status,
     int F, int Tmax, int D, ChunkMap cmap, int RS, int tile_bytes) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   constexpr int WS = K | 1;
   const int M = num_items(D);
+  const int CP = coef_pitch(D);
   const int lane = threadIdx.x & (kWave - 1);
-  const int wave = threadIdx.x / kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   long sf;
   int chunk, tiles_per_chunk;
   chunk_decode(cmap, blockIdx.x, sf, chunk, tiles_per_chunk);
@@ -164,10 +177,13 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
   float2* __restrict__ sY = reinterpret_cast<float2*>(lds_raw + (size_t)wave * tile_bytes);
   double* __restrict__ sW = reinterpret_cast<double*>(lds_raw + (size_t)wave * tile_bytes + (size_t)kWave * RS * sizeof(float2));
 
-  const double* __restrict__ cf = coef + sf * (long)M * K * 2;
+  const double* __restrict__ cf = coef + sf * (long)K * CP + (lane & 15);   // + k * CP + 16 * group
   const double* __restrict__ cm = cmant + sf * K;
   const int32_t* __restrict__ ce = cexp + sf * K;
-  const uint8_t* __restrict__ arow = act + (long)s * K * Tmax;
+  const uint8_t* __restrict__ abrow = abyte + (long)s * Tmax;
+  const int tiles_total = (Tmax + kWave - 1) / kWave;
+  typedef const __attribute__((address_space(4))) uint32_t* mask_ptr_t;
+  const mask_ptr_t tmrow = (mask_ptr_t)(uintptr_t)(tmask + (long)s * tiles_total);
 
   int oi[NR], oj[NR];
   double acc[NR][2][K];
@@ -183,6 +199,7 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
 #pragma unroll
   for (int k = 0; k < K; ++k) nacc[k] = 0.0;
 
+  const int groups = CP / 16;
   const int tile_lo = chunk * tiles_per_chunk;
   int tile_hi = tile_lo + tiles_per_chunk;
   const int tile_end = (t_end + kWave - 1) / kWave;
@@ -191,105 +208,68 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
     const int t0 = tile * kWave;
     const int t = t0 + lane;
     const bool valid = t < T;
+    const unsigned mask = tmrow[tile] & ((1u << K) - 1u);
+    if constexpr (FINAL) {
+      static_for<0, K>([&](auto KI) {
+        constexpr int k = KI.value;
+        if (!class_on(mask, k)) {
+          if (t < Tmax) gamma[(((long)s * K + k) * F + f) * Tmax + t] = 0.f;
+        }
+      });
+    }
+    if (mask == 0u) continue;                // no frame of the tile has an active class
     load_tile(Yrow, t0, T, D, RS, sY, lane);
-    unsigned abits = 0;
-#pragma unroll
-    for (int k = 0; k < K; ++k) abits |= (arow[(long)k * Tmax + (valid ? t : 0)] != 0 ? 1u : 0u) << k;
-    if (!valid) abits = 0;
+    unsigned abits = abrow[valid ? t : 0];
+    abits = valid ? abits : 0u;
     wave_lds_sync();
 
     // ---- phase 1: q_k = <coef_k, y y^H> for the lane's frame ----
-    double q[K];
+    double q[K][2];
 #pragma unroll
-    for (int k = 0; k < K; ++k) q[k] = 0.0;
+    for (int k = 0; k < K; ++k) { q[k][0] = 0.0; q[k][1] = 0.0; }
     double n2 = 0.0;
     const float2* __restrict__ yrow = sY + lane * RS;
-    // The items in storage order (i ascending, j = i .. D-1), U at a time.  Their coefficients are
-    // wave-uniform and come through the scalar path; two groups are resident in SGPRs and the loads of the
-    // next group are issued during the arithmetic of the current one (the empty asm statements fix that
-    // order: the next group's offset becomes known after the first product of the current group, and every
-    // partial sum passes a fence at the end of the group).  The items' y values are fetched from LDS along
-    // with the coefficients, one group ahead (LDS and scalar loads share one counter: a wait for either is a
-    // wait for both).  A diagonal item is y_i conj(y_i): its imaginary part is exactly zero and its second
-    // coefficient is stored as zero.  The pipeline fetches up to two groups past the last item it uses; the
-    // coefficient array is followed by padding so that those loads stay in bounds.
-    constexpr int U = kLargeGroup<K>;
-    typedef const __attribute__((address_space(4))) double* cptr_t;
-    const cptr_t c4 = (cptr_t)(uintptr_t)cf;
-    const int Mmain = M / (2 * U) * (2 * U);   // items taken by the pipelined loop, two groups per trip
-    double cA[U][2 * K], cB[U][2 * K];         // coefficients of a group (SGPRs)
-    float2 yA[U][2], yB[U][2];                 // y_i, y_j of the group's items, fetched with them
-    int ii = 0, jj = 0;                        // wave-uniform coordinates of the next item to fetch
-    auto fetch = [&](double (&c)[U][2 * K], float2 (&y)[U][2], int off, int m0) {
-      const cptr_t cg = c4 + off;
+    // coefficient registers of this group and of the next one (fetched one group ahead of its use)
+    double ccur[K], cnxt[K];
+    static_for<0, K>([&](auto KI) {
+      constexpr int k = KI.value;
+      ccur[k] = 0.0;
+      cnxt[k] = 0.0;
+      if (class_on(mask, k)) ccur[k] = cf[k * CP];
+    });
+    int ii = 0, jj = 0;                      // wave-uniform coordinates of the next item
+    for (int g = 0; g < groups; ++g) {
+      if (g + 1 < groups) {
+        static_for<0, K>([&](auto KI) {
+          constexpr int k = KI.value;
+          if (class_on(mask, k)) cnxt[k] = cf[k * CP + 16 * (g + 1)];
+        });
+      }
+      double re[8], im[8];
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-#pragma unroll
-        for (int x = 0; x < 2 * K; ++x) c[u][x] = cg[u * 2 * K + x];
-        y[u][0] = yrow[ii];
-        y[u][1] = yrow[jj];
-        if (m0 + u + 1 < M) {                  // step to the next item, never past the last one
-          ++jj;
+      for (int u = 0; u < 8; ++u) {
+        const float2 a = yrow[ii], b = yrow[jj];
+        const double ar = a.x, ai = a.y, br = b.x, bi = b.y;
+        re[u] = ar * br + ai * bi;
+        im[u] = ai * br - ar * bi;
+        if (ii == jj && 8 * g + u < M) n2 += re[u];           // a diagonal item: |y_i|^2 (uniform test)
+        if (8 * g + u + 1 < M) {             // step to the next item, never past the last one (the padding
+          ++jj;                              // coefficients behind it are zero)
           if (jj == D) { ++ii; jj = ii; }
         }
       }
-    };
-    {
-      int off0 = 0;
-      asm volatile("" : "+s"(off0));          // opaque offset: keeps the loads inside this tile
-      fetch(cA, yA, off0, 0);
-    }
-    auto group = [&](double (&cur)[U][2 * K], float2 (&ycur)[U][2], double (&nxt)[U][2 * K], float2 (&ynxt)[U][2],
-                     int m0) {
-      double re[U], im[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const double ar = ycur[u][0].x, ai = ycur[u][0].y, br = ycur[u][1].x, bi = ycur[u][1].y;
-        re[u] = ar * br + ai * bi;
-        im[u] = ai * br - ar * bi;
-      }
-      q[0] = fma(cur[0][0], re[0], q[0]);      // first use of this group: the wait for its loads lands here
-      int noff = (m0 + U) * 2 * K;
-      asm volatile("" : "+s"(noff), "+v"(q[0]));
-      fetch(nxt, ynxt, noff, m0 + U);
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-          if (!(u == 0 && k == 0)) q[k] = fma(cur[u][2 * k], re[u], q[k]);
-          q[k] = fma(cur[u][2 * k + 1], im[u], q[k]);
+      static_for<0, K>([&](auto KI) {
+        constexpr int k = KI.value;
+        if (class_on(mask, k)) {
+          static_for<0, 8>([&](auto UI) {
+            constexpr int u = UI.value;
+            fma_bcast<2 * u, u == 0>(q[k][0], ccur[k], re[u]);
+            fma_bcast<2 * u + 1, false>(q[k][1], ccur[k], im[u]);
+          });
         }
-      }
+      });
 #pragma unroll
-      for (int k = 0; k < K; ++k) asm volatile("" : "+v"(q[k]));
-    };
-    for (int m0 = 0; m0 < Mmain; m0 += 2 * U) {
-      group(cA, yA, cB, yB, m0);
-      group(cB, yB, cA, yA, m0 + U);
-    }
-    // the last M - Mmain items, one by one
-    {
-      int i, j;
-      if (Mmain < M) item_ij(Mmain, D, i, j); else { i = 0; j = 0; }
-      for (int m = Mmain; m < M; ++m) {
-        const float2 a = yrow[i], b = yrow[j];
-        const double ar = a.x, ai = a.y, br = b.x, bi = b.y;
-        const double re = ar * br + ai * bi;
-        const double im = ai * br - ar * bi;
-        const double* __restrict__ c = cf + (long)m * 2 * K;
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-          q[k] = fma(c[2 * k], re, q[k]);
-          q[k] = fma(c[2 * k + 1], im, q[k]);
-        }
-        ++j;
-        if (j == D) { ++i; j = i; }
-      }
-    }
-    // ||y||^2 from the diagonal items
-    for (int d = 0; d < D; ++d) {
-      const float2 a = yrow[d];
-      n2 += (double)a.x * (double)a.x + (double)a.y * (double)a.y;
+      for (int k = 0; k < K; ++k) ccur[k] = cnxt[k];
     }
     // posterior over the active classes: pi_k / det B_k * q_k^-D, mantissa / exponent form
     const double n2c = fmax(n2, GSS_EPS_NORM_SQ);
@@ -297,18 +277,23 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
     double rq[K], mant[K];
     int ex[K];
     int emax = -(1 << 28);
-#pragma unroll
-    for (int k = 0; k < K; ++k) {
-      const bool a = (abits >> k) & 1u;
-      rq[k] = rcp_f64(fmax(q[k], qfloor));
-      const double u = rq[k] * n2c;
-      const double mu = __builtin_amdgcn_frexp_mant(u);
-      const int eu = __builtin_amdgcn_frexp_exp(u);
-      const double pw = ipow_rt(mu, D);            // >= 2^-32
-      mant[k] = cm[k] * __builtin_amdgcn_frexp_mant(pw);
-      ex[k] = a ? ce[k] + eu * D + __builtin_amdgcn_frexp_exp(pw) : -(1 << 28);
-      emax = ex[k] > emax ? ex[k] : emax;
-    }
+    static_for<0, K>([&](auto KI) {
+      constexpr int k = KI.value;
+      rq[k] = 0.0;
+      mant[k] = 0.0;
+      ex[k] = -(1 << 28);
+      if (class_on(mask, k)) {
+        const bool a = (abits >> k) & 1u;
+        rq[k] = rcp_f64(fmax(q[k][0] + q[k][1], qfloor));
+        const double u = rq[k] * n2c;
+        const double mu = __builtin_amdgcn_frexp_mant(u);
+        const int eu = __builtin_amdgcn_frexp_exp(u);
+        const double pw = ipow_rt(mu, D);            // >= 2^-32
+        mant[k] = cm[k] * __builtin_amdgcn_frexp_mant(pw);
+        ex[k] = a ? ce[k] + eu * D + __builtin_amdgcn_frexp_exp(pw) : -(1 << 28);
+        emax = ex[k] > emax ? ex[k] : emax;
+      }
+    });
     double v[K], Z = 0.0;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
@@ -320,10 +305,12 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
     const double rz = Z > 0.0 ? rcp_f64(Z) : 0.0;
     if (FINAL) {
       if (valid && !(n2 >= GSS_EPS_NORM_SQ)) atomicOr(status, GSS_STATUS_ZERO_FRAME);
-      if (t < Tmax) {
-#pragma unroll
-        for (int k = 0; k < K; ++k) gamma[(((long)s * K + k) * F + f) * Tmax + t] = (float)(v[k] * rz);
-      }
+      static_for<0, K>([&](auto KI) {
+        constexpr int k = KI.value;
+        if (class_on(mask, k)) {
+          if (t < Tmax) gamma[(((long)s * K + k) * F + f) * Tmax + t] = (float)(v[k] * rz);
+        }
+      });
       wave_lds_sync();                       // the tile is overwritten by the next iteration
       continue;
     }
@@ -335,7 +322,7 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
     }
     wave_lds_sync();
     // ---- phase 2 ----
-    accumulate_items<K, NR>(sY, sW, RS, WS, oi, oj, acc);
+    accumulate_items<K, NR>(sY, sW, RS, WS, oi, oj, mask, acc);
     wave_lds_sync();
   }
   if (FINAL) return;
@@ -507,13 +494,15 @@ __global__ __launch_bounds__(1024) void em_factor_large(
   double detm;
   int dete;
   const int where = gauss_jordan_large_2buf(sMr, sMi, sM2r, sM2i, D, i, j, on, status, GSS_STATUS_NONPD_B, detm, dete);
+  const int CP = coef_pitch(D);
   if (on && i <= j) {
     const int m = item_index(i, j, D);
-    double* c = coef + ((sf * (long)M + m) * K + k) * 2;
+    double* c = coef + (sf * K + k) * (long)CP + 2 * m;
     const double ar = where ? sM2r[i][j] : sMr[i][j], ai = where ? sM2i[i][j] : sMi[i][j];
     if (i == j) { c[0] = ar; c[1] = 0.0; }
     else { c[0] = 2.0 * ar; c[1] = 2.0 * ai; }
   }
+  if (tid < CP - 2 * M) coef[(sf * K + k) * (long)CP + 2 * M + tid] = 0.0;       // the padding stays zero
   if (tid == 0) {
     double pi;
     if (weight_mode == 1) {
@@ -585,7 +574,7 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void mvdr_cov_large(
     sW[lane * WS + 0] = valid ? wt : 0.0;
     sW[lane * WS + 1] = valid ? wb : 0.0;
     wave_lds_sync();
-    accumulate_items<2, NR>(sY, sW, RS, WS, oi, oj, acc);
+    accumulate_items<2, NR>(sY, sW, RS, WS, oi, oj, 3u, acc);
     wave_lds_sync();
   }
   double* __restrict__ red = reinterpret_cast<double*>(lds_raw);
@@ -753,14 +742,19 @@ int run_em_large(gss_ctx* ctx, const gss_yview& Y, const uint8_t* act, const int
   const long wgs_acc = chunk_map_wgs(acc_map, n_sf), wgs_fin = chunk_map_wgs(fin_map, n_sf);
   if (wgs_acc > 0x7fffffffL || wgs_fin > 0x7fffffffL || n_sf * K > 0x7fffffffL) return GSS_EUNSUPPORTED;
   size_t o = 0;
-  const size_t off_coef = o;  o = gss_align_up(o + ((size_t)n_sf * M * K * 2 + kCoefPadDoubles) * sizeof(double), 256);
+  const size_t off_coef = o;  o = gss_align_up(o + (size_t)n_sf * K * coef_pitch(D) * sizeof(double), 256);
   const size_t off_cm = o;    o = gss_align_up(o + (size_t)n_sf * K * sizeof(double), 256);
   const size_t off_ce = o;    o = gss_align_up(o + (size_t)n_sf * K * sizeof(int32_t), 256);
   const size_t off_part = o;  o = gss_align_up(o + (size_t)wgs_acc * M * K * 2 * sizeof(double), 256);
   const size_t off_npart = o; o = gss_align_up(o + (size_t)wgs_acc * K * sizeof(double), 256);
+  const size_t off_abyte = o; o = gss_align_up(o + (size_t)S * Tmax, 256);
+  const size_t off_tmask = o; o = gss_align_up(o + (size_t)S * tiles * sizeof(uint32_t), 256);
+  if ((long)S * tiles > 0x7fffffffL) return GSS_EUNSUPPORTED;
   int rc = gss_ensure_scratch(ctx, o);
   if (rc != GSS_OK) return rc;
   char* base = (char*)ctx->scratch;
+  uint8_t* abyte = (uint8_t*)(base + off_abyte);
+  uint32_t* tmask = (uint32_t*)(base + off_tmask);
   double* coef = (double*)(base + off_coef);
   double* cm = (double*)(base + off_cm);
   int32_t* ce = (int32_t*)(base + off_ce);
@@ -768,19 +762,21 @@ int run_em_large(gss_ctx* ctx, const gss_yview& Y, const uint8_t* act, const int
   double* npart = (double*)(base + off_npart);
   const dim3 block(kWave * kLargeWaves);
   const int fthreads = (D * D + 63) / 64 * 64;
-  hipLaunchKernelGGL(em_init_coef_large, dim3(1024), dim3(256), 0, st, coef, cm, ce, D, K, n_sf, kCoefPadDoubles);
+  hipLaunchKernelGGL(em_init_coef_large, dim3(1024), dim3(256), 0, st, coef, cm, ce, D, K, n_sf);
+  hipLaunchKernelGGL(em_pack_activity, dim3((unsigned)(S * tiles)), dim3(kWave), 0, st, Y, act, T_len, abyte, tmask, K,
+                     Tmax, tiles);
   for (int it = 0; it < iters; ++it) {
     gss_profile_begin(ctx, 0, st);
-    hipLaunchKernelGGL((em_pass_large<K, NR, false>), dim3((unsigned)wgs_acc), block, p.lds_bytes, st, Y, act, T_len, coef,
-                       cm, ce, part, npart, (float*)nullptr, ctx->status, F, Tmax, D, acc_map, p.RS, p.tile_bytes);
+    hipLaunchKernelGGL((em_pass_large<K, NR, false>), dim3((unsigned)wgs_acc), block, p.lds_bytes, st, Y, abyte, tmask, T_len,
+                       coef, cm, ce, part, npart, (float*)nullptr, ctx->status, F, Tmax, D, acc_map, p.RS, p.tile_bytes);
     gss_profile_end(ctx, 0, st);
     gss_profile_begin(ctx, 1, st);
     hipLaunchKernelGGL(em_factor_large, dim3((unsigned)(n_sf * K)), dim3(fthreads), 0, st, part, npart, coef, cm, ce,
                        ctx->status, D, K, acc_map, weight_mode);
     gss_profile_end(ctx, 1, st);
   }
-  hipLaunchKernelGGL((em_pass_large<K, NR, true>), dim3((unsigned)wgs_fin), block, p.lds_bytes, st, Y, act, T_len, coef, cm,
-                     ce, (double*)nullptr, (double*)nullptr, gamma, ctx->status, F, Tmax, D, fin_map, p.RS, p.tile_bytes);
+  hipLaunchKernelGGL((em_pass_large<K, NR, true>), dim3((unsigned)wgs_fin), block, p.lds_bytes, st, Y, abyte, tmask, T_len, coef,
+                     cm, ce, (double*)nullptr, (double*)nullptr, gamma, ctx->status, F, Tmax, D, fin_map, p.RS, p.tile_bytes);
   if (hipGetLastError() != hipSuccess) return GSS_EHIP;
   return GSS_OK;
 }
