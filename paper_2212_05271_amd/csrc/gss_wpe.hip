@@ -44,24 +44,43 @@ __device__ inline double block_max(const double* __restrict__ lam, int T, double
   return r;
 }
 
-// lambda of the observation itself (first iteration): one thread per frame.
+// Frame kernels (power, apply) run one workgroup per block of 256 frames of a (segment, frequency) row.
+// Workgroups are dealt to the 8 accelerator dies round-robin by their index; xcd_block() turns the index into
+// the logical block so that consecutive logical blocks (the blocks of one row, which share the row's
+// prediction coefficients and the frames at their common edge) run on the same die and meet in its L2.
+// The grid has 8 * ceil(n / 8) workgroups; the surplus ones get an index >= n and leave.
+__device__ __forceinline__ long xcd_block(unsigned b, long per_xcd) { return (long)(b & 7u) * per_xcd + (long)(b >> 3); }
+
+// lambda of the observation itself (first iteration).  The block's frames are read as one contiguous run
+// (coalesced), |y|^2 per component goes to LDS, then thread = frame sums its D values in channel order.
 __global__ __launch_bounds__(kWpeThreads) void wpe_power_kernel(const float2* __restrict__ Y, const int32_t* __restrict__ T_len,
                                                                 double* __restrict__ lam, int F, int Tmax, int D,
-                                                                int blocks_per_sf) {
-  const long sf = blockIdx.x / blocks_per_sf;
-  const int t = (blockIdx.x % blocks_per_sf) * kWpeThreads + threadIdx.x;
+                                                                int blocks_per_sf, long n_blocks, long per_xcd) {
+  __shared__ double sP[kWpeThreads * (GSS_WPE_MAX_D + 1)];
+  const long blk = xcd_block(blockIdx.x, per_xcd);
+  if (blk >= n_blocks) return;
+  const long sf = blk / blocks_per_sf;
+  const int t0 = (int)(blk % blocks_per_sf) * kWpeThreads;
   const int T = clamp_T(T_len, (int)(sf / F), Tmax);
+  const int pitch = D | 1;                                // odd: the frames' rows start in different banks
+  const float2* __restrict__ Yblk = Y + (sf * Tmax + t0) * D;
+  const int n_valid = (T - t0 < kWpeThreads ? (T - t0 > 0 ? T - t0 : 0) : kWpeThreads) * D;
+  for (int e = threadIdx.x; e < kWpeThreads * D; e += kWpeThreads) {
+    const int r = e / D, d = e - r * D;
+    double p = 0.0;
+    if (e < n_valid) {
+      const float2 v = Yblk[e];
+      const double re = v.x, im = v.y;
+      p = re * re + im * im;
+    }
+    sP[r * pitch + d] = p;
+  }
+  __syncthreads();
+  const int t = t0 + threadIdx.x;
   if (t >= Tmax) return;
   double p = 0.0;
-  if (t < T) {
-    const float2* __restrict__ y = Y + (sf * Tmax + t) * D;
-    for (int d = 0; d < D; ++d) {
-      const double re = y[d].x, im = y[d].y;
-      p += re * re + im * im;
-    }
-    p /= (double)D;
-  }
-  lam[sf * Tmax + t] = p;
+  for (int d = 0; d < D; ++d) p += sP[threadIdx.x * pitch + d];
+  lam[sf * Tmax + t] = p / (double)D;
 }
 
 // Lane l of the covariance kernel owns one 4 x 4 block: the first nb(nb+1)/2 lanes the blocks (bi >= bj) of
@@ -363,11 +382,13 @@ template <int D, bool FINAL>
 __global__ __launch_bounds__(kWpeThreads) void wpe_apply_kernel(const float2* __restrict__ Y, const int32_t* __restrict__ T_len,
                                                                 const double2* __restrict__ Gc, double* __restrict__ lam,
                                                                 float2* __restrict__ X, int F, int Tmax, int taps, int delay,
-                                                                int blocks_per_sf, int pitch) {
+                                                                int blocks_per_sf, int pitch, long n_blocks, long per_xcd) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   float2* __restrict__ sWin = reinterpret_cast<float2*>(lds_raw);
-  const long sf = blockIdx.x / blocks_per_sf;
-  const int t0 = (blockIdx.x % blocks_per_sf) * kWpeThreads;
+  const long blk = xcd_block(blockIdx.x, per_xcd);
+  if (blk >= n_blocks) return;
+  const long sf = blk / blocks_per_sf;
+  const int t0 = (int)(blk % blocks_per_sf) * kWpeThreads;
   const int T = clamp_T(T_len, (int)(sf / F), Tmax);
   const int t = t0 + threadIdx.x;
   const int N = D * taps;
@@ -508,7 +529,7 @@ int run_wpe(gss_ctx* ctx, const float2* Y, const int32_t* T_len, int S, int F, i
   const ChunkMap cmap = plan_chunk_map((long)ctx->num_cu * per_cu, n_sf, tiles, 1, 0, true);
   const long wgs = chunk_map_wgs(cmap, n_sf);
   const long blocks_per_sf = (Tmax + kWpeThreads - 1) / kWpeThreads;
-  if (wgs > 0x7fffffffL || n_sf * blocks_per_sf > 0x7fffffffL || n_sf * 4 > 0x7fffffffL) return GSS_EUNSUPPORTED;
+  if (wgs > 0x7fffffffL || n_sf * blocks_per_sf + 8 > 0x7fffffffL || n_sf * 4 > 0x7fffffffL) return GSS_EUNSUPPORTED;
   // apply kernel: row pitch odd for even D
   const int apitch = D | 1;
   const int apply_lds = (int)((size_t)(kWpeThreads + delay + taps - 1) * apitch * sizeof(float2));
@@ -528,8 +549,10 @@ int run_wpe(gss_ctx* ctx, const float2* Y, const int32_t* T_len, int S, int F, i
   double2* A = (double2*)(base + off_a);
 
   const dim3 block(kWpeThreads);
-  const dim3 frame_grid((unsigned)(n_sf * blocks_per_sf));
-  hipLaunchKernelGGL(wpe_power_kernel, frame_grid, block, 0, st, Y, T_len, lam, F, Tmax, D, (int)blocks_per_sf);
+  const long n_blocks = n_sf * blocks_per_sf, per_xcd = (n_blocks + 7) / 8;
+  const dim3 frame_grid((unsigned)(8 * per_xcd));
+  hipLaunchKernelGGL(wpe_power_kernel, frame_grid, block, 0, st, Y, T_len, lam, F, Tmax, D, (int)blocks_per_sf, n_blocks,
+                     per_xcd);
   for (int it = 0; it < iters; ++it) {
     gss_profile_begin(ctx, 2, st);
     hipLaunchKernelGGL(wpe_cov_kernel, dim3((unsigned)wgs), block, cov_lds, st, Y, T_len, lam, part, F, Tmax, D, taps, delay,
@@ -539,10 +562,10 @@ int run_wpe(gss_ctx* ctx, const float2* Y, const int32_t* T_len, int S, int F, i
     hipLaunchKernelGGL(wpe_solve_kernel, dim3((unsigned)n_sf), dim3(kSolveThreads), 0, st, A, Gc, ctx->status, D, taps);
     if (it + 1 < iters)
       hipLaunchKernelGGL((wpe_apply_kernel<D, false>), frame_grid, block, apply_lds, st, Y, T_len, Gc, lam, X, F, Tmax, taps,
-                         delay, (int)blocks_per_sf, apitch);
+                         delay, (int)blocks_per_sf, apitch, n_blocks, per_xcd);
     else
       hipLaunchKernelGGL((wpe_apply_kernel<D, true>), frame_grid, block, apply_lds, st, Y, T_len, Gc, lam, X, F, Tmax, taps,
-                         delay, (int)blocks_per_sf, apitch);
+                         delay, (int)blocks_per_sf, apitch, n_blocks, per_xcd);
   }
   if (hipGetLastError() != hipSuccess) return GSS_EHIP;
   return GSS_OK;
