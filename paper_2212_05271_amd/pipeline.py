@@ -22,7 +22,7 @@ HOP = 256
 N_FFT = 1024
 
 
-def plan_batches(n_frames, max_batch_frames=200_000, max_segments=64):
+def plan_batches(n_frames, max_batch_frames=400_000, max_segments=128):
     """Sort segments by length (longest first) and cut the order into batches whose padded size
     (segments x longest) stays below max_batch_frames.  Returns a list of index lists."""
     order = np.argsort(-np.asarray(n_frames), kind="stable")
@@ -39,7 +39,7 @@ def plan_batches(n_frames, max_batch_frames=200_000, max_segments=64):
 
 
 def enhance_recording(ctx, x, act_samples, seg_start, seg_end, seg_spk, ctx_left, ctx_right, iters=15,
-                      weight_mode=1, max_batch_frames=200_000, Yrec=None, wpe_taps=0, wpe_delay=2, wpe_iters=3):
+                      weight_mode=1, max_batch_frames=400_000, Yrec=None, wpe_taps=0, wpe_delay=2, wpe_iters=3):
     """x[D, N] float32 CUDA tensor, act_samples[n_spk, N] uint8 (host), segments (host arrays).
 
     Classes per segment: the n_spk speakers in recording order plus a noise class that is always active
@@ -113,7 +113,7 @@ def block_spans(seg_start, seg_end, block):
 
 
 def enhance_recording_blocks(ctx, x, act_samples, seg_start, seg_end, seg_spk, block, history, iters=15,
-                             weight_mode=1, max_batch_frames=200_000, Yrec=None):
+                             weight_mode=1, max_batch_frames=400_000, Yrec=None):
     """Block-wise processing for speakers that move (Section 3, "Segment batching", keeps one set of statistics
     and one reference channel per batch for stationary speakers only; Section 1 cites block-online GSS): every
     segment is cut into consecutive blocks of `block` samples, and every block is enhanced as a segment of its
@@ -209,7 +209,7 @@ def merge_runs(ext_start, ext_end, hop=HOP):
 
 
 def enhance_recording_super(ctx, x, act_samples, seg_start, seg_end, seg_spk, ctx_left, ctx_right,
-                            max_batch_s=50.0, iters=15, weight_mode=1, max_batch_frames=200_000, Yrec=None,
+                            max_batch_s=50.0, iters=15, weight_mode=1, max_batch_frames=400_000, Yrec=None,
                             wpe_taps=0, wpe_delay=2, wpe_iters=3):
     """Super-segment batching.  Arguments as enhance_recording; max_batch_s bounds the summed member
     duration of a super-segment (seconds at 16 kHz).
@@ -243,21 +243,31 @@ def enhance_recording_super(ctx, x, act_samples, seg_start, seg_end, seg_spk, ct
                           T=int(sum(r[1] for r in runs))))
     outputs = [None] * n_seg
     super_ref = np.zeros(len(supers), dtype=np.int32)
-    member_X = []                                   # (segment index, X slice [F, n], cut_start, cut_end)
+    Yr = Yrec[0]
+    Trec = Yr.shape[1]
+    # frame-level activity of the whole recording once; a run's rows are a slice of it
+    act_rec = gss.gss_frame_activity(act_samples, 0, Trec, HOP)
     for batch in plan_batches([p["T"] for p in plans], max_batch_frames):
         S = len(batch)
         Tmax = max(plans[b]["T"] for b in batch)
-        Y = torch.zeros((S, F, Tmax, D), dtype=torch.complex64, device=x.device)
+        # recording frame of every frame of the concatenations (padding: frame 0, zeroed below); the runs are
+        # gathered with one indexed copy per super-segment
+        src = np.zeros((S, Tmax), dtype=np.int64)
         act = np.zeros((S, K, Tmax), dtype=np.uint8)
         T_len = np.zeros(S, dtype=np.int32)
         for bi, b in enumerate(batch):
             off = 0
             for f0, nf, _ in plans[b]["runs"]:
-                Y[bi, :, off:off + nf] = Yrec[0, :, f0:f0 + nf]
-                act[bi, :n_spk, off:off + nf] = gss.gss_frame_activity(act_samples, f0, nf, HOP)
+                src[bi, off:off + nf] = np.arange(f0, f0 + nf)
+                act[bi, :n_spk, off:off + nf] = act_rec[:, f0:f0 + nf]
                 off += nf
             act[bi, n_spk, :off] = 1
             T_len[bi] = off
+        src_d = torch.from_numpy(src).to(x.device)
+        Y = torch.empty((S, F, Tmax, D), dtype=torch.complex64, device=x.device)
+        for bi in range(S):
+            torch.index_select(Yr, 1, src_d[bi], out=Y[bi])
+            Y[bi, :, int(T_len[bi]):] = 0
         T_d = torch.from_numpy(T_len).to(x.device)
         tgt = torch.from_numpy(np.asarray([seg_spk[plans[b]["members"][0]] for b in batch], dtype=np.int32)).to(x.device)
         ref = torch.full((S,), -1, dtype=torch.int32, device=x.device)
@@ -265,7 +275,9 @@ def enhance_recording_super(ctx, x, act_samples, seg_start, seg_end, seg_spk, ct
             Y = gss.gss_wpe(ctx, Y, T_d, wpe_taps, wpe_delay, wpe_iters)
         gamma = gss.gss_cacgmm_em(ctx, Y, torch.from_numpy(act).to(x.device), T_d, iters, weight_mode)
         X = gss.gss_mvdr(ctx, Y, gamma, tgt, ref, T_d)
+        del Y, gamma
         ref_h = ref.cpu().numpy()
+        members = []                                # (segment index, position in X's [S * Tmax] frame axis, frames, cut)
         for bi, b in enumerate(batch):
             super_ref[b] = ref_h[bi]
             fr, runs = plans[b]["fr"], plans[b]["runs"]
@@ -277,17 +289,24 @@ def enhance_recording_super(ctx, x, act_samples, seg_start, seg_end, seg_spk, ct
                 f0, nf = int(fr["frame0"][p]), int(fr["n_frames"][p])
                 r = next(q for q, run in enumerate(runs) if p in run[2])
                 off = int(run_off[r]) + f0 - runs[r][0]
-                member_X.append((i, X[bi, :, off:off + nf], int(fr["cut_start"][p]), int(fr["cut_end"][p])))
-    # every member's slice is inverted on its own, in padded batches of similar length
-    for batch in plan_batches([m[1].shape[1] for m in member_X], max_batch_frames):
-        Tm = max(member_X[b][1].shape[1] for b in batch)
-        Xp = torch.zeros((len(batch), F, Tm), dtype=torch.complex64, device=x.device)
-        for bi, b in enumerate(batch):
-            Xp[bi, :, :member_X[b][1].shape[1]] = member_X[b][1]
-        xh = gss.gss_istft(ctx, Xp, (Tm - 3) * HOP)
-        for bi, b in enumerate(batch):
-            i, _, c0, c1 = member_X[b]
-            outputs[i] = xh[bi, c0:c1]
+                members.append((i, bi * Tmax + off, nf, int(fr["cut_start"][p]), int(fr["cut_end"][p])))
+        # every member's slice is inverted on its own, in padded batches of similar length, each gathered from the
+        # beamformed STFT (frequency-major copy, one zero frame appended for the padding) with one indexed copy
+        Xf = torch.zeros((F, S * Tmax + 1), dtype=torch.complex64, device=x.device)
+        Xf[:, :S * Tmax].view(F, S, Tmax).copy_(X.permute(1, 0, 2))
+        del X
+        for mb in plan_batches([m[2] for m in members], max_batch_frames, max_segments=1024):
+            Tm = max(members[m][2] for m in mb)
+            idx = np.full((len(mb), Tm), S * Tmax, dtype=np.int64)
+            for q, m in enumerate(mb):
+                idx[q, :members[m][2]] = np.arange(members[m][1], members[m][1] + members[m][2])
+            idx_d = torch.from_numpy(idx.reshape(-1)).to(x.device)
+            Xp = Xf.index_select(1, idx_d).view(F, len(mb), Tm).permute(1, 0, 2).contiguous()
+            xh = gss.gss_istft(ctx, Xp, (Tm - 3) * HOP)
+            for q, m in enumerate(mb):
+                i, _, _, c0, c1 = members[m]
+                outputs[i] = xh[q, c0:c1]
+        del Xf
     info = dict(supers=supers, T=np.asarray([p["T"] for p in plans], dtype=np.int32), ref=super_ref,
                 pieces=[(p["member_of"], p["fr"]) for p in plans], runs=[p["runs"] for p in plans])
     return outputs, info

@@ -10,6 +10,12 @@
 (`bench.py --copy-calibration`: 256 MiB device-to-device copies of known size), scales each counter by what it
 reads for the copy, and writes the bytes per launch of the kernels whose name contains --kernel.  bench.py reads
 the line "bytes per launch" of profiles/em_pass_hbm_traffic.md.
+
+    python -m paper_2212_05271_amd.profile_summary counters COUNTERS.csv [MORE.csv ...] --title T --command C --out profiles/X.md
+
+`counters` writes the mean per launch of every counter in the given counter_collection.csv files, one row per
+kernel.  When the read-request counters TCC_EA0_RDREQ_32B/64B/128B_sum are among them it adds the bytes they
+stand for (32, 64 and 128 bytes per request), and with WRITE_SIZE (KiB) the bytes written.
 """
 
 from __future__ import annotations
@@ -89,6 +95,43 @@ def traffic(a):
     open(a.out, "w").write("\n".join(out) + "\n")
 
 
+def counters(a):
+    per = collections.defaultdict(lambda: collections.defaultdict(list))
+    for fn in a.files:
+        for r in csv.DictReader(open(fn)):
+            per[r["Kernel_Name"]][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    names = []
+    for k in per:
+        for c in per[k]:
+            if c not in names:
+                names.append(c)
+    sizes = {"TCC_EA0_RDREQ_32B_sum": 32, "TCC_EA0_RDREQ_64B_sum": 64, "TCC_EA0_RDREQ_128B_sum": 128}
+    with_bytes = all(s in names for s in sizes)
+    head = ["kernel", "launches"] + names + (["read per launch (MB)"] if with_bytes else []) + \
+           (["written per launch (MB)"] if "WRITE_SIZE" in names else [])
+    out = [f"# {a.title}\n", "Commands (run from /tmp with TMPDIR=/tmp, repository root as working directory):\n"]
+    out += ["    " + c for c in a.command]
+    if a.note:
+        out.append("\n" + a.note)
+    out.append("\nMean per launch.\n")
+    out.append("| " + " | ".join(head) + " |")
+    out.append("|---|" + "---:|" * (len(head) - 1))
+    for k in sorted(per, key=lambda k: -sum(sum(v) for v in per[k].values())):
+        if "rocclr" in k and not a.keep_copies:
+            continue
+        if "at::native" in k:
+            continue
+        mean = {c: sum(v) / len(v) for c, v in per[k].items()}
+        n = max(len(v) for v in per[k].values())
+        row = [short_name(k) if "rocclr" not in k else k, str(n)] + ["%.4g" % mean[c] if c in mean else "" for c in names]
+        if with_bytes:
+            row.append("%.2f" % (sum(mean.get(c, 0.0) * b for c, b in sizes.items()) / 1e6))
+        if "WRITE_SIZE" in names:
+            row.append("%.2f" % (mean.get("WRITE_SIZE", 0.0) * 1024.0 / 1e6))
+        out.append("| " + " | ".join(row) + " |")
+    open(a.out, "w").write("\n".join(out) + "\n")
+
+
 def main():
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -107,11 +150,20 @@ def main():
     f.add_argument("--algorithmic-bytes", type=int, default=0)
     f.add_argument("--algorithmic-note", default="")
     f.add_argument("--out", required=True)
+    c = sub.add_parser("counters")
+    c.add_argument("files", nargs="+")
+    c.add_argument("--title", required=True)
+    c.add_argument("--command", action="append", required=True)
+    c.add_argument("--note", default="")
+    c.add_argument("--keep-copies", action="store_true", help="keep the runtime's copy / fill kernels in the table")
+    c.add_argument("--out", required=True)
     a = ap.parse_args()
     if a.cmd == "trace":
         trace(a)
-    else:
+    elif a.cmd == "traffic":
         traffic(a)
+    else:
+        counters(a)
 
 
 if __name__ == "__main__":
