@@ -51,6 +51,8 @@ typedef enum gss_status {
 #define GSS_MAX_K 8
 #define GSS_WPE_MAX_D 8  /* gss_wpe: channels                                   */
 #define GSS_WPE_MAX_N 80 /* gss_wpe: channels x taps (size of the linear system) */
+#define GSS_WPE_LARGE_MAX_D 32  /* gss_wpe, large arrays: channels                  */
+#define GSS_WPE_LARGE_MAX_N 320 /* gss_wpe, large arrays: channels x taps           */
 #define GSS_STATIC_SCRATCH_BYTES (64u << 20) /* gss_cacgmm_em_noalloc: size of the static scratch array per GPU */
 
 /* Bits of the device status word (gss_get_status). */
@@ -130,7 +132,10 @@ int gss_stft(gss_ctx* ctx, const float* x, int S, int D, int64_t N, int n_fft, i
  *   taps >= 1, delay >= 1, iters >= 0 (0 copies the input); the usual setting is 10, 2, 3
  *   X      [S][F][Tmax][D] complex64 out, must not overlap Y; exact 0 at t >= T_len[s].  A bin that is
  *          silent, or too short for any frame to have a past, comes back unchanged.
- * Limits: D <= GSS_WPE_MAX_D, D * taps <= GSS_WPE_MAX_N, delay <= 64.  Arithmetic: fp64 throughout.
+ * Limits: D <= GSS_WPE_LARGE_MAX_D, D * taps <= GSS_WPE_LARGE_MAX_N, delay <= 64 (up to D = GSS_WPE_MAX_D and
+ * D * taps = GSS_WPE_MAX_N the linear system of a frequency is solved in the registers of one workgroup, beyond
+ * that by a blocked factorisation in global memory, which needs 16 * (D taps) * (D taps + D) bytes of scratch per
+ * segment and frequency).  Arithmetic: fp64 throughout.
  */
 int gss_wpe(gss_ctx* ctx, const float* Y, const int32_t* T_len, int S, int F, int Tmax, int D,
             int taps, int delay, int iters, float* X, void* stream);

@@ -53,19 +53,20 @@ __device__ __forceinline__ long xcd_block(unsigned b, long per_xcd) { return (lo
 
 // lambda of the observation itself (first iteration).  The block's frames are read as one contiguous run
 // (coalesced), |y|^2 per component goes to LDS, then thread = frame sums its D values in channel order.
+// fb = frames per block (256 for D <= 8, 64 for larger arrays: fb * (D | 1) doubles of LDS).
 __global__ __launch_bounds__(kWpeThreads) void wpe_power_kernel(const float2* __restrict__ Y, const int32_t* __restrict__ T_len,
                                                                 double* __restrict__ lam, int F, int Tmax, int D,
-                                                                int blocks_per_sf, long n_blocks, long per_xcd) {
+                                                                int blocks_per_sf, long n_blocks, long per_xcd, int fb) {
   __shared__ double sP[kWpeThreads * (GSS_WPE_MAX_D + 1)];
   const long blk = xcd_block(blockIdx.x, per_xcd);
   if (blk >= n_blocks) return;
   const long sf = blk / blocks_per_sf;
-  const int t0 = (int)(blk % blocks_per_sf) * kWpeThreads;
+  const int t0 = (int)(blk % blocks_per_sf) * fb;
   const int T = clamp_T(T_len, (int)(sf / F), Tmax);
   const int pitch = D | 1;                                // odd: the frames' rows start in different banks
   const float2* __restrict__ Yblk = Y + (sf * Tmax + t0) * D;
-  const int n_valid = (T - t0 < kWpeThreads ? (T - t0 > 0 ? T - t0 : 0) : kWpeThreads) * D;
-  for (int e = threadIdx.x; e < kWpeThreads * D; e += kWpeThreads) {
+  const int n_valid = (T - t0 < fb ? (T - t0 > 0 ? T - t0 : 0) : fb) * D;
+  for (int e = threadIdx.x; e < fb * D; e += kWpeThreads) {
     const int r = e / D, d = e - r * D;
     double p = 0.0;
     if (e < n_valid) {
@@ -77,7 +78,7 @@ __global__ __launch_bounds__(kWpeThreads) void wpe_power_kernel(const float2* __
   }
   __syncthreads();
   const int t = t0 + threadIdx.x;
-  if (t >= Tmax) return;
+  if ((int)threadIdx.x >= fb || t >= Tmax) return;
   double p = 0.0;
   for (int d = 0; d < D; ++d) p += sP[threadIdx.x * pitch + d];
   lam[sf * Tmax + t] = p / (double)D;
@@ -108,11 +109,13 @@ __host__ __device__ inline void wpe_block(int l, int nb, int nbd, int& bi, int& 
 // before it, whatever D is.  Each lane keeps its 4 x 4 block in registers and adds, frame by frame,
 // (w_t a_i) conj(b_j) for its four row values a and four column values b.  Rows >= N and columns >= N (or
 // >= D) of the last blocks take whatever follows in the window; nothing ever reads them.
-// part[(wg * 32 + j) * 256 + lane]: the 32 doubles (re, im of entry [i][j'], j = (i*4 + j')*2 + {0,1}).
+// More than 256 blocks (large arrays): G workgroups per chunk, workgroup g of them takes the blocks
+// 256 g .. 256 g + 255 (blockIdx.x = chunk slot * G + g).
+// part[(blockIdx.x * 32 + j) * 256 + lane]: the 32 doubles (re, im of entry [i][j'], j = (i*4 + j')*2 + {0,1}).
 __global__ __launch_bounds__(kWpeThreads) void wpe_cov_kernel(const float2* __restrict__ Y, const int32_t* __restrict__ T_len,
                                                               const double* __restrict__ lam, double* __restrict__ part,
                                                               int F, int Tmax, int D, int taps, int delay, ChunkMap cmap,
-                                                              int win_elems) {
+                                                              int win_elems, int G) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   double2* __restrict__ sWin = reinterpret_cast<double2*>(lds_raw);
   double* __restrict__ sWt = reinterpret_cast<double*>(lds_raw + (size_t)win_elems * sizeof(double2));
@@ -120,13 +123,13 @@ __global__ __launch_bounds__(kWpeThreads) void wpe_cov_kernel(const float2* __re
 
   long sf;
   int chunk, tpc;
-  chunk_decode(cmap, blockIdx.x, sf, chunk, tpc);
+  chunk_decode(cmap, blockIdx.x / (unsigned)G, sf, chunk, tpc);
   const int T = clamp_T(T_len, (int)(sf / F), Tmax);
   const int N = D * taps;
   const int nb = (N + 3) / 4, nbd = (D + 3) / 4;
   int bi, bj;
   bool is_p, valid;
-  wpe_block(threadIdx.x, nb, nbd, bi, bj, is_p, valid);
+  wpe_block((int)(blockIdx.x % (unsigned)G) * kWpeThreads + (int)threadIdx.x, nb, nbd, bi, bj, is_p, valid);
   if (!valid) { bi = 0; bj = 0; is_p = false; }
   const int aoff = delay * D + 4 * bi;
   const int boff = is_p ? 4 * bj : delay * D + 4 * bj;
@@ -205,9 +208,10 @@ __global__ __launch_bounds__(kWpeThreads) void wpe_cov_kernel(const float2* __re
 // work per thread on purpose: the kernel is a gather and scatter that wants many wavefronts in flight; one
 // workgroup per bin took 85 us on 513 bins, four take 42 us, eight 47 us.)
 __global__ __launch_bounds__(kWpeThreads) void wpe_assemble_kernel(const double* __restrict__ part, double2* __restrict__ A,
-                                                                   int D, int taps, ChunkMap cmap) {
-  const long sf = blockIdx.x >> 2;
+                                                                   int D, int taps, ChunkMap cmap, int G) {
+  const long sf = blockIdx.x / (unsigned)(4 * G);
   const int i = blockIdx.x & 3;
+  const int g = (int)(blockIdx.x % (unsigned)(4 * G)) >> 2;      // group of 256 blocks (large arrays: G > 1)
   const int N = D * taps;
   const int W = N + D;
   const int nb = (N + 3) / 4, nbd = (D + 3) / 4;
@@ -217,14 +221,14 @@ __global__ __launch_bounds__(kWpeThreads) void wpe_assemble_kernel(const double*
 
   int bi, bj;
   bool is_p, valid;
-  wpe_block(threadIdx.x, nb, nbd, bi, bj, is_p, valid);
+  wpe_block(g * kWpeThreads + (int)threadIdx.x, nb, nbd, bi, bj, is_p, valid);
   if (!valid) return;
   double v[8];
 #pragma unroll
   for (int q = 0; q < 8; ++q) v[q] = 0.0;
   for (int c = 0; c < count; ++c) {
     const double* __restrict__ src =
-        part + ((size_t)(wg0 + c) * kWpeBlockDoubles + (size_t)i * 8) * kWpeThreads + threadIdx.x;
+        part + (((size_t)(wg0 + c) * G + g) * kWpeBlockDoubles + (size_t)i * 8) * kWpeThreads + threadIdx.x;
 #pragma unroll
     for (int q = 0; q < 8; ++q) v[q] += src[(size_t)q * kWpeThreads];
   }
@@ -234,13 +238,13 @@ __global__ __launch_bounds__(kWpeThreads) void wpe_assemble_kernel(const double*
     const int b = 4 * bj + j;
     const double re = v[2 * j], im = v[2 * j + 1];
     if (is_p) {
-      if (a < N && b < D) M[a * W + N + b] = make_double2(re, im);
+      if (a < N && b < D) M[(long)a * W + N + b] = make_double2(re, im);
     } else if (a < N && b < N) {
       if (bi != bj || i > j) {                           // below the diagonal: the entry and its mirror image
-        M[a * W + b] = make_double2(re, im);
-        M[b * W + a] = make_double2(re, -im);
+        M[(long)a * W + b] = make_double2(re, im);
+        M[(long)b * W + a] = make_double2(re, -im);
       } else if (i == j) {
-        M[a * W + a] = make_double2(re, 0.0);
+        M[(long)a * W + a] = make_double2(re, 0.0);
       }
     }
   }
@@ -512,6 +516,375 @@ __global__ __launch_bounds__(kWpeThreads) void wpe_copy_kernel(const float2* __r
   X[i] = t < clamp_T(T_len, s, Tmax) ? Y[i] : make_float2(0.f, 0.f);
 }
 
+// ----------------------------------------------------------------------------------------------
+// Large arrays (D > 8 or D * taps > 80; up to D = 32, D * taps = 320).  The covariance, assemble and power
+// kernels above serve them too (several groups of 256 blocks); the linear system no longer fits the
+// registers of a workgroup, so it is solved in global memory, and the prediction is applied by a kernel
+// with a run-time channel count.
+// ----------------------------------------------------------------------------------------------
+constexpr int kLsNB = 8;                      // columns per panel of the blocked factorisation
+constexpr int kLsPitch = kLsNB + 1;           // LDS row pitch of a panel (in double2)
+constexpr int kLsThreads = 256;
+
+__device__ __forceinline__ double2 cmul_conj(double2 a, double2 b) {          // a conj(b)
+  return make_double2(a.x * b.x + a.y * b.y, a.y * b.x - a.x * b.y);
+}
+
+// Solve for large systems: one workgroup per (segment, frequency), the augmented matrix [R | P] stays in
+// global memory (it is L2-resident while its workgroup runs).  Blocked right-looking Cholesky factorisation
+// R + loading = L L^H, panels of 8 columns staged in LDS; the right-hand side rides along as D extra rows of
+// the virtual lower-triangular matrix V (row N + d of V is column d of P, conjugated: V = [R ; P^H]), so that
+// after the last panel the storage of P holds L^-1 P.  Then a blocked back substitution L^H G = L^-1 P.
+// No pivoting (the matrix is Hermitian positive definite; a pivot <= 1e-300 is floored and flagged).
+// Out: Gc[sf][a][d] = conj(G[a][d]).
+__global__ __launch_bounds__(kLsThreads) void wpe_solve_large_kernel(double2* __restrict__ A, double2* __restrict__ Gc,
+                                                                     uint32_t* __restrict__ status, int D, int taps) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  const int N = D * taps;
+  const int W = N + D;
+  const int R = N + D;                                    // rows of V
+  double2* __restrict__ sPanel = reinterpret_cast<double2*>(lds_raw);         // [R][kLsPitch]: V(r, k0 + c)
+  double2* __restrict__ sRhs = sPanel + (size_t)R * kLsPitch;                 // [kLsNB][D]: back substitution
+  __shared__ double sRed[kLsThreads / kWave];
+  const long sf = blockIdx.x;
+  double2* __restrict__ M = A + sf * (long)N * W;
+  double2* __restrict__ out = Gc + sf * (long)N * D;
+  const int tid = threadIdx.x;
+  // V(r, c), c < N: r < N: M[r][c]; r >= N: conj(M[c][N + r - N])
+  auto ldv = [&](int r, int c) -> double2 {
+    if (r < N) return M[(long)r * W + c];
+    double2 v = M[(long)c * W + N + (r - N)];
+    v.y = -v.y;
+    return v;
+  };
+  auto stv = [&](int r, int c, double2 v) {
+    if (r < N) {
+      M[(long)r * W + c] = v;
+    } else {
+      v.y = -v.y;
+      M[(long)c * W + N + (r - N)] = v;
+    }
+  };
+
+  double tr = 0.0;
+  for (int a = tid; a < N; a += kLsThreads) tr += M[(long)a * W + a].x;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) tr += __shfl_xor(tr, o);
+  if ((tid & (kWave - 1)) == 0) sRed[tid / kWave] = tr;
+  __syncthreads();
+  tr = 0.0;
+  for (int w = 0; w < kLsThreads / kWave; ++w) tr += sRed[w];
+  if (!(tr > 0.0)) {                                     // no frame has a past (or silence): G = 0
+    for (int e = tid; e < N * D; e += kLsThreads) out[e] = make_double2(0.0, 0.0);
+    return;
+  }
+  const double load = kWpeLoadRel * tr / (double)N;
+  const double tiny = 1e-300;
+
+  for (int k0 = 0; k0 < N; k0 += kLsNB) {
+    const int bs = N - k0 < kLsNB ? N - k0 : kLsNB;
+    // the panel: rows k0 .. R-1, columns k0 .. k0+bs-1 (of the diagonal block only the lower triangle is used)
+    for (int e = tid; e < (R - k0) * bs; e += kLsThreads) {
+      const int r = k0 + e / bs, c = e % bs;
+      double2 v = make_double2(0.0, 0.0);
+      if (r >= k0 + c) v = ldv(r, k0 + c);
+      if (r == k0 + c) { v.x += load; v.y = 0.0; }
+      sPanel[r * kLsPitch + c] = v;
+    }
+    __syncthreads();
+    // Cholesky of the diagonal block, thread (i, j) of the first 64
+    {
+      const int i = tid >> 3, j = tid & 7;
+      const bool on = tid < 64 && i < bs && j < bs;
+      for (int p = 0; p < bs; ++p) {
+        if (tid == 0) {
+          double d = sPanel[(k0 + p) * kLsPitch + p].x;
+          if (!(d > tiny)) {
+            d = tiny;
+            atomicOr(status, GSS_STATUS_NONPD_WPE);
+          }
+          sPanel[(k0 + p) * kLsPitch + p] = make_double2(sqrt(d), 0.0);
+        }
+        __syncthreads();
+        if (on && j == p && i > p) {
+          const double inv = 1.0 / sPanel[(k0 + p) * kLsPitch + p].x;
+          double2 v = sPanel[(k0 + i) * kLsPitch + p];
+          sPanel[(k0 + i) * kLsPitch + p] = make_double2(v.x * inv, v.y * inv);
+        }
+        __syncthreads();
+        if (on && j > p && i >= j) {
+          const double2 a = sPanel[(k0 + i) * kLsPitch + p], b = sPanel[(k0 + j) * kLsPitch + p];
+          const double2 m = cmul_conj(a, b);
+          double2 v = sPanel[(k0 + i) * kLsPitch + j];
+          sPanel[(k0 + i) * kLsPitch + j] = make_double2(v.x - m.x, v.y - m.y);
+        }
+        __syncthreads();
+      }
+    }
+    // rows below the block: x L_kk^H = a, one row per thread; the factor goes back to memory
+    for (int r = k0 + tid; r < R; r += kLsThreads) {
+      if (r < k0 + bs) {
+        for (int c = 0; c <= r - k0; ++c) stv(r, k0 + c, sPanel[r * kLsPitch + c]);
+        continue;
+      }
+      double2 x[kLsNB];
+#pragma unroll
+      for (int c = 0; c < kLsNB; ++c) {
+        if (c < bs) {
+          double2 acc = sPanel[r * kLsPitch + c];
+#pragma unroll
+          for (int m = 0; m < kLsNB; ++m)
+            if (m < c) {
+              const double2 t = cmul_conj(x[m], sPanel[(k0 + c) * kLsPitch + m]);
+              acc.x -= t.x;
+              acc.y -= t.y;
+            }
+          const double inv = 1.0 / sPanel[(k0 + c) * kLsPitch + c].x;
+          x[c] = make_double2(acc.x * inv, acc.y * inv);
+        } else {
+          x[c] = make_double2(0.0, 0.0);
+        }
+      }
+#pragma unroll
+      for (int c = 0; c < kLsNB; ++c)
+        if (c < bs) {
+          sPanel[r * kLsPitch + c] = x[c];
+          stv(r, k0 + c, x[c]);
+        }
+    }
+    __syncthreads();
+    // trailing update: V(r, c) -= sum_m L(r, m) conj(L(c, m)) for k0+bs <= c < N, c <= r < R
+    const int c_lo = k0 + bs;
+    const int ncols = N - c_lo;
+    if (ncols > 0) {
+      const int nrows = R - c_lo;
+      for (int e = tid; e < nrows * ncols; e += kLsThreads) {
+        const int r = c_lo + e / ncols, c = c_lo + e % ncols;
+        if (c > r) continue;
+        double2 acc = make_double2(0.0, 0.0);
+#pragma unroll
+        for (int m = 0; m < kLsNB; ++m)
+          if (m < bs) {
+            const double2 t = cmul_conj(sPanel[r * kLsPitch + m], sPanel[c * kLsPitch + m]);
+            acc.x += t.x;
+            acc.y += t.y;
+          }
+        double2 v = ldv(r, c);
+        stv(r, c, make_double2(v.x - acc.x, v.y - acc.y));
+      }
+    }
+    __syncthreads();
+  }
+
+  // back substitution L^H G = Z with Z = L^-1 P in the storage of P (M[c][N + d]); G overwrites it
+  const int last = (N - 1) / kLsNB * kLsNB;
+  for (int k0 = last; k0 >= 0; k0 -= kLsNB) {
+    const int bs = N - k0 < kLsNB ? N - k0 : kLsNB;
+    for (int e = tid; e < bs * bs; e += kLsThreads) {     // L_kk (lower triangle)
+      const int i = e / bs, j = e % bs;
+      if (j <= i) sPanel[i * kLsPitch + j] = M[(long)(k0 + i) * W + k0 + j];
+    }
+    for (int e = tid; e < bs * D; e += kLsThreads) sRhs[e] = M[(long)(k0 + e / D) * W + N + e % D];
+    __syncthreads();
+    if (tid < D) {                                         // one right-hand side per thread
+      for (int c = bs - 1; c >= 0; --c) {
+        double2 acc = sRhs[c * D + tid];
+        for (int m = c + 1; m < bs; ++m) {                 // conj(L(m, c)) g_m
+          const double2 lmc = sPanel[m * kLsPitch + c], g = sRhs[m * D + tid];
+          acc.x -= lmc.x * g.x + lmc.y * g.y;
+          acc.y -= lmc.x * g.y - lmc.y * g.x;
+        }
+        const double inv = 1.0 / sPanel[c * kLsPitch + c].x;
+        acc.x *= inv;
+        acc.y *= inv;
+        sRhs[c * D + tid] = acc;
+        M[(long)(k0 + c) * W + N + tid] = acc;
+      }
+    }
+    __syncthreads();
+    // rows above the block: Z(r, d) -= sum_m conj(L(k0 + m, r)) G(k0 + m, d)
+    for (int e = tid; e < k0 * D; e += kLsThreads) {
+      const int r = e % k0, d = e / k0;
+      double2 acc = make_double2(0.0, 0.0);
+      for (int m = 0; m < bs; ++m) {
+        const double2 lmr = M[(long)(k0 + m) * W + r], g = sRhs[m * D + d];
+        acc.x += lmr.x * g.x + lmr.y * g.y;
+        acc.y += lmr.x * g.y - lmr.y * g.x;
+      }
+      double2 z = M[(long)r * W + N + d];
+      M[(long)r * W + N + d] = make_double2(z.x - acc.x, z.y - acc.y);
+    }
+    __syncthreads();
+  }
+  for (int e = tid; e < N * D; e += kLsThreads) {
+    const double2 g = M[(long)(e / D) * W + N + e % D];
+    out[e] = make_double2(g.x, -g.y);
+  }
+}
+
+// Apply for large arrays: lane = frame, fb frames per workgroup (+ the needed past) staged in LDS as they
+// came; a lane holds all D outputs (up to 32) and walks the D * taps components of ytilde_t; the
+// coefficients are the same for all lanes and come through the scalar path, 8 outputs at a time.  A row of
+// coefficients is read in whole groups of 8: the last group of a row may reach into the next row (or, at the
+// very end of the array, into its padding); those values only enter accumulators that are never stored.
+template <bool FINAL>
+__global__ __launch_bounds__(kWpeThreads) void wpe_apply_large_kernel(const float2* __restrict__ Y, const int32_t* __restrict__ T_len,
+                                                                      const double2* __restrict__ Gc, double* __restrict__ lam,
+                                                                      float2* __restrict__ X, int F, int Tmax, int D, int taps,
+                                                                      int delay, int blocks_per_sf, int pitch, int fb,
+                                                                      long n_blocks, long per_xcd) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  float2* __restrict__ sWin = reinterpret_cast<float2*>(lds_raw);
+  const long blk = xcd_block(blockIdx.x, per_xcd);
+  if (blk >= n_blocks) return;
+  const long sf = blk / blocks_per_sf;
+  const int t0 = (int)(blk % blocks_per_sf) * fb;
+  const int T = clamp_T(T_len, (int)(sf / F), Tmax);
+  const int t = t0 + threadIdx.x;
+  const bool mine_on = (int)threadIdx.x < fb && t < Tmax;
+  const int N = D * taps;
+  if (t0 >= T) {                                         // nothing valid in this block
+    if (mine_on) {
+      if constexpr (FINAL) {
+        for (int d = 0; d < D; ++d) X[(sf * Tmax + t) * D + d] = make_float2(0.f, 0.f);
+      } else {
+        lam[sf * Tmax + t] = 0.0;
+      }
+    }
+    return;
+  }
+  const int past = delay + taps - 1;
+  const int rows = fb + past;
+  const float2* __restrict__ Yrow = Y + sf * (long)Tmax * D;
+  for (int e = threadIdx.x; e < rows * D; e += kWpeThreads) {
+    const int r = e / D, d = e - r * D;
+    const int tt = t0 - past + r;
+    float2 v = make_float2(0.f, 0.f);
+    if (tt >= 0 && tt < T) v = Yrow[(long)tt * D + d];
+    sWin[r * pitch + d] = v;
+  }
+  __syncthreads();
+  if ((int)threadIdx.x >= fb) return;
+  constexpr int DM = 32;
+  double xr[DM], xi[DM];
+  const float2* __restrict__ mine = sWin + (threadIdx.x + past) * pitch;
+#pragma unroll
+  for (int d = 0; d < DM; ++d) {
+    xr[d] = 0.0;
+    xi[d] = 0.0;
+    if (d < D) {
+      xr[d] = (double)mine[d].x;
+      xi[d] = (double)mine[d].y;
+    }
+  }
+  typedef const __attribute__((address_space(4))) double* cptr_t;
+  const cptr_t g4 = (cptr_t)(uintptr_t)(Gc + sf * (long)N * D);
+  for (int tau = 0; tau < taps; ++tau) {
+    const float2* __restrict__ src = mine - (delay + tau) * pitch;
+    for (int dp = 0; dp < D; ++dp) {
+      const float2 v = src[dp];
+      const double vr = (double)v.x, vi = (double)v.y;
+      const cptr_t c = g4 + ((long)(tau * D + dp) * D) * 2;
+      static_for<0, DM / 8>([&](auto GI) {
+        constexpr int g = GI.value;
+        if (8 * g < D) {
+#pragma unroll
+          for (int d = 0; d < 8; ++d) {                  // x_d -= c[d] * v
+            const double cr = c[2 * (8 * g + d)], ci = c[2 * (8 * g + d) + 1];
+            xr[8 * g + d] = fma(-cr, vr, fma(ci, vi, xr[8 * g + d]));
+            xi[8 * g + d] = fma(-cr, vi, fma(-ci, vr, xi[8 * g + d]));
+          }
+        }
+      });
+    }
+  }
+  if (t >= Tmax) return;
+  if constexpr (FINAL) {
+    float2* __restrict__ o = X + (sf * Tmax + t) * D;
+#pragma unroll
+    for (int d = 0; d < DM; ++d)
+      if (d < D) o[d] = t < T ? make_float2((float)xr[d], (float)xi[d]) : make_float2(0.f, 0.f);
+  } else {
+    double p = 0.0;
+#pragma unroll
+    for (int d = 0; d < DM; ++d)
+      if (d < D) p += xr[d] * xr[d] + xi[d] * xi[d];
+    lam[sf * Tmax + t] = t < T ? p / (double)D : 0.0;
+  }
+}
+
+int run_wpe_large(gss_ctx* ctx, const float2* Y, const int32_t* T_len, int S, int F, int Tmax, int D, int taps, int delay,
+                  int iters, float2* X, hipStream_t st) {
+  const long n_sf = (long)S * F;
+  const int N = D * taps;
+  const int W = N + D;
+  const int tiles = (Tmax + kWpeTile - 1) / kWpeTile;
+  const int nb = (N + 3) / 4, nbd = (D + 3) / 4;
+  const int G = (nb * (nb + 1) / 2 + nb * nbd + kWpeThreads - 1) / kWpeThreads;
+  const int win_elems = (kWpeTile + delay + taps) * D + 8;
+  const int cov_lds = (int)(win_elems * sizeof(double2) + (kWpeTile + kWpeThreads / kWave) * sizeof(double));
+  const int fb_apply = D > 24 ? 128 : 256, fb_power = 64;
+  const int apitch = D | 1;
+  const int apply_lds = (int)((size_t)(fb_apply + delay + taps - 1) * apitch * sizeof(float2));
+  const int solve_lds = (int)(((size_t)(N + D) * kLsPitch + (size_t)kLsNB * D) * sizeof(double2));
+  if (apply_lds > 64 * 1024 || cov_lds > 64 * 1024 || solve_lds > 64 * 1024) return GSS_EUNSUPPORTED;
+  if (hipFuncSetAttribute((const void*)wpe_solve_large_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, solve_lds) !=
+          hipSuccess ||
+      hipFuncSetAttribute((const void*)wpe_apply_large_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                          apply_lds) != hipSuccess ||
+      hipFuncSetAttribute((const void*)wpe_apply_large_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                          apply_lds) != hipSuccess ||
+      hipFuncSetAttribute((const void*)wpe_cov_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, cov_lds) != hipSuccess)
+    return GSS_EHIP;
+  int per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, wpe_cov_kernel, kWpeThreads, (size_t)cov_lds) != hipSuccess ||
+      per_cu < 1)
+    per_cu = 1;
+  // G workgroups per chunk: the chunks are planned for a G-th of the resident workgroups
+  long slots = (long)ctx->num_cu * per_cu / G;
+  if (slots < 1) slots = 1;
+  const ChunkMap cmap = plan_chunk_map(slots, n_sf, tiles, 1, 0, true);
+  const long wgs = chunk_map_wgs(cmap, n_sf);
+  const long bps_apply = (Tmax + fb_apply - 1) / fb_apply, bps_power = (Tmax + fb_power - 1) / fb_power;
+  if (wgs * G > 0x7fffffffL || n_sf * bps_power + 8 > 0x7fffffffL || n_sf * 4 * G > 0x7fffffffL) return GSS_EUNSUPPORTED;
+
+  size_t o = 0;
+  const size_t off_lam = o;  o = gss_align_up(o + (size_t)n_sf * Tmax * sizeof(double), 256);
+  const size_t off_g = o;    o = gss_align_up(o + (size_t)n_sf * N * D * sizeof(double2) + 1024, 256);   // + read-ahead padding
+  const size_t off_part = o; o = gss_align_up(o + (size_t)wgs * G * kWpeBlockDoubles * kWpeThreads * sizeof(double), 256);
+  const size_t off_a = o;    o = gss_align_up(o + (size_t)n_sf * N * W * sizeof(double2), 256);
+  const int rc = gss_ensure_scratch(ctx, o);
+  if (rc != GSS_OK) return rc;
+  char* base = (char*)ctx->scratch;
+  double* lam = (double*)(base + off_lam);
+  double2* Gc = (double2*)(base + off_g);
+  double* part = (double*)(base + off_part);
+  double2* A = (double2*)(base + off_a);
+
+  const dim3 block(kWpeThreads);
+  const long nb_power = n_sf * bps_power, px_power = (nb_power + 7) / 8;
+  const long nb_apply = n_sf * bps_apply, px_apply = (nb_apply + 7) / 8;
+  hipLaunchKernelGGL(wpe_power_kernel, dim3((unsigned)(8 * px_power)), block, 0, st, Y, T_len, lam, F, Tmax, D,
+                     (int)bps_power, nb_power, px_power, fb_power);
+  for (int it = 0; it < iters; ++it) {
+    gss_profile_begin(ctx, 2, st);
+    hipLaunchKernelGGL(wpe_cov_kernel, dim3((unsigned)(wgs * G)), block, cov_lds, st, Y, T_len, lam, part, F, Tmax, D, taps,
+                       delay, cmap, win_elems, G);
+    gss_profile_end(ctx, 2, st);
+    hipLaunchKernelGGL(wpe_assemble_kernel, dim3((unsigned)(n_sf * 4 * G)), block, 0, st, part, A, D, taps, cmap, G);
+    hipLaunchKernelGGL(wpe_solve_large_kernel, dim3((unsigned)n_sf), dim3(kLsThreads), solve_lds, st, A, Gc, ctx->status, D,
+                       taps);
+    if (it + 1 < iters)
+      hipLaunchKernelGGL((wpe_apply_large_kernel<false>), dim3((unsigned)(8 * px_apply)), block, apply_lds, st, Y, T_len, Gc,
+                         lam, X, F, Tmax, D, taps, delay, (int)bps_apply, apitch, fb_apply, nb_apply, px_apply);
+    else
+      hipLaunchKernelGGL((wpe_apply_large_kernel<true>), dim3((unsigned)(8 * px_apply)), block, apply_lds, st, Y, T_len, Gc,
+                         lam, X, F, Tmax, D, taps, delay, (int)bps_apply, apitch, fb_apply, nb_apply, px_apply);
+  }
+  if (hipGetLastError() != hipSuccess) return GSS_EHIP;
+  return GSS_OK;
+}
+
 template <int D>
 int run_wpe(gss_ctx* ctx, const float2* Y, const int32_t* T_len, int S, int F, int Tmax, int taps, int delay, int iters,
             float2* X, hipStream_t st) {
@@ -552,13 +925,13 @@ int run_wpe(gss_ctx* ctx, const float2* Y, const int32_t* T_len, int S, int F, i
   const long n_blocks = n_sf * blocks_per_sf, per_xcd = (n_blocks + 7) / 8;
   const dim3 frame_grid((unsigned)(8 * per_xcd));
   hipLaunchKernelGGL(wpe_power_kernel, frame_grid, block, 0, st, Y, T_len, lam, F, Tmax, D, (int)blocks_per_sf, n_blocks,
-                     per_xcd);
+                     per_xcd, kWpeThreads);
   for (int it = 0; it < iters; ++it) {
     gss_profile_begin(ctx, 2, st);
     hipLaunchKernelGGL(wpe_cov_kernel, dim3((unsigned)wgs), block, cov_lds, st, Y, T_len, lam, part, F, Tmax, D, taps, delay,
-                       cmap, win_elems);
+                       cmap, win_elems, 1);
     gss_profile_end(ctx, 2, st);
-    hipLaunchKernelGGL(wpe_assemble_kernel, dim3((unsigned)(n_sf * 4)), block, 0, st, part, A, D, taps, cmap);
+    hipLaunchKernelGGL(wpe_assemble_kernel, dim3((unsigned)(n_sf * 4)), block, 0, st, part, A, D, taps, cmap, 1);
     hipLaunchKernelGGL(wpe_solve_kernel, dim3((unsigned)n_sf), dim3(kSolveThreads), 0, st, A, Gc, ctx->status, D, taps);
     if (it + 1 < iters)
       hipLaunchKernelGGL((wpe_apply_kernel<D, false>), frame_grid, block, apply_lds, st, Y, T_len, Gc, lam, X, F, Tmax, taps,
@@ -577,10 +950,11 @@ extern "C" int gss_wpe(gss_ctx* ctx, const float* Y, const int32_t* T_len, int S
                        int taps, int delay, int iters, float* X, void* stream) {
   if (!ctx || !Y || !X || Y == X) return GSS_EINVAL;
   if (S <= 0 || F <= 0 || Tmax <= 0 || D <= 0 || taps <= 0 || delay <= 0 || iters < 0) return GSS_EINVAL;
-  if (D > GSS_WPE_MAX_D || (long)D * taps > GSS_WPE_MAX_N || (long)D * taps > kWpeThreads || delay > 64) return GSS_EUNSUPPORTED;
-  {
+  if (D > GSS_WPE_LARGE_MAX_D || (long)D * taps > GSS_WPE_LARGE_MAX_N || delay > 64) return GSS_EUNSUPPORTED;
+  bool small = D <= GSS_WPE_MAX_D && (long)D * taps <= GSS_WPE_MAX_N;
+  if (small) {
     const int N = D * taps, nb = (N + 3) / 4, nbd = (D + 3) / 4;
-    if (nb * (nb + 1) / 2 + nb * nbd > kWpeThreads) return GSS_EUNSUPPORTED;   // one block per lane
+    if (nb * (nb + 1) / 2 + nb * nbd > kWpeThreads) small = false;               // more than one block per lane
   }
   if (hipSetDevice(ctx->device) != hipSuccess) return GSS_EHIP;
   hipStream_t st = (hipStream_t)stream;
@@ -593,6 +967,7 @@ extern "C" int gss_wpe(gss_ctx* ctx, const float* Y, const int32_t* T_len, int S
     hipLaunchKernelGGL(wpe_copy_kernel, dim3((unsigned)blocks), dim3(kWpeThreads), 0, st, Yc, T_len, Xc, F, Tmax, D, n);
     return hipGetLastError() == hipSuccess ? GSS_OK : GSS_EHIP;
   }
+  if (!small) return run_wpe_large(ctx, Yc, T_len, S, F, Tmax, D, taps, delay, iters, Xc, st);
   switch (D) {
 #define GSS_CASE_D(DD) \
   case DD: return run_wpe<DD>(ctx, Yc, T_len, S, F, Tmax, taps, delay, iters, Xc, st);

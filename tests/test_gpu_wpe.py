@@ -101,16 +101,46 @@ def test_wpe_degenerate(env):
 def test_wpe_rejects_unsupported_shapes(env):
     t = env["torch"]
     gss = env["gss"]
-    Y = t.zeros((1, 2, 50, 9), dtype=t.complex64).cuda()
+    Y = t.zeros((1, 2, 50, 33), dtype=t.complex64).cuda()
     with pytest.raises(Exception):
-        gss.gss_wpe(env["ctx"], Y, None, 2, 2, 1)        # more than 8 channels
+        gss.gss_wpe(env["ctx"], Y, None, 2, 2, 1)        # more than 32 channels
+    Y = t.zeros((1, 2, 50, 32), dtype=t.complex64).cuda()
+    with pytest.raises(Exception):
+        gss.gss_wpe(env["ctx"], Y, None, 11, 2, 1)       # 32 x 11 > 320
     Y = t.zeros((1, 2, 50, 8), dtype=t.complex64).cuda()
-    with pytest.raises(Exception):
-        gss.gss_wpe(env["ctx"], Y, None, 11, 2, 1)       # 8 x 11 > 80
     with pytest.raises(Exception):
         gss.gss_wpe(env["ctx"], Y, None, 10, 0, 1)       # delay must be positive
     with pytest.raises(Exception):
         gss.gss_wpe(env["ctx"], Y, None, 10, 2, 1, out=Y)   # in place is not allowed
+
+
+@pytest.mark.parametrize("D,taps,delay,T", [(9, 3, 2, 200), (12, 5, 2, 300), (16, 10, 2, 500), (24, 10, 2, 700),
+                                             (32, 10, 1, 800), (8, 12, 2, 400), (10, 1, 1, 130), (13, 7, 3, 450)])
+def test_wpe_large_arrays(env, D, taps, delay, T):
+    """More than 8 channels, or more than 80 unknowns per channel: several groups of covariance blocks, the
+    blocked factorisation in global memory, the run-time-D apply kernel."""
+    Y, _, _ = env["synth"].reverberant_stft(F=3, T=T, D=D, order=min(taps, 6), delay=delay, seed=D * 100 + taps)
+    _check(env, Y[None], None, taps, delay, 3)
+    assert env["ctx"].get_status() == 0
+
+
+def test_wpe_large_ragged_and_degenerate(env):
+    S, F, T, D = 2, 3, 420, 12
+    Y = np.stack([env["synth"].reverberant_stft(F=F, T=T, D=D, seed=40 + s)[0] for s in range(S)])
+    Y[1, 1] = 0.0                                        # a silent bin
+    T_len = np.array([420, 131], dtype=np.int32)
+    rng = np.random.default_rng(5)
+    Y[1, :, 131:] = (rng.standard_normal((F, T - 131, D)) * 1e3).astype(np.complex64)   # garbage in the padding
+    _check(env, Y, T_len, 6, 2, 2)
+    _check(env, Y[:, :, :2], None, 6, 2, 3)              # no frame has a past: unchanged
+    _check(env, Y, np.array([0, 5], dtype=np.int32), 6, 2, 3)
+
+
+def test_wpe_config3_shape_sampled_bins(env):
+    """24 channels at configuration 3's size (513 x 1500 x 24, 10 taps, delay 2, 3 iterations): all bins on the
+    GPU, a sample of them on the oracle."""
+    Y, _, _ = env["synth"].reverberant_stft(F=513, T=1500, D=24, seed=3)
+    _check(env, Y[None], None, 10, 2, 3, fsel=[0, 257, 512])
 
 
 def test_wpe_full_size_sampled_bins(env):
