@@ -658,19 +658,39 @@ __global__ __launch_bounds__(kLsThreads) void wpe_solve_large_kernel(double2* __
     const int ncols = N - c_lo;
     if (ncols > 0) {
       const int nrows = R - c_lo;
-      for (int e = tid; e < nrows * ncols; e += kLsThreads) {
-        const int r = c_lo + e / ncols, c = c_lo + e % ncols;
-        if (c > r) continue;
-        double2 acc = make_double2(0.0, 0.0);
+      // four entries per thread and step: their loads are issued together (the entries of different threads and
+      // steps are distinct, which the compiler cannot know)
+      constexpr int U = 4;
+      for (int e0 = tid; e0 < nrows * ncols; e0 += U * kLsThreads) {
+        int rr[U], cc[U];
+        bool on[U];
+        double2 v[U];
 #pragma unroll
-        for (int m = 0; m < kLsNB; ++m)
-          if (m < bs) {
-            const double2 t = cmul_conj(sPanel[r * kLsPitch + m], sPanel[c * kLsPitch + m]);
-            acc.x += t.x;
-            acc.y += t.y;
-          }
-        double2 v = ldv(r, c);
-        stv(r, c, make_double2(v.x - acc.x, v.y - acc.y));
+        for (int u = 0; u < U; ++u) {
+          const int e = e0 + u * kLsThreads;
+          rr[u] = c_lo + e / ncols;
+          cc[u] = c_lo + e % ncols;
+          on[u] = e < nrows * ncols && cc[u] <= rr[u];
+          v[u] = make_double2(0.0, 0.0);
+          if (on[u]) v[u] = ldv(rr[u], cc[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          if (!on[u]) continue;
+          double2 acc = make_double2(0.0, 0.0);
+#pragma unroll
+          for (int m = 0; m < kLsNB; ++m)
+            if (m < bs) {
+              const double2 t = cmul_conj(sPanel[rr[u] * kLsPitch + m], sPanel[cc[u] * kLsPitch + m]);
+              acc.x += t.x;
+              acc.y += t.y;
+            }
+          v[u].x -= acc.x;
+          v[u].y -= acc.y;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (on[u]) stv(rr[u], cc[u], v[u]);
       }
     }
     __syncthreads();

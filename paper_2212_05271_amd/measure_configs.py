@@ -169,17 +169,18 @@ def sweeps(torch, gss, ctx, synth):
               flush=True)
 
 
-def wpe_rows(torch, gss, ctx, synth):
-    """gss_wpe on a reverberant stand-in of config 1's shape (513 x 1560 x 8), 10 taps, delay 2: time per
-    call, audio seconds per second, and the algorithmic fp64 rate of the covariance kernel
-    (8 flops per complex multiply-add, N(N+1)/2 + N D entries per frame, N = D taps)."""
-    Y, _, _ = synth.reverberant_stft(F=513, T=1560, D=8, seed=0)
+def wpe_rows(torch, gss, ctx, synth, large=False):
+    """gss_wpe on a reverberant stand-in of config 1's shape (513 x 1560 x 8; large: config 3's, 513 x 1500 x
+    24), 10 taps, delay 2: time per call, audio seconds per second, and the algorithmic fp64 rate of the
+    covariance kernel (8 flops per complex multiply-add, N(N+1)/2 + N D entries per frame, N = D taps)."""
+    Y, _, _ = synth.reverberant_stft(F=513, T=1500, D=24, seed=3) if large else synth.reverberant_stft(F=513, T=1560, D=8, seed=0)
     F, T, D = Y.shape
     taps, delay = 10, 2
     N = D * taps
     Yd = torch.from_numpy(Y[None]).cuda()
     X = gss.gss_wpe(ctx, Yd, None, taps, delay, 3)
     audio = T * HOP / FS
+    print(f"{D} channels, {T} frames:")
     print("| WPE iterations | ms | audio-s/s | covariance kernel: launches, mean us, TFLOP/s (alg.), of 78.6 |")
     print("|---:|---:|---:|---|")
     for it in (1, 2, 3):
@@ -200,6 +201,7 @@ def main():
     ap.add_argument("--sweeps", action="store_true",
                     help="only the parameter sweeps on config 1 (iterations, channels, noise class, weight mode)")
     ap.add_argument("--wpe", action="store_true", help="only the dereverberation timing (config 1's shape)")
+    ap.add_argument("--wpe-large", action="store_true", help="only the dereverberation timing at config 3's shape (24 channels)")
     ap.add_argument("--config", choices=("c0", "c1", "c2", "c3"), default=None,
                     help="only this configuration (for a kernel trace of its own)")
     a = ap.parse_args()
@@ -213,8 +215,8 @@ def main():
         sweeps(torch, gss, ctx, synth)
         ctx.close()
         return
-    if a.wpe:
-        wpe_rows(torch, gss, ctx, synth)
+    if a.wpe or a.wpe_large:
+        wpe_rows(torch, gss, ctx, synth, large=a.wpe_large)
         ctx.close()
         return
     print("| config | S | Tmax | D | K | iters | EM ms | MVDR ms | audio-s/s (EM+MVDR) | EM iters/s | bin-iters/s | "
