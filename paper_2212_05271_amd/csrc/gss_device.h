@@ -33,6 +33,31 @@ __device__ __forceinline__ double rcp_f64_fast(double x) {
   return fma(fma(-x, r, 1.0), r, r);
 }
 
+// Sum of a double over the 64 lanes of the wavefront, the same value in every lane, in a fixed order.  Within
+// a row of 16 lanes four butterfly steps through the lane-permute modifier of the vector move (on the two
+// halves of the double): neighbours, pairs, the mirrored half of 8, the mirrored row; then the four row sums
+// are read into scalar registers and added.  No LDS traffic (a shuffle goes through the LDS crossbar and costs
+// a round trip per step).
+__device__ __forceinline__ double wave_sum_f64(double v) {
+  auto step = [](double x, auto CTRL) {
+    constexpr int ctrl = decltype(CTRL)::value;
+    const int lo = __double2loint(x), hi = __double2hiint(x);
+    const int plo = __builtin_amdgcn_update_dpp(0, lo, ctrl, 0xf, 0xf, false);
+    const int phi = __builtin_amdgcn_update_dpp(0, hi, ctrl, 0xf, 0xf, false);
+    return x + __hiloint2double(phi, plo);
+  };
+  v = step(v, std::integral_constant<int, 0xB1>{});     // quad_perm [1, 0, 3, 2]
+  v = step(v, std::integral_constant<int, 0x4E>{});     // quad_perm [2, 3, 0, 1]
+  v = step(v, std::integral_constant<int, 0x141>{});    // row_half_mirror
+  v = step(v, std::integral_constant<int, 0x140>{});    // row_mirror
+  const int lo = __double2loint(v), hi = __double2hiint(v);
+  double r[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    r[q] = __hiloint2double(__builtin_amdgcn_readlane(hi, 16 * q), __builtin_amdgcn_readlane(lo, 16 * q));
+  return (r[0] + r[1]) + (r[2] + r[3]);
+}
+
 template <int N>
 __device__ __forceinline__ double ipow(double x) {
   if constexpr (N == 1) {
@@ -311,9 +336,7 @@ __device__ __forceinline__ void reduce_and_store_partials(double (&acc)[8][KW], 
   if constexpr (WITH_N) {                    // per-lane scalars (one per class): summed over the wavefront
 #pragma unroll
     for (int k = 0; k < KW; ++k) {
-      double nv = nvals[k];
-#pragma unroll
-      for (int off = 1; off < kWave; off <<= 1) nv += __shfl_xor(nv, off, kWave);
+      double nv = wave_sum_f64(nvals[k]);
       nvals[k] = nv;
     }
   }

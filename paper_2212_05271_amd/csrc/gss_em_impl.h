@@ -90,17 +90,25 @@ __host__ __device__ constexpr int weight_stride(int K) { return K | 1; }
 __host__ __device__ constexpr int coef_regs(int D) { return (D * D + 15) / 16; }
 constexpr int kResidentRegs = 20;
 
+// The lane's frame of a tile in fp64 and its activity bits, kept in registers by the kernel for tiny problems.
+template <int D>
+struct TileRegs {
+  double yr[D], yi[D];
+  unsigned abits;
+};
+
 // One tile of 64 frames starting at frame t0.  `tmask` (wave-uniform) is the tile's activity mask.
 //   creg : the resident coefficient registers [K * coef_regs(D)] (used when RESIDENT)
 //   sC   : LDS copy of the coefficients, [K * coef_regs(D)][16] doubles (used otherwise)
 //   cc   : class constants pi_k / det B_k (wave-uniform)
-template <int D, int K, bool FINAL, bool RESIDENT>
+//   pre  : PRE: the lane's frame, loaded by the caller (nothing is read from Yrow / abrow)
+template <int D, int K, bool FINAL, bool RESIDENT, bool PRE = false>
 __device__ __forceinline__ void pass_tile(
     const float2* __restrict__ Yrow, const uint8_t* __restrict__ abrow, const double (&creg)[RESIDENT ? K * coef_regs(D) : 1],
     const double* __restrict__ sC, const double (&cc)[K], float* __restrict__ gamma_row /* + k*F*Tmax */,
     uint32_t* __restrict__ status, long gamma_kstride, int T, int Tmax, int t0, int lane, unsigned tmask,
-    double* __restrict__ sY, double* __restrict__ sW, double (&acc)[8][K], double (&nacc)[K]
-    ) {
+    double* __restrict__ sY, double* __restrict__ sW, double (&acc)[8][K], double (&nacc)[K],
+    const TileRegs<D>* pre = nullptr) {
   constexpr int E = D * D;
   constexpr int R = coef_regs(D);
   constexpr int WS = weight_stride(K);
@@ -123,14 +131,24 @@ __device__ __forceinline__ void pass_tile(
   // padding in the final pass); its activity bits are zero, so its posterior and weights are zero.
   const bool valid = t < T;
   double yr[D], yi[D];
+  unsigned abits;
+  if constexpr (PRE) {
 #pragma unroll
-  for (int d = 0; d < D; ++d) {
-    const float2 v = Yrow[(long)(valid ? t : 0) * D + d];
-    yr[d] = (double)v.x;
-    yi[d] = (double)v.y;
+    for (int d = 0; d < D; ++d) {
+      yr[d] = pre->yr[d];
+      yi[d] = pre->yi[d];
+    }
+    abits = pre->abits;
+  } else {
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+      const float2 v = Yrow[(long)(valid ? t : 0) * D + d];
+      yr[d] = (double)v.x;
+      yi[d] = (double)v.y;
+    }
+    abits = abrow[valid ? t : 0];
+    abits = valid ? abits : 0u;
   }
-  unsigned abits = abrow[valid ? t : 0];
-  abits = valid ? abits : 0u;
 
   // ---- q_k = <coef_k, y y^H>, 16 entries of the outer product at a time; three partial sums per class (an FMA
   // does not wait for the one before it) ----
@@ -443,12 +461,17 @@ __global__ __launch_bounds__(kWave * K) void em_factor_small(
 }
 
 // ----------------------------------------------------------------------------------------------
-// Whole-EM kernel for batches with many problems (segments x frequencies >> resident wavefronts): ONE
-// wavefront owns one (segment, frequency) for all iterations.  Per iteration it walks the problem's tiles
-// (pass_tile above), sums its accumulators over the 8 frame groups through LDS, and factorises the K class
-// matrices itself, so that the coefficients of the next iteration go from LDS straight back into its
-// registers: no partial sums in memory, no second kernel, no launch per iteration, nothing shared between
-// wavefronts (a workgroup is one wavefront), and the same fixed summation order on every run.
+// Whole-EM kernel: a workgroup of NW wavefronts owns one (segment, frequency) for all iterations.  Per
+// iteration every wavefront walks its tiles (pass_tile above), sums its accumulators over the 8 frame groups
+// through LDS, and factorises the K class matrices itself, so that the coefficients of the next iteration go
+// from LDS straight back into its registers: no partial sums in memory, no second kernel, no launch per
+// iteration, and the same fixed summation order on every run.
+//   NW = 1: for batches with many problems (segments x frequencies >> resident wavefronts); the wavefront
+//           walks all tiles of its problem; nothing is shared between wavefronts.
+//   NW = 4: for tiny problems (at most NW tiles, i.e. 256 frames; few of them, few channels): wavefront w owns
+//           tile w and keeps its frames in registers for all iterations, so an iteration reads nothing from
+//           memory.  The wavefronts' sums meet in LDS (two buffers, used in turn, one barrier per iteration),
+//           and every wavefront adds them up in the same order and runs the same factorisation on its own copy.
 //
 // Factorisation in the wavefront: lane (k, i) = (lane / 8, lane % 8) holds row i of the matrix of class k
 // (8 complex numbers) in registers.  B_k = D R_k / N_k is Hermitised by construction (packed sums), scaled
@@ -456,8 +479,8 @@ __global__ __launch_bounds__(kWave * K) void em_factor_small(
 // without pivoting (the pivots of a Hermitian positive-definite matrix are positive; their product is
 // det B): the owner of pivot row p publishes it in LDS, the 8 lanes of the class read it back.
 // ----------------------------------------------------------------------------------------------
-template <int D, int K>
-__global__ __launch_bounds__(kWave, 2) void em_whole_small(
+template <int D, int K, int NW>
+__global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
     gss_yview yv, const uint8_t* __restrict__ abyte, const uint32_t* __restrict__ tmask,
     const int32_t* __restrict__ T_len, float* __restrict__ gamma, uint32_t* __restrict__ status,
     int F, int Tmax, int iters, int weight_mode) {
@@ -468,28 +491,57 @@ __global__ __launch_bounds__(kWave, 2) void em_whole_small(
   constexpr int kTileDoubles = kWave * kYStride + kWave * WS;
   constexpr int kCoefDoubles = K * R * 16;             // packed coefficients, padded to whole registers
   constexpr int kRowDoubles = K * 16;                  // one published pivot row (8 complex) per class
-  __shared__ __attribute__((aligned(16))) double lds[kTileDoubles + kCoefDoubles + K * E + kRowDoubles + 2 * K + 8];
-  double* __restrict__ sY = lds;
+  constexpr int kSumDoubles = K * E + K;               // packed weighted scatter sums, then the class counts
+  constexpr int kWaveDoubles = (kTileDoubles + kCoefDoubles + kSumDoubles + kRowDoubles + K + 1) / 2 * 2;
+  constexpr int kShareDoubles = NW > 1 ? 2 * NW * kSumDoubles : 0;
+  __shared__ __attribute__((aligned(16))) double lds[NW * kWaveDoubles + kShareDoubles];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = NW > 1 ? __builtin_amdgcn_readfirstlane(threadIdx.x / kWave) : 0;
+  double* __restrict__ sY = lds + wave * kWaveDoubles;
   double* __restrict__ sW = sY + kWave * kYStride;
-  double* __restrict__ sC = lds + kTileDoubles;        // [K][R * 16] coefficients of B^-1 for the next pass
+  double* __restrict__ sC = sY + kTileDoubles;         // [K][R * 16] coefficients of B^-1 for the next pass
   double* __restrict__ sR = sC + kCoefDoubles;         // [K][E] packed weighted scatter sums
-  double* __restrict__ sP = sR + K * E;                // [K][16] published pivot rows
-  double* __restrict__ sN = sP + kRowDoubles;          // [K] class counts
-  double* __restrict__ sCC = sN + K;                   // [K] class constants pi / det B
+  double* __restrict__ sN = sR + K * E;                // [K] class counts
+  double* __restrict__ sP = sN + K;                    // [K][16] published pivot rows
+  double* __restrict__ sCC = sP + kRowDoubles;         // [K] class constants pi / det B
+  double* __restrict__ sShare = lds + NW * kWaveDoubles;   // [2][NW][kSumDoubles] sums of the wavefronts (NW > 1)
+  __shared__ int sSlotAll[NW * kWave];
+  int* __restrict__ sSlot = sSlotAll + wave * kWave;       // [64] packed index and sign of the lane's reduction slot
 
-  const int lane = threadIdx.x;
   const long sf = blockIdx.x;
   const int s = (int)((unsigned)sf / (unsigned)F);
   const int f = (int)((unsigned)sf % (unsigned)F);
   int T;
   const float2* __restrict__ Yrow = y_row(yv, T_len, s, f, D, Tmax, T);
   const uint8_t* __restrict__ abrow = abyte + (long)s * Tmax;
-  const int tiles_total = (Tmax + kWave - 1) / kWave;
+  const int tiles_total = (Tmax + kWave - 1) / kWave;   // NW > 1: at most NW (checked by the host)
   typedef const __attribute__((address_space(4))) uint32_t* mask_ptr_t;
   const mask_ptr_t tmrow = (mask_ptr_t)(uintptr_t)(tmask + (long)s * tiles_total);
   float* __restrict__ gamma_row = gamma + ((long)s * K * F + f) * Tmax;
   const long gamma_kstride = (long)F * Tmax;
   const int tiles = (T + kWave - 1) / kWave;
+
+  // NW > 1: this wavefront's one tile: its mask, and the lane's frame in registers
+  TileRegs<D> pre;
+  unsigned my_mask = 0u;
+  if constexpr (NW > 1) {
+#pragma unroll
+    for (int d = 0; d < D; ++d) { pre.yr[d] = 0.0; pre.yi[d] = 0.0; }
+    pre.abits = 0u;
+    if (wave < tiles_total) my_mask = tmrow[wave] & ((1u << K) - 1u);
+    if (my_mask != 0u) {                                // some frame of the tile lies below T: frame 0 exists
+      const int t = wave * kWave + lane;
+      const bool valid = t < T;
+#pragma unroll
+      for (int d = 0; d < D; ++d) {
+        const float2 v = Yrow[(long)(valid ? t : 0) * D + d];
+        pre.yr[d] = (double)v.x;
+        pre.yi[d] = (double)v.y;
+      }
+      const unsigned a = abrow[valid ? t : 0];
+      pre.abits = valid ? a : 0u;
+    }
+  }
 
   // pass 0: B = I, uniform weights
   double creg[RESIDENT ? K * R : 1];
@@ -513,7 +565,18 @@ __global__ __launch_bounds__(kWave, 2) void em_whole_small(
     wave_lds_sync();
   }
 
-  const int fk = lane >> 3, fi = lane & 7;              // factorisation: class and row of this lane
+  // Where the lane's share of the frame-group sums goes: looked up once (the table sits in memory) and parked in
+  // LDS.  Everything the end of an iteration derives from the lane number is derived there anew, from a copy of
+  // the lane number that the compiler cannot see through: values computed ahead of the iteration loop would be
+  // live across the tile loop, where there is no register for them, and come back from scratch memory one
+  // dependent load at a time.
+  {
+    static constexpr SlotTable kSlots = make_slot_table();
+    const int slot = (lane & 7) * 8 + (lane >> 3);     // lane o = 8 n + eg reads back slot (eg, n)
+    const int pi0 = kSlots.v[D][slot];
+    sSlot[lane] = (pi0 < 0 ? 0x4000 : pi0) | (kSlots.sign[slot] < 0 ? 0x8000 : 0);
+  }
+  wave_lds_sync();
   for (int it = 0; it < iters; ++it) {
     double acc[8][K];
     double nacc[K];
@@ -523,30 +586,37 @@ __global__ __launch_bounds__(kWave, 2) void em_whole_small(
 #pragma unroll
       for (int n = 0; n < 8; ++n) acc[n][k] = 0.0;
     }
-    for (int tile = 0; tile < tiles; ++tile)
-      pass_tile<D, K, false, RESIDENT>(Yrow, abrow, creg, sC, cc, nullptr, status, gamma_kstride, T, Tmax, tile * kWave,
-                                       lane, tmrow[tile], sY, sW, acc, nacc
-                                       );
+    if constexpr (NW > 1) {
+      if (wave < tiles)
+        pass_tile<D, K, false, RESIDENT, true>(Yrow, abrow, creg, sC, cc, nullptr, status, gamma_kstride, T, Tmax,
+                                               wave * kWave, lane, my_mask, sY, sW, acc, nacc, &pre);
+    } else {
+      for (int tile = 0; tile < tiles; ++tile)
+        pass_tile<D, K, false, RESIDENT>(Yrow, abrow, creg, sC, cc, nullptr, status, gamma_kstride, T, Tmax, tile * kWave,
+                                         lane, tmrow[tile], sY, sW, acc, nacc);
+    }
 
+    int le = lane;                                      // the lane number again, opaque
+    asm volatile("" : "+v"(le));
+    const int fk = le >> 3, fi = le & 7;                // factorisation: class and row of this lane
+    const int code = sSlot[le];
+    const int pidx = (code & 0x4000) ? -1 : (code & 0x3fff);
+    const double sgn = (code & 0x8000) ? -1.0 : 1.0;
     // ---- sums over the 8 frame groups -> packed sR[k][e]; class counts over the lanes -> sN[k] ----
+    // (NW > 1: into this wavefront's slot of the shared buffer of this iteration)
+    double* __restrict__ sOut = NW > 1 ? sShare + ((it & 1) * NW + wave) * kSumDoubles : sR;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      double nv = nacc[k];
-#pragma unroll
-      for (int off = 1; off < kWave; off <<= 1) nv += __shfl_xor(nv, off, kWave);
-      if (lane == 0) sN[k] = nv;
+      double nv = wave_sum_f64(nacc[k]);
+      if (le == 0) sOut[K * E + k] = nv;
     }
-    static constexpr SlotTable kSlots = make_slot_table();
-    const int slot = (lane & 7) * 8 + (lane >> 3);     // lane o = 8 n + eg reads back slot (eg, n)
-    const int pidx = kSlots.v[D][slot];
-    const double sgn = kSlots.sign[slot] < 0 ? -1.0 : 1.0;
 #pragma unroll
     for (int k0 = 0; k0 < K; k0 += 2) {
 #pragma unroll
       for (int c = 0; c < 2; ++c)
         if (k0 + c < K) {
 #pragma unroll
-          for (int n = 0; n < 8; ++n) sY[(c * 8 + n) * kReduceRow + lane] = acc[n][k0 + c];
+          for (int n = 0; n < 8; ++n) sY[(c * 8 + n) * kReduceRow + le] = acc[n][k0 + c];
         }
       wave_lds_sync();
 #pragma unroll
@@ -554,41 +624,63 @@ __global__ __launch_bounds__(kWave, 2) void em_whole_small(
         if (k0 + c < K) {
           double sum = 0.0;
 #pragma unroll
-          for (int tg = 0; tg < 8; ++tg) sum += sY[(c * 8 + (lane >> 3)) * kReduceRow + tg * 8 + (lane & 7)];
-          if (pidx >= 0) sR[(k0 + c) * E + pidx] = sgn * sum;
+          for (int tg = 0; tg < 8; ++tg) sum += sY[(c * 8 + (le >> 3)) * kReduceRow + tg * 8 + (le & 7)];
+          if (pidx >= 0) sOut[(k0 + c) * E + pidx] = sgn * sum;
         }
+      wave_lds_sync();
+    }
+    if constexpr (NW > 1) {
+      __syncthreads();                                  // every wavefront's sums of this iteration are in place
+      const double* __restrict__ all = sShare + (it & 1) * NW * kSumDoubles;
+      for (int e = le; e < kSumDoubles; e += kWave) {
+        double sum = all[e];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) sum += all[w * kSumDoubles + e];
+        sR[e] = sum;                                    // sN follows sR
+      }
       wave_lds_sync();
     }
 
     // ---- M-step: B_k from (R_k, N_k), regularised, inverted; coefficients and class constants ----
+    // (Written without branches: every lane reads from valid addresses and the unused values are deselected,
+    // so that the LDS reads go out together instead of one wait per row entry.)
     const bool on = fk < K && fi < D;
+    const int fkc = fk < K ? fk : K - 1, fic = fi < D ? fi : D - 1;
+    const double* __restrict__ sRk = sR + fkc * E;
     double ar[8], ai[8];                                  // row fi of class fk
     double tr = 0.0;
-    if (fk < K) {
 #pragma unroll
-      for (int d = 0; d < D; ++d) tr += sR[fk * E + gss_packed_row(d, D)];
-    }
-    const double Nk = fk < K ? sN[fk] : 1.0;
+    for (int d = 0; d < D; ++d) tr += sRk[gss_packed_row(d, D)];
+    const double Nk = sN[fkc];
     double Ntot = 0.0;
 #pragma unroll
     for (int k = 0; k < K; ++k) Ntot += sN[k];
     // B = D R / max(N, eps); dead if its trace <= eps; else rescaled to trace D (= R * D / tr R)
     const bool dead = !((double)D * tr / fmax(Nk, GSS_EPS_N) > GSS_EPS_N);
     const double sc = dead ? 0.0 : (double)D / tr;
+    {
+      double v0[8], v1[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      ar[j] = 0.0;
-      ai[j] = 0.0;
-      if (on && j < D) {
-        if (j == fi) {
-          ar[j] = (dead ? 1.0 : sR[fk * E + gss_packed_row(fi, D)] * sc) + GSS_DELTA;
-        } else if (!dead) {
-          const int lo = fi < j ? fi : j, hi = fi < j ? j : fi;
-          const int p = gss_packed_row(lo, D) + 1 + 2 * (hi - lo - 1);
-          ar[j] = sR[fk * E + p] * sc;
-          ai[j] = sR[fk * E + p + 1] * sc;
-          if (fi > j) ai[j] = -ai[j];                    // lower triangle = conjugate
-        }
+      for (int j = 0; j < 8; ++j) {
+        // packed position of entry (min, max) of the row's pair (fi, j): the diagonal entry for j = fi (its
+        // neighbour is read along and dropped), Re and Im of the off-diagonal entry otherwise
+        const int jc = j < D ? j : D - 1;
+        const int lo = fic < jc ? fic : jc, hi = fic < jc ? jc : fic;
+        int p = gss_packed_row(lo, D) + (hi > lo ? 1 + 2 * (hi - lo - 1) : 0);
+        p = p > E - 2 ? E - 2 : p;                          // the last diagonal entry has no neighbour (D = 1: none at all)
+        v0[j] = sRk[hi > lo ? p : gss_packed_row(lo, D)];
+        v1[j] = sRk[E > 1 ? p + 1 : 0];
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const bool diag = j == fi;
+        const bool use = on && j < D && (diag || !dead);
+        double re = v0[j] * sc;
+        double im = v1[j] * sc;
+        re = diag ? (dead ? 1.0 : re) + GSS_DELTA : re;
+        im = diag ? 0.0 : (fi > j ? -im : im);              // lower triangle = conjugate
+        ar[j] = use ? re : 0.0;
+        ai[j] = use ? im : 0.0;
       }
     }
     double det = 1.0;
@@ -663,7 +755,7 @@ __global__ __launch_bounds__(kWave, 2) void em_whole_small(
       if constexpr (RESIDENT) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-          const int e = 16 * r + (lane & 15);
+          const int e = 16 * r + (le & 15);
           creg[k * R + r] = sC[k * (R * 16) + (e < E ? e : E - 1)];
         }
       }
@@ -681,10 +773,15 @@ __global__ __launch_bounds__(kWave, 2) void em_whole_small(
 #pragma unroll
       for (int n = 0; n < 8; ++n) acc[n][k] = 0.0;
     }
-    for (int tile = 0; tile < tiles_total; ++tile)
-      pass_tile<D, K, true, RESIDENT>(Yrow, abrow, creg, sC, cc, gamma_row, status, gamma_kstride, T, Tmax, tile * kWave,
-                                      lane, tmrow[tile], sY, sW, acc, nacc
-                                      );
+    if constexpr (NW > 1) {
+      if (wave < tiles_total)
+        pass_tile<D, K, true, RESIDENT, true>(Yrow, abrow, creg, sC, cc, gamma_row, status, gamma_kstride, T, Tmax,
+                                              wave * kWave, lane, my_mask, sY, sW, acc, nacc, &pre);
+    } else {
+      for (int tile = 0; tile < tiles_total; ++tile)
+        pass_tile<D, K, true, RESIDENT>(Yrow, abrow, creg, sC, cc, gamma_row, status, gamma_kstride, T, Tmax, tile * kWave,
+                                        lane, tmrow[tile], sY, sW, acc, nacc);
+    }
   }
 }
 
@@ -695,6 +792,8 @@ __global__ __launch_bounds__(kWave, 2) void em_whole_small(
 // the last, partly filled round of wavefronts is a small part of the run).
 constexpr int kWholeMinRounds = 3;
 constexpr int kWholeMaxTilesAlways = 5;
+constexpr int kWholeQuad = 4;                 // wavefronts per problem of the variant for tiny problems
+constexpr int kWholeQuadMaxD = 4;             // ... which is built for up to this many channels
 
 struct EmPlan {
   ChunkMap acc;          // chunking of the accumulating passes
@@ -751,16 +850,29 @@ int run_small(gss_ctx* ctx, const gss_yview& Y, const uint8_t* act, const int32_
   // Many problems per resident wavefront: one wavefront runs the whole EM of a problem (no partial sums, no
   // factor launches).  Few problems: each one is cut into chunks over several workgroups, one pass and one
   // factor launch per iteration.
-  static const int waves_per_cu = resident_wgs(em_whole_small<D, K>, kWave, 8);
+  static const int waves_per_cu = resident_wgs(em_whole_small<D, K, 1>, kWave, 8);
   const long whole_min = ctx->em_whole_min_problems >= 0 ? (long)ctx->em_whole_min_problems
                                                          : (long)kWholeMinRounds * ctx->num_cu * waves_per_cu;
   // (Problems of a few tiles also go there whatever their number: two launches per iteration cost more than
   // the whole EM of such a problem in one wavefront.)
   const bool whole = n_sf >= whole_min || (ctx->em_whole_min_problems < 0 && tiles <= kWholeMaxTilesAlways);
   if (iters > 0 && whole && n_sf <= 0x7fffffffL) {
+    // Tiny problems (at most 4 tiles, at most 4 channels) that fit the GPU in one round of four-wavefront
+    // workgroups: one tile per wavefront, its frames resident in registers.
+    bool tiny = false;
+    if constexpr (D <= kWholeQuadMaxD) {
+      static const int quads_per_cu = resident_wgs(em_whole_small<D, K, kWholeQuad>, kWave * kWholeQuad, 2);
+      tiny = ctx->em_whole_min_problems < 0 && tiles <= kWholeQuad && n_sf <= (long)ctx->num_cu * quads_per_cu;
+    }
     gss_profile_begin(ctx, 0, st);
-    hipLaunchKernelGGL((em_whole_small<D, K>), dim3((unsigned)n_sf), dim3(kWave), 0, st, Y, abyte, tmask, T_len, gamma,
-                       ctx->status, F, Tmax, iters, weight_mode);
+    if constexpr (D <= kWholeQuadMaxD) {
+      if (tiny)
+        hipLaunchKernelGGL((em_whole_small<D, K, kWholeQuad>), dim3((unsigned)n_sf), dim3(kWave * kWholeQuad), 0, st, Y,
+                           abyte, tmask, T_len, gamma, ctx->status, F, Tmax, iters, weight_mode);
+    }
+    if (!tiny)
+      hipLaunchKernelGGL((em_whole_small<D, K, 1>), dim3((unsigned)n_sf), dim3(kWave), 0, st, Y, abyte, tmask, T_len, gamma,
+                         ctx->status, F, Tmax, iters, weight_mode);
     gss_profile_end(ctx, 0, st);
     if (hipGetLastError() != hipSuccess) return GSS_EHIP;
     return GSS_OK;

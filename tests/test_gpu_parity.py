@@ -177,6 +177,42 @@ def test_every_whole_em_instantiation(env, D):
         ctx.set_option(gss.GSS_OPT_EM_WHOLE_MIN_PROBLEMS, -1)
 
 
+@pytest.mark.parametrize("D", [1, 2, 3, 4])
+def test_every_tiny_problem_instantiation(env, D):
+    """Few problems of at most 4 tiles and at most 4 channels take the whole-EM kernel with four wavefronts per
+    problem (one tile each, frames resident in registers) by default: every (D, K), a ragged batch of two segments
+    (4 and 2 tiles of 4: two wavefronts of the second segment own padding only), weights from the masks and
+    uniform, a zero-energy frame, frames without any active class, a class that is never active; the same bits on
+    a second run; and agreement with the one-wavefront kernel (forced through the context option) far inside the
+    tolerance."""
+    gss, ctx = env["gss"], env["ctx"]
+    for K in range(1, 9):
+        rng = np.random.default_rng(70 * D + K)
+        S, F, T = 2, 3, 200
+        Y = (_cn(rng, (S, F, T, D)) * np.exp(rng.standard_normal((S, F, T, 1)))).astype(np.complex64)
+        Y[0, :, 40] = 0
+        act = (rng.random((S, K, T)) < 0.5).astype(np.uint8)
+        act[:, K - 1] = 1
+        act[1, :, 20:30] = 0
+        if K > 1:
+            act[0, 0] = 0
+        T_len = np.array([T, 70], dtype=np.int32)
+        for wm in (1, 0):
+            g = _gpu_em(env, Y, act, T_len, 4, wm)
+            go = env["o"].cacgmm_em_batch(Y, act, T_len, 4, wm)
+            assert np.max(np.abs(g - go)) <= TOL_GAMMA, (D, K, wm)
+            for s_ in range(S):
+                assert np.all(g[s_, :, :, T_len[s_]:] == 0)
+        assert np.array_equal(g, _gpu_em(env, Y, act, T_len, 4, 0))
+        ctx.set_option(gss.GSS_OPT_EM_WHOLE_MIN_PROBLEMS, 0)
+        try:
+            g1 = _gpu_em(env, Y, act, T_len, 4, 0)
+        finally:
+            ctx.set_option(gss.GSS_OPT_EM_WHOLE_MIN_PROBLEMS, -1)
+        assert np.max(np.abs(g - g1)) <= 1e-5, (D, K)
+    assert env["ctx"].get_status() == 16                                # the zero-energy frame, nothing else
+
+
 @pytest.mark.parametrize("D", [10, 20, 26, 32])
 def test_every_large_instantiation(env, D):
     """Every (class count, items-per-lane) instantiation of the large-array kernels: K = 1..8 at one channel
