@@ -58,6 +58,19 @@ __device__ __forceinline__ double wave_sum_f64(double v) {
   return (r[0] + r[1]) + (r[2] + r[3]);
 }
 
+// The value that lane 8 * (lane / 8) + N holds, in every lane of that group of 8: a row of 16 lanes is served by
+// two lane-permute moves, each confined to one half of the row by its bank mask.  Every lane of the wavefront
+// must be active.  (s_nop: a vector write of the source needs two wait states before the permute reads it.)
+template <int N>
+__device__ __forceinline__ double class_row_bcast(double src) {
+  double r;
+  asm("s_nop 1\n\tv_mov_b64_dpp %0, %1 row_newbcast:%2 row_mask:0xf bank_mask:0x3\n\t"
+      "v_mov_b64_dpp %0, %1 row_newbcast:%3 row_mask:0xf bank_mask:0xc"
+      : "=&v"(r)
+      : "v"(src), "n"(N), "n"(N + 8));
+  return r;
+}
+
 template <int N>
 __device__ __forceinline__ double ipow(double x) {
   if constexpr (N == 1) {

@@ -683,70 +683,58 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
         ai[j] = use ? im : 0.0;
       }
     }
+    // Gauss-Jordan sweeps.  The 8 lanes of a class sit in one half of a row of 16 lanes, so the pivot row
+    // reaches them through the lane-permute move (class_row_bcast): nothing goes through LDS, nothing waits.
+    // Executed by all lanes (the permute reads lanes, so none may be switched off); lanes without a row carry
+    // zeros or garbage that is never stored.  Pivot lane: row scaled by 1 / pivot; the others: row minus
+    // (a_ip / pivot) x pivot row -- one expression with the factors selected per lane.
     double det = 1.0;
+    static_for<0, D>([&](auto PI) {
+      constexpr int p = PI.value;
+      double pr[D], pi[D];
 #pragma unroll
-    for (int p = 0; p < D; ++p) {
-      if (on && fi == p) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) *reinterpret_cast<double2*>(&sP[fk * 16 + 2 * j]) = make_double2(ar[j], ai[j]);
+      for (int j = 0; j < D; ++j) {
+        pr[j] = class_row_bcast<p>(ar[j]);
+        pi[j] = class_row_bcast<p>(ai[j]);
       }
-      wave_lds_sync();
-      if (on) {
-        double pr[8], pi[8];
+      double piv = pr[p];
+      if (!(piv > 1e-300)) {
+        piv = 1e-300;
+        if (on && fi == 0) atomicOr(status, GSS_STATUS_NONPD_B);
+      }
+      det *= piv;
+      const double rp = rcp_f64(piv);
+      const bool is_piv = fi == p;
+      const double fr = ar[p] * rp, fim = ai[p] * rp;      // M_ip / pivot
+      const double cr = is_piv ? -rp : fr, ci = is_piv ? 0.0 : fim;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const double2 v = *reinterpret_cast<const double2*>(&sP[fk * 16 + 2 * j]);
-          pr[j] = v.x;
-          pi[j] = v.y;
-        }
-        double piv = pr[p];
-        if (!(piv > 1e-300)) {
-          piv = 1e-300;
-          if (fi == 0) atomicOr(status, GSS_STATUS_NONPD_B);
-        }
-        det *= piv;
-        const double rp = rcp_f64(piv);
-        if (fi == p) {
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            ar[j] = pr[j] * rp;
-            ai[j] = pi[j] * rp;
-          }
-          ar[p] = rp;
-          ai[p] = 0.0;
-        } else {
-          const double fr = ar[p] * rp, fim = ai[p] * rp;    // M_ip / pivot
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            if (j != p) {
-              ar[j] -= fr * pr[j] - fim * pi[j];
-              ai[j] -= fr * pi[j] + fim * pr[j];
-            }
-          }
-          ar[p] = -fr;
-          ai[p] = -fim;
+      for (int j = 0; j < D; ++j) {
+        if (j != p) {
+          const double br = is_piv ? 0.0 : ar[j], bi = is_piv ? 0.0 : ai[j];
+          ar[j] = br - (cr * pr[j] - ci * pi[j]);
+          ai[j] = bi - (cr * pi[j] + ci * pr[j]);
         }
       }
-      wave_lds_sync();
-    }
+      ar[p] = is_piv ? rp : -fr;
+      ai[p] = is_piv ? 0.0 : -fim;
+    });
     // packed coefficients of q = sum_i A_ii P_ii + 2 sum_{i<j} (Re A_ij Re P_ij + Im A_ij Im P_ij), A = B^-1
-    if (on) {
+    // (one predicate per entry, the divisions as reciprocals: every lane computes the class constant, one stores)
+    {
+      double* __restrict__ sCk = sC + fkc * (R * 16);
+      const int prow = gss_packed_row(fic, D);
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        if (j < D && j >= fi) {
-          if (j == fi) {
-            sC[fk * (R * 16) + gss_packed_row(fi, D)] = ar[j];
-          } else {
-            const int p = gss_packed_row(fi, D) + 1 + 2 * (j - fi - 1);
-            sC[fk * (R * 16) + p] = 2.0 * ar[j];
-            sC[fk * (R * 16) + p + 1] = 2.0 * ai[j];
-          }
+      for (int j = 0; j < D; ++j) {
+        const bool diag = j == fi;
+        const int pj = diag ? prow : prow + 1 + 2 * (j - fic - 1);
+        if (on && j >= fi) {
+          sCk[pj] = diag ? ar[j] : 2.0 * ar[j];
+          if (!diag) sCk[pj + 1] = 2.0 * ai[j];
         }
       }
-      if (fi == 0) {
-        const double pi_k = weight_mode == 1 ? Nk / fmax(Ntot, GSS_EPS_N) : 1.0 / (double)K;
-        sCC[fk] = fmax(pi_k, GSS_EPS_PI) / det;
-      }
+      const double pi_k = weight_mode == 1 ? Nk * rcp_f64(fmax(Ntot, GSS_EPS_N)) : 1.0 / (double)K;
+      const double cck = fmax(pi_k, GSS_EPS_PI) * rcp_f64(det);
+      if (on && fi == 0) sCC[fk] = cck;
     }
     wave_lds_sync();
 #pragma unroll
