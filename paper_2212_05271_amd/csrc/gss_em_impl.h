@@ -338,6 +338,117 @@ __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
 }
 
 // ----------------------------------------------------------------------------------------------
+// M-step in one wavefront: the K class matrices B_k = D R_k / N_k from the packed sums sR[K][E] and the class
+// counts sN[K] (both in LDS), Hermitised by construction, scaled to trace D, loaded with delta I (identity for a
+// class without data), inverted in place; the packed coefficients of B_k^-1 go to sC[K][coef_regs(D) * 16] and
+// the class constants pi_k / det B_k to sCC[K] (LDS).  Lane (k, i) = (le / 8, le % 8) holds row i of the matrix
+// of class k (8 complex numbers) in registers.  Every lane of the wavefront must be active.  The caller orders
+// the LDS traffic before and after (wave_lds_sync).
+// ----------------------------------------------------------------------------------------------
+template <int D, int K>
+__device__ __forceinline__ void factor_classes_in_wave(const double* __restrict__ sR, const double* __restrict__ sN,
+                                                       double* __restrict__ sC, double* __restrict__ sCC, int le,
+                                                       int weight_mode, uint32_t* __restrict__ status) {
+  constexpr int E = D * D;
+  constexpr int R = coef_regs(D);
+  const int fk = le >> 3, fi = le & 7;                  // class and row of this lane
+  // (Written without branches: every lane reads from valid addresses and the unused values are deselected,
+  // so that the LDS reads go out together instead of one wait per row entry.)
+  const bool on = fk < K && fi < D;
+  const int fkc = fk < K ? fk : K - 1, fic = fi < D ? fi : D - 1;
+  const double* __restrict__ sRk = sR + fkc * E;
+  double ar[8], ai[8];                                  // row fi of class fk
+  double tr = 0.0;
+#pragma unroll
+  for (int d = 0; d < D; ++d) tr += sRk[gss_packed_row(d, D)];
+  const double Nk = sN[fkc];
+  double Ntot = 0.0;
+#pragma unroll
+  for (int k = 0; k < K; ++k) Ntot += sN[k];
+  // B = D R / max(N, eps); dead if its trace <= eps; else rescaled to trace D (= R * D / tr R)
+  const bool dead = !((double)D * tr / fmax(Nk, GSS_EPS_N) > GSS_EPS_N);
+  const double sc = dead ? 0.0 : (double)D / tr;
+  {
+    double v0[8], v1[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      // packed position of entry (min, max) of the row's pair (fi, j): the diagonal entry for j = fi (its
+      // neighbour is read along and dropped), Re and Im of the off-diagonal entry otherwise
+      const int jc = j < D ? j : D - 1;
+      const int lo = fic < jc ? fic : jc, hi = fic < jc ? jc : fic;
+      int p = gss_packed_row(lo, D) + (hi > lo ? 1 + 2 * (hi - lo - 1) : 0);
+      p = p > E - 2 ? E - 2 : p;                          // the last diagonal entry has no neighbour (D = 1: none at all)
+      v0[j] = sRk[hi > lo ? p : gss_packed_row(lo, D)];
+      v1[j] = sRk[E > 1 ? p + 1 : 0];
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const bool diag = j == fi;
+      const bool use = on && j < D && (diag || !dead);
+      double re = v0[j] * sc;
+      double im = v1[j] * sc;
+      re = diag ? (dead ? 1.0 : re) + GSS_DELTA : re;
+      im = diag ? 0.0 : (fi > j ? -im : im);              // lower triangle = conjugate
+      ar[j] = use ? re : 0.0;
+      ai[j] = use ? im : 0.0;
+    }
+  }
+  // Gauss-Jordan sweeps.  The 8 lanes of a class sit in one half of a row of 16 lanes, so the pivot row
+  // reaches them through the lane-permute move (class_row_bcast): nothing goes through LDS, nothing waits.
+  // Executed by all lanes (the permute reads lanes, so none may be switched off); lanes without a row carry
+  // zeros or garbage that is never stored.  Pivot lane: row scaled by 1 / pivot; the others: row minus
+  // (a_ip / pivot) x pivot row -- one expression with the factors selected per lane.
+  double det = 1.0;
+  static_for<0, D>([&](auto PI) {
+    constexpr int p = PI.value;
+    double pr[D], pi[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+      pr[j] = class_row_bcast<p>(ar[j]);
+      pi[j] = class_row_bcast<p>(ai[j]);
+    }
+    double piv = pr[p];
+    if (!(piv > 1e-300)) {
+      piv = 1e-300;
+      if (on && fi == 0) atomicOr(status, GSS_STATUS_NONPD_B);
+    }
+    det *= piv;
+    const double rp = rcp_f64(piv);
+    const bool is_piv = fi == p;
+    const double fr = ar[p] * rp, fim = ai[p] * rp;      // M_ip / pivot
+    const double cr = is_piv ? -rp : fr, ci = is_piv ? 0.0 : fim;
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+      if (j != p) {
+        const double br = is_piv ? 0.0 : ar[j], bi = is_piv ? 0.0 : ai[j];
+        ar[j] = br - (cr * pr[j] - ci * pi[j]);
+        ai[j] = bi - (cr * pi[j] + ci * pr[j]);
+      }
+    }
+    ar[p] = is_piv ? rp : -fr;
+    ai[p] = is_piv ? 0.0 : -fim;
+  });
+  // packed coefficients of q = sum_i A_ii P_ii + 2 sum_{i<j} (Re A_ij Re P_ij + Im A_ij Im P_ij), A = B^-1
+  // (one predicate per entry, the divisions as reciprocals: every lane computes the class constant, one stores)
+  {
+    double* __restrict__ sCk = sC + fkc * (R * 16);
+    const int prow = gss_packed_row(fic, D);
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+      const bool diag = j == fi;
+      const int pj = diag ? prow : prow + 1 + 2 * (j - fic - 1);
+      if (on && j >= fi) {
+        sCk[pj] = diag ? ar[j] : 2.0 * ar[j];
+        if (!diag) sCk[pj + 1] = 2.0 * ai[j];
+      }
+    }
+    const double pi_k = weight_mode == 1 ? Nk * rcp_f64(fmax(Ntot, GSS_EPS_N)) : 1.0 / (double)K;
+    const double cck = fmax(pi_k, GSS_EPS_PI) * rcp_f64(det);
+    if (on && fi == 0) sCC[fk] = cck;
+  }
+}
+
+// ----------------------------------------------------------------------------------------------
 // Factor kernel for D <= 8: one workgroup per (segment, frequency), one wavefront per class.
 // Sums the chunk partials in a fixed order (deterministic), forms B = D R / N, regularises (trace D,
 // + delta I; identity for a class without data), inverts by in-place Gauss-Jordan sweeps in fp64
@@ -598,7 +709,6 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
 
     int le = lane;                                      // the lane number again, opaque
     asm volatile("" : "+v"(le));
-    const int fk = le >> 3, fi = le & 7;                // factorisation: class and row of this lane
     const int code = sSlot[le];
     const int pidx = (code & 0x4000) ? -1 : (code & 0x3fff);
     const double sgn = (code & 0x8000) ? -1.0 : 1.0;
@@ -642,100 +752,7 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
     }
 
     // ---- M-step: B_k from (R_k, N_k), regularised, inverted; coefficients and class constants ----
-    // (Written without branches: every lane reads from valid addresses and the unused values are deselected,
-    // so that the LDS reads go out together instead of one wait per row entry.)
-    const bool on = fk < K && fi < D;
-    const int fkc = fk < K ? fk : K - 1, fic = fi < D ? fi : D - 1;
-    const double* __restrict__ sRk = sR + fkc * E;
-    double ar[8], ai[8];                                  // row fi of class fk
-    double tr = 0.0;
-#pragma unroll
-    for (int d = 0; d < D; ++d) tr += sRk[gss_packed_row(d, D)];
-    const double Nk = sN[fkc];
-    double Ntot = 0.0;
-#pragma unroll
-    for (int k = 0; k < K; ++k) Ntot += sN[k];
-    // B = D R / max(N, eps); dead if its trace <= eps; else rescaled to trace D (= R * D / tr R)
-    const bool dead = !((double)D * tr / fmax(Nk, GSS_EPS_N) > GSS_EPS_N);
-    const double sc = dead ? 0.0 : (double)D / tr;
-    {
-      double v0[8], v1[8];
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        // packed position of entry (min, max) of the row's pair (fi, j): the diagonal entry for j = fi (its
-        // neighbour is read along and dropped), Re and Im of the off-diagonal entry otherwise
-        const int jc = j < D ? j : D - 1;
-        const int lo = fic < jc ? fic : jc, hi = fic < jc ? jc : fic;
-        int p = gss_packed_row(lo, D) + (hi > lo ? 1 + 2 * (hi - lo - 1) : 0);
-        p = p > E - 2 ? E - 2 : p;                          // the last diagonal entry has no neighbour (D = 1: none at all)
-        v0[j] = sRk[hi > lo ? p : gss_packed_row(lo, D)];
-        v1[j] = sRk[E > 1 ? p + 1 : 0];
-      }
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const bool diag = j == fi;
-        const bool use = on && j < D && (diag || !dead);
-        double re = v0[j] * sc;
-        double im = v1[j] * sc;
-        re = diag ? (dead ? 1.0 : re) + GSS_DELTA : re;
-        im = diag ? 0.0 : (fi > j ? -im : im);              // lower triangle = conjugate
-        ar[j] = use ? re : 0.0;
-        ai[j] = use ? im : 0.0;
-      }
-    }
-    // Gauss-Jordan sweeps.  The 8 lanes of a class sit in one half of a row of 16 lanes, so the pivot row
-    // reaches them through the lane-permute move (class_row_bcast): nothing goes through LDS, nothing waits.
-    // Executed by all lanes (the permute reads lanes, so none may be switched off); lanes without a row carry
-    // zeros or garbage that is never stored.  Pivot lane: row scaled by 1 / pivot; the others: row minus
-    // (a_ip / pivot) x pivot row -- one expression with the factors selected per lane.
-    double det = 1.0;
-    static_for<0, D>([&](auto PI) {
-      constexpr int p = PI.value;
-      double pr[D], pi[D];
-#pragma unroll
-      for (int j = 0; j < D; ++j) {
-        pr[j] = class_row_bcast<p>(ar[j]);
-        pi[j] = class_row_bcast<p>(ai[j]);
-      }
-      double piv = pr[p];
-      if (!(piv > 1e-300)) {
-        piv = 1e-300;
-        if (on && fi == 0) atomicOr(status, GSS_STATUS_NONPD_B);
-      }
-      det *= piv;
-      const double rp = rcp_f64(piv);
-      const bool is_piv = fi == p;
-      const double fr = ar[p] * rp, fim = ai[p] * rp;      // M_ip / pivot
-      const double cr = is_piv ? -rp : fr, ci = is_piv ? 0.0 : fim;
-#pragma unroll
-      for (int j = 0; j < D; ++j) {
-        if (j != p) {
-          const double br = is_piv ? 0.0 : ar[j], bi = is_piv ? 0.0 : ai[j];
-          ar[j] = br - (cr * pr[j] - ci * pi[j]);
-          ai[j] = bi - (cr * pi[j] + ci * pr[j]);
-        }
-      }
-      ar[p] = is_piv ? rp : -fr;
-      ai[p] = is_piv ? 0.0 : -fim;
-    });
-    // packed coefficients of q = sum_i A_ii P_ii + 2 sum_{i<j} (Re A_ij Re P_ij + Im A_ij Im P_ij), A = B^-1
-    // (one predicate per entry, the divisions as reciprocals: every lane computes the class constant, one stores)
-    {
-      double* __restrict__ sCk = sC + fkc * (R * 16);
-      const int prow = gss_packed_row(fic, D);
-#pragma unroll
-      for (int j = 0; j < D; ++j) {
-        const bool diag = j == fi;
-        const int pj = diag ? prow : prow + 1 + 2 * (j - fic - 1);
-        if (on && j >= fi) {
-          sCk[pj] = diag ? ar[j] : 2.0 * ar[j];
-          if (!diag) sCk[pj + 1] = 2.0 * ai[j];
-        }
-      }
-      const double pi_k = weight_mode == 1 ? Nk * rcp_f64(fmax(Ntot, GSS_EPS_N)) : 1.0 / (double)K;
-      const double cck = fmax(pi_k, GSS_EPS_PI) * rcp_f64(det);
-      if (on && fi == 0) sCC[fk] = cck;
-    }
+    factor_classes_in_wave<D, K>(sR, sN, sC, sCC, le, weight_mode, status);
     wave_lds_sync();
 #pragma unroll
     for (int k = 0; k < K; ++k) {
