@@ -252,23 +252,26 @@ def main():
         def run():
             return pipeline.enhance_recording(ctx, xd, act_s, st, en, spk, ctx_samples, ctx_samples, iters=15)
 
-        run()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        outs, fr = run()
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
+        def timed(fn):
+            """Median wall time of three calls after a warm-up call (the allocator settles), and the last result."""
+            fn()
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(3):
+                t0 = time.perf_counter()
+                res = fn()
+                torch.cuda.synchronize()
+                ts.append(time.perf_counter() - t0)
+            return sorted(ts)[1], res
+
+        dt, (outs, fr) = timed(run)
         proc = float(np.sum(fr["n_frames"])) * HOP / FS
         def run_super():
             return pipeline.enhance_recording_super(ctx, xd, act_s, st, en, spk, ctx_samples, ctx_samples,
                                                     max_batch_s=50.0, iters=15)
 
-        run_super()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        _, info = run_super()
-        torch.cuda.synchronize()
-        dts = time.perf_counter() - t0
+        del outs
+        dts, (_, info) = timed(run_super)
         procs = float(np.sum(info["T"])) * HOP / FS
         print(f"\nc4 pipeline: {a.meeting_s:.0f} s meeting, 8 channels, {n_seg} segments with 7.5 s of context per side "
               f"({proc:.0f} s of audio processed), 15 iterations: {dt * 1e3:.1f} ms end to end = "
@@ -282,12 +285,7 @@ def main():
             return pipeline.enhance_recording_super(ctx, xd, act_s, st, en, spk, ctx_samples, ctx_samples,
                                                     max_batch_s=50.0, iters=15, wpe_taps=10, wpe_delay=2, wpe_iters=3)
 
-        run_super_wpe()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        run_super_wpe()
-        torch.cuda.synchronize()
-        dtw = time.perf_counter() - t0
+        dtw, _ = timed(run_super_wpe)
         print(f"super-segments with dereverberation (WPE, 10 taps, delay 2, 3 iterations) before the mask estimation: "
               f"{dtw * 1e3:.1f} ms = {a.meeting_s / dtw:,.0f} recording-s/s (WPE adds {(dtw - dts) * 1e3:.1f} ms)")
     ctx.close()
