@@ -601,9 +601,8 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
   constexpr int WS = weight_stride(K);
   constexpr int kTileDoubles = kWave * kYStride + kWave * WS;
   constexpr int kCoefDoubles = K * R * 16;             // packed coefficients, padded to whole registers
-  constexpr int kRowDoubles = K * 16;                  // one published pivot row (8 complex) per class
   constexpr int kSumDoubles = K * E + K;               // packed weighted scatter sums, then the class counts
-  constexpr int kWaveDoubles = (kTileDoubles + kCoefDoubles + kSumDoubles + kRowDoubles + K + 1) / 2 * 2;
+  constexpr int kWaveDoubles = (kTileDoubles + kCoefDoubles + kSumDoubles + K + 1) / 2 * 2;
   constexpr int kShareDoubles = NW > 1 ? 2 * NW * kSumDoubles : 0;
   __shared__ __attribute__((aligned(16))) double lds[NW * kWaveDoubles + kShareDoubles];
   const int lane = threadIdx.x & (kWave - 1);
@@ -613,8 +612,7 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
   double* __restrict__ sC = sY + kTileDoubles;         // [K][R * 16] coefficients of B^-1 for the next pass
   double* __restrict__ sR = sC + kCoefDoubles;         // [K][E] packed weighted scatter sums
   double* __restrict__ sN = sR + K * E;                // [K] class counts
-  double* __restrict__ sP = sN + K;                    // [K][16] published pivot rows
-  double* __restrict__ sCC = sP + kRowDoubles;         // [K] class constants pi / det B
+  double* __restrict__ sCC = sN + K;                   // [K] class constants pi / det B
   double* __restrict__ sShare = lds + NW * kWaveDoubles;   // [2][NW][kSumDoubles] sums of the wavefronts (NW > 1)
   __shared__ int sSlotAll[NW * kWave];
   int* __restrict__ sSlot = sSlotAll + wave * kWave;       // [64] packed index and sign of the lane's reduction slot
