@@ -92,6 +92,48 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
+// Sums of N per-lane doubles over the 64 lanes of the wavefront, all at once and in a fixed order: six
+// butterfly steps, and at each step a lane keeps only half of its values (of each pair of values one lane of
+// the exchanging pair keeps the first and the other the second), so the work halves from step to step
+// instead of every value paying six steps.  Afterwards lane l holds in v[j] the wavefront's total of value
+// 64 j + transposed_index(l) (where that is below N; the other entries are meaningless).  The first four steps
+// stay inside a row of 16 lanes and use the lane-permute modifier of the vector move (mirrored row, mirrored
+// half, pairs, neighbours, in this order: each permutation leaves the bits that earlier steps selected on
+// unchanged), the last two cross the rows with a shuffle.  Every lane of the wavefront must be active.
+template <int CTRL>
+__device__ __forceinline__ double dpp_permute_f64(double x) {
+  const int lo = __double2loint(x), hi = __double2hiint(x);
+  const int plo = __builtin_amdgcn_update_dpp(0, lo, CTRL, 0xf, 0xf, false);
+  const int phi = __builtin_amdgcn_update_dpp(0, hi, CTRL, 0xf, 0xf, false);
+  return __hiloint2double(phi, plo);
+}
+__device__ __forceinline__ int transposed_index(int lane) {
+  return (int)(__brev((unsigned)(lane & 15)) >> 28) | (lane & 48);
+}
+template <int N>
+__device__ __forceinline__ void transpose_reduce(double (&v)[N], int lane) {
+  auto step = [&](auto CNT, bool second, auto perm) {
+    constexpr int n = decltype(CNT)::value;
+    static_for<0, n / 2>([&](auto MI) {
+      constexpr int m = MI.value;
+      const double a = v[2 * m], b = v[2 * m + 1];
+      const double keep = second ? b : a, send = second ? a : b;
+      v[m] = keep + perm(send);
+    });
+    if constexpr (n & 1) {            // a value without a partner: both lanes keep its sum
+      const double a = v[n - 1];
+      v[n / 2] = a + perm(a);
+    }
+  };
+  constexpr int n1 = (N + 1) / 2, n2 = (n1 + 1) / 2, n3 = (n2 + 1) / 2, n4 = (n3 + 1) / 2, n5 = (n4 + 1) / 2;
+  step(std::integral_constant<int, N>{}, (lane & 8) != 0, [](double x) { return dpp_permute_f64<0x140>(x); });   // row_mirror
+  step(std::integral_constant<int, n1>{}, (lane & 4) != 0, [](double x) { return dpp_permute_f64<0x141>(x); });  // row_half_mirror
+  step(std::integral_constant<int, n2>{}, (lane & 2) != 0, [](double x) { return dpp_permute_f64<0x4E>(x); });   // quad_perm [2, 3, 0, 1]
+  step(std::integral_constant<int, n3>{}, (lane & 1) != 0, [](double x) { return dpp_permute_f64<0xB1>(x); });   // quad_perm [1, 0, 3, 2]
+  step(std::integral_constant<int, n4>{}, (lane & 16) != 0, [](double x) { return __shfl_xor(x, 16, kWave); });
+  step(std::integral_constant<int, n5>{}, (lane & 32) != 0, [](double x) { return __shfl_xor(x, 32, kWave); });
+}
+
 // Position (row i, column j >= i, part: 0 diagonal, 1 real, 2 imaginary) of packed index idx.
 __host__ __device__ constexpr int packed_i(int idx, int D) {
   int i = 0;

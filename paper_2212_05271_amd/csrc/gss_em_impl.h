@@ -90,12 +90,48 @@ __host__ __device__ constexpr int weight_stride(int K) { return K | 1; }
 __host__ __device__ constexpr int coef_regs(int D) { return (D * D + 15) / 16; }
 constexpr int kResidentRegs = 20;
 
-// The lane's frame of a tile in fp64 and its activity bits, kept in registers by the kernel for tiny problems.
+// Few channels: the lane that owns a frame in phase 1 has all D * D entries of its outer product in registers
+// anyway (one block of at most 16), so it adds w_k * P[e] to K * D * D accumulators of its own, and there is no
+// LDS tile and no phase 2 (whose 8 x 8 lane layout would run mostly on zero padding below 5 channels).  Used
+// when the accumulators fit in registers beside phase 1.  The accumulators are acc[k][e] then (packed order)
+// instead of acc[slot n][k], and the sums over the lanes are taken at the end of the pass (transpose_reduce).
+constexpr int kDirectMaxAcc = 80;
+constexpr int kPrefetchMaxAcc = 64;            // the whole-EM kernel requests the next tile ahead up to this many
+__host__ __device__ constexpr bool direct_layout(int D, int K) { return D <= 4 && D * D * K <= kDirectMaxAcc; }
+template <int D, int K>
+struct PassAcc {
+  static constexpr bool direct = direct_layout(D, K);
+  static constexpr int rows = direct ? K : 8, cols = direct ? D * D : K;
+  using type = double[rows][cols];
+};
+template <int A, int B>
+__device__ __forceinline__ void zero_acc(double (&acc)[A][B]) {
+#pragma unroll
+  for (int a = 0; a < A; ++a)
+#pragma unroll
+    for (int b = 0; b < B; ++b) acc[a][b] = 0.0;
+}
+
+// The lane's frame of a tile as stored in memory and its activity bits: loaded by the caller of pass_tile
+// ahead of time (the whole-EM kernel keeps the one tile of a tiny problem for all iterations, and requests
+// the next tile of a streamed problem before it works on the current one).
 template <int D>
 struct TileRegs {
-  double yr[D], yi[D];
+  float2 y[D];
   unsigned abits;
 };
+// A lane whose frame lies beyond T reads frame 0 instead (it exists whenever the tile's mask is not empty); its
+// activity bits are cleared by pass_tile, not here: nothing in this function waits for a loaded value, so the
+// loads of the next tile stay in flight while the current one is worked on.
+template <int D>
+__device__ __forceinline__ void load_tile_regs(TileRegs<D>& r, const float2* __restrict__ Yrow,
+                                               const uint8_t* __restrict__ abrow, int t0, int lane, int T) {
+  const int t = t0 + lane;
+  const bool valid = t < T;
+#pragma unroll
+  for (int d = 0; d < D; ++d) r.y[d] = Yrow[(long)(valid ? t : 0) * D + d];
+  r.abits = abrow[valid ? t : 0];
+}
 
 // One tile of 64 frames starting at frame t0.  `tmask` (wave-uniform) is the tile's activity mask.
 //   creg : the resident coefficient registers [K * coef_regs(D)] (used when RESIDENT)
@@ -107,11 +143,12 @@ __device__ __forceinline__ void pass_tile(
     const float2* __restrict__ Yrow, const uint8_t* __restrict__ abrow, const double (&creg)[RESIDENT ? K * coef_regs(D) : 1],
     const double* __restrict__ sC, const double (&cc)[K], float* __restrict__ gamma_row /* + k*F*Tmax */,
     uint32_t* __restrict__ status, long gamma_kstride, int T, int Tmax, int t0, int lane, unsigned tmask,
-    double* __restrict__ sY, double* __restrict__ sW, double (&acc)[8][K], double (&nacc)[K],
+    double* __restrict__ sY, double* __restrict__ sW, typename PassAcc<D, K>::type& acc, double (&nacc)[K],
     const TileRegs<D>* pre = nullptr) {
   constexpr int E = D * D;
   constexpr int R = coef_regs(D);
   constexpr int WS = weight_stride(K);
+  constexpr bool DIRECT = PassAcc<D, K>::direct;
   const int tg = lane >> 3, eg = lane & 7;
   tmask &= (1u << K) - 1u;
   const int t = t0 + lane;
@@ -135,10 +172,10 @@ __device__ __forceinline__ void pass_tile(
   if constexpr (PRE) {
 #pragma unroll
     for (int d = 0; d < D; ++d) {
-      yr[d] = pre->yr[d];
-      yi[d] = pre->yi[d];
+      yr[d] = (double)pre->y[d].x;
+      yi[d] = (double)pre->y[d].y;
     }
-    abits = pre->abits;
+    abits = valid ? pre->abits : 0u;
   } else {
 #pragma unroll
     for (int d = 0; d < D; ++d) {
@@ -152,8 +189,10 @@ __device__ __forceinline__ void pass_tile(
 
   // ---- q_k = <coef_k, y y^H>, 16 entries of the outer product at a time; three partial sums per class (an FMA
   // does not wait for the one before it) ----
+  constexpr int NQ = DIRECT ? 2 : 3;          // (fewer registers where the accumulators need them)
   double q[K][3];
   double n2 = 0.0;
+  double Pd[DIRECT && !FINAL ? E : 1];        // DIRECT: the frame's packed outer product (one block)
 #pragma unroll
   for (int k = 0; k < K; ++k) { q[k][0] = 0.0; q[k][1] = 0.0; q[k][2] = 0.0; }
   static_for<0, R>([&](auto RI) {
@@ -170,6 +209,7 @@ __device__ __forceinline__ void pass_tile(
       constexpr int e = EI.value;
       P[e] = packed_entry<D, 16 * r + e>(yr, yi);
       if constexpr (packed_part(16 * r + e, D) == 0) n2 += P[e];
+      if constexpr (DIRECT && !FINAL) Pd[16 * r + e] = P[e];
     });
     static_for<0, K>([&](auto KI) {
       constexpr int k = KI.value;
@@ -178,7 +218,7 @@ __device__ __forceinline__ void pass_tile(
         if constexpr (RESIDENT) ck = creg[k * R + r]; else ck = c[k];
         static_for<0, ng>([&](auto EI) {
           constexpr int e = EI.value;
-          fma_bcast<e, e == 0>(q[k][e % 3], ck, P[e]);
+          fma_bcast<e, e == 0>(q[k][e % NQ], ck, P[e]);
         });
       }
     });
@@ -196,7 +236,7 @@ __device__ __forceinline__ void pass_tile(
     rq[k] = 0.0;
     v[k] = 0.0;
     if (class_on(tmask, k)) {
-      rq[k] = rcp_f64_fast(fmax(q[k][0] + q[k][1] + q[k][2], qfloor));   // 1 / (q * n2c): the M-step weight is gamma * rq
+      rq[k] = rcp_f64_fast(fmax(NQ == 3 ? q[k][0] + q[k][1] + q[k][2] : q[k][0] + q[k][1], qfloor));   // 1 / (q * n2c): the M-step weight is gamma * rq
       const double u = rq[k] * n2c;                             // 1 / q
       const double p = cc[k] * ipow<D>(u);
       v[k] = ((abits >> k) & 1u) ? p : 0.0;
@@ -210,6 +250,17 @@ __device__ __forceinline__ void pass_tile(
       constexpr int k = KI.value;
       if (class_on(tmask, k)) {
         if (t < Tmax) gamma_row[k * gamma_kstride + t] = (float)(v[k] * rz);
+      }
+    });
+  } else if constexpr (DIRECT) {
+    static_for<0, K>([&](auto KI) {
+      constexpr int k = KI.value;
+      if (class_on(tmask, k)) {
+        const double g = v[k] * rz;
+        nacc[k] += g;
+        const double w = g * rq[k];
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[k][e] = fma(w, Pd[e], acc[k][e]);
       }
     });
   } else {
@@ -236,6 +287,26 @@ __device__ __forceinline__ void pass_tile(
   }
 }
 
+// Direct layout: the wavefront's totals of the accumulators acc[k][e] and the class counts nacc[k], written as
+// out[k * E + e] and out[K * E + k] (LDS; the caller orders the traffic).
+template <int D, int K>
+__device__ __forceinline__ void store_direct_sums(const typename PassAcc<D, K>::type& acc, const double (&nacc)[K],
+                                                  double* __restrict__ out, int lane) {
+  constexpr int E = D * D, N = K * E + K;
+  double v[N];
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+#pragma unroll
+    for (int e = 0; e < E; ++e) v[k * E + e] = acc[k][e];
+    v[K * E + k] = nacc[k];
+  }
+  transpose_reduce<N>(v, lane);
+  const int n0 = transposed_index(lane);
+#pragma unroll
+  for (int j = 0; j < (N + kWave - 1) / kWave; ++j)
+    if (n0 + kWave * j < N) out[n0 + kWave * j] = v[j];
+}
+
 template <int D, int K, bool FINAL>
 __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
     gss_yview yv, const uint8_t* __restrict__ abyte, const uint32_t* __restrict__ tmask,
@@ -247,11 +318,12 @@ __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
   constexpr int R = coef_regs(D);
   constexpr bool RESIDENT = K * R <= kResidentRegs;
   constexpr int WS = weight_stride(K);
-  constexpr int kTileDoubles = kWave * kYStride + kWave * WS;
+  constexpr bool DIRECT = PassAcc<D, K>::direct;        // no tiles in LDS then
+  constexpr int kTileDoubles = DIRECT ? 0 : kWave * kYStride + kWave * WS;
   constexpr int kCoefDoubles = RESIDENT ? 0 : K * R * 16;
   // per-wavefront tiles (+ the coefficient copy); the tiles are reused at the end for the cross-wavefront
-  // reduction (needs kPassWaves * (64 * K + K))
-  constexpr int kRedDoubles = kPassWaves * (64 * K + K);
+  // reduction (needs kPassWaves * (64 * K + K); DIRECT: kPassWaves * (K * E + K))
+  constexpr int kRedDoubles = DIRECT ? kPassWaves * (K * E + K) : kPassWaves * (64 * K + K);
   constexpr int kTilesDoubles = FINAL ? 2 : (kPassWaves * kTileDoubles > kRedDoubles ? kPassWaves * kTileDoubles : kRedDoubles);
   __shared__ __attribute__((aligned(16))) double lds[kTilesDoubles + kCoefDoubles];
 
@@ -300,14 +372,11 @@ __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
     for (int k = 0; k < K; ++k) cc[k] = ccp[k];
   }
 
-  double acc[8][K];
+  typename PassAcc<D, K>::type acc;
   double nacc[K];
+  zero_acc(acc);
 #pragma unroll
-  for (int k = 0; k < K; ++k) {
-    nacc[k] = 0.0;
-#pragma unroll
-    for (int n = 0; n < 8; ++n) acc[n][k] = 0.0;
-  }
+  for (int k = 0; k < K; ++k) nacc[k] = 0.0;
   const uint8_t* __restrict__ abrow = abyte + (long)s * Tmax;
   const int tiles_total = (Tmax + kWave - 1) / kWave;
   // the tile masks are read through the scalar path (they were written by an earlier kernel)
@@ -332,9 +401,23 @@ __global__ __launch_bounds__(kWave * kPassWaves, 2) void em_pass_small(
   }
   if (FINAL) return;
 
-  // Reduce over the 8 frame groups and over the wavefronts; write the chunk's packed partial sums and counts.
-  reduce_and_store_partials<D, K, true>(acc, nacc, sY, lds, part + (long)blockIdx.x * (K * E),
-                                        npart + (long)blockIdx.x * K, lane, wave);
+  if constexpr (DIRECT) {
+    // every wavefront's totals meet in LDS and are added in the order of the wavefronts
+    constexpr int N = K * E + K;
+    store_direct_sums<D, K>(acc, nacc, lds + wave * N, lane);
+    __syncthreads();
+    for (int x = threadIdx.x; x < N; x += kWave * kPassWaves) {
+      double sum = lds[x];
+#pragma unroll
+      for (int w = 1; w < kPassWaves; ++w) sum += lds[w * N + x];
+      if (x < K * E) part[(long)blockIdx.x * (K * E) + x] = sum;
+      else npart[(long)blockIdx.x * K + (x - K * E)] = sum;
+    }
+  } else {
+    // Reduce over the 8 frame groups and over the wavefronts; write the chunk's packed partial sums and counts.
+    reduce_and_store_partials<D, K, true>(acc, nacc, sY, lds, part + (long)blockIdx.x * (K * E),
+                                          npart + (long)blockIdx.x * K, lane, wave);
+  }
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -571,6 +654,56 @@ __global__ __launch_bounds__(kWave * K) void em_factor_small(
   }
 }
 
+// One pass of a wavefront of the whole-EM kernel over its tiles below tile_end: the one resident tile (NW > 1,
+// resident_tiles), or tiles wave, wave + NW, ...  With the direct layout and not too many accumulators there are
+// registers to spare, and the frames of the next tile are requested from memory before the current tile is worked on.
+template <int D, int K, int NW, bool FINAL, bool RESIDENT, class MaskPtr>
+__device__ __forceinline__ void whole_pass(
+    const float2* __restrict__ Yrow, const uint8_t* __restrict__ abrow, MaskPtr tmrow,
+    const double (&creg)[RESIDENT ? K * coef_regs(D) : 1], const double* __restrict__ sC, const double (&cc)[K],
+    float* __restrict__ gamma_row, uint32_t* __restrict__ status, long gamma_kstride, int T, int Tmax, int tile_end,
+    bool resident_tiles, int wave, int lane, unsigned my_mask, const TileRegs<D>& pre, double* __restrict__ sY,
+    double* __restrict__ sW, typename PassAcc<D, K>::type& acc, double (&nacc)[K]) {
+  if constexpr (NW > 1) {
+    if (resident_tiles) {
+      if (wave < tile_end)
+        pass_tile<D, K, FINAL, RESIDENT, true>(Yrow, abrow, creg, sC, cc, gamma_row, status, gamma_kstride, T, Tmax,
+                                               wave * kWave, lane, my_mask, sY, sW, acc, nacc, &pre);
+      return;
+    }
+  }
+  if constexpr (PassAcc<D, K>::direct && D * D * K <= kPrefetchMaxAcc) {
+    constexpr unsigned kmask = (1u << K) - 1u;
+    TileRegs<D> cur = pre;                               // (zeros; replaced below when the first tile is live)
+    int tile = wave;
+    unsigned m = 0u;
+    if (tile < tile_end) {
+      m = tmrow[tile] & kmask;
+      if (m != 0u) load_tile_regs<D>(cur, Yrow, abrow, tile * kWave, lane, T);
+    }
+    while (tile < tile_end) {
+      const int next = tile + NW;
+      TileRegs<D> nxt = cur;
+      unsigned mn = 0u;
+      if (next < tile_end) {
+        mn = tmrow[next] & kmask;
+        if (mn != 0u) load_tile_regs<D>(nxt, Yrow, abrow, next * kWave, lane, T);
+      }
+      // (the mask is the same in every lane; the compiler has to be told after the loop-carried copy)
+      pass_tile<D, K, FINAL, RESIDENT, true>(Yrow, abrow, creg, sC, cc, gamma_row, status, gamma_kstride, T, Tmax,
+                                             tile * kWave, lane, __builtin_amdgcn_readfirstlane(m), sY, sW, acc, nacc,
+                                             &cur);
+      cur = nxt;
+      m = mn;
+      tile = next;
+    }
+  } else {
+    for (int tile = wave; tile < tile_end; tile += NW)
+      pass_tile<D, K, FINAL, RESIDENT>(Yrow, abrow, creg, sC, cc, gamma_row, status, gamma_kstride, T, Tmax, tile * kWave,
+                                       lane, tmrow[tile], sY, sW, acc, nacc);
+  }
+}
+
 // ----------------------------------------------------------------------------------------------
 // Whole-EM kernel: a workgroup of NW wavefronts owns one (segment, frequency) for all iterations.  Per
 // iteration every wavefront walks its tiles (pass_tile above), sums its accumulators over the 8 frame groups
@@ -599,7 +732,8 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
   constexpr int R = coef_regs(D);
   constexpr bool RESIDENT = K * R <= kResidentRegs;
   constexpr int WS = weight_stride(K);
-  constexpr int kTileDoubles = kWave * kYStride + kWave * WS;
+  constexpr bool DIRECT = PassAcc<D, K>::direct;       // no tiles in LDS then
+  constexpr int kTileDoubles = DIRECT ? 0 : kWave * kYStride + kWave * WS;
   constexpr int kCoefDoubles = K * R * 16;             // packed coefficients, padded to whole registers
   constexpr int kSumDoubles = K * E + K;               // packed weighted scatter sums, then the class counts
   constexpr int kWaveDoubles = (kTileDoubles + kCoefDoubles + kSumDoubles + K + 1) / 2 * 2;
@@ -630,25 +764,18 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
   const long gamma_kstride = (long)F * Tmax;
   const int tiles = (T + kWave - 1) / kWave;
 
-  // NW > 1: this wavefront's one tile: its mask, and the lane's frame in registers
+  // NW > 1 and at most NW tiles: this wavefront's one tile: its mask, and the lane's frame in registers.
+  // (NW > 1 and more tiles: wavefront w walks tiles w, w + NW, ... like the single wavefront of NW = 1.)
+  const bool resident_tiles = NW > 1 && tiles_total <= NW;
   TileRegs<D> pre;
   unsigned my_mask = 0u;
+#pragma unroll
+  for (int d = 0; d < D; ++d) pre.y[d] = make_float2(0.f, 0.f);
+  pre.abits = 0u;
   if constexpr (NW > 1) {
-#pragma unroll
-    for (int d = 0; d < D; ++d) { pre.yr[d] = 0.0; pre.yi[d] = 0.0; }
-    pre.abits = 0u;
-    if (wave < tiles_total) my_mask = tmrow[wave] & ((1u << K) - 1u);
-    if (my_mask != 0u) {                                // some frame of the tile lies below T: frame 0 exists
-      const int t = wave * kWave + lane;
-      const bool valid = t < T;
-#pragma unroll
-      for (int d = 0; d < D; ++d) {
-        const float2 v = Yrow[(long)(valid ? t : 0) * D + d];
-        pre.yr[d] = (double)v.x;
-        pre.yi[d] = (double)v.y;
-      }
-      const unsigned a = abrow[valid ? t : 0];
-      pre.abits = valid ? a : 0u;
+    if (resident_tiles) {
+      if (wave < tiles_total) my_mask = tmrow[wave] & ((1u << K) - 1u);
+      if (my_mask != 0u) load_tile_regs<D>(pre, Yrow, abrow, wave * kWave, lane, T);   // a frame below T exists
     }
   }
 
@@ -679,7 +806,7 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
   // the lane number that the compiler cannot see through: values computed ahead of the iteration loop would be
   // live across the tile loop, where there is no register for them, and come back from scratch memory one
   // dependent load at a time.
-  {
+  if constexpr (!DIRECT) {
     static constexpr SlotTable kSlots = make_slot_table();
     const int slot = (lane & 7) * 8 + (lane >> 3);     // lane o = 8 n + eg reads back slot (eg, n)
     const int pi0 = kSlots.v[D][slot];
@@ -687,32 +814,26 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
   }
   wave_lds_sync();
   for (int it = 0; it < iters; ++it) {
-    double acc[8][K];
+    typename PassAcc<D, K>::type acc;
     double nacc[K];
+    zero_acc(acc);
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-      nacc[k] = 0.0;
-#pragma unroll
-      for (int n = 0; n < 8; ++n) acc[n][k] = 0.0;
-    }
-    if constexpr (NW > 1) {
-      if (wave < tiles)
-        pass_tile<D, K, false, RESIDENT, true>(Yrow, abrow, creg, sC, cc, nullptr, status, gamma_kstride, T, Tmax,
-                                               wave * kWave, lane, my_mask, sY, sW, acc, nacc, &pre);
-    } else {
-      for (int tile = 0; tile < tiles; ++tile)
-        pass_tile<D, K, false, RESIDENT>(Yrow, abrow, creg, sC, cc, nullptr, status, gamma_kstride, T, Tmax, tile * kWave,
-                                         lane, tmrow[tile], sY, sW, acc, nacc);
-    }
+    for (int k = 0; k < K; ++k) nacc[k] = 0.0;
+    whole_pass<D, K, NW, false, RESIDENT>(Yrow, abrow, tmrow, creg, sC, cc, nullptr, status, gamma_kstride, T, Tmax, tiles,
+                                          resident_tiles, wave, lane, my_mask, pre, sY, sW, acc, nacc);
 
     int le = lane;                                      // the lane number again, opaque
     asm volatile("" : "+v"(le));
-    const int code = sSlot[le];
-    const int pidx = (code & 0x4000) ? -1 : (code & 0x3fff);
-    const double sgn = (code & 0x8000) ? -1.0 : 1.0;
     // ---- sums over the 8 frame groups -> packed sR[k][e]; class counts over the lanes -> sN[k] ----
     // (NW > 1: into this wavefront's slot of the shared buffer of this iteration)
     double* __restrict__ sOut = NW > 1 ? sShare + ((it & 1) * NW + wave) * kSumDoubles : sR;
+    if constexpr (DIRECT) {
+      store_direct_sums<D, K>(acc, nacc, sOut, le);
+      wave_lds_sync();
+    } else {
+    const int code = sSlot[le];
+    const int pidx = (code & 0x4000) ? -1 : (code & 0x3fff);
+    const double sgn = (code & 0x8000) ? -1.0 : 1.0;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
       double nv = wave_sum_f64(nacc[k]);
@@ -737,6 +858,7 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
         }
       wave_lds_sync();
     }
+    }
     if constexpr (NW > 1) {
       __syncthreads();                                  // every wavefront's sums of this iteration are in place
       const double* __restrict__ all = sShare + (it & 1) * NW * kSumDoubles;
@@ -754,7 +876,12 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
     wave_lds_sync();
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      cc[k] = sCC[k];
+      {
+        // the class constant is the same in every lane: kept in scalar registers across the tile loop
+        const double c = sCC[k];
+        cc[k] = __hiloint2double(__builtin_amdgcn_readfirstlane(__double2hiint(c)),
+                                 __builtin_amdgcn_readfirstlane(__double2loint(c)));
+      }
       if constexpr (RESIDENT) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -768,23 +895,13 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
 
   // final pass: the posteriors = the masks, zero padding included
   {
-    double acc[8][K];
+    typename PassAcc<D, K>::type acc;
     double nacc[K];
+    zero_acc(acc);
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-      nacc[k] = 0.0;
-#pragma unroll
-      for (int n = 0; n < 8; ++n) acc[n][k] = 0.0;
-    }
-    if constexpr (NW > 1) {
-      if (wave < tiles_total)
-        pass_tile<D, K, true, RESIDENT, true>(Yrow, abrow, creg, sC, cc, gamma_row, status, gamma_kstride, T, Tmax,
-                                              wave * kWave, lane, my_mask, sY, sW, acc, nacc, &pre);
-    } else {
-      for (int tile = 0; tile < tiles_total; ++tile)
-        pass_tile<D, K, true, RESIDENT>(Yrow, abrow, creg, sC, cc, gamma_row, status, gamma_kstride, T, Tmax, tile * kWave,
-                                        lane, tmrow[tile], sY, sW, acc, nacc);
-    }
+    for (int k = 0; k < K; ++k) nacc[k] = 0.0;
+    whole_pass<D, K, NW, true, RESIDENT>(Yrow, abrow, tmrow, creg, sC, cc, gamma_row, status, gamma_kstride, T, Tmax,
+                                         tiles_total, resident_tiles, wave, lane, my_mask, pre, sY, sW, acc, nacc);
   }
 }
 
@@ -797,6 +914,7 @@ constexpr int kWholeMinRounds = 3;
 constexpr int kWholeMaxTilesAlways = 5;
 constexpr int kWholeQuad = 4;                 // wavefronts per problem of the variant for tiny problems
 constexpr int kWholeQuadMaxD = 4;             // ... which is built for up to this many channels
+constexpr int kWholeDirectMaxTiles = 25;      // direct layout: tiles in a row up to which a pass costs less than its launches
 
 struct EmPlan {
   ChunkMap acc;          // chunking of the accumulating passes
@@ -858,15 +976,30 @@ int run_small(gss_ctx* ctx, const gss_yview& Y, const uint8_t* act, const int32_
                                                          : (long)kWholeMinRounds * ctx->num_cu * waves_per_cu;
   // (Problems of a few tiles also go there whatever their number: two launches per iteration cost more than
   // the whole EM of such a problem in one wavefront.)
-  const bool whole = n_sf >= whole_min || (ctx->em_whole_min_problems < 0 && tiles <= kWholeMaxTilesAlways);
-  if (iters > 0 && whole && n_sf <= 0x7fffffffL) {
-    // Tiny problems (at most 4 tiles, at most 4 channels) that fit the GPU in one round of four-wavefront
-    // workgroups: one tile per wavefront, its frames resident in registers.
-    bool tiny = false;
-    if constexpr (D <= kWholeQuadMaxD) {
+  bool whole = n_sf >= whole_min || (ctx->em_whole_min_problems < 0 && tiles <= kWholeMaxTilesAlways);
+  // Up to 4 channels there is the variant with four wavefronts per problem.  Tiny problems (at most 4 tiles) that
+  // fit the GPU in one round of such workgroups: one tile per wavefront, its frames resident in registers.  With
+  // the direct layout (cheap tiles, a launch costs as much as a few dozen of them) also longer problems, the
+  // wavefronts taking every fourth tile, when that means fewer tiles in a row than one wavefront per problem
+  // (rounds of resident wavefronts x tiles each; the meeting of the four sums counts as one tile); such batches
+  // go to the whole-EM kernel unless a pass is so long that the launches per iteration no longer matter.
+  bool tiny = false;
+  if constexpr (D <= kWholeQuadMaxD) {
+    if (ctx->em_whole_min_problems < 0 && n_sf > 0) {
       static const int quads_per_cu = resident_wgs(em_whole_small<D, K, kWholeQuad>, kWave * kWholeQuad, 2);
-      tiny = ctx->em_whole_min_problems < 0 && tiles <= kWholeQuad && n_sf <= (long)ctx->num_cu * quads_per_cu;
+      const long slots1 = (long)ctx->num_cu * waves_per_cu, slots4 = (long)ctx->num_cu * quads_per_cu;
+      const long cost1 = (n_sf + slots1 - 1) / slots1 * tiles;
+      const long cost4 = (n_sf + slots4 - 1) / slots4 * ((tiles + kWholeQuad - 1) / kWholeQuad + 1);
+      if (tiles <= kWholeQuad && n_sf <= slots4) {
+        tiny = whole;
+      } else if (direct_layout(D, K) && tiles > 1) {
+        const long best = cost4 < cost1 ? cost4 : cost1;
+        if (!whole && best <= kWholeDirectMaxTiles) whole = true;
+        tiny = whole && cost4 < cost1;
+      }
     }
+  }
+  if (iters > 0 && whole && n_sf <= 0x7fffffffL) {
     gss_profile_begin(ctx, 0, st);
     if constexpr (D <= kWholeQuadMaxD) {
       if (tiny)

@@ -129,20 +129,26 @@ def test_channel_and_class_counts(env, D, K):
 
 @pytest.mark.parametrize("D", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_every_small_instantiation(env, D):
-    """Every (D, K) kernel instantiation for D <= 8, K = 1..8, on two problems of 10 tiles with a ragged tail:
-    few problems on many workgroup slots, so every problem is cut into chunks and the factor kernel adds
-    several partial sums."""
-    for K in range(1, 9):
-        rng = np.random.default_rng(10 * D + K)
-        F, T = 2, 600
-        Y = (_cn(rng, (F, T, D)) * np.exp(rng.standard_normal((F, T, 1)))).astype(np.complex64)
-        act = (rng.random((K, T)) < 0.5).astype(np.uint8)
-        act[K - 1] = 1
-        T_len = np.array([T - 13], dtype=np.int32)
-        g = _gpu_em(env, Y[None], act[None], T_len, 3)[0]
-        go = env["o"].cacgmm_em_batch(Y[None], act[None], T_len, 3)[0]
-        assert np.max(np.abs(g - go)) <= TOL_GAMMA, (D, K)
-        assert np.all(g[:, :, T - 13:] == 0)
+    """Every (D, K) instantiation of the chunked kernels (one pass and one factor launch per iteration; forced
+    through the context option, few channels would take the whole-EM kernel here) for D <= 8, K = 1..8, on two
+    problems of 10 tiles with a ragged tail: few problems on many workgroup slots, so every problem is cut into
+    chunks and the factor kernel adds several partial sums."""
+    gss, ctx = env["gss"], env["ctx"]
+    ctx.set_option(gss.GSS_OPT_EM_WHOLE_MIN_PROBLEMS, 1 << 40)
+    try:
+        for K in range(1, 9):
+            rng = np.random.default_rng(10 * D + K)
+            F, T = 2, 600
+            Y = (_cn(rng, (F, T, D)) * np.exp(rng.standard_normal((F, T, 1)))).astype(np.complex64)
+            act = (rng.random((K, T)) < 0.5).astype(np.uint8)
+            act[K - 1] = 1
+            T_len = np.array([T - 13], dtype=np.int32)
+            g = _gpu_em(env, Y[None], act[None], T_len, 3)[0]
+            go = env["o"].cacgmm_em_batch(Y[None], act[None], T_len, 3)[0]
+            assert np.max(np.abs(g - go)) <= TOL_GAMMA, (D, K)
+            assert np.all(g[:, :, T - 13:] == 0)
+    finally:
+        ctx.set_option(gss.GSS_OPT_EM_WHOLE_MIN_PROBLEMS, -1)
     assert env["ctx"].get_status() == 0
 
 
@@ -210,6 +216,45 @@ def test_every_tiny_problem_instantiation(env, D):
         finally:
             ctx.set_option(gss.GSS_OPT_EM_WHOLE_MIN_PROBLEMS, -1)
         assert np.max(np.abs(g - g1)) <= 1e-5, (D, K)
+    assert env["ctx"].get_status() == 16                                # the zero-energy frame, nothing else
+
+
+@pytest.mark.parametrize("D", [1, 2, 3, 4])
+def test_few_channels_four_wavefronts_many_tiles(env, D):
+    """Few problems of more than 4 tiles at up to 4 channels: where the per-lane accumulators fit in registers
+    (D * D * K <= 80) the default is the whole-EM kernel with four wavefronts per problem, each walking every
+    fourth tile with the next tile requested ahead.  Every such (D, K): a ragged batch (13 and 6 tiles of 13,
+    the last one partly filled; in the short segment two wavefronts get one tile and two get two), tiles without
+    any active class, a zero-energy frame, both weight modes, the same bits on a second run, and agreement with
+    the one-wavefront kernel and the chunked kernels (forced through the context option) far inside the
+    tolerance."""
+    gss, ctx = env["gss"], env["ctx"]
+    for K in range(1, 9):
+        rng = np.random.default_rng(170 * D + K)
+        S, F, T = 2, 3, 800
+        Y = (_cn(rng, (S, F, T, D)) * np.exp(rng.standard_normal((S, F, T, 1)))).astype(np.complex64)
+        Y[0, :, 300] = 0
+        act = (rng.random((S, K, T)) < 0.5).astype(np.uint8)
+        act[:, K - 1] = 1
+        act[:, :, 128:256] = 0                         # two tiles in which nothing is active
+        if K > 1:
+            act[0, 0] = 0
+            act[1, 1 % K, :500] = 0
+        T_len = np.array([T, 370], dtype=np.int32)
+        for wm in (1, 0):
+            g = _gpu_em(env, Y, act, T_len, 4, wm)
+            go = env["o"].cacgmm_em_batch(Y, act, T_len, 4, wm)
+            assert np.max(np.abs(g - go)) <= TOL_GAMMA, (D, K, wm)
+            for s_ in range(S):
+                assert np.all(g[s_, :, :, T_len[s_]:] == 0)
+        assert np.array_equal(g, _gpu_em(env, Y, act, T_len, 4, 0))
+        for forced in (0, 1 << 40):
+            ctx.set_option(gss.GSS_OPT_EM_WHOLE_MIN_PROBLEMS, forced)
+            try:
+                g1 = _gpu_em(env, Y, act, T_len, 4, 0)
+            finally:
+                ctx.set_option(gss.GSS_OPT_EM_WHOLE_MIN_PROBLEMS, -1)
+            assert np.max(np.abs(g - g1)) <= 1e-5, (D, K, forced)
     assert env["ctx"].get_status() == 16                                # the zero-energy frame, nothing else
 
 
