@@ -712,10 +712,11 @@ __device__ __forceinline__ void whole_pass(
 // iteration, and the same fixed summation order on every run.
 //   NW = 1: for batches with many problems (segments x frequencies >> resident wavefronts); the wavefront
 //           walks all tiles of its problem; nothing is shared between wavefronts.
-//   NW = 4: for tiny problems (at most NW tiles, i.e. 256 frames; few of them, few channels): wavefront w owns
-//           tile w and keeps its frames in registers for all iterations, so an iteration reads nothing from
-//           memory.  The wavefronts' sums meet in LDS (two buffers, used in turn, one barrier per iteration),
-//           and every wavefront adds them up in the same order and runs the same factorisation on its own copy.
+//   NW = 4: for few problems of few channels.  At most NW tiles (256 frames): wavefront w owns tile w and keeps
+//           its frames in registers for all iterations, so an iteration reads nothing from memory.  More tiles:
+//           wavefront w walks tiles w, w + NW, ...  The wavefronts' sums meet in LDS (two buffers, used in turn,
+//           one barrier per iteration), and every wavefront adds them up in the same order and runs the same
+//           factorisation on its own copy.
 //
 // Factorisation in the wavefront: lane (k, i) = (lane / 8, lane % 8) holds row i of the matrix of class k
 // (8 complex numbers) in registers.  B_k = D R_k / N_k is Hermitised by construction (packed sums), scaled
@@ -757,7 +758,7 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
   int T;
   const float2* __restrict__ Yrow = y_row(yv, T_len, s, f, D, Tmax, T);
   const uint8_t* __restrict__ abrow = abyte + (long)s * Tmax;
-  const int tiles_total = (Tmax + kWave - 1) / kWave;   // NW > 1: at most NW (checked by the host)
+  const int tiles_total = (Tmax + kWave - 1) / kWave;
   typedef const __attribute__((address_space(4))) uint32_t* mask_ptr_t;
   const mask_ptr_t tmrow = (mask_ptr_t)(uintptr_t)(tmask + (long)s * tiles_total);
   float* __restrict__ gamma_row = gamma + ((long)s * K * F + f) * Tmax;
