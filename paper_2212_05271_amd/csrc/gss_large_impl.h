@@ -386,132 +386,172 @@ __device__ __forceinline__ void gauss_jordan_large(double (*sMr)[33], double (*s
   }
 }
 
-// The same sweeps with two copies of the matrix, read from one and written to the other: one barrier per
-// sweep, and every thread keeps its own entry in registers.  (sAr, sAi) holds the input; returns 0 if the
-// inverse ends up there, 1 if it is in (sBr, sBi).
-__device__ __forceinline__ int gauss_jordan_large_2buf(double (*sAr)[33], double (*sAi)[33], double (*sBr)[33],
-                                                       double (*sBi)[33], int D, int i, int j, bool on, uint32_t* status,
-                                                       uint32_t flag, double& detm, int& dete) {
-  detm = 1.0;
-  dete = 0;
-  double mr = 0.0, mi = 0.0;
-  if (on) { mr = sAr[i][j]; mi = sAi[i][j]; }
-  int cur = 0;
-  for (int p = 0; p < D; ++p) {
-    double (*rr)[33] = cur ? sBr : sAr;
-    double (*ri)[33] = cur ? sBi : sAi;
-    double (*wr)[33] = cur ? sAr : sBr;
-    double (*wi)[33] = cur ? sAi : sBi;
-    double piv = rr[p][p];
-    if (!(piv > 1e-300)) {
-      piv = 1e-300;
-      if (threadIdx.x == 0) atomicOr(status, flag);
-    }
-    detm *= piv;
-    dete += __builtin_amdgcn_frexp_exp(detm);
-    detm = __builtin_amdgcn_frexp_mant(detm);
-    const double rp = rcp_f64(piv);
-    if (on) {
-      const double air = rr[i][p], aii = ri[i][p];
-      const double apr = rr[p][j], api = ri[p][j];
-      double nr, ni;
-      if (i == p && j == p) {
-        nr = rp; ni = 0.0;
-      } else if (i == p) {
-        nr = apr * rp; ni = api * rp;
-      } else if (j == p) {
-        nr = -air * rp; ni = -aii * rp;
-      } else {
-        nr = mr - (air * apr - aii * api) * rp;
-        ni = mi - (air * api + aii * apr) * rp;
-      }
-      mr = nr;
-      mi = ni;
-      wr[i][j] = nr;
-      wi[i][j] = ni;
-    }
-    __syncthreads();       // the sweep's writes are visible; the buffer just read may be overwritten next
-    cur ^= 1;
-  }
-  return cur;
-}
-
 // ----------------------------------------------------------------------------------------------
-// Factor kernel, 9 <= D <= 32: one workgroup per (segment, frequency, class), D*D active threads.
+// Factor kernel, 9 <= D <= 32: one wavefront per (segment, frequency, class), a workgroup = the K classes of a
+// (segment, frequency).  The D x D matrix sits in the registers of the wavefront: lane (a, b) = (lane / 8,
+// lane % 8) holds the BS x BS block of rows a BS .. and columns b BS .. (BS = ceil(D / 8); rows and columns
+// beyond D are those of the identity and stay so).  In-place Gauss-Jordan sweeps without pivoting (B is Hermitian
+// positive definite after the loading; the product of the pivots is det B): the lanes that hold pivot row p and
+// pivot column p publish them in the wavefront's LDS, every lane reads back the entries of its own columns and
+// rows.  Nothing is shared between wavefronts, so there is no workgroup barrier.
 // ----------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void em_factor_large(
+template <int BS>
+__global__ __launch_bounds__(kWave * GSS_MAX_K) void em_factor_large(
     const double* __restrict__ part, const double* __restrict__ npart,
     double* __restrict__ coef, double* __restrict__ cmant, int32_t* __restrict__ cexp, uint32_t* __restrict__ status,
     int D, int K, ChunkMap cmap, int weight_mode) {
-  __shared__ double sMr[32][33], sMi[32][33], sM2r[32][33], sM2i[32][33];
-  __shared__ double sN[GSS_MAX_K];
+  constexpr int W = 8 * BS;                                // padded matrix size
+  __shared__ double sPiv[GSS_MAX_K][4][W];                 // per wavefront: pivot row (re, im), pivot column (re, im)
+  const int lane = threadIdx.x & (kWave - 1);
+  const int k = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const long sf = blockIdx.x;
+  const int a = lane >> 3, b = lane & 7;
   const int M = num_items(D);
-  const long sf = blockIdx.x / K;
-  const int k = blockIdx.x % K;
   int C;
   const long slot0 = chunk_base(cmap, sf, C);
-  const int tid = threadIdx.x;
-  const int i = tid / D, j = tid % D;
-  const bool on = tid < D * D;
+  double* __restrict__ rowR = sPiv[k][0];
+  double* __restrict__ rowI = sPiv[k][1];
+  double* __restrict__ colR = sPiv[k][2];
+  double* __restrict__ colI = sPiv[k][3];
 
-  if (tid < K) {
-    double n = 0.0;
-    for (int c = 0; c < C; ++c) n += npart[(slot0 + c) * K + tid];
-    sN[tid] = n;
-  }
-  if (on && i <= j) {
-    const int m = item_index(i, j, D);
-    double re = 0.0, im = 0.0;
-    for (int c = 0; c < C; ++c) {
-      const double* p = part + (((slot0 + c) * (long)M + m) * K + k) * 2;
-      re += p[0];
-      im += p[1];
+  // class counts: lane l < K adds the chunks' counts of class l (in chunk order)
+  double nl = 0.0;
+  if (lane < K)
+    for (int c = 0; c < C; ++c) nl += npart[(slot0 + c) * K + lane];
+  const double Nk = __shfl(nl, k, kWave);
+  double Ntot = 0.0;
+  for (int kk = 0; kk < K; ++kk) Ntot += __shfl(nl, kk, kWave);
+
+  // the lane's block of R_k = sum over the chunks (in chunk order) of the packed partial sums; entry (i, j) with
+  // i > j is the conjugate of item (j, i)
+  double mr[BS][BS], mi[BS][BS];
+  int item[BS][BS];
+#pragma unroll
+  for (int r = 0; r < BS; ++r)
+#pragma unroll
+    for (int c = 0; c < BS; ++c) {
+      const int i = a * BS + r, j = b * BS + c;
+      const int lo = i < j ? i : j, hi = i < j ? j : i;
+      item[r][c] = (hi < D) ? item_index(lo, hi, D) : 0;
+      mr[r][c] = 0.0;
+      mi[r][c] = 0.0;
     }
-    sMr[i][j] = re; sMi[i][j] = im;
-    if (i != j) { sMr[j][i] = re; sMi[j][i] = -im; }
+  for (int ch = 0; ch < C; ++ch) {
+    const double* __restrict__ pc = part + ((slot0 + ch) * (long)M * K + k) * 2;
+#pragma unroll
+    for (int r = 0; r < BS; ++r)
+#pragma unroll
+      for (int c = 0; c < BS; ++c) {
+        const double2 v = *reinterpret_cast<const double2*>(pc + (long)item[r][c] * K * 2);
+        mr[r][c] += v.x;
+        mi[r][c] += v.y;
+      }
   }
-  __syncthreads();
-  double tr = 0.0;
-  for (int r = 0; r < D; ++r) tr += sMr[r][r];
-  const double Nk = sN[k];
+  double trl = 0.0;
+#pragma unroll
+  for (int r = 0; r < BS; ++r)
+#pragma unroll
+    for (int c = 0; c < BS; ++c) {
+      const int i = a * BS + r, j = b * BS + c;
+      const bool in = i < D && j < D;
+      mr[r][c] = in ? mr[r][c] : 0.0;
+      mi[r][c] = in ? (i < j ? mi[r][c] : (i > j ? -mi[r][c] : 0.0)) : 0.0;
+      if (r == c && a == b) trl += mr[r][c];
+    }
+  const double tr = wave_sum_f64(trl);
+  // B = D R / max(N, eps); dead if its trace <= eps; else rescaled to trace D (= R * D / tr R); loading delta I
   const double trB = (double)D * tr / fmax(Nk, GSS_EPS_N);
   const bool dead = !(trB > GSS_EPS_N);
-  __syncthreads();
-  if (on) {
-    double mr, mi;
-    if (dead) {
-      mr = (i == j) ? 1.0 : 0.0;
-      mi = 0.0;
-    } else {
-      const double sc = (double)D / tr;
-      mr = sMr[i][j] * sc;
-      mi = (i == j) ? 0.0 : sMi[i][j] * sc;
+  const double sc = dead ? 0.0 : (double)D / tr;
+#pragma unroll
+  for (int r = 0; r < BS; ++r)
+#pragma unroll
+    for (int c = 0; c < BS; ++c) {
+      const int i = a * BS + r, j = b * BS + c;
+      const bool in = i < D && j < D;
+      double vr = dead ? 0.0 : mr[r][c] * sc, vi = dead ? 0.0 : mi[r][c] * sc;
+      if (i == j) {
+        vr = dead ? 1.0 : vr;
+        vi = 0.0;
+        vr = in ? vr + GSS_DELTA : 1.0;                    // beyond D: the identity
+      }
+      mr[r][c] = vr;
+      mi[r][c] = vi;
     }
-    if (i == j) mr += GSS_DELTA;
-    sMr[i][j] = mr; sMi[i][j] = mi;
+
+  double detm = 1.0;
+  int dete = 0;
+  // (kept as a loop: unrolled, the 8 BS sweeps are straight-line code that every wavefront runs once, and the
+  // kernel then waits for instruction fetches most of the time)
+#pragma unroll 1
+  for (int pg = 0; pg < 8; ++pg) {
+    static_for<0, BS>([&](auto PP) {
+      constexpr int pp = decltype(PP)::value;
+      const int p = pg * BS + pp;
+      if (p < D) {                                         // the same in every lane
+        if (a == pg) {
+#pragma unroll
+          for (int c = 0; c < BS; ++c) { rowR[b * BS + c] = mr[pp][c]; rowI[b * BS + c] = mi[pp][c]; }
+        }
+        if (b == pg) {
+#pragma unroll
+          for (int r = 0; r < BS; ++r) { colR[a * BS + r] = mr[r][pp]; colI[a * BS + r] = mi[r][pp]; }
+        }
+        wave_lds_sync();
+        double piv = rowR[p];
+        double pr[BS], pim[BS], cr[BS], cim[BS];
+#pragma unroll
+        for (int c = 0; c < BS; ++c) { pr[c] = rowR[b * BS + c]; pim[c] = rowI[b * BS + c]; }
+#pragma unroll
+        for (int r = 0; r < BS; ++r) { cr[r] = colR[a * BS + r]; cim[r] = colI[a * BS + r]; }
+        wave_lds_sync();                                   // read before the next sweep writes
+        if (!(piv > 1e-300)) {
+          piv = 1e-300;
+          if (lane == 0) atomicOr(status, GSS_STATUS_NONPD_B);
+        }
+        detm *= piv;
+        dete += __builtin_amdgcn_frexp_exp(detm);
+        detm = __builtin_amdgcn_frexp_mant(detm);
+        const double rp = rcp_f64(piv);
+        // Every entry takes m - (column entry)(row entry) / pivot.  With pivot - 1 in place of the column entry
+        // of the pivot row this gives (row entry) / pivot there, and with pivot + 1 in place of the row entry of
+        // the pivot column it gives -(column entry) / pivot there; the pivot itself becomes 1 / pivot.
+        const bool prow = a == pg, pcol = b == pg;
+        cr[pp] = prow ? piv - 1.0 : cr[pp];
+        cim[pp] = prow ? 0.0 : cim[pp];
+        pr[pp] = pcol ? piv + 1.0 : pr[pp];
+        pim[pp] = pcol ? 0.0 : pim[pp];
+#pragma unroll
+        for (int r = 0; r < BS; ++r)
+#pragma unroll
+          for (int c = 0; c < BS; ++c) {
+            const double air = cr[r], aii = cim[r], apr = pr[c], api = pim[c];
+            mr[r][c] -= (air * apr - aii * api) * rp;
+            mi[r][c] -= (air * api + aii * apr) * rp;
+          }
+        if (prow && pcol) { mr[pp][pp] = rp; mi[pp][pp] = 0.0; }
+      }
+    });
   }
-  __syncthreads();
-  double detm;
-  int dete;
-  const int where = gauss_jordan_large_2buf(sMr, sMi, sM2r, sM2i, D, i, j, on, status, GSS_STATUS_NONPD_B, detm, dete);
+
+  // coefficients of <B^-1, y y^H> over the items: the diagonal entry, twice the off-diagonal entry
   const int CP = coef_pitch(D);
-  if (on && i <= j) {
-    const int m = item_index(i, j, D);
-    double* c = coef + (sf * K + k) * (long)CP + 2 * m;
-    const double ar = where ? sM2r[i][j] : sMr[i][j], ai = where ? sM2i[i][j] : sMi[i][j];
-    if (i == j) { c[0] = ar; c[1] = 0.0; }
-    else { c[0] = 2.0 * ar; c[1] = 2.0 * ai; }
-  }
-  if (tid < CP - 2 * M) coef[(sf * K + k) * (long)CP + 2 * M + tid] = 0.0;       // the padding stays zero
-  if (tid == 0) {
-    double pi;
-    if (weight_mode == 1) {
-      double tot = 0.0;
-      for (int kk = 0; kk < K; ++kk) tot += sN[kk];
-      pi = Nk / fmax(tot, GSS_EPS_N);
-    } else {
-      pi = 1.0 / (double)K;
+  double* __restrict__ cf = coef + (sf * K + k) * (long)CP;
+#pragma unroll
+  for (int r = 0; r < BS; ++r)
+#pragma unroll
+    for (int c = 0; c < BS; ++c) {
+      const int i = a * BS + r, j = b * BS + c;
+      if (i <= j && j < D) {
+        double2 v;
+        if (i == j) v = make_double2(mr[r][c], 0.0);
+        else v = make_double2(2.0 * mr[r][c], 2.0 * mi[r][c]);
+        *reinterpret_cast<double2*>(cf + 2 * item[r][c]) = v;
+      }
     }
+  if (lane < CP - 2 * M) cf[2 * M + lane] = 0.0;           // the padding stays zero (fewer than 16 entries)
+  if (lane == 0) {
+    const double pi = weight_mode == 1 ? Nk / fmax(Ntot, GSS_EPS_N) : 1.0 / (double)K;
     const double cst = fmax(pi, GSS_EPS_PI) / detm;
     cmant[sf * K + k] = __builtin_amdgcn_frexp_mant(cst);
     cexp[sf * K + k] = __builtin_amdgcn_frexp_exp(cst) - dete;
@@ -761,7 +801,6 @@ int run_em_large(gss_ctx* ctx, const gss_yview& Y, const uint8_t* act, const int
   double* part = (double*)(base + off_part);
   double* npart = (double*)(base + off_npart);
   const dim3 block(kWave * kLargeWaves);
-  const int fthreads = (D * D + 63) / 64 * 64;
   hipLaunchKernelGGL(em_init_coef_large, dim3(1024), dim3(256), 0, st, coef, cm, ce, D, K, n_sf);
   hipLaunchKernelGGL(em_pack_activity, dim3((unsigned)(S * tiles)), dim3(kWave), 0, st, Y, act, T_len, abyte, tmask, K,
                      Tmax, tiles);
@@ -771,8 +810,15 @@ int run_em_large(gss_ctx* ctx, const gss_yview& Y, const uint8_t* act, const int
                        coef, cm, ce, part, npart, (float*)nullptr, ctx->status, F, Tmax, D, acc_map, p.RS, p.tile_bytes);
     gss_profile_end(ctx, 0, st);
     gss_profile_begin(ctx, 1, st);
-    hipLaunchKernelGGL(em_factor_large, dim3((unsigned)(n_sf * K)), dim3(fthreads), 0, st, part, npart, coef, cm, ce,
-                       ctx->status, D, K, acc_map, weight_mode);
+    if (D <= 16)
+      hipLaunchKernelGGL(em_factor_large<2>, dim3((unsigned)n_sf), dim3(kWave * K), 0, st, part, npart, coef, cm, ce,
+                         ctx->status, D, K, acc_map, weight_mode);
+    else if (D <= 24)
+      hipLaunchKernelGGL(em_factor_large<3>, dim3((unsigned)n_sf), dim3(kWave * K), 0, st, part, npart, coef, cm, ce,
+                         ctx->status, D, K, acc_map, weight_mode);
+    else
+      hipLaunchKernelGGL(em_factor_large<4>, dim3((unsigned)n_sf), dim3(kWave * K), 0, st, part, npart, coef, cm, ce,
+                         ctx->status, D, K, acc_map, weight_mode);
     gss_profile_end(ctx, 1, st);
   }
   hipLaunchKernelGGL((em_pass_large<K, NR, true>), dim3((unsigned)wgs_fin), block, p.lds_bytes, st, Y, abyte, tmask, T_len, coef,
