@@ -110,7 +110,9 @@ __device__ __forceinline__ double dpp_permute_f64(double x) {
 __device__ __forceinline__ int transposed_index(int lane) {
   return (int)(__brev((unsigned)(lane & 15)) >> 28) | (lane & 48);
 }
-template <int N>
+// ROWS_ONLY: only the four steps inside the rows of 16 lanes: lane l then holds in v[j] the sum over its row of
+// value 16 j + transposed_index(l & 15), and the caller adds the four rows itself.
+template <int N, bool ROWS_ONLY = false>
 __device__ __forceinline__ void transpose_reduce(double (&v)[N], int lane) {
   auto step = [&](auto CNT, bool second, auto perm) {
     constexpr int n = decltype(CNT)::value;
@@ -130,8 +132,10 @@ __device__ __forceinline__ void transpose_reduce(double (&v)[N], int lane) {
   step(std::integral_constant<int, n1>{}, (lane & 4) != 0, [](double x) { return dpp_permute_f64<0x141>(x); });  // row_half_mirror
   step(std::integral_constant<int, n2>{}, (lane & 2) != 0, [](double x) { return dpp_permute_f64<0x4E>(x); });   // quad_perm [2, 3, 0, 1]
   step(std::integral_constant<int, n3>{}, (lane & 1) != 0, [](double x) { return dpp_permute_f64<0xB1>(x); });   // quad_perm [1, 0, 3, 2]
-  step(std::integral_constant<int, n4>{}, (lane & 16) != 0, [](double x) { return __shfl_xor(x, 16, kWave); });
-  step(std::integral_constant<int, n5>{}, (lane & 32) != 0, [](double x) { return __shfl_xor(x, 32, kWave); });
+  if constexpr (!ROWS_ONLY) {
+    step(std::integral_constant<int, n4>{}, (lane & 16) != 0, [](double x) { return __shfl_xor(x, 16, kWave); });
+    step(std::integral_constant<int, n5>{}, (lane & 32) != 0, [](double x) { return __shfl_xor(x, 32, kWave); });
+  }
 }
 
 // Position (row i, column j >= i, part: 0 diagonal, 1 real, 2 imaginary) of packed index idx.

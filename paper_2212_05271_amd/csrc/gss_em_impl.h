@@ -288,8 +288,10 @@ __device__ __forceinline__ void pass_tile(
 }
 
 // Direct layout: the wavefront's totals of the accumulators acc[k][e] and the class counts nacc[k], written as
-// out[k * E + e] and out[K * E + k] (LDS; the caller orders the traffic).
-template <int D, int K>
+// out[k * E + e] and out[K * E + k] (LDS; the caller orders the traffic).  ROWS: the sums of the four rows of 16
+// lanes separately, row r at out[r * (K * E + K) + ...], for a caller that adds several such sets anyway (two
+// exchange steps less).
+template <int D, int K, bool ROWS = false>
 __device__ __forceinline__ void store_direct_sums(const typename PassAcc<D, K>::type& acc, const double (&nacc)[K],
                                                   double* __restrict__ out, int lane) {
   constexpr int E = D * D, N = K * E + K;
@@ -300,11 +302,19 @@ __device__ __forceinline__ void store_direct_sums(const typename PassAcc<D, K>::
     for (int e = 0; e < E; ++e) v[k * E + e] = acc[k][e];
     v[K * E + k] = nacc[k];
   }
-  transpose_reduce<N>(v, lane);
-  const int n0 = transposed_index(lane);
+  transpose_reduce<N, ROWS>(v, lane);
+  if constexpr (ROWS) {
+    const int n0 = transposed_index(lane & 15);
+    double* __restrict__ orow = out + (lane >> 4) * N;
 #pragma unroll
-  for (int j = 0; j < (N + kWave - 1) / kWave; ++j)
-    if (n0 + kWave * j < N) out[n0 + kWave * j] = v[j];
+    for (int j = 0; j < (N + 15) / 16; ++j)
+      if (n0 + 16 * j < N) orow[n0 + 16 * j] = v[j];
+  } else {
+    const int n0 = transposed_index(lane);
+#pragma unroll
+    for (int j = 0; j < (N + kWave - 1) / kWave; ++j)
+      if (n0 + kWave * j < N) out[n0 + kWave * j] = v[j];
+  }
 }
 
 template <int D, int K, bool FINAL>
@@ -449,8 +459,9 @@ __device__ __forceinline__ void factor_classes_in_wave(const double* __restrict_
 #pragma unroll
   for (int k = 0; k < K; ++k) Ntot += sN[k];
   // B = D R / max(N, eps); dead if its trace <= eps; else rescaled to trace D (= R * D / tr R)
-  const bool dead = !((double)D * tr / fmax(Nk, GSS_EPS_N) > GSS_EPS_N);
-  const double sc = dead ? 0.0 : (double)D / tr;
+  // (the test without its division, the scale with a reciprocal: both sit in front of the sweeps)
+  const bool dead = !((double)D * tr > GSS_EPS_N * fmax(Nk, GSS_EPS_N));
+  const double sc = dead ? 0.0 : (double)D * rcp_f64(tr);
   {
     double v0[8], v1[8];
 #pragma unroll
@@ -738,7 +749,8 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
   constexpr int kCoefDoubles = K * R * 16;             // packed coefficients, padded to whole registers
   constexpr int kSumDoubles = K * E + K;               // packed weighted scatter sums, then the class counts
   constexpr int kWaveDoubles = (kTileDoubles + kCoefDoubles + kSumDoubles + K + 1) / 2 * 2;
-  constexpr int kShareDoubles = NW > 1 ? 2 * NW * kSumDoubles : 0;
+  constexpr int kShareRows = DIRECT ? 4 : 1;           // sets of sums per wavefront in the shared buffer (NW > 1)
+  constexpr int kShareDoubles = NW > 1 ? 2 * NW * kShareRows * kSumDoubles : 0;
   __shared__ __attribute__((aligned(16))) double lds[NW * kWaveDoubles + kShareDoubles];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = NW > 1 ? __builtin_amdgcn_readfirstlane(threadIdx.x / kWave) : 0;
@@ -748,7 +760,7 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
   double* __restrict__ sR = sC + kCoefDoubles;         // [K][E] packed weighted scatter sums
   double* __restrict__ sN = sR + K * E;                // [K] class counts
   double* __restrict__ sCC = sN + K;                   // [K] class constants pi / det B
-  double* __restrict__ sShare = lds + NW * kWaveDoubles;   // [2][NW][kSumDoubles] sums of the wavefronts (NW > 1)
+  double* __restrict__ sShare = lds + NW * kWaveDoubles;   // [2][NW][kShareRows][kSumDoubles] sums of the wavefronts (NW > 1)
   __shared__ int sSlotAll[NW * kWave];
   int* __restrict__ sSlot = sSlotAll + wave * kWave;       // [64] packed index and sign of the lane's reduction slot
 
@@ -827,9 +839,9 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
     asm volatile("" : "+v"(le));
     // ---- sums over the 8 frame groups -> packed sR[k][e]; class counts over the lanes -> sN[k] ----
     // (NW > 1: into this wavefront's slot of the shared buffer of this iteration)
-    double* __restrict__ sOut = NW > 1 ? sShare + ((it & 1) * NW + wave) * kSumDoubles : sR;
+    double* __restrict__ sOut = NW > 1 ? sShare + ((it & 1) * NW + wave) * (kShareRows * kSumDoubles) : sR;
     if constexpr (DIRECT) {
-      store_direct_sums<D, K>(acc, nacc, sOut, le);
+      store_direct_sums<D, K, (NW > 1)>(acc, nacc, sOut, le);
       wave_lds_sync();
     } else {
     const int code = sSlot[le];
@@ -862,11 +874,11 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
     }
     if constexpr (NW > 1) {
       __syncthreads();                                  // every wavefront's sums of this iteration are in place
-      const double* __restrict__ all = sShare + (it & 1) * NW * kSumDoubles;
+      const double* __restrict__ all = sShare + (it & 1) * (NW * kShareRows * kSumDoubles);
       for (int e = le; e < kSumDoubles; e += kWave) {
         double sum = all[e];
 #pragma unroll
-        for (int w = 1; w < NW; ++w) sum += all[w * kSumDoubles + e];
+        for (int w = 1; w < NW * kShareRows; ++w) sum += all[w * kSumDoubles + e];
         sR[e] = sum;                                    // sN follows sR
       }
       wave_lds_sync();
