@@ -72,13 +72,33 @@ __global__ void em_init_coef_large(double* __restrict__ coef, double* __restrict
 
 // Cooperative, coalesced copy of one tile of frames [t0, t0 + 64) of a (segment, frequency) row into the
 // wavefront's LDS tile sY[frame][D] (float2, row stride RS float2); frames at or beyond T become zero.
+// The tile is one contiguous run of 64 D values in memory; lane l copies values l, l + 64, ... (D of them).  Their
+// frame and channel are stepped without divisions, and the loads go out six at a time before the first of them
+// is stored (one at a time, every value would wait out a full memory latency).
 __device__ __forceinline__ void load_tile(const float2* __restrict__ Yrow, int t0, int T, int D, int RS,
                                           float2* __restrict__ sY, int lane) {
-  const int n = kWave * D;
-  for (int x = lane; x < n; x += kWave) {
-    const int r = x / D, c = x - r * D;
-    const int t = t0 + r;
-    sY[r * RS + c] = (t < T) ? Yrow[(long)t * D + c] : make_float2(0.f, 0.f);
+  constexpr int kBatch = 12;
+  const int rstep = kWave / D, cstep = kWave % D;          // frame and channel advance per 64 values
+  int r = lane / D, c = lane - r * D;
+  const float2* __restrict__ src = Yrow + (long)t0 * D + lane;
+  const int rows = T - t0;                                   // frames of the tile that exist (may exceed 64)
+  for (int i0 = 0; i0 < D; i0 += kBatch) {
+    float2 v[kBatch];
+    int off[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      v[u] = make_float2(0.f, 0.f);
+      off[u] = r * RS + c;
+      if (i0 + u < D) {
+        if (r < rows) v[u] = src[(long)(i0 + u) * kWave];
+        c += cstep;
+        r += rstep;
+        if (c >= D) { c -= D; ++r; }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u)
+      if (i0 + u < D) sY[off[u]] = v[u];
   }
 }
 
