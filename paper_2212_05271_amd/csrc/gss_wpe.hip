@@ -19,6 +19,27 @@
 namespace {
 
 constexpr int kWpeThreads = 256;
+
+// Staging loop of a workgroup: elements e = first, first + stride, ... below n; load(e) fetches one from memory,
+// store(e, v) puts it where it belongs (LDS).  BATCH loads are issued before the first of them is stored: written
+// as a plain loop, each element waits out a full memory latency before the next load goes out.
+template <int BATCH, class V, class Load, class Store>
+__device__ __forceinline__ void staged_copy(int first, int n, int stride, Load load, Store store) {
+  for (int e0 = first; e0 < n; e0 += BATCH * stride) {
+    V v[BATCH];
+#pragma unroll
+    for (int u = 0; u < BATCH; ++u) {
+      const int e = e0 + u * stride;
+      v[u] = V{};
+      if (e < n) v[u] = load(e);
+    }
+#pragma unroll
+    for (int u = 0; u < BATCH; ++u) {
+      const int e = e0 + u * stride;
+      if (e < n) store(e, v[u]);
+    }
+  }
+}
 constexpr int kWpeTile = 64;                  // frames per LDS window of the covariance kernel
 constexpr int kWpeBlockDoubles = 32;          // a 4 x 4 complex block of R or P per lane
 constexpr double kWpeEpsPowerRel = 1e-10;
@@ -66,16 +87,14 @@ __global__ __launch_bounds__(kWpeThreads) void wpe_power_kernel(const float2* __
   const int pitch = D | 1;                                // odd: the frames' rows start in different banks
   const float2* __restrict__ Yblk = Y + (sf * Tmax + t0) * D;
   const int n_valid = (T - t0 < fb ? (T - t0 > 0 ? T - t0 : 0) : fb) * D;
-  for (int e = threadIdx.x; e < fb * D; e += kWpeThreads) {
-    const int r = e / D, d = e - r * D;
-    double p = 0.0;
-    if (e < n_valid) {
-      const float2 v = Yblk[e];
-      const double re = v.x, im = v.y;
-      p = re * re + im * im;
-    }
-    sP[r * pitch + d] = p;
-  }
+  staged_copy<4, float2>(
+      threadIdx.x, fb * D, kWpeThreads,
+      [&](int e) { return e < n_valid ? Yblk[e] : make_float2(0.f, 0.f); },
+      [&](int e, float2 v) {
+        const int r = e / D, d = e - r * D;
+        const double re = v.x, im = v.y;
+        sP[r * pitch + d] = re * re + im * im;
+      });
   __syncthreads();
   const int t = t0 + threadIdx.x;
   if ((int)threadIdx.x >= fb || t >= Tmax) return;
@@ -152,13 +171,14 @@ __global__ __launch_bounds__(kWpeThreads) void wpe_cov_kernel(const float2* __re
     const int t0 = tile * kWpeTile;
     const int tmax = t0 + kWpeTile - 1;
     __syncthreads();                                    // the previous tile's window is no longer read
-    for (int e = threadIdx.x; e < win_elems; e += kWpeThreads) {
-      const int r = e / D, d = e - r * D;
-      const int t = tmax - r;
-      float2 v = make_float2(0.f, 0.f);
-      if (r < win_frames && t >= 0 && t < T) v = Yrow[(long)t * D + d];
-      sWin[e] = make_double2((double)v.x, (double)v.y);  // converted once here, not at every use
-    }
+    staged_copy<4, float2>(
+        threadIdx.x, win_elems, kWpeThreads,
+        [&](int e) {
+          const int r = e / D, d = e - r * D;
+          const int t = tmax - r;
+          return (r < win_frames && t >= 0 && t < T) ? Yrow[(long)t * D + d] : make_float2(0.f, 0.f);
+        },
+        [&](int e, float2 v) { sWin[e] = make_double2((double)v.x, (double)v.y); });   // converted once here, not at every use
     if (threadIdx.x < kWpeTile) {
       const int t = t0 + threadIdx.x;
       double w = 0.0;
@@ -410,13 +430,17 @@ __global__ __launch_bounds__(kWpeThreads) void wpe_apply_kernel(const float2* __
   const int past = delay + taps - 1;                     // frames before t0 that the block needs
   const int rows = kWpeThreads + past;
   const float2* __restrict__ Yrow = Y + sf * (long)Tmax * D;
-  for (int e = threadIdx.x; e < rows * D; e += kWpeThreads) {
-    const int r = e / D, d = e - r * D;
-    const int tt = t0 - past + r;
-    float2 v = make_float2(0.f, 0.f);
-    if (tt >= 0 && tt < T) v = Yrow[(long)tt * D + d];
-    sWin[r * pitch + d] = v;
-  }
+  staged_copy<6, float2>(
+      threadIdx.x, rows * D, kWpeThreads,
+      [&](int e) {
+        const int r = e / D, d = e - r * D;
+        const int tt = t0 - past + r;
+        return (tt >= 0 && tt < T) ? Yrow[(long)tt * D + d] : make_float2(0.f, 0.f);
+      },
+      [&](int e, float2 v) {
+        const int r = e / D, d = e - r * D;
+        sWin[r * pitch + d] = v;
+      });
   __syncthreads();
   double xr[D], xi[D];
   const float2* __restrict__ mine = sWin + (threadIdx.x + past) * pitch;
@@ -776,13 +800,17 @@ __global__ __launch_bounds__(kWpeThreads) void wpe_apply_large_kernel(const floa
   const int past = delay + taps - 1;
   const int rows = fb + past;
   const float2* __restrict__ Yrow = Y + sf * (long)Tmax * D;
-  for (int e = threadIdx.x; e < rows * D; e += kWpeThreads) {
-    const int r = e / D, d = e - r * D;
-    const int tt = t0 - past + r;
-    float2 v = make_float2(0.f, 0.f);
-    if (tt >= 0 && tt < T) v = Yrow[(long)tt * D + d];
-    sWin[r * pitch + d] = v;
-  }
+  staged_copy<6, float2>(
+      threadIdx.x, rows * D, kWpeThreads,
+      [&](int e) {
+        const int r = e / D, d = e - r * D;
+        const int tt = t0 - past + r;
+        return (tt >= 0 && tt < T) ? Yrow[(long)tt * D + d] : make_float2(0.f, 0.f);
+      },
+      [&](int e, float2 v) {
+        const int r = e / D, d = e - r * D;
+        sWin[r * pitch + d] = v;
+      });
   __syncthreads();
   if ((int)threadIdx.x >= fb) return;
   constexpr int DM = 32;
