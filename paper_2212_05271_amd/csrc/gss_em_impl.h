@@ -665,6 +665,28 @@ __global__ __launch_bounds__(kWave * K) void em_factor_small(
   }
 }
 
+// Order in which the whole-EM kernel takes the segments of a ragged batch: longest first (equal lengths in index
+// order), so that the long problems start early and the launch does not end with a few wavefronts still walking
+// the longest segments.  order[rank] = segment; one thread per segment counts the segments ahead of its own.
+// Beyond kOrderMaxSegments the order is left as it is (the count is quadratic in the number of segments).
+constexpr int kOrderMaxSegments = 4096;
+__global__ __launch_bounds__(256) void em_order_segments(gss_yview yv, const int32_t* __restrict__ T_len, int Tmax, int S,
+                                                         int32_t* __restrict__ order) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= S) return;
+  if (S > kOrderMaxSegments) {
+    order[s] = s;
+    return;
+  }
+  const int T = y_frames(yv, T_len, s, Tmax);
+  int rank = 0;
+  for (int o = 0; o < S; ++o) {
+    const int To = y_frames(yv, T_len, o, Tmax);
+    rank += (To > T || (To == T && o < s)) ? 1 : 0;
+  }
+  order[rank] = s;
+}
+
 // One pass of a wavefront of the whole-EM kernel over its tiles below tile_end: the one resident tile (NW > 1,
 // resident_tiles), or tiles wave, wave + NW, ...  With the direct layout and not too many accumulators there are
 // registers to spare, and the frames of the next tile are requested from memory before the current tile is worked on.
@@ -738,8 +760,8 @@ __device__ __forceinline__ void whole_pass(
 template <int D, int K, int NW>
 __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
     gss_yview yv, const uint8_t* __restrict__ abyte, const uint32_t* __restrict__ tmask,
-    const int32_t* __restrict__ T_len, float* __restrict__ gamma, uint32_t* __restrict__ status,
-    int F, int Tmax, int iters, int weight_mode) {
+    const int32_t* __restrict__ T_len, const int32_t* __restrict__ seg_order, float* __restrict__ gamma,
+    uint32_t* __restrict__ status, int F, int Tmax, int iters, int weight_mode) {
   constexpr int E = D * D;
   constexpr int R = coef_regs(D);
   constexpr bool RESIDENT = K * R <= kResidentRegs;
@@ -764,9 +786,14 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
   __shared__ int sSlotAll[NW * kWave];
   int* __restrict__ sSlot = sSlotAll + wave * kWave;       // [64] packed index and sign of the lane's reduction slot
 
+  // workgroup -> (segment, frequency): the segments in the order of seg_order (longest first), if given
   const long sf = blockIdx.x;
-  const int s = (int)((unsigned)sf / (unsigned)F);
+  int s = (int)((unsigned)sf / (unsigned)F);
   const int f = (int)((unsigned)sf % (unsigned)F);
+  if (seg_order) {
+    typedef const __attribute__((address_space(4))) int32_t* order_ptr_t;
+    s = ((order_ptr_t)(uintptr_t)seg_order)[s];
+  }
   int T;
   const float2* __restrict__ Yrow = y_row(yv, T_len, s, f, D, Tmax, T);
   const uint8_t* __restrict__ abrow = abyte + (long)s * Tmax;
@@ -933,7 +960,7 @@ struct EmPlan {
   ChunkMap acc;          // chunking of the accumulating passes
   ChunkMap fin;          // chunking of the final pass
   long wgs_acc, wgs_fin;
-  size_t off_coef, off_cc, off_part, off_npart, off_abyte, off_tmask, total;
+  size_t off_coef, off_cc, off_part, off_npart, off_abyte, off_tmask, off_order, total;
 };
 
 EmPlan make_plan(const gss_ctx* ctx, long n_sf, int S, int Tmax, int D, int K, int wgs_per_cu, int wgs_per_cu_fin) {
@@ -953,6 +980,7 @@ EmPlan make_plan(const gss_ctx* ctx, long n_sf, int S, int Tmax, int D, int K, i
   p.off_npart = o; o = gss_align_up(o + (size_t)p.wgs_acc * K * sizeof(double), 256);
   p.off_abyte = o; o = gss_align_up(o + (size_t)S * Tmax, 256);
   p.off_tmask = o; o = gss_align_up(o + (size_t)S * tiles * sizeof(uint32_t), 256);
+  p.off_order = o; o = gss_align_up(o + (size_t)S * sizeof(int32_t), 256);
   p.total = o;
   return p;
 }
@@ -974,6 +1002,7 @@ int run_small(gss_ctx* ctx, const gss_yview& Y, const uint8_t* act, const int32_
   double* npart = (double*)(base + p.off_npart);
   uint8_t* abyte = (uint8_t*)(base + p.off_abyte);
   uint32_t* tmask = (uint32_t*)(base + p.off_tmask);
+  int32_t* order = (int32_t*)(base + p.off_order);
   const int tiles = (Tmax + kWave - 1) / kWave;
 
   if ((long)S * tiles > 0x7fffffffL) return GSS_EUNSUPPORTED;
@@ -1013,15 +1042,21 @@ int run_small(gss_ctx* ctx, const gss_yview& Y, const uint8_t* act, const int32_
     }
   }
   if (iters > 0 && whole && n_sf <= 0x7fffffffL) {
+    // a ragged batch is taken longest segment first
+    const int32_t* seg_order = nullptr;
+    if (S > 1 && T_len) {
+      hipLaunchKernelGGL(em_order_segments, dim3((unsigned)((S + 255) / 256)), dim3(256), 0, st, Y, T_len, Tmax, S, order);
+      seg_order = order;
+    }
     gss_profile_begin(ctx, 0, st);
     if constexpr (D <= kWholeQuadMaxD) {
       if (tiny)
         hipLaunchKernelGGL((em_whole_small<D, K, kWholeQuad>), dim3((unsigned)n_sf), dim3(kWave * kWholeQuad), 0, st, Y,
-                           abyte, tmask, T_len, gamma, ctx->status, F, Tmax, iters, weight_mode);
+                           abyte, tmask, T_len, seg_order, gamma, ctx->status, F, Tmax, iters, weight_mode);
     }
     if (!tiny)
-      hipLaunchKernelGGL((em_whole_small<D, K, 1>), dim3((unsigned)n_sf), dim3(kWave), 0, st, Y, abyte, tmask, T_len, gamma,
-                         ctx->status, F, Tmax, iters, weight_mode);
+      hipLaunchKernelGGL((em_whole_small<D, K, 1>), dim3((unsigned)n_sf), dim3(kWave), 0, st, Y, abyte, tmask, T_len,
+                         seg_order, gamma, ctx->status, F, Tmax, iters, weight_mode);
     gss_profile_end(ctx, 0, st);
     if (hipGetLastError() != hipSuccess) return GSS_EHIP;
     return GSS_OK;

@@ -74,22 +74,43 @@ def sub_records(torch, gss, ctx, synth):
 
     for name, seg in (("c0", synth.config0()), ("c1", synth.config1()), ("c3", synth.config3())):
         recs.append(rec(measure_batch(torch, gss, ctx, name, seg.Y[None], seg.activity[None], None, seg.iters)))
+    for r in config2_rows(torch, gss, ctx, synth):
+        recs.append(rec(r))
+    return recs
+
+
+def config2_rows(torch, gss, ctx, synth, progress=None):
+    """Config 2 three ways: each of its four length buckets as a padded batch of its own, their sum, and all 64
+    segments in one ragged batch (the kernels skip what lies beyond a segment's length, so nothing is gained by
+    bucketing; the one call is the faster way)."""
+    rows = []
     T, ns = synth.config2_plan()
+    all_segs = [synth.config2_segment(i, T[i], ns[i]) for i in range(len(T))]
     tot = None
     for bi, idx in enumerate(synth.buckets_by_length(T, 4)):
-        segs = [synth.config2_segment(i, T[i], ns[i]) for i in idx]
+        segs = [all_segs[i] for i in idx]
         Y, act, T_len, target = synth.pad_batch(segs)
         r = measure_batch(torch, gss, ctx, f"c2 bucket {bi}", Y, act, T_len, 15, target)
-        recs.append(rec(r))
+        rows.append(r)
+        if progress:
+            progress(r)
         if tot is None:
-            tot = dict(r, name="c2 all 64 segments")
+            tot = dict(r, name="c2 four buckets, summed")
         else:
             for k in ("S", "frames", "em_ms", "mvdr_ms", "audio_s", "flops", "bins_iters"):
                 tot[k] += r[k]
             tot["T"] = max(tot["T"], r["T"])
         del Y, act
-    recs.append(rec(tot))
-    return recs
+    rows.append(tot)
+    if progress:
+        progress(tot)
+    Y, act, T_len, target = synth.pad_batch(all_segs)
+    del all_segs
+    r = measure_batch(torch, gss, ctx, "c2 one call, 64 ragged segments", Y, act, T_len, 15, target)
+    rows.append(r)
+    if progress:
+        progress(r)
+    return rows
 
 
 def sweeps(torch, gss, ctx, synth):
@@ -226,22 +247,8 @@ def main():
         if a.config in (None, name):
             seg = make()
             print(row(measure_batch(torch, gss, ctx, name, seg.Y[None], seg.activity[None], None, seg.iters)), flush=True)
-    T, ns = synth.config2_plan()
-    tot = None
-    for bi, idx in enumerate(synth.buckets_by_length(T, 4) if a.config in (None, "c2") else []):
-        segs = [synth.config2_segment(i, T[i], ns[i]) for i in idx]
-        Y, act, T_len, target = synth.pad_batch(segs)
-        r = measure_batch(torch, gss, ctx, f"c2 bucket {bi}", Y, act, T_len, 15, target)
-        print(row(r), flush=True)
-        if tot is None:
-            tot = dict(r, name="c2 all 64 segments")
-        else:
-            for k in ("S", "frames", "em_ms", "mvdr_ms", "audio_s", "flops", "bins_iters"):
-                tot[k] += r[k]
-            tot["T"] = max(tot["T"], r["T"])
-        del Y, act
-    if tot is not None:
-        print(row(tot), flush=True)
+    if a.config in (None, "c2"):
+        config2_rows(torch, gss, ctx, synth, progress=lambda r: print(row(r), flush=True))
 
     if a.meeting_s > 0 and a.config is None:
         n_seg = max(4, int(round(1200 * a.meeting_s / 3600.0)))
