@@ -144,11 +144,14 @@ int gss_wpe(gss_ctx* ctx, const float* Y, const int32_t* T_len, int S, int F, in
  * Guided cACGMM EM, independent per (segment, frequency): Eq. (2)-(5) and the EM loop of Section 2.2.
  *   Y        [S][F][Tmax][D] complex64, any scale (unit-normalised internally, Eq. (2))
  *   activity [S][K][Tmax] uint8, non-zero = class k may be active in frame t (a_{t,k} of Eq. (5))
- *   T_len    [S] int32 or NULL
+ *   T_len    [S] int32 or NULL.  Segments of any mix of lengths go in one call: no work is done beyond a
+ *            segment's own length, so grouping segments of similar length into separate calls saves only the
+ *            memory of the padded arrays, not time
  *   iters    >= 0 EM iterations (each = M-step then E-step); 0 returns the normalised activity
  *   weight_mode  1: pi_{f,k} proportional to sum_t gamma; 0: pi uniform
  *   gamma    [S][K][F][Tmax] float32 out: the state posteriors after the last E-step = the masks.
- *            Exact 0 where activity is 0 and at t >= T_len[s].
+ *            Exact 0 where activity is 0 and at t >= T_len[s].  The same bits on every run (all sums are taken
+ *            in a fixed order).
  * Limits: 1 <= D <= GSS_MAX_D, 1 <= K <= GSS_MAX_K.
  */
 int gss_cacgmm_em(gss_ctx* ctx, const float* Y, const uint8_t* activity, const int32_t* T_len,
