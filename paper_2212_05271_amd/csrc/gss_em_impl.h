@@ -493,6 +493,7 @@ __device__ __forceinline__ void factor_classes_in_wave(const double* __restrict_
   // zeros or garbage that is never stored.  Pivot lane: row scaled by 1 / pivot; the others: row minus
   // (a_ip / pivot) x pivot row -- one expression with the factors selected per lane.
   double det = 1.0;
+  double minp = 1.0;                                    // smallest pivot (an identity matrix has 1 + delta)
   static_for<0, D>([&](auto PI) {
     constexpr int p = PI.value;
     double pr[D], pi[D];
@@ -507,6 +508,7 @@ __device__ __forceinline__ void factor_classes_in_wave(const double* __restrict_
       if (on && fi == 0) atomicOr(status, GSS_STATUS_NONPD_B);
     }
     det *= piv;
+    minp = fmin(minp, piv);
     const double rp = rcp_f64(piv);
     const bool is_piv = fi == p;
     const double fr = ar[p] * rp, fim = ai[p] * rp;      // M_ip / pivot
@@ -538,7 +540,10 @@ __device__ __forceinline__ void factor_classes_in_wave(const double* __restrict_
     }
     const double pi_k = weight_mode == 1 ? Nk * rcp_f64(fmax(Ntot, GSS_EPS_N)) : 1.0 / (double)K;
     const double cck = fmax(pi_k, GSS_EPS_PI) * rcp_f64(det);
-    if (on && fi == 0) sCC[fk] = cck;
+    if (on && fi == 0) {
+      sCC[fk] = cck;
+      if (minp < GSS_ILLCOND_PIVOT) atomicOr(status, GSS_STATUS_ILLCOND_B);
+    }
   }
 }
 
@@ -610,12 +615,14 @@ __global__ __launch_bounds__(kWave * K) void em_factor_small(
 
   double detm = 1.0;   // det B = detm * 2^dete, renormalised after every pivot
   int dete = 0;
+  double minp = 1.0;
   for (int p = 0; p < D; ++p) {
     double piv = sMr[k][p][p];
     if (!(piv > 1e-300)) {
       piv = 1e-300;
       if (l == 0) atomicOr(status, GSS_STATUS_NONPD_B);
     }
+    minp = fmin(minp, piv);
     detm *= piv;
     dete += __builtin_amdgcn_frexp_exp(detm);
     detm = __builtin_amdgcn_frexp_mant(detm);
@@ -662,6 +669,7 @@ __global__ __launch_bounds__(kWave * K) void em_factor_small(
     }
     const double c = fmax(pi, GSS_EPS_PI) / detm;            // pi_k / det B_k = c * 2^-dete
     cconst[sf * K + k] = ldexp(c, -dete);
+    if (minp < GSS_ILLCOND_PIVOT) atomicOr(status, GSS_STATUS_ILLCOND_B);
   }
 }
 

@@ -501,6 +501,7 @@ __global__ __launch_bounds__(kWave * GSS_MAX_K) void em_factor_large(
 
   double detm = 1.0;
   int dete = 0;
+  double minp = 1.0;
   // (kept as a loop: unrolled, the 8 BS sweeps are straight-line code that every wavefront runs once, and the
   // kernel then waits for instruction fetches most of the time)
 #pragma unroll 1
@@ -529,6 +530,7 @@ __global__ __launch_bounds__(kWave * GSS_MAX_K) void em_factor_large(
           piv = 1e-300;
           if (lane == 0) atomicOr(status, GSS_STATUS_NONPD_B);
         }
+        minp = fmin(minp, piv);
         detm *= piv;
         dete += __builtin_amdgcn_frexp_exp(detm);
         detm = __builtin_amdgcn_frexp_mant(detm);
@@ -575,6 +577,7 @@ __global__ __launch_bounds__(kWave * GSS_MAX_K) void em_factor_large(
     const double cst = fmax(pi, GSS_EPS_PI) / detm;
     cmant[sf * K + k] = __builtin_amdgcn_frexp_mant(cst);
     cexp[sf * K + k] = __builtin_amdgcn_frexp_exp(cst) - dete;
+    if (minp < GSS_ILLCOND_PIVOT) atomicOr(status, GSS_STATUS_ILLCOND_B);
   }
 }
 
