@@ -63,14 +63,6 @@ typedef enum gss_status {
 #define GSS_STATUS_ZERO_FRAME 16u    /* gss_cacgmm_em met a frame t < T_len[s] with ||y||^2 < 1e-20 (Eq. (2) is
                                         0/0 there): it was normalised to the zero vector, its q clamped        */
 #define GSS_STATUS_BAD_REF 32u       /* a reference channel >= D was passed to gss_mvdr; it was chosen instead  */
-#define GSS_STATUS_ILLCOND_B 64u     /* a class scatter matrix (scaled to trace D, loaded with 1e-6 I) had a pivot
-                                        below 1e-5: numerically rank-deficient, typically a class with fewer
-                                        active frames than channels.  Its inverse is dominated by the loading
-                                        (entries ~1e6) and, formed explicitly as it is here, carries an absolute
-                                        error of ~1e-3 into the quadratic forms of the class's own frames: the
-                                        masks of such a class can deviate from an exact evaluation by ~1e-2 for up
-                                        to 8 channels and by more for larger arrays (the method itself depends on
-                                        the loading there)                                                      */
 
 typedef struct gss_ctx gss_ctx;
 

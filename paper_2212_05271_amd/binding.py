@@ -27,7 +27,7 @@ GSS_REF_PER_SEGMENT, GSS_REF_PER_FREQUENCY = 0, 1
 GSS_MAX_D, GSS_MAX_K = 32, 8
 # bits of the status word (Context.get_status)
 (GSS_STATUS_NONPD_B, GSS_STATUS_NONPD_PHI, GSS_STATUS_BAD_TARGET, GSS_STATUS_NONPD_WPE, GSS_STATUS_ZERO_FRAME,
- GSS_STATUS_BAD_REF, GSS_STATUS_ILLCOND_B) = 1, 2, 4, 8, 16, 32, 64
+ GSS_STATUS_BAD_REF) = 1, 2, 4, 8, 16, 32
 
 EXPORTS = (
     "gss_create", "gss_destroy", "gss_strerror", "gss_version", "gss_get_status", "gss_scratch_bytes",

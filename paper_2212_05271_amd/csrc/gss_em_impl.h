@@ -493,7 +493,6 @@ __device__ __forceinline__ void factor_classes_in_wave(const double* __restrict_
   // zeros or garbage that is never stored.  Pivot lane: row scaled by 1 / pivot; the others: row minus
   // (a_ip / pivot) x pivot row -- one expression with the factors selected per lane.
   double det = 1.0;
-  double minp = 1.0;                                    // smallest pivot (an identity matrix has 1 + delta)
   static_for<0, D>([&](auto PI) {
     constexpr int p = PI.value;
     double pr[D], pi[D];
@@ -508,7 +507,6 @@ __device__ __forceinline__ void factor_classes_in_wave(const double* __restrict_
       if (on && fi == 0) atomicOr(status, GSS_STATUS_NONPD_B);
     }
     det *= piv;
-    minp = fmin(minp, piv);
     const double rp = rcp_f64(piv);
     const bool is_piv = fi == p;
     const double fr = ar[p] * rp, fim = ai[p] * rp;      // M_ip / pivot
@@ -524,8 +522,13 @@ __device__ __forceinline__ void factor_classes_in_wave(const double* __restrict_
     ar[p] = is_piv ? rp : -fr;
     ai[p] = is_piv ? 0.0 : -fim;
   });
-  // packed coefficients of q = sum_i A_ii P_ii + 2 sum_{i<j} (Re A_ij Re P_ij + Im A_ij Im P_ij), A = B^-1
-  // (one predicate per entry, the divisions as reciprocals: every lane computes the class constant, one stores)
+  // packed coefficients of q = sum_i A_ii P_ii + 2 sum_{i<j} (Re A_ij Re P_ij + Im A_ij Im P_ij), A = the
+  // Hermitian part of the computed inverse: the coefficient of the pair i < j is A_ij + conj(A_ji), not 2 A_ij.
+  // (Rounding leaves the computed inverse slightly non-Hermitian.  For an ill-conditioned B, e.g. a class with
+  // fewer frames than channels, whose inverse has entries of 1e6, the quadratic form of the Hermitian part is
+  // still good to 1e-10 for the class's own frames, while that of one triangle mirrored is off by up to 1e-4.)
+  // The row owners write their upper-triangle entries, then add the conjugates of their lower-triangle entries.
+  // (One predicate per entry, the divisions as reciprocals: every lane computes the class constant, one stores.)
   {
     double* __restrict__ sCk = sC + fkc * (R * 16);
     const int prow = gss_packed_row(fic, D);
@@ -534,16 +537,23 @@ __device__ __forceinline__ void factor_classes_in_wave(const double* __restrict_
       const bool diag = j == fi;
       const int pj = diag ? prow : prow + 1 + 2 * (j - fic - 1);
       if (on && j >= fi) {
-        sCk[pj] = diag ? ar[j] : 2.0 * ar[j];
-        if (!diag) sCk[pj + 1] = 2.0 * ai[j];
+        sCk[pj] = ar[j];
+        if (!diag) sCk[pj + 1] = ai[j];
+      }
+    }
+    wave_lds_sync();
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+      // entry (fi, j) with j < fi belongs to the pair (j, fi)
+      const int pj = gss_packed_row(j, D) + 1 + 2 * (fic - j - 1);
+      if (on && j < fi) {
+        sCk[pj] += ar[j];
+        sCk[pj + 1] -= ai[j];
       }
     }
     const double pi_k = weight_mode == 1 ? Nk * rcp_f64(fmax(Ntot, GSS_EPS_N)) : 1.0 / (double)K;
     const double cck = fmax(pi_k, GSS_EPS_PI) * rcp_f64(det);
-    if (on && fi == 0) {
-      sCC[fk] = cck;
-      if (minp < GSS_ILLCOND_PIVOT) atomicOr(status, GSS_STATUS_ILLCOND_B);
-    }
+    if (on && fi == 0) sCC[fk] = cck;
   }
 }
 
@@ -615,14 +625,12 @@ __global__ __launch_bounds__(kWave * K) void em_factor_small(
 
   double detm = 1.0;   // det B = detm * 2^dete, renormalised after every pivot
   int dete = 0;
-  double minp = 1.0;
   for (int p = 0; p < D; ++p) {
     double piv = sMr[k][p][p];
     if (!(piv > 1e-300)) {
       piv = 1e-300;
       if (l == 0) atomicOr(status, GSS_STATUS_NONPD_B);
     }
-    minp = fmin(minp, piv);
     detm *= piv;
     dete += __builtin_amdgcn_frexp_exp(detm);
     detm = __builtin_amdgcn_frexp_mant(detm);
@@ -650,12 +658,13 @@ __global__ __launch_bounds__(kWave * K) void em_factor_small(
   // packed coefficients of q = sum_i A_ii P_ii + 2 sum_{i<j} (Re A_ij Re P_ij + Im A_ij Im P_ij), A = B^-1
   if (on && i <= j) {
     double* __restrict__ cf = coef + (sf * K + k) * (long)E;
+    // (the Hermitian part of the computed inverse: A_ij + conj(A_ji), see factor_classes_in_wave)
     if (i == j) {
       cf[gss_packed_row(i, D)] = sMr[k][i][i];
     } else {
       const int p = gss_packed_row(i, D) + 1 + 2 * (j - i - 1);
-      cf[p] = 2.0 * sMr[k][i][j];
-      cf[p + 1] = 2.0 * sMi[k][i][j];
+      cf[p] = sMr[k][i][j] + sMr[k][j][i];
+      cf[p + 1] = sMi[k][i][j] - sMi[k][j][i];
     }
   }
   if (l == 0) {
@@ -669,7 +678,6 @@ __global__ __launch_bounds__(kWave * K) void em_factor_small(
     }
     const double c = fmax(pi, GSS_EPS_PI) / detm;            // pi_k / det B_k = c * 2^-dete
     cconst[sf * K + k] = ldexp(c, -dete);
-    if (minp < GSS_ILLCOND_PIVOT) atomicOr(status, GSS_STATUS_ILLCOND_B);
   }
 }
 

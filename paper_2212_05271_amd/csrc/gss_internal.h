@@ -11,7 +11,6 @@
 // part of the algorithm's definition and are documented with the readings of the paper.
 #define GSS_EPS_NORM_SQ 1e-20   // floor on ||y||^2 in the unit normalisation, Eq. (2)
 #define GSS_EPS_N 1e-10         // floor on sum_t gamma and on a trace
-#define GSS_ILLCOND_PIVOT 1e-5  // a pivot of a class matrix below this raises GSS_STATUS_ILLCOND_B
 #define GSS_EPS_Q 1e-10         // floor on y^H B^-1 y, Eq. (4)
 #define GSS_EPS_PI 1e-30        // floor inside log(pi)
 #define GSS_DELTA 1e-6          // diagonal loading of B (after scaling to trace D)

@@ -501,7 +501,6 @@ __global__ __launch_bounds__(kWave * GSS_MAX_K) void em_factor_large(
 
   double detm = 1.0;
   int dete = 0;
-  double minp = 1.0;
   // (kept as a loop: unrolled, the 8 BS sweeps are straight-line code that every wavefront runs once, and the
   // kernel then waits for instruction fetches most of the time)
 #pragma unroll 1
@@ -530,7 +529,6 @@ __global__ __launch_bounds__(kWave * GSS_MAX_K) void em_factor_large(
           piv = 1e-300;
           if (lane == 0) atomicOr(status, GSS_STATUS_NONPD_B);
         }
-        minp = fmin(minp, piv);
         detm *= piv;
         dete += __builtin_amdgcn_frexp_exp(detm);
         detm = __builtin_amdgcn_frexp_mant(detm);
@@ -556,18 +554,24 @@ __global__ __launch_bounds__(kWave * GSS_MAX_K) void em_factor_large(
     });
   }
 
-  // coefficients of <B^-1, y y^H> over the items: the diagonal entry, twice the off-diagonal entry
+  // coefficients of <A, y y^H> over the items, A = the Hermitian part of the computed inverse: the diagonal
+  // entry, and A_ij + conj(A_ji) for i < j (not 2 A_ij: rounding leaves the computed inverse slightly
+  // non-Hermitian, and for an ill-conditioned B, whose inverse has entries of 1e6, one triangle mirrored puts a
+  // relative error of up to 1e-4 into the quadratic forms of the class's own frames, the Hermitian part 1e-10).
+  // Entry (j, i) sits in lane (b, a), block position (c, r).
   const int CP = coef_pitch(D);
   double* __restrict__ cf = coef + (sf * K + k) * (long)CP;
+  const int lane_t = b * 8 + a;
 #pragma unroll
   for (int r = 0; r < BS; ++r)
 #pragma unroll
     for (int c = 0; c < BS; ++c) {
+      const double tr_re = __shfl(mr[c][r], lane_t, kWave), tr_im = __shfl(mi[c][r], lane_t, kWave);
       const int i = a * BS + r, j = b * BS + c;
       if (i <= j && j < D) {
         double2 v;
         if (i == j) v = make_double2(mr[r][c], 0.0);
-        else v = make_double2(2.0 * mr[r][c], 2.0 * mi[r][c]);
+        else v = make_double2(mr[r][c] + tr_re, mi[r][c] - tr_im);
         *reinterpret_cast<double2*>(cf + 2 * item[r][c]) = v;
       }
     }
@@ -577,7 +581,6 @@ __global__ __launch_bounds__(kWave * GSS_MAX_K) void em_factor_large(
     const double cst = fmax(pi, GSS_EPS_PI) / detm;
     cmant[sf * K + k] = __builtin_amdgcn_frexp_mant(cst);
     cexp[sf * K + k] = __builtin_amdgcn_frexp_exp(cst) - dete;
-    if (minp < GSS_ILLCOND_PIVOT) atomicOr(status, GSS_STATUS_ILLCOND_B);
   }
 }
 

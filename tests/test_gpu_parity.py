@@ -262,40 +262,42 @@ def test_few_channels_four_wavefronts_many_tiles(env, D):
     assert env["ctx"].get_status() == 16                                # the zero-energy frame, nothing else
 
 
-@pytest.mark.parametrize("D,mode", [(8, 0), (8, 1 << 40), (4, -1), (18, -1)])
-def test_rank_deficient_class_is_flagged(env, D, mode):
-    """A class with fewer active frames than channels has a rank-deficient scatter matrix: B is then the 1e-6 loading
-    plus a low-rank part, its inverse has entries of 1e6, and the explicitly formed inverse of the kernels carries an
-    absolute error of about 1e-3 into the quadratic forms of that class's own frames (the oracle solves instead of
-    inverting).  The library reports the condition (GSS_STATUS_ILLCOND_B) on every M-step implementation (whole-EM
-    kernel, chunked kernels, large arrays); the masks stay finite, sum to one where a class is active, are exact
-    zeros where the activity is zero, and stay within 5e-2 of the oracle here (1e-3 does not hold in this regime for
-    more than 4 channels).  The same problem with enough frames per class raises nothing."""
+@pytest.mark.parametrize("D,mode", [(8, 0), (8, 1 << 40), (6, -1), (4, -1), (18, -1), (24, -1), (32, -1)])
+def test_rank_deficient_classes(env, D, mode):
+    """Classes with fewer active frames than channels have rank-deficient scatter matrices: B is then the 1e-6
+    loading plus a low-rank part, its condition number is about 1e7 and its inverse has entries of 1e6, and the
+    quadratic forms of the class's own frames come out of a cancellation of such terms.  That is accurate only
+    if the coefficients are those of the Hermitian part of the computed inverse (one triangle of it mirrored was
+    off by up to 1e-4 relative in q, 1e-2 and more in the masks after a few iterations): every M-step implementation
+    (whole-EM kernel, chunked kernels, large arrays).  Two cases: five frames in all with two classes of three frames
+    each that contest one frame, and a long segment with one class of three frames; tolerance as everywhere."""
     gss, ctx = env["gss"], env["ctx"]
     rng = np.random.default_rng(900 + D)
-    F, T, K = 3, 300, 3
-    Y = (_cn(rng, (F, T, D)) * np.exp(rng.standard_normal((F, T, 1)))).astype(np.complex64)
-    act = np.zeros((K, T), dtype=np.uint8)
-    act[K - 1] = 1
-    act[0, 10:200] = 1
-    act[1, 250:253] = 1                                  # three frames: fewer than channels (for D > 3)
     ctx.get_status()
     ctx.set_option(gss.GSS_OPT_EM_WHOLE_MIN_PROBLEMS, mode)
     try:
+        F, T, K = 4, 5, 2
+        Y = (_cn(rng, (F, T, D)) * np.exp(rng.standard_normal((F, T, 1)))).astype(np.complex64)
+        act = np.zeros((K, T), dtype=np.uint8)
+        act[0, :3] = 1
+        act[1, 2:5] = 1
+        for iters in (1, 2, 4):
+            g = _gpu_em(env, Y[None], act[None], None, iters, 0)[0]
+            go = env["o"].cacgmm_em(Y, act, iters, 0)
+            assert np.max(np.abs(g - go)) <= 1e-5, (D, iters)
+        F, T, K = 3, 300, 3
+        Y = (_cn(rng, (F, T, D)) * np.exp(rng.standard_normal((F, T, 1)))).astype(np.complex64)
+        act = np.zeros((K, T), dtype=np.uint8)
+        act[K - 1] = 1
+        act[0, 10:200] = 1
+        act[1, 250:253] = 1
         g = _gpu_em(env, Y[None], act[None], None, 4)[0]
-        st = ctx.get_status()
-        act2 = act.copy()
-        act2[1, 100:250] = 1
-        g2 = _gpu_em(env, Y[None], act2[None], None, 4)[0]
-        st2 = ctx.get_status()
+        go = env["o"].cacgmm_em(Y, act, 4)
+        assert np.max(np.abs(g - go)) <= 1e-5
+        assert np.all(g[np.broadcast_to((act == 0)[:, None, :], g.shape)] == 0)
     finally:
         ctx.set_option(gss.GSS_OPT_EM_WHOLE_MIN_PROBLEMS, -1)
-    assert st == gss.GSS_STATUS_ILLCOND_B and st2 == 0
-    go = env["o"].cacgmm_em(Y, act, 4)
-    assert np.isfinite(g).all() and np.all(g[np.broadcast_to((act == 0)[:, None, :], g.shape)] == 0)
-    assert np.all(np.abs(g.sum(axis=0) - 1.0) < 1e-5)
-    assert np.max(np.abs(g - go)) <= (1e-3 if D <= 4 else 5e-2)
-    assert np.max(np.abs(g2 - env["o"].cacgmm_em(Y, act2, 4))) <= TOL_GAMMA
+    assert ctx.get_status() == 0
 
 
 @pytest.mark.parametrize("D", [10, 20, 26, 32])
