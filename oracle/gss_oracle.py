@@ -37,7 +37,8 @@ definition, not numerical noise):
   R6  The beamformer (Eq. 6-9) uses whatever Y it is handed (no normalisation
       inside); the EM normalises internally (Eq. 2).
   R7  Phi_bg gets relative diagonal loading DELTA_BF * tr(Phi_bg) / D; the
-      filter's denominator is Re tr(G) + EPS_TRACE.
+      filter's denominator is Re tr(G) + EPS_TRACE.  A frequency without any
+      background energy (tr Phi_bg = 0: Eq. (8) has no solution) gets the zero filter.
   R8  One reference channel per segment: the channel r maximising
       sum_f Re(h_r^H Phi_k h_r) / sum_f Re(h_r^H Phi_bg h_r), lowest index on ties.
   R9  Frames without any active class have gamma = 0 for every class.
@@ -238,8 +239,12 @@ def load_background(phi_bg):
 
 
 def souden_filters(phi_k, phi_bg_loaded):
-    """H[F, D(channel), D(ref)]: column r is the filter of Eq. (8) for reference channel r."""
-    G = np.linalg.solve(phi_bg_loaded, phi_k)
+    """H[F, D(channel), D(ref)]: column r is the filter of Eq. (8) for reference channel r; zero where the
+    background covariance is zero (R7)."""
+    D = phi_k.shape[-1]
+    none = ~(np.trace(phi_bg_loaded, axis1=-2, axis2=-1).real > 0.0)
+    G = np.linalg.solve(np.where(none[:, None, None], np.eye(D), phi_bg_loaded), phi_k)
+    G[none] = 0.0
     tr = np.trace(G, axis1=-2, axis2=-1).real
     return G / (tr + EPS_TRACE)[:, None, None]
 

@@ -102,6 +102,27 @@ def test_zero_target_gives_zero_output():
     assert np.all(X == 0) and np.all(h == 0) and ref == 0
 
 
+def test_no_background_gives_zero_filter():
+    """R7: a frequency whose background covariance is exactly zero (every frame belongs to the target with mask 1,
+    or the bin is silent) has no solution of Eq. (8): the filter and the output are zero there, and the other
+    frequencies are what they are without that bin."""
+    rng = np.random.default_rng(11)
+    F, T, D, K = 3, 40, 4, 2
+    Y = (rng.standard_normal((F, T, D)) + 1j * rng.standard_normal((F, T, D))) / np.sqrt(2)
+    gamma = rng.random((K, F, T))
+    gamma /= gamma.sum(axis=0, keepdims=True)
+    gamma[0, 1] = 1.0
+    gamma[1, 1] = 0.0                                   # bin 1: all of it is target
+    X, ref, h = o.mvdr(Y, gamma, 0)
+    assert np.all(h[1] == 0) and np.all(X[1] == 0)
+    keep = [0, 2]
+    X2, ref2, h2 = o.mvdr(Y[keep], gamma[:, keep], 0, ref)
+    assert np.allclose(X[keep], X2, rtol=0, atol=1e-12) and np.allclose(h[keep], h2, rtol=0, atol=1e-12)
+    # and a single frame with the target's mask at one: nothing but zeros, no exception
+    X1, _, h1 = o.mvdr(Y[:, :1], np.stack([np.ones((F, 1)), np.zeros((F, 1))]), 0)
+    assert np.all(X1 == 0) and np.all(h1 == 0)
+
+
 def test_reference_channel_brute_force_and_dead_mic():
     rng = np.random.default_rng(6)
     F, T, D = 6, 400, 4
