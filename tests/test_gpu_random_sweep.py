@@ -1,0 +1,180 @@
+"""Randomised sweeps of the entry points against the oracle (fixed seeds, a few hundred small problems each):
+shapes, class and channel counts, ragged lengths, sparse and dense activities, degenerate sizes (a single frame,
+fewer frames than channels, empty segments) and the kernel path (default choice or forced) are drawn at random.
+The same tolerances as everywhere: masks 1e-3, beamformed STFT 1e-4 relative L2, STFT / iSTFT 1e-5, structural
+zeros exact.  (A sweep of this kind found that the class coefficients have to come from the Hermitian part of the
+computed inverse; see test_rank_deficient_classes.)
+"""
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from oracle import gss_oracle as o
+    from oracle import wpe_oracle as wo
+    from paper_2212_05271_amd import binding as gss
+    ctx = gss.Context(0)
+    yield dict(torch=torch, o=o, wo=wo, gss=gss, ctx=ctx)
+    ctx.close()
+
+
+def _cn(rng, shape):
+    return (rng.standard_normal(shape) + 1j * rng.standard_normal(shape)) / np.sqrt(2)
+
+
+@pytest.mark.parametrize("seed", [11, 12])
+def test_random_em_problems(env, seed):
+    t, o, gss, ctx = env["torch"], env["o"], env["gss"], env["ctx"]
+    rng = np.random.default_rng(seed)
+    worst = 0.0
+    try:
+        for case in range(250):
+            D = int(rng.integers(1, 9)) if rng.random() < 0.8 else int(rng.integers(9, 33))
+            K, S, F = int(rng.integers(1, 9)), int(rng.integers(1, 5)), int(rng.integers(1, 6))
+            T = int(rng.choice([1, 5, 63, 64, 65, 127, 200, 257, 330, 520, 700]))
+            if D > 8:
+                T = min(T, 330)
+            iters, wm = int(rng.integers(0, 5)), int(rng.integers(0, 2))
+            Y = (_cn(rng, (S, F, T, D)) * np.exp(rng.standard_normal((S, F, T, 1)))).astype(np.complex64)
+            act = (rng.random((S, K, T)) < rng.choice([0.05, 0.3, 0.6, 1.0])).astype(np.uint8)
+            if rng.random() < 0.7:
+                act[:, K - 1] = 1
+            if rng.random() < 0.3 and T > 70:
+                act[:, :, 64:128] = 0
+            T_len = rng.integers(0, T + 1, size=S).astype(np.int32) if rng.random() < 0.6 else None
+            if T_len is not None and rng.random() < 0.5:
+                T_len[0] = T
+            ctx.set_option(gss.GSS_OPT_EM_WHOLE_MIN_PROBLEMS, int(rng.choice([-1, -1, 0, 1 << 40])))
+            Yd, ad = t.from_numpy(Y).cuda(), t.from_numpy(act).cuda()
+            Td = None if T_len is None else t.from_numpy(T_len).cuda()
+            g = gss.gss_cacgmm_em(ctx, Yd, ad, Td, iters, wm).cpu().numpy()
+            TL = np.full(S, T, np.int32) if T_len is None else T_len
+            go = o.cacgmm_em_batch(Y, act, TL, iters, wm)
+            what = (seed, case, D, K, S, F, T, iters, wm)
+            assert np.isfinite(g).all(), what
+            d = float(np.max(np.abs(g - go))) if g.size else 0.0
+            worst = max(worst, d)
+            assert d <= 1e-3, (what, d)
+            for s_ in range(S):
+                assert np.all(g[s_, :, :, TL[s_]:] == 0), what
+                assert np.all(g[s_][np.broadcast_to((act[s_] == 0)[:, None, :], g[s_].shape)] == 0), what
+    finally:
+        ctx.set_option(gss.GSS_OPT_EM_WHOLE_MIN_PROBLEMS, -1)
+    assert worst <= 2e-4          # measured: 3e-8 .. 1.4e-4 (the latter with fewer frames than channels)
+
+
+@pytest.mark.parametrize("seed", [21])
+def test_random_beamformer_problems(env, seed):
+    t, o, gss, ctx = env["torch"], env["o"], env["gss"], env["ctx"]
+    rng = np.random.default_rng(seed)
+    for case in range(400):
+        D = int(rng.integers(1, 9)) if rng.random() < 0.7 else int(rng.integers(9, 33))
+        K, S, F = int(rng.integers(2, 7)), int(rng.integers(1, 4)), int(rng.integers(1, 6))
+        T = int(rng.choice([1, 3, 7, 63, 64, 65, 130, 257, 400]))
+        Y = _cn(rng, (S, F, T, D)) * np.exp(rng.standard_normal((S, F, T, 1)))
+        Y = (Y + 2.0 * _cn(rng, (S, F, 1, D)) * _cn(rng, (S, F, T, 1)) * (rng.random((S, 1, T, 1)) < 0.5)).astype(np.complex64)
+        g = rng.random((S, K, F, T)) ** 3
+        if rng.random() < 0.5:
+            g *= (rng.random((S, K, 1, T)) < 0.6)
+        g = (g / np.maximum(g.sum(axis=1, keepdims=True), 1e-12)).astype(np.float32)
+        T_len = rng.integers(0, T + 1, size=S).astype(np.int32) if rng.random() < 0.5 else None
+        target = rng.integers(0, K, size=S).astype(np.int32)
+        Xo, ro = o.mvdr_batch(Y, g.astype(np.float64), T_len, target, None)
+        Yd, gd, tg = t.from_numpy(Y).cuda(), t.from_numpy(g).cuda(), t.from_numpy(target).cuda()
+        Td = None if T_len is None else t.from_numpy(T_len).cuda()
+        rf = t.from_numpy(ro.astype(np.int32)).cuda()                 # the oracle's channel: X is compared on equal terms
+        X = gss.gss_mvdr(ctx, Yd, gd, tg, rf, Td).cpu().numpy()
+        what = (seed, case, D, K, S, F, T)
+        assert np.isfinite(X.view(np.float32)).all(), what
+        nrm = np.linalg.norm(Xo)
+        rel = float(np.linalg.norm(X - Xo) / nrm) if nrm > 0 else float(np.linalg.norm(X))
+        assert rel <= 1e-4, (what, rel)
+        TL = np.full(S, T) if T_len is None else T_len
+        for s_ in range(S):
+            assert np.all(X[s_, :, TL[s_]:] == 0), what
+        # the channel the library chooses itself is the oracle's unless the oracle's two best scores tie
+        rf2 = t.full((S,), -1, dtype=t.int32).cuda()
+        gss.gss_mvdr(ctx, Yd, gd, tg, rf2, Td)
+        r2 = rf2.cpu().numpy()
+        for s_ in range(S):
+            if TL[s_] > 0 and r2[s_] != ro[s_]:
+                Ys, gs = Y[s_, :, :TL[s_]].astype(np.complex128), g[s_, :, :, :TL[s_]].astype(np.float64)
+                pk, pb = o.masked_covariances(Ys, gs, int(target[s_]))
+                pbl = o.load_background(pb)
+                sc = np.sort(o.reference_channel_scores(o.souden_filters(pk, pbl), pk, pbl))[::-1]
+                assert len(sc) > 1 and (sc[0] - sc[1]) <= 1e-4 * max(abs(sc[0]), 1e-300), (what, r2[s_], ro[s_])
+    ctx.get_status()
+
+
+@pytest.mark.parametrize("seed", [31])
+def test_random_stft_frame_range_and_wpe_problems(env, seed):
+    t, o, wo, gss, ctx = env["torch"], env["o"], env["wo"], env["gss"], env["ctx"]
+    rng = np.random.default_rng(seed)
+    for case in range(240):
+        kind = case % 3
+        if kind == 0:
+            S, D = int(rng.integers(1, 3)), int(rng.integers(1, 9))
+            N = int(rng.choice([1, 255, 256, 257, 1000, 1024, 4096, 5000, 16000]))
+            x = rng.standard_normal((S, D, N)).astype(np.float32) * float(np.exp(rng.standard_normal()))
+            Yg = gss.gss_stft(ctx, t.from_numpy(x).cuda()).cpu().numpy()
+            X = np.ascontiguousarray(Yg[:, :, :, 0])
+            xg = gss.gss_istft(ctx, t.from_numpy(X).cuda(), N).cpu().numpy()
+            for s_ in range(S):
+                Yo = o.stft_channels_last(x[s_].astype(np.float64))
+                assert Yg[s_].shape == Yo.shape
+                assert np.linalg.norm(Yg[s_] - Yo) <= 1e-5 * max(np.linalg.norm(Yo), 1e-300), (seed, case, S, D, N)
+                xo = o.istft(X[s_].astype(np.complex128), N)
+                assert np.linalg.norm(xg[s_] - xo) <= 1e-5 * max(np.linalg.norm(xo), 1e-300), (seed, case, S, D, N)
+        elif kind == 1:
+            D = int(rng.integers(1, 9)) if rng.random() < 0.8 else int(rng.integers(9, 25))
+            K, S, F = int(rng.integers(1, 6)), int(rng.integers(1, 5)), int(rng.integers(1, 5))
+            Trec = int(rng.choice([70, 200, 500]))
+            Tmax = int(rng.integers(1, min(Trec, 260) + 1))
+            Yrec = (_cn(rng, (F, Trec, D)) * np.exp(rng.standard_normal((F, Trec, 1)))).astype(np.complex64)
+            T_len = rng.integers(0, Tmax + 1, size=S).astype(np.int32)
+            T_len[0] = Tmax
+            frame0 = np.array([rng.integers(0, Trec - T_len[s_] + 1) for s_ in range(S)], dtype=np.int64)
+            act = (rng.random((S, K, Tmax)) < 0.6).astype(np.uint8)
+            act[:, K - 1] = 1
+            iters = int(rng.integers(0, 4))
+            Yd, f0 = t.from_numpy(Yrec).cuda(), t.from_numpy(frame0).cuda()
+            ad, Td = t.from_numpy(act).cuda(), t.from_numpy(T_len).cuda()
+            g = gss.gss_cacgmm_em_frames(ctx, Yd, f0, ad, Td, iters).cpu().numpy()
+            Ypad = np.zeros((S, F, Tmax, D), dtype=np.complex64)
+            for s_ in range(S):
+                Ypad[s_, :, :T_len[s_]] = Yrec[:, frame0[s_]:frame0[s_] + T_len[s_]]
+            go = o.cacgmm_em_batch(Ypad, act, T_len, iters)
+            what = (seed, case, D, K, S, F, Trec, Tmax, iters)
+            assert np.max(np.abs(g - go)) <= 1e-3, what
+            target = rng.integers(0, K, size=S).astype(np.int32)
+            g32 = go.astype(np.float32)                                # the masks as the library gets them
+            Xo, ro = o.mvdr_batch(Ypad, g32.astype(np.float64), T_len, target, None)
+            rf = t.from_numpy(ro.astype(np.int32)).cuda()
+            X = gss.gss_mvdr_frames(ctx, Yd, f0, t.from_numpy(g32).cuda(), t.from_numpy(target).cuda(), rf, Td).cpu().numpy()
+            nrm = np.linalg.norm(Xo)
+            rel = float(np.linalg.norm(X - Xo) / nrm) if nrm > 0 else float(np.linalg.norm(X))
+            assert rel <= 1e-4, (what, rel)
+        else:
+            D = int(rng.integers(1, 9)) if rng.random() < 0.8 else int(rng.integers(9, 17))
+            taps = int(rng.integers(1, min(10, 80 // D if D <= 8 else 320 // D) + 1))
+            delay, iters = int(rng.integers(1, 4)), int(rng.integers(0, 4))
+            S, F = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+            T = int(rng.choice([1, 5, 30, 64, 100, 300]))
+            Y = _cn(rng, (S, F, T, D))
+            for tt in range(1, T):                                     # a short recursion: correlated over time
+                Y[:, :, tt] += 0.5 * Y[:, :, tt - 1] * np.exp(0.3j)
+            Y = (Y * np.exp(rng.standard_normal((S, F, 1, 1)))).astype(np.complex64)
+            T_len = rng.integers(0, T + 1, size=S).astype(np.int32) if rng.random() < 0.5 else None
+            Xg = gss.gss_wpe(ctx, t.from_numpy(Y).cuda(), None if T_len is None else t.from_numpy(T_len).cuda(),
+                             taps, delay, iters).cpu().numpy()
+            for s_ in range(S):
+                Xo = wo.wpe(Y[s_], taps, delay, iters, None if T_len is None else int(T_len[s_]))
+                nrm = np.linalg.norm(Xo)
+                rel = float(np.linalg.norm(Xg[s_] - Xo) / nrm) if nrm > 0 else float(np.linalg.norm(Xg[s_]))
+                assert rel <= 1e-4, (seed, case, D, taps, delay, iters, S, F, T, rel)
+    ctx.get_status()
