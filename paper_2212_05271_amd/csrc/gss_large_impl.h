@@ -422,6 +422,7 @@ __global__ __launch_bounds__(kWave * GSS_MAX_K) void em_factor_large(
     int D, int K, ChunkMap cmap, int weight_mode) {
   constexpr int W = 8 * BS;                                // padded matrix size
   __shared__ double sPiv[GSS_MAX_K][4][W];                 // per wavefront: pivot row (re, im), pivot column (re, im)
+  __shared__ __attribute__((aligned(16))) double sCoef[GSS_MAX_K][W * (W + 1)];   // per wavefront: the packed coefficients
   const int lane = threadIdx.x & (kWave - 1);
   const int k = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const long sf = blockIdx.x;
@@ -558,23 +559,33 @@ __global__ __launch_bounds__(kWave * GSS_MAX_K) void em_factor_large(
   // entry, and A_ij + conj(A_ji) for i < j (not 2 A_ij: rounding leaves the computed inverse slightly
   // non-Hermitian, and for an ill-conditioned B, whose inverse has entries of 1e6, one triangle mirrored puts a
   // relative error of up to 1e-4 into the quadratic forms of the class's own frames, the Hermitian part 1e-10).
-  // Entry (j, i) sits in lane (b, a), block position (c, r).
+  // The two triangles meet in the wavefront's LDS: the owners of the upper triangle write, then the owners of the
+  // lower triangle add their conjugates, and the packed coefficients leave as one contiguous run.
   const int CP = coef_pitch(D);
   double* __restrict__ cf = coef + (sf * K + k) * (long)CP;
-  const int lane_t = b * 8 + a;
+  double* __restrict__ sCo = sCoef[k];
 #pragma unroll
   for (int r = 0; r < BS; ++r)
 #pragma unroll
     for (int c = 0; c < BS; ++c) {
-      const double tr_re = __shfl(mr[c][r], lane_t, kWave), tr_im = __shfl(mi[c][r], lane_t, kWave);
       const int i = a * BS + r, j = b * BS + c;
-      if (i <= j && j < D) {
-        double2 v;
-        if (i == j) v = make_double2(mr[r][c], 0.0);
-        else v = make_double2(mr[r][c] + tr_re, mi[r][c] - tr_im);
-        *reinterpret_cast<double2*>(cf + 2 * item[r][c]) = v;
+      if (i <= j && j < D) *reinterpret_cast<double2*>(sCo + 2 * item[r][c]) = make_double2(mr[r][c], i == j ? 0.0 : mi[r][c]);
+    }
+  wave_lds_sync();
+#pragma unroll
+  for (int r = 0; r < BS; ++r)
+#pragma unroll
+    for (int c = 0; c < BS; ++c) {
+      const int i = a * BS + r, j = b * BS + c;
+      if (i > j && i < D) {                                // entry (i, j) of the lower triangle: item (j, i)
+        double2 v = *reinterpret_cast<double2*>(sCo + 2 * item[r][c]);
+        v.x += mr[r][c];
+        v.y -= mi[r][c];
+        *reinterpret_cast<double2*>(sCo + 2 * item[r][c]) = v;
       }
     }
+  wave_lds_sync();
+  for (int x = lane; x < 2 * M; x += kWave) cf[x] = sCo[x];
   if (lane < CP - 2 * M) cf[2 * M + lane] = 0.0;           // the padding stays zero (fewer than 16 entries)
   if (lane == 0) {
     const double pi = weight_mode == 1 ? Nk / fmax(Ntot, GSS_EPS_N) : 1.0 / (double)K;
