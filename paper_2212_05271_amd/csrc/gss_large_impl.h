@@ -45,9 +45,22 @@ __device__ __forceinline__ double ipow_rt(double x, int n) {   // x^n, n >= 1
   return r;
 }
 
-// Coefficient layout for 9 <= D <= 32: class-major, coef[sf][k][CP] with entry 2 m (2 m + 1) the coefficient of
-// Re (Im) of item m and CP = 2 M rounded up to whole groups of 16 (the padding is zero).
-__host__ __device__ inline int coef_pitch(int D) { return (2 * num_items(D) + 15) / 16 * 16; }
+// Coefficient layout for 9 <= D <= 32: class-major, coef[sf][k][CP], in groups of 16 doubles = (Re, Im) of 8 items.
+// The items (i, j), i <= j, of row i fill ceil((D - i) / 8) groups of their own, in the order of j; the last group
+// of a row is padded (the padding is zero and never used).  A group never spans two rows, so the pass kernel
+// walks a group with one y_i and consecutive y_j.
+__host__ __device__ inline int groups_of_lengths_up_to(int n) {      // sum over L = 1 .. n of ceil(L / 8)
+  const int q = n >> 3, r = n & 7;
+  return 4 * q * (q + 1) + r * (q + 1);
+}
+__host__ __device__ inline int coef_groups(int D) { return groups_of_lengths_up_to(D); }
+__host__ __device__ inline int coef_pitch(int D) { return 16 * coef_groups(D); }
+// first group of row i (rows 0 .. i - 1 have the lengths D, D - 1, ..., D - i + 1)
+__host__ __device__ inline int row_group(int i, int D) { return groups_of_lengths_up_to(D) - groups_of_lengths_up_to(D - i); }
+// position (in doubles) of the Re coefficient of item (i, j), i <= j; Im follows
+__host__ __device__ inline int coef_pos(int i, int j, int D) {
+  return 16 * (row_group(i, D) + ((j - i) >> 3)) + 2 * ((j - i) & 7);
+}
 
 __global__ void em_init_coef_large(double* __restrict__ coef, double* __restrict__ cmant, int32_t* __restrict__ cexp,
                                    int D, int K, long n_sf) {
@@ -56,10 +69,10 @@ __global__ void em_init_coef_large(double* __restrict__ coef, double* __restrict
   for (long x = blockIdx.x * (long)blockDim.x + threadIdx.x; x < total; x += (long)gridDim.x * blockDim.x) {
     const int c = (int)(x % CP);
     double v = 0.0;
-    if (c < 2 * num_items(D) && (c & 1) == 0) {
-      int i, j;
-      item_ij(c >> 1, D, i, j);
-      v = (i == j) ? 1.0 : 0.0;
+    if ((c & 15) == 0) {                     // first entry of a group: 1 if the group opens a row (the diagonal item)
+      int g = c >> 4, r = 0;
+      while (r < D && g >= (D - r + 7) / 8) { g -= (D - r + 7) / 8; ++r; }
+      v = (r < D && g == 0) ? 1.0 : 0.0;
     }
     coef[x] = v;
   }
@@ -219,7 +232,7 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
 #pragma unroll
   for (int k = 0; k < K; ++k) nacc[k] = 0.0;
 
-  const int groups = CP / 16;
+  const int groups = coef_groups(D);
   const int tile_lo = chunk * tiles_per_chunk;
   int tile_hi = tile_lo + tiles_per_chunk;
   const int tile_end = (t_end + kWave - 1) / kWave;
@@ -249,47 +262,70 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
     for (int k = 0; k < K; ++k) { q[k][0] = 0.0; q[k][1] = 0.0; }
     double n2 = 0.0;
     const float2* __restrict__ yrow = sY + lane * RS;
-    // coefficient registers of this group and of the next one (fetched one group ahead of its use)
+    // Coefficient registers of this group and of the next one.  The fetches go out for every class, active or
+    // not, one group ahead of their use: a fetch under a branch would make every wait for a group's coefficients
+    // a wait for all fetches in flight, the next group's included.
     double ccur[K], cnxt[K];
-    static_for<0, K>([&](auto KI) {
-      constexpr int k = KI.value;
-      ccur[k] = 0.0;
-      cnxt[k] = 0.0;
-      if (class_on(mask, k)) ccur[k] = cf[k * CP];
-    });
-    int ii = 0, jj = 0;                      // wave-uniform coordinates of the next item
-    for (int g = 0; g < groups; ++g) {
-      if (g + 1 < groups) {
-        static_for<0, K>([&](auto KI) {
-          constexpr int k = KI.value;
-          if (class_on(mask, k)) cnxt[k] = cf[k * CP + 16 * (g + 1)];
-        });
-      }
-      double re[8], im[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const float2 a = yrow[ii], b = yrow[jj];
-        const double ar = a.x, ai = a.y, br = b.x, bi = b.y;
-        re[u] = ar * br + ai * bi;
-        im[u] = ai * br - ar * bi;
-        if (ii == jj && 8 * g + u < M) n2 += re[u];           // a diagonal item: |y_i|^2 (uniform test)
-        if (8 * g + u + 1 < M) {             // step to the next item, never past the last one (the padding
-          ++jj;                              // coefficients behind it are zero)
-          if (jj == D) { ++ii; jj = ii; }
+    for (int k = 0; k < K; ++k) ccur[k] = cf[k * CP];
+    int ri = 0, j0 = 0;                      // wave-uniform: row and first column of the group
+    double ar, ai;
+    {
+      const float2 a = yrow[0];
+      ar = a.x;
+      ai = a.y;
+    }
+    for (int g = 0; g < groups; ++g) {
+      const int gn = g + 1 < groups ? g + 1 : g;
+#pragma unroll
+      for (int k = 0; k < K; ++k) cnxt[k] = cf[k * CP + 16 * gn];
+      const float2* __restrict__ yb = yrow + j0;
+      const bool opens_row = j0 == ri;
+      // the group's items (ri, j0 + u), u < CNT, against the row-broadcast coefficients 2 u and 2 u + 1
+      auto group_items = [&](auto CNT) {
+        constexpr int cnt = decltype(CNT)::value;
+        double re[cnt], im[cnt];
+#pragma unroll
+        for (int u = 0; u < cnt; ++u) {
+          const float2 bq = yb[u];
+          const double br = bq.x, bi = bq.y;
+          re[u] = ar * br + ai * bi;
+          im[u] = ai * br - ar * bi;
         }
+        if (opens_row) n2 += re[0];            // the diagonal item: |y_i|^2
+        static_for<0, K>([&](auto KI) {
+          constexpr int k = decltype(KI)::value;
+          if (class_on(mask, k)) {
+            static_for<0, cnt>([&](auto UI) {
+              constexpr int u = decltype(UI)::value;
+              fma_bcast<2 * u, u == 0>(q[k][0], ccur[k], re[u]);
+              fma_bcast<2 * u + 1, false>(q[k][1], ccur[k], im[u]);
+            });
+          }
+        });
+      };
+      switch (D - j0) {                        // the same in every lane
+        case 1: group_items(std::integral_constant<int, 1>{}); break;
+        case 2: group_items(std::integral_constant<int, 2>{}); break;
+        case 3: group_items(std::integral_constant<int, 3>{}); break;
+        case 4: group_items(std::integral_constant<int, 4>{}); break;
+        case 5: group_items(std::integral_constant<int, 5>{}); break;
+        case 6: group_items(std::integral_constant<int, 6>{}); break;
+        case 7: group_items(std::integral_constant<int, 7>{}); break;
+        default: group_items(std::integral_constant<int, 8>{}); break;
       }
-      static_for<0, K>([&](auto KI) {
-        constexpr int k = KI.value;
-        if (class_on(mask, k)) {
-          static_for<0, 8>([&](auto UI) {
-            constexpr int u = UI.value;
-            fma_bcast<2 * u, u == 0>(q[k][0], ccur[k], re[u]);
-            fma_bcast<2 * u + 1, false>(q[k][1], ccur[k], im[u]);
-          });
-        }
-      });
 #pragma unroll
       for (int k = 0; k < K; ++k) ccur[k] = cnxt[k];
+      j0 += 8;
+      if (j0 >= D) {                           // next row
+        ++ri;
+        j0 = ri;
+        if (ri < D) {
+          const float2 a = yrow[ri];
+          ar = a.x;
+          ai = a.y;
+        }
+      }
     }
     // posterior over the active classes: pi_k / det B_k * q_k^-D, mantissa / exponent form
     const double n2c = fmax(n2, GSS_EPS_NORM_SQ);
@@ -422,7 +458,7 @@ __global__ __launch_bounds__(kWave * GSS_MAX_K) void em_factor_large(
     int D, int K, ChunkMap cmap, int weight_mode) {
   constexpr int W = 8 * BS;                                // padded matrix size
   __shared__ double sPiv[GSS_MAX_K][4][W];                 // per wavefront: pivot row (re, im), pivot column (re, im)
-  __shared__ __attribute__((aligned(16))) double sCoef[GSS_MAX_K][W * (W + 1)];   // per wavefront: the packed coefficients
+  extern __shared__ __attribute__((aligned(16))) double sCoef[];   // per wavefront: the class's coef_pitch(D) coefficients
   const int lane = threadIdx.x & (kWave - 1);
   const int k = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const long sf = blockIdx.x;
@@ -560,16 +596,27 @@ __global__ __launch_bounds__(kWave * GSS_MAX_K) void em_factor_large(
   // non-Hermitian, and for an ill-conditioned B, whose inverse has entries of 1e6, one triangle mirrored puts a
   // relative error of up to 1e-4 into the quadratic forms of the class's own frames, the Hermitian part 1e-10).
   // The two triangles meet in the wavefront's LDS: the owners of the upper triangle write, then the owners of the
-  // lower triangle add their conjugates, and the packed coefficients leave as one contiguous run.
+  // lower triangle add their conjugates, and the coefficients leave in the pass kernel's layout as one contiguous run.
   const int CP = coef_pitch(D);
   double* __restrict__ cf = coef + (sf * K + k) * (long)CP;
-  double* __restrict__ sCo = sCoef[k];
+  double* __restrict__ sCo = sCoef + (long)k * CP;
+  for (int x = lane; x < CP; x += kWave) sCo[x] = 0.0;     // the padding of the groups stays zero
+  wave_lds_sync();
+  int cpos[BS][BS];
 #pragma unroll
   for (int r = 0; r < BS; ++r)
 #pragma unroll
     for (int c = 0; c < BS; ++c) {
       const int i = a * BS + r, j = b * BS + c;
-      if (i <= j && j < D) *reinterpret_cast<double2*>(sCo + 2 * item[r][c]) = make_double2(mr[r][c], i == j ? 0.0 : mi[r][c]);
+      const int lo = i < j ? i : j, hi = i < j ? j : i;
+      cpos[r][c] = (hi < D) ? coef_pos(lo, hi, D) : 0;
+    }
+#pragma unroll
+  for (int r = 0; r < BS; ++r)
+#pragma unroll
+    for (int c = 0; c < BS; ++c) {
+      const int i = a * BS + r, j = b * BS + c;
+      if (i <= j && j < D) *reinterpret_cast<double2*>(sCo + cpos[r][c]) = make_double2(mr[r][c], i == j ? 0.0 : mi[r][c]);
     }
   wave_lds_sync();
 #pragma unroll
@@ -578,15 +625,14 @@ __global__ __launch_bounds__(kWave * GSS_MAX_K) void em_factor_large(
     for (int c = 0; c < BS; ++c) {
       const int i = a * BS + r, j = b * BS + c;
       if (i > j && i < D) {                                // entry (i, j) of the lower triangle: item (j, i)
-        double2 v = *reinterpret_cast<double2*>(sCo + 2 * item[r][c]);
+        double2 v = *reinterpret_cast<double2*>(sCo + cpos[r][c]);
         v.x += mr[r][c];
         v.y -= mi[r][c];
-        *reinterpret_cast<double2*>(sCo + 2 * item[r][c]) = v;
+        *reinterpret_cast<double2*>(sCo + cpos[r][c]) = v;
       }
     }
   wave_lds_sync();
-  for (int x = lane; x < 2 * M; x += kWave) cf[x] = sCo[x];
-  if (lane < CP - 2 * M) cf[2 * M + lane] = 0.0;           // the padding stays zero (fewer than 16 entries)
+  for (int x = lane; x < CP; x += kWave) cf[x] = sCo[x];
   if (lane == 0) {
     const double pi = weight_mode == 1 ? Nk / fmax(Ntot, GSS_EPS_N) : 1.0 / (double)K;
     const double cst = fmax(pi, GSS_EPS_PI) / detm;
@@ -811,6 +857,11 @@ int run_em_large(gss_ctx* ctx, const gss_yview& Y, const uint8_t* act, const int
       hipFuncSetAttribute((const void*)em_pass_large<K, NR, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
                           p.lds_bytes) != hipSuccess)
     return GSS_EHIP;
+  // the factor kernel stages every class's coefficients in LDS (up to 80 KB: 8 classes of 32 channels)
+  const int factor_lds = K * coef_pitch(D) * (int)sizeof(double);
+  const void* factor_kern = D <= 16 ? (const void*)em_factor_large<2> : D <= 24 ? (const void*)em_factor_large<3>
+                                                                                 : (const void*)em_factor_large<4>;
+  if (hipFuncSetAttribute(factor_kern, hipFuncAttributeMaxDynamicSharedMemorySize, factor_lds) != hipSuccess) return GSS_EHIP;
   const int tiles = (Tmax + kWave - 1) / kWave;
   const long slots = large_slots(ctx, em_pass_large<K, NR, false>, p.lds_bytes);
   const ChunkMap acc_map = plan_chunk_map(slots, n_sf, tiles, kLargeWaves, 0, true);
@@ -848,13 +899,13 @@ int run_em_large(gss_ctx* ctx, const gss_yview& Y, const uint8_t* act, const int
     gss_profile_end(ctx, 0, st);
     gss_profile_begin(ctx, 1, st);
     if (D <= 16)
-      hipLaunchKernelGGL(em_factor_large<2>, dim3((unsigned)n_sf), dim3(kWave * K), 0, st, part, npart, coef, cm, ce,
+      hipLaunchKernelGGL(em_factor_large<2>, dim3((unsigned)n_sf), dim3(kWave * K), factor_lds, st, part, npart, coef, cm, ce,
                          ctx->status, D, K, acc_map, weight_mode);
     else if (D <= 24)
-      hipLaunchKernelGGL(em_factor_large<3>, dim3((unsigned)n_sf), dim3(kWave * K), 0, st, part, npart, coef, cm, ce,
+      hipLaunchKernelGGL(em_factor_large<3>, dim3((unsigned)n_sf), dim3(kWave * K), factor_lds, st, part, npart, coef, cm, ce,
                          ctx->status, D, K, acc_map, weight_mode);
     else
-      hipLaunchKernelGGL(em_factor_large<4>, dim3((unsigned)n_sf), dim3(kWave * K), 0, st, part, npart, coef, cm, ce,
+      hipLaunchKernelGGL(em_factor_large<4>, dim3((unsigned)n_sf), dim3(kWave * K), factor_lds, st, part, npart, coef, cm, ce,
                          ctx->status, D, K, acc_map, weight_mode);
     gss_profile_end(ctx, 1, st);
   }
