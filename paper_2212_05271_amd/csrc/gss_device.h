@@ -228,6 +228,52 @@ __device__ __forceinline__ void fma_bcast(double& acc, double c, double p) {
     asm("v_fmac_f64_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(c), "v"(p), "n"(N));
 }
 
+// q0 += sum over u < n of c[2 u] re[u] and q1 += sum over u < n of c[2 u + 1] im[u], 1 <= n (8 and more: all 8
+// items), c[x] being the value that `c` holds in lane x of the lane's row of 16.  n must be the same in every lane.
+// The items run from the last to the first, and a shorter run enters the chain further down, so each accumulator
+// stays in one register whatever n is (a switch over n in C++ gives every length its own copy of the chain and
+// moves the accumulators between the copies' registers around every one of them).  Idle states: the two scalar
+// instructions in front of every entry separate the first FMA from the last vector write before the statement,
+// and within the chain an accumulator is read two issue slots after it was written, one of them the s_nop.
+__device__ __forceinline__ void fma_bcast_run(double& q0, double& q1, double c, const double (&re)[8],
+                                              const double (&im)[8], int n) {
+#define GSS_BCAST_ITEM(label, u, a, b)                                                               \
+  label ":\n\t"                                                                                      \
+  "v_fmac_f64_dpp %[q0], %[c], %[re" #u "] row_newbcast:" #a " row_mask:0xf bank_mask:0xf\n\t"        \
+  "v_fmac_f64_dpp %[q1], %[c], %[im" #u "] row_newbcast:" #b " row_mask:0xf bank_mask:0xf\n\t"
+  asm("s_cmp_gt_i32 %[n], 7\n\t"
+      "s_cbranch_scc1 18f\n\t"
+      "s_cmp_gt_i32 %[n], 3\n\t"
+      "s_cbranch_scc1 10f\n\t"
+      "s_cmp_eq_u32 %[n], 3\n\t"
+      "s_cbranch_scc1 13f\n\t"
+      "s_cmp_eq_u32 %[n], 2\n\t"
+      "s_cbranch_scc1 12f\n\t"
+      "s_branch 11f\n\t"
+      "10:\n\t"
+      "s_cmp_eq_u32 %[n], 7\n\t"
+      "s_cbranch_scc1 17f\n\t"
+      "s_cmp_eq_u32 %[n], 6\n\t"
+      "s_cbranch_scc1 16f\n\t"
+      "s_cmp_eq_u32 %[n], 5\n\t"
+      "s_cbranch_scc1 15f\n\t"
+      "s_branch 14f\n\t"
+      GSS_BCAST_ITEM("18", 7, 14, 15) "s_nop 0\n\t"
+      GSS_BCAST_ITEM("17", 6, 12, 13) "s_nop 0\n\t"
+      GSS_BCAST_ITEM("16", 5, 10, 11) "s_nop 0\n\t"
+      GSS_BCAST_ITEM("15", 4, 8, 9) "s_nop 0\n\t"
+      GSS_BCAST_ITEM("14", 3, 6, 7) "s_nop 0\n\t"
+      GSS_BCAST_ITEM("13", 2, 4, 5) "s_nop 0\n\t"
+      GSS_BCAST_ITEM("12", 1, 2, 3) "s_nop 0\n\t"
+      GSS_BCAST_ITEM("11", 0, 0, 1)
+      : [q0] "+v"(q0), [q1] "+v"(q1)
+      : [c] "v"(c), [n] "s"(n), [re0] "v"(re[0]), [re1] "v"(re[1]), [re2] "v"(re[2]), [re3] "v"(re[3]),
+        [re4] "v"(re[4]), [re5] "v"(re[5]), [re6] "v"(re[6]), [re7] "v"(re[7]), [im0] "v"(im[0]), [im1] "v"(im[1]),
+        [im2] "v"(im[2]), [im3] "v"(im[3]), [im4] "v"(im[4]), [im5] "v"(im[5]), [im6] "v"(im[6]), [im7] "v"(im[7])
+      : "scc");
+#undef GSS_BCAST_ITEM
+}
+
 // Wave-uniform test of bit k of `mask`, re-evaluated from the one scalar register that holds the mask at every
 // use (the empty asm statement keeps the compiler from caching the K booleans in scalar register pairs).
 __device__ __forceinline__ bool class_on(unsigned mask, int k) {

@@ -280,40 +280,23 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
 #pragma unroll
       for (int k = 0; k < K; ++k) cnxt[k] = cf[k * CP + 16 * gn];
       const float2* __restrict__ yb = yrow + j0;
-      const bool opens_row = j0 == ri;
-      // the group's items (ri, j0 + u), u < CNT, against the row-broadcast coefficients 2 u and 2 u + 1
-      auto group_items = [&](auto CNT) {
-        constexpr int cnt = decltype(CNT)::value;
-        double re[cnt], im[cnt];
+      const int cnt = __builtin_amdgcn_readfirstlane(D - j0);   // items of the group: 8, fewer at the end of a row
+      // The group's items (ri, j0 + u), u < cnt, against the row-broadcast coefficients 2 u and 2 u + 1.  All 8
+      // are formed, whatever cnt is: the reads beyond the row land in the rows of the following frames or, for
+      // the last frame, in the weights behind the tile, and what is formed from them is not used.
+      double re[8], im[8];
 #pragma unroll
-        for (int u = 0; u < cnt; ++u) {
-          const float2 bq = yb[u];
-          const double br = bq.x, bi = bq.y;
-          re[u] = ar * br + ai * bi;
-          im[u] = ai * br - ar * bi;
-        }
-        if (opens_row) n2 += re[0];            // the diagonal item: |y_i|^2
-        static_for<0, K>([&](auto KI) {
-          constexpr int k = decltype(KI)::value;
-          if (class_on(mask, k)) {
-            static_for<0, cnt>([&](auto UI) {
-              constexpr int u = decltype(UI)::value;
-              fma_bcast<2 * u, u == 0>(q[k][0], ccur[k], re[u]);
-              fma_bcast<2 * u + 1, false>(q[k][1], ccur[k], im[u]);
-            });
-          }
-        });
-      };
-      switch (D - j0) {                        // the same in every lane
-        case 1: group_items(std::integral_constant<int, 1>{}); break;
-        case 2: group_items(std::integral_constant<int, 2>{}); break;
-        case 3: group_items(std::integral_constant<int, 3>{}); break;
-        case 4: group_items(std::integral_constant<int, 4>{}); break;
-        case 5: group_items(std::integral_constant<int, 5>{}); break;
-        case 6: group_items(std::integral_constant<int, 6>{}); break;
-        case 7: group_items(std::integral_constant<int, 7>{}); break;
-        default: group_items(std::integral_constant<int, 8>{}); break;
+      for (int u = 0; u < 8; ++u) {
+        const float2 bq = yb[u];
+        const double br = bq.x, bi = bq.y;
+        re[u] = ar * br + ai * bi;
+        im[u] = ai * br - ar * bi;
       }
+      if (j0 == ri) n2 += re[0];               // the diagonal item: |y_i|^2
+      static_for<0, K>([&](auto KI) {
+        constexpr int k = decltype(KI)::value;
+        if (class_on(mask, k)) fma_bcast_run(q[k][0], q[k][1], ccur[k], re, im, cnt);
+      });
 #pragma unroll
       for (int k = 0; k < K; ++k) ccur[k] = cnxt[k];
       j0 += 8;
