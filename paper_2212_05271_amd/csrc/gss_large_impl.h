@@ -264,10 +264,11 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
     const float2* __restrict__ yrow = sY + lane * RS;
     // Coefficient registers of this group and of the next one.  The fetches go out for every class, active or
     // not, one group ahead of their use: a fetch under a branch would make every wait for a group's coefficients
-    // a wait for all fetches in flight, the next group's included.
-    double ccur[K], cnxt[K];
+    // a wait for all fetches in flight, the next group's included.  The two register sets swap roles from group
+    // to group (the loop takes two groups per round), so nothing is moved between them.
+    double ca[K], cb[K];
 #pragma unroll
-    for (int k = 0; k < K; ++k) ccur[k] = cf[k * CP];
+    for (int k = 0; k < K; ++k) ca[k] = cf[k * CP];
     int ri = 0, j0 = 0;                      // wave-uniform: row and first column of the group
     double ar, ai;
     {
@@ -275,7 +276,7 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
       ar = a.x;
       ai = a.y;
     }
-    for (int g = 0; g < groups; ++g) {
+    auto group = [&](const double (&ccur)[K], double (&cnxt)[K], int g) {
       const int gn = g + 1 < groups ? g + 1 : g;
 #pragma unroll
       for (int k = 0; k < K; ++k) cnxt[k] = cf[k * CP + 16 * gn];
@@ -283,22 +284,22 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
       const int cnt = __builtin_amdgcn_readfirstlane(D - j0);   // items of the group: 8, fewer at the end of a row
       // The group's items (ri, j0 + u), u < cnt, against the row-broadcast coefficients 2 u and 2 u + 1.  All 8
       // are formed, whatever cnt is: the reads beyond the row land in the rows of the following frames or, for
-      // the last frame, in the weights behind the tile, and what is formed from them is not used.
+      // the last frame, in the weights behind the tile, and what is formed from them is not used.  (Forming the
+      // upper four under a branch costs more than it saves: the compiler then clears their registers first.)
       double re[8], im[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      auto form = [&](int u) {
         const float2 bq = yb[u];
         const double br = bq.x, bi = bq.y;
         re[u] = ar * br + ai * bi;
         im[u] = ai * br - ar * bi;
-      }
+      };
+#pragma unroll
+      for (int u = 0; u < 8; ++u) form(u);
       if (j0 == ri) n2 += re[0];               // the diagonal item: |y_i|^2
       static_for<0, K>([&](auto KI) {
         constexpr int k = decltype(KI)::value;
         if (class_on(mask, k)) fma_bcast_run(q[k][0], q[k][1], ccur[k], re, im, cnt);
       });
-#pragma unroll
-      for (int k = 0; k < K; ++k) ccur[k] = cnxt[k];
       j0 += 8;
       if (j0 >= D) {                           // next row
         ++ri;
@@ -309,6 +310,14 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
           ai = a.y;
         }
       }
+    };
+    {
+      int g = 0;
+      for (; g + 1 < groups; g += 2) {
+        group(ca, cb, g);
+        group(cb, ca, g + 1);
+      }
+      if (g < groups) group(ca, cb, g);
     }
     // posterior over the active classes: pi_k / det B_k * q_k^-D, mantissa / exponent form
     const double n2c = fmax(n2, GSS_EPS_NORM_SQ);
