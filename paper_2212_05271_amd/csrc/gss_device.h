@@ -284,25 +284,44 @@ __device__ __forceinline__ bool class_on(unsigned mask, int k) {
 // Tile geometry shared by the kernels that accumulate weighted outer products: a workgroup is
 // kPassWaves wavefronts, each wavefront owns whole tiles of 64 frames and a private LDS region.
 constexpr int kPassWaves = 4;
-constexpr int kYStride = 18;   // doubles per frame row of the y tile: 8 complex + 2 pad (16-byte units: 9 per row)
+// Doubles per frame row of the y tile: the 8 complex channels, then -i y_c for the channels c < 4 (the lanes that
+// pair a channel with the one four below it read that copy, see slot_entry), then 2 of padding (16-byte units: 13
+// per row, odd, so that the rows of adjacent frames start in different banks).
+constexpr int kYStride = 26;
+constexpr int kYTurned = 16;   // offset of the turned copies within a row
+static_assert(kYStride == kYTurned + 8 + 2, "a row is 8 channels, 4 turned copies and two padding entries");
+
+// Writes one frame row of the y tile: channel d at 2 d (zero beyond D) and the turned copies of channels 0..3.
+template <int D>
+__device__ __forceinline__ void store_tile_row(double* __restrict__ row, const double (&yr)[D], const double (&yi)[D]) {
+#pragma unroll
+  for (int d = 0; d < 8; ++d) {
+    double2 yv = make_double2(0.0, 0.0);
+    if (d < D) yv = make_double2(yr[d < D ? d : 0], yi[d < D ? d : 0]);
+    *reinterpret_cast<double2*>(&row[2 * d]) = yv;
+    if (d < 4) *reinterpret_cast<double2*>(&row[kYTurned + 2 * d]) = make_double2(yv.y, -yv.x);
+  }
+}
 
 
 // Phase-2 lane type eg = channel i.  Its 8 accumulator slots: n = 0..5 are Re and Im of y_i conj(y_b),
-// b = (i + d) mod 8 for d = 1, 2, 3; n = 6, 7 are Re and Im of y_i conj(y_(i+4)) for i < 4, and the two real
-// diagonal entries |y_i|^2, |y_(i-4)|^2 for i >= 4.  The pairs at circular distance 1..4 are all 28 pairs
-// once; where b < i the slot holds the conjugate of the stored (upper-triangle) entry, i.e. its imaginary
-// part with the opposite sign.
+// b = (i + d) mod 8 for d = 1, 2, 3; n = 6 is the real diagonal entry |y_i|^2; n = 7 is one half of the pair at
+// distance 4: Re of y_i conj(y_(i+4)) for i < 4 and Im of y_(i-4) conj(y_i) for i >= 4.  Both halves are
+// y_i.re * a + y_i.im * b of a second operand (a, b) = y_(i+4) or -i y_(i-4), which the lane reads from the tile
+// (the row holds the turned copies), so every lane type runs the same instructions.  The pairs at circular
+// distance 1..4 are all 28 pairs once; where b < i the slot holds the conjugate of the stored (upper-triangle)
+// entry, i.e. its imaginary part with the opposite sign.
 struct SlotEntry { int i, j, part, sign; };     // part: 0 real diagonal, 1 Re, 2 Im
 __host__ __device__ constexpr SlotEntry slot_entry(int eg, int n) {
-  if (n < 6 || eg < 4) {
-    const int d = n < 6 ? n / 2 + 1 : 4;
+  if (n < 6) {
+    const int d = n / 2 + 1;
     const int part = 1 + (n & 1);
     const int a = eg, b = (eg + d) % 8;
     if (a < b) return SlotEntry{a, b, part, 1};
     return SlotEntry{b, a, part, part == 2 ? -1 : 1};
   }
-  const int c = n == 6 ? eg : eg - 4;
-  return SlotEntry{c, c, 0, 1};
+  if (n == 6) return SlotEntry{eg, eg, 0, 1};
+  return eg < 4 ? SlotEntry{eg, eg + 4, 1, 1} : SlotEntry{eg - 4, eg, 2, 1};
 }
 
 // Packed index (gss_packed_row order, matrix size D) of accumulator slot n of lane type eg, or -1 if the
@@ -329,7 +348,8 @@ constexpr SlotTable make_slot_table() {
 template <int KW, int WS, int UNROLL = 2>
 __device__ __forceinline__ void accumulate_tile(const double* __restrict__ sY, const double* __restrict__ sW,
                                                 int tg, int eg, double (&acc)[8][KW]) {
-  const int c1 = 2 * ((eg + 1) & 7), c2 = 2 * ((eg + 2) & 7), c3 = 2 * ((eg + 3) & 7), c4 = 2 * ((eg + 4) & 7);
+  const int c1 = 2 * ((eg + 1) & 7), c2 = 2 * ((eg + 2) & 7), c3 = 2 * ((eg + 3) & 7);
+  const int c4 = eg < 4 ? 2 * (eg + 4) : kYTurned + 2 * (eg - 4);
 #pragma unroll UNROLL
   for (int j = 0; j < 8; ++j) {
     const int r = tg + 8 * j;              // rows of the 8 frame groups are adjacent: distinct LDS banks
@@ -346,11 +366,7 @@ __device__ __forceinline__ void accumulate_tile(const double* __restrict__ sY, c
     e[0] = x.x * y1.x + x.y * y1.y;  e[1] = x.y * y1.x - x.x * y1.y;
     e[2] = x.x * y2.x + x.y * y2.y;  e[3] = x.y * y2.x - x.x * y2.y;
     e[4] = x.x * y3.x + x.y * y3.y;  e[5] = x.y * y3.x - x.x * y3.y;
-    if (eg < 4) {   // the pair at distance 4
-      e[6] = x.x * y4.x + x.y * y4.y;  e[7] = x.y * y4.x - x.x * y4.y;
-    } else {        // the diagonal entries of the two channels
-      e[6] = x.x * x.x + x.y * x.y;    e[7] = y4.x * y4.x + y4.y * y4.y;
-    }
+    e[6] = x.x * x.x + x.y * x.y;    e[7] = x.x * y4.x + x.y * y4.y;
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
 #pragma unroll
@@ -373,7 +389,7 @@ __device__ __forceinline__ void accumulate_tile_masked(const double* __restrict_
   const double* __restrict__ p1 = sY + tg * kYStride + 2 * ((eg + 1) & 7);
   const double* __restrict__ p2 = sY + tg * kYStride + 2 * ((eg + 2) & 7);
   const double* __restrict__ p3 = sY + tg * kYStride + 2 * ((eg + 3) & 7);
-  const double* __restrict__ p4 = sY + tg * kYStride + 2 * ((eg + 4) & 7);
+  const double* __restrict__ p4 = sY + tg * kYStride + (eg < 4 ? 2 * (eg + 4) : kYTurned + 2 * (eg - 4));
   const double* __restrict__ pw = sW + tg * WS;
   double2 y[5];
   double w[KW];
@@ -396,11 +412,7 @@ __device__ __forceinline__ void accumulate_tile_masked(const double* __restrict_
       e[0] = x.x * y1.x + x.y * y1.y;  e[1] = x.y * y1.x - x.x * y1.y;
       e[2] = x.x * y2.x + x.y * y2.y;  e[3] = x.y * y2.x - x.x * y2.y;
       e[4] = x.x * y3.x + x.y * y3.y;  e[5] = x.y * y3.x - x.x * y3.y;
-      if (eg < 4) {   // the pair at distance 4
-        e[6] = x.x * y4.x + x.y * y4.y;  e[7] = x.y * y4.x - x.x * y4.y;
-      } else {        // the diagonal entries of the two channels
-        e[6] = x.x * x.x + x.y * x.y;    e[7] = y4.x * y4.x + y4.y * y4.y;
-      }
+      e[6] = x.x * x.x + x.y * x.y;    e[7] = x.x * y4.x + x.y * y4.y;
 #pragma unroll
       for (int k = 0; k < KW; ++k) wc[k] = w[k];
     }

@@ -265,12 +265,7 @@ __device__ __forceinline__ void pass_tile(
     });
   } else {
     // this tile's y and weights go to LDS, then phase 2 runs over it
-#pragma unroll
-    for (int d = 0; d < 8; ++d) {
-      double2 yv = make_double2(0.0, 0.0);
-      if (d < D) yv = make_double2(yr[d < D ? d : 0], yi[d < D ? d : 0]);
-      *reinterpret_cast<double2*>(&sY[lane * kYStride + 2 * d]) = yv;
-    }
+    store_tile_row<D>(sY + lane * kYStride, yr, yi);
     static_for<0, K>([&](auto KI) {
       constexpr int k = KI.value;
       if (class_on(tmask, k)) {
@@ -786,7 +781,13 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
   constexpr int kTileDoubles = DIRECT ? 0 : kWave * kYStride + kWave * WS;
   constexpr int kCoefDoubles = K * R * 16;             // packed coefficients, padded to whole registers
   constexpr int kSumDoubles = K * E + K;               // packed weighted scatter sums, then the class counts
-  constexpr int kWaveDoubles = (kTileDoubles + kCoefDoubles + kSumDoubles + K + 1) / 2 * 2;
+  // With the coefficients resident in registers, the sums, counts, coefficients and class constants of the M-step
+  // live only between the last tile of a pass and the first tile of the next one: they share the tile's region,
+  // behind the rows that the reduction of the accumulators uses for staging.
+  constexpr bool SHARED_MSTEP = !DIRECT && RESIDENT;
+  static_assert(!SHARED_MSTEP || kReduceWaveDoubles + kCoefDoubles + kSumDoubles + K <= kTileDoubles,
+                "the M-step's buffers must fit behind the reduction rows inside the tile region");
+  constexpr int kWaveDoubles = SHARED_MSTEP ? kTileDoubles : (kTileDoubles + kCoefDoubles + kSumDoubles + K + 1) / 2 * 2;
   constexpr int kShareRows = DIRECT ? 4 : 1;           // sets of sums per wavefront in the shared buffer (NW > 1)
   constexpr int kShareDoubles = NW > 1 ? 2 * NW * kShareRows * kSumDoubles : 0;
   __shared__ __attribute__((aligned(16))) double lds[NW * kWaveDoubles + kShareDoubles];
@@ -794,7 +795,7 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
   const int wave = NW > 1 ? __builtin_amdgcn_readfirstlane(threadIdx.x / kWave) : 0;
   double* __restrict__ sY = lds + wave * kWaveDoubles;
   double* __restrict__ sW = sY + kWave * kYStride;
-  double* __restrict__ sC = sY + kTileDoubles;         // [K][R * 16] coefficients of B^-1 for the next pass
+  double* __restrict__ sC = sY + (SHARED_MSTEP ? kReduceWaveDoubles : kTileDoubles);   // [K][R * 16] coefficients of B^-1 for the next pass
   double* __restrict__ sR = sC + kCoefDoubles;         // [K][E] packed weighted scatter sums
   double* __restrict__ sN = sR + K * E;                // [K] class counts
   double* __restrict__ sCC = sN + K;                   // [K] class constants pi / det B

@@ -30,8 +30,10 @@ __global__ __launch_bounds__(kWave * kPassWaves) void mvdr_cov_small(
     const int32_t* __restrict__ target, double* __restrict__ part, uint32_t* __restrict__ status,
     int F, int Tmax, int K, int C, int tiles_per_chunk) {
   constexpr int E = D * D;
-  constexpr int WS = 3;
-  constexpr int kTileDoubles = kWave * kYStride + kWave * WS;
+  // the two weights of a frame sit in the two padding entries at the end of its row of the y tile (three
+  // workgroups per CU fit that way)
+  constexpr int WS = kYStride;
+  constexpr int kTileDoubles = kWave * kYStride;
   constexpr int kRedDoubles = kPassWaves * 64 * 2;
   constexpr int kLdsDoubles = kPassWaves * kTileDoubles > kRedDoubles ? kPassWaves * kTileDoubles : kRedDoubles;
   __shared__ __attribute__((aligned(16))) double lds[kLdsDoubles];
@@ -51,7 +53,7 @@ __global__ __launch_bounds__(kWave * kPassWaves) void mvdr_cov_small(
   }
 
   double* __restrict__ sY = lds + wave * kTileDoubles;
-  double* __restrict__ sW = sY + kWave * kYStride;
+  double* __restrict__ sW = sY + kYTurned + 8;
   double acc[8][2];
 #pragma unroll
   for (int n = 0; n < 8; ++n) { acc[n][0] = 0.0; acc[n][1] = 0.0; }
@@ -80,11 +82,11 @@ __global__ __launch_bounds__(kWave * kPassWaves) void mvdr_cov_small(
   if (tile < tile_hi) load_tile(tile);
   for (; tile < tile_hi; tile += kPassWaves) {
     const bool valid = tile * kWave + lane < T;
+    {
+      double yr[D], yi[D];
 #pragma unroll
-    for (int d = 0; d < 8; ++d) {
-      double2 v = make_double2(0.0, 0.0);
-      if (d < D) v = make_double2((double)yraw[d < D ? d : 0].x, (double)yraw[d < D ? d : 0].y);
-      *reinterpret_cast<double2*>(&sY[lane * kYStride + 2 * d]) = v;
+      for (int d = 0; d < D; ++d) { yr[d] = (double)yraw[d].x; yi[d] = (double)yraw[d].y; }
+      store_tile_row<D>(sY + lane * kYStride, yr, yi);
     }
     double wt = 0.0, wb = 0.0;
 #pragma unroll
