@@ -319,9 +319,11 @@ def test_every_large_instantiation(env, D):
     assert env["ctx"].get_status() == 0
 
 
-@pytest.mark.parametrize("D,K,T", [(9, 3, 100), (12, 5, 150), (16, 2, 70), (24, 5, 200), (32, 4, 130)])
+@pytest.mark.parametrize("D,K,T", [(9, 3, 100), (11, 2, 70), (12, 5, 150), (14, 2, 60), (16, 2, 70), (21, 3, 90),
+                                   (23, 3, 90), (24, 5, 200), (29, 2, 80), (32, 4, 130)])
 def test_large_arrays(env, D, K, T):
-    """9 <= D <= 32 channels (run-time D kernels)."""
+    """9 <= D <= 32 channels (run-time D kernels; the rows of the packed triangle end in coefficient groups of
+    every length 1..8, and the channel counts cover every remainder of D modulo 8 between them and the tests above)."""
     rng = np.random.default_rng(1000 + D)
     F = 5
     v = _cn(rng, (K, F, D))
