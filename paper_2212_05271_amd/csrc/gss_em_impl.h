@@ -781,13 +781,17 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
   constexpr int kTileDoubles = DIRECT ? 0 : kWave * kYStride + kWave * WS;
   constexpr int kCoefDoubles = K * R * 16;             // packed coefficients, padded to whole registers
   constexpr int kSumDoubles = K * E + K;               // packed weighted scatter sums, then the class counts
-  // With the coefficients resident in registers, the sums, counts, coefficients and class constants of the M-step
-  // live only between the last tile of a pass and the first tile of the next one: they share the tile's region,
-  // behind the rows that the reduction of the accumulators uses for staging.
-  constexpr bool SHARED_MSTEP = !DIRECT && RESIDENT;
-  static_assert(!SHARED_MSTEP || kReduceWaveDoubles + kCoefDoubles + kSumDoubles + K <= kTileDoubles,
+  // The sums, counts and class constants of the M-step live only between the last tile of a pass and the first
+  // tile of the next one: they share the tile's region, behind the rows that the reduction of the accumulators
+  // uses for staging.  So do the coefficients when they are resident in registers during a pass (otherwise the
+  // pass reads them from LDS and they keep a place of their own behind the tile).
+  constexpr bool SHARED_MSTEP = !DIRECT;
+  constexpr int kSharedDoubles = kSumDoubles + K + (RESIDENT ? kCoefDoubles : 0);
+  static_assert(!SHARED_MSTEP || kReduceWaveDoubles + kSharedDoubles <= kTileDoubles,
                 "the M-step's buffers must fit behind the reduction rows inside the tile region");
-  constexpr int kWaveDoubles = SHARED_MSTEP ? kTileDoubles : (kTileDoubles + kCoefDoubles + kSumDoubles + K + 1) / 2 * 2;
+  constexpr int kWaveDoubles = !SHARED_MSTEP ? (kTileDoubles + kCoefDoubles + kSumDoubles + K + 1) / 2 * 2
+                               : RESIDENT    ? kTileDoubles
+                                             : (kTileDoubles + kCoefDoubles + 1) / 2 * 2;
   constexpr int kShareRows = DIRECT ? 4 : 1;           // sets of sums per wavefront in the shared buffer (NW > 1)
   constexpr int kShareDoubles = NW > 1 ? 2 * NW * kShareRows * kSumDoubles : 0;
   __shared__ __attribute__((aligned(16))) double lds[NW * kWaveDoubles + kShareDoubles];
@@ -795,8 +799,8 @@ __global__ __launch_bounds__(kWave * NW, 2) void em_whole_small(
   const int wave = NW > 1 ? __builtin_amdgcn_readfirstlane(threadIdx.x / kWave) : 0;
   double* __restrict__ sY = lds + wave * kWaveDoubles;
   double* __restrict__ sW = sY + kWave * kYStride;
-  double* __restrict__ sC = sY + (SHARED_MSTEP ? kReduceWaveDoubles : kTileDoubles);   // [K][R * 16] coefficients of B^-1 for the next pass
-  double* __restrict__ sR = sC + kCoefDoubles;         // [K][E] packed weighted scatter sums
+  double* __restrict__ sC = sY + (SHARED_MSTEP && RESIDENT ? kReduceWaveDoubles : kTileDoubles);   // [K][R * 16] coefficients of B^-1 for the next pass
+  double* __restrict__ sR = SHARED_MSTEP && !RESIDENT ? sY + kReduceWaveDoubles : sC + kCoefDoubles;   // [K][E] packed weighted scatter sums
   double* __restrict__ sN = sR + K * E;                // [K] class counts
   double* __restrict__ sCC = sN + K;                   // [K] class constants pi / det B
   double* __restrict__ sShare = lds + NW * kWaveDoubles;   // [2][NW][kShareRows][kSumDoubles] sums of the wavefronts (NW > 1)
