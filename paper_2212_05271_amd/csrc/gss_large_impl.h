@@ -265,7 +265,7 @@ __global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
     // Coefficient registers of this group and of the next one.  The fetches go out for every class, active or
     // not, one group ahead of their use: a fetch under a branch would make every wait for a group's coefficients
     // a wait for all fetches in flight, the next group's included.  The two register sets swap roles from group
-    // to group (the loop takes two groups per round), so nothing is moved between them.
+    // to group (the loop body handles two groups), so nothing is moved between them.
     double ca[K], cb[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) ca[k] = cf[k * CP];
