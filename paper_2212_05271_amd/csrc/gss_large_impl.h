@@ -185,8 +185,15 @@ __device__ __forceinline__ void reduce_items(double (&acc)[NR][2][KW], double* _
 // (a coalesced 128-byte read that the four rows of the wavefront share); the FMAs take them through the
 // row-broadcast selector of the fp64 FMA.  Classes outside the tile's activity mask are skipped.
 // ----------------------------------------------------------------------------------------------
+// Wavefronts per SIMD that the register allocation of the pass kernel is held to: two where the 4 K NR registers
+// of the phase-2 accumulators leave room for most of the rest within 256 (some values then go to scratch memory,
+// which costs far less than the second wavefront brings: 20 to 36 % less time at 25 to 32 channels or 6 to 8
+// classes), one otherwise (beyond 180 accumulator registers the spills reach the inner loops and the kernel gets
+// two to three times slower than with one wavefront).
+constexpr int pass_waves_per_simd(int K, int NR) { return 4 * K * NR <= 180 ? 2 : 1; }
+
 template <int K, int NR, bool FINAL>
-__global__ __launch_bounds__(kWave * kLargeWaves) void em_pass_large(
+__global__ __launch_bounds__(kWave * kLargeWaves, pass_waves_per_simd(K, NR)) void em_pass_large(
     gss_yview yv, const uint8_t* __restrict__ abyte, const uint32_t* __restrict__ tmask,
     const int32_t* __restrict__ T_len,
     const double* __restrict__ coef, const double* __restrict__ cmant, const int32_t* __restrict__ cexp,
